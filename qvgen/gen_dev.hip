@@ -1,0 +1,58 @@
+// Device-side twin of the host feature generator: fills an n x dim feature table directly in
+// HBM so that tables of tens of GB never pass through host memory.  Pure data generation; the
+// integer part is exact and the single fp32 multiply (and the fp16 conversion, round to nearest
+// even) round identically on host and device, so both produce the same bits.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <cstdint>
+
+namespace {
+
+__device__ __forceinline__ uint64_t mix64(uint64_t x) {
+    x ^= x >> 30; x *= 0xBF58476D1CE4E5B9ull;
+    x ^= x >> 27; x *= 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    return x;
+}
+__device__ __forceinline__ uint64_t hash4(uint64_t seed, uint64_t dom, uint64_t a, uint64_t b) {
+    uint64_t x = mix64(seed ^ (dom * 0xD6E8FEB86659FD93ull + 0x9E3779B97F4A7C15ull));
+    x = mix64(x + a * 0x9E3779B97F4A7C15ull + 1);
+    x = mix64(x ^ (b * 0xC2B2AE3D27D4EB4Full + 2));
+    return x;
+}
+__device__ __forceinline__ float feature_value(uint64_t seed, uint64_t i, uint64_t j) {
+    uint64_t h = hash4(seed, 3, i, j);
+    int32_t s = (int32_t)(h & 0xFFFF) + (int32_t)((h >> 16) & 0xFFFF) +
+                (int32_t)((h >> 32) & 0xFFFF) + (int32_t)(h >> 48) - 131070;
+    return __fmul_rn((float)s, 2.6428998e-5f);
+}
+
+template <typename T>
+__global__ void fill_features(uint64_t seed, int64_t row_begin, int64_t n_rows, int64_t dim, T* out) {
+    int64_t total = n_rows * dim;
+    for (int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; idx < total;
+         idx += (int64_t)gridDim.x * blockDim.x) {
+        int64_t r = idx / dim, j = idx - r * dim;
+        float v = feature_value(seed, (uint64_t)(row_begin + r), (uint64_t)j);
+        if constexpr (sizeof(T) == 4) out[idx] = v;
+        else out[idx] = __float2half_rn(v);
+    }
+}
+
+}  // namespace
+
+extern "C" int qg_features_device(uint64_t seed, int64_t row_begin, int64_t n_rows, int64_t dim,
+                                  int elem_bytes, void* out, void* stream) {
+    if (n_rows <= 0 || dim <= 0) return 0;
+    int64_t total = n_rows * dim;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 256 * 64) blocks = 256 * 64;
+    hipStream_t s = (hipStream_t)stream;
+    if (elem_bytes == 4)
+        hipLaunchKernelGGL(fill_features<float>, dim3((unsigned)blocks), dim3(256), 0, s, seed, row_begin, n_rows, dim, (float*)out);
+    else if (elem_bytes == 2)
+        hipLaunchKernelGGL(fill_features<__half>, dim3((unsigned)blocks), dim3(256), 0, s, seed, row_begin, n_rows, dim, (__half*)out);
+    else
+        return -1;
+    return (int)hipGetLastError();
+}

@@ -1,0 +1,35 @@
+import os
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+GOLDEN = os.path.join(ROOT, "tests", "golden")
+
+
+def pytest_configure(config):
+    config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+
+
+def read_golden(name):
+    """Parse a golden text fixture into {key: [tokens]} (first occurrence of each key)."""
+    out = {}
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            k, *rest = line.split()
+            out.setdefault(k, rest)
+    return out
+
+
+@pytest.fixture(scope="session")
+def tiny_graph():
+    import qvgen
+    w = qvgen.workload("tiny")
+    rowptr, col = w.graph()
+    return w, rowptr, col
