@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: sample -> reindex -> gather per batch.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload citation] [--streams S]
+
+A step is one batch through qv_sample (all hops, dedup, relabel) and qv_gather (feature rows of
+every distinct sampled node).  All inputs (graph, features, seed batches) are synthetic, seeded
+and resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
+
+
+def log(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
+
+
+def algorithmic_bytes(n_frontier_entries, n_edges, n_unique, n_rows, row_bytes, rowptr_bytes, tiered):
+    """Bytes the method must move for one batch (per-unit figures: see the design doc, 'Measurement')."""
+    sample = n_frontier_entries * (4 + 2 * rowptr_bytes + 8) + n_edges * (4 + 4)
+    reindex = n_edges * (4 + 8 + 8) + n_unique * 4 + n_frontier_entries * 4
+    gather = n_rows * (4 + (4 if tiered else 0) + 2 * row_bytes)
+    return sample, reindex, gather
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="citation")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
+    ap.add_argument("--streams", type=int, default=1, help="batches in flight (one context per stream)")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-metrics", action="store_true", help="skip the PSGS / FAP whole-graph passes")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
+              "Re-run with --gpus 1." % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import qvgen
+    import paper_2305_10863_amd as qv
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    qv.lib()
+    torch.cuda.set_device(0)
+    w = qvgen.workload(args.workload, args.scale)
+    batch = args.batch or w.batch
+    K, W, S = args.steps, args.warmup, max(1, args.streams)
+
+    # ---- inputs -----------------------------------------------------------------------------
+    t0 = time.time()
+    rowptr, col = w.graph()
+    n_edges_graph = len(col)
+    log("graph %s: %d nodes, %d edges generated in %.1fs" % (w.name, w.n, n_edges_graph, time.time() - t0))
+    t0 = time.time()
+    d_rowptr, d_col = torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda()
+    tdtype = torch.float16 if w.feat_dtype == np.float16 else torch.float32
+    table = qvgen.features_device(w.seed, w.n, w.dim, tdtype)
+    torch.cuda.synchronize()
+    log("graph uploaded, %.1f GB feature table filled in HBM in %.1fs" % (w.n * w.row_bytes / 1e9, time.time() - t0))
+
+    ctx0 = qv.Context(0)
+    g = qv.Graph(ctx0, d_rowptr, d_col, validate=True)
+    tiered = w.hbm_budget is not None and w.hbm_budget < w.n * w.row_bytes
+
+    # ---- whole-graph metrics (deployment-time passes; not part of a step) ---------------------
+    extra = {}
+    Pdev = None
+    if not args.no_metrics:
+        p0 = None
+        if w.seed_mode == 1:
+            p0 = torch.from_numpy(qvgen.seed_popularity(w.seed, w.n).astype(np.float32)).cuda()
+        for name, fn in (("psgs", lambda: qv.qv_psgs(ctx0, g, w.fanouts)),
+                         ("access_prob", lambda: qv.qv_access_prob(ctx0, g, w.fanouts, p0=p0))):
+            fn()
+            ctx0.sync()                                    # first call sizes the scratch arena
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(ctx0.stream)
+            res = fn()
+            e1.record(ctx0.stream)
+            ctx0.sync()
+            ms = e0.elapsed_time(e1)
+            sweeps = len(w.fanouts) - 1 if name == "psgs" else len(w.fanouts)
+            rp = rowptr.dtype.itemsize
+            per_sweep = (w.n + 1) * rp + n_edges_graph * 8 + w.n * 8
+            extra[name + "_ms"] = round(ms, 3)
+            extra[name + "_algorithmic_GBps"] = round(max(sweeps, 1) * per_sweep / ms / 1e6, 1)
+            if name == "access_prob":
+                Pdev = res
+        log("psgs %.2f ms, access_prob %.2f ms over the whole graph" % (extra["psgs_ms"], extra["access_prob_ms"]))
+
+    if tiered:
+        if Pdev is None:
+            Pdev = qv.qv_access_prob(ctx0, g, w.fanouts)
+        rank = qv.qv_place_rank(ctx0, Pdev)
+        ctx0.sync()
+        feat = qv.Features(ctx0, table, hbm_budget_bytes=w.hbm_budget, rank=rank)
+        del table
+        torch.cuda.empty_cache()
+        log("tiered features: %d of %d rows in HBM" % (feat.n_hot, w.n))
+    else:
+        feat = qv.Features(ctx0, table)
+
+    # ---- batches, contexts, buffers -------------------------------------------------------------
+    n_batches = K + W
+    seeds_host = [w.seeds(b, batch) for b in range(n_batches)]
+    seeds_dev = [torch.from_numpy(s).cuda() for s in seeds_host]
+    rng_seeds = [w.rng_seed(b) for b in range(n_batches)]
+    ctxs = [ctx0] + [qv.Context(0, torch.cuda.Stream()) for _ in range(S - 1)]
+    nb, eb, fb = qv.qv_sample_bounds(batch, w.fanouts, w.n)
+    bufs, rows = [], []
+    for c in ctxs:
+        c.reserve(batch, w.fanouts, w.n)
+        bufs.append(qv.SampleBuffers(c, batch, w.fanouts, w.n))
+        rows.append(torch.empty((nb, w.dim), dtype=tdtype, device="cuda"))
+    Kh = len(w.fanouts)
+    # per-step size blocks so that counts can be read after the timed region
+    offs = [(torch.zeros(Kh + 2, dtype=torch.int64, device="cuda"), torch.zeros(Kh + 1, dtype=torch.int64, device="cuda"),
+             torch.zeros(Kh + 2, dtype=torch.int64, device="cuda")) for _ in range(n_batches)]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_batches)]
+
+    def step(i):
+        c, b = ctxs[i % S], bufs[i % S]
+        b.node_off, b.edge_off, b.frontier_off = offs[i]
+        ev[i][0].record(c.stream)
+        qv.qv_sample(c, g, seeds_dev[i], w.fanouts, rng_seeds[i], out=b)
+        ev[i][1].record(c.stream)
+        qv.qv_gather(c, feat, b.n_id, n_ids_dev=b.node_off[Kh + 1:], out=rows[i % S], n_ids=nb)
+        ev[i][2].record(c.stream)
+
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    for c in ctxs:
+        c.sync()
+    t_start = time.perf_counter()
+    for i in range(W, W + K):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+    for c in ctxs:
+        c.sync()                                           # raises on a deferred device error
+
+    # ---- accounting -------------------------------------------------------------------------
+    tot_edges = tot_unique = tot_front = 0
+    samp_b = reidx_b = gath_b = 0
+    gather_ms, sample_ms, batch_ms = [], [], []
+    for i in range(W, W + K):
+        no, eo, fo = (t.cpu().numpy() for t in offs[i])
+        U, E, F = int(no[-1]), int(eo[-1]), int(fo[Kh])        # frontier entries expanded = F_0..F_{K-1}
+        tot_edges += E
+        tot_unique += U
+        tot_front += F
+        sb, rb, gb = algorithmic_bytes(F, E, U, U, w.row_bytes, rowptr.dtype.itemsize, tiered)
+        samp_b += sb
+        reidx_b += rb
+        gath_b += gb
+        sample_ms.append(ev[i][0].elapsed_time(ev[i][1]))
+        gather_ms.append(ev[i][1].elapsed_time(ev[i][2]))
+        batch_ms.append(ev[i][0].elapsed_time(ev[i][2]))
+    ms_per_step = elapsed * 1e3 / K
+    gather_avg_ms = float(np.mean(gather_ms))
+    gather_bytes_per_launch = gath_b / K
+    achieved = gather_bytes_per_launch / (gather_avg_ms * 1e-3) / 1e9
+    path_bytes = samp_b + reidx_b + gath_b
+
+    result = {
+        "metric": "sampled_edges_per_s",
+        "value": round(tot_edges / elapsed, 1),
+        "unit": "edges/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32 ids, %s rows copied bit for bit" % ("f16" if tdtype == torch.float16 else "f32"),
+        "data": "synthetic",
+        "config": {"workload": "%s: %d nodes, %d edges, %s x %d features, fanouts %s, batch %d%s" %
+                   (w.name, w.n, n_edges_graph, "fp16" if tdtype == torch.float16 else "fp32", w.dim, w.fanouts,
+                    batch, ", %d rows in HBM / rest host-pinned" % feat.n_hot if tiered else ", features all in HBM"),
+                   "streams": S, "scale": args.scale},
+        "sampled_edges_per_batch": round(tot_edges / K, 1),
+        "unique_nodes_per_batch": round(tot_unique / K, 1),
+        "gathered_feature_GBps": round(tot_unique * w.row_bytes / (sum(gather_ms) * 1e-3) / 1e9, 2),
+        "gather_frac_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
+        "path_algorithmic_GBps": round(path_bytes / elapsed / 1e9, 2),
+        "path_frac_hbm_peak": round(path_bytes / elapsed / 1e9 / HBM_PEAK_GBPS, 4),
+        "p50_batch_latency_ms": round(float(np.percentile(batch_ms, 50)), 4),
+        "p99_batch_latency_ms": round(float(np.percentile(batch_ms, 99)), 4),
+        "sample_ms_avg": round(float(np.mean(sample_ms)), 4),
+        "gather_ms_avg": round(gather_avg_ms, 4),
+        "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": round(gather_bytes_per_launch), "avg_launch_ms": round(gather_avg_ms, 5)},
+    }
+    result.update(extra)
+
+    # ---- the oracle on this machine's host cores (a reported baseline, not the target) ------------
+    if not args.no_cpu_baseline:
+        import oracle
+        sub_rows = min(w.n, 4_000_000)
+        host_table = qvgen.features_host(w.seed, sub_rows, w.dim, w.feat_dtype)
+        t_budget, t_used, e_cpu, nb_cpu = 15.0, 0.0, 0, 0
+        for i in range(W, W + K):
+            t1 = time.perf_counter()
+            o = oracle.sample(rowptr, col, seeds_host[i], w.fanouts, rng_seeds[i])
+            oracle.gather(host_table, o["n_id"] % sub_rows)
+            t_used += time.perf_counter() - t1
+            e_cpu += int(o["edge_off"][-1])
+            nb_cpu += 1
+            if t_used > t_budget:
+                break
+        result["cpu_baseline"] = {
+            "value": round(e_cpu / t_used, 1), "unit": "edges/s", "cores": 1, "kind": "oracle",
+            "sample": "%d of the timed batches, single-threaded oracle sample+reindex+gather; gather rows taken "
+                      "modulo a %d-row host table" % (nb_cpu, sub_rows),
+            "ms_per_batch": round(t_used * 1e3 / nb_cpu, 3)}
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

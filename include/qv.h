@@ -1,0 +1,218 @@
+/*
+ * qv -- the data-parallel hot path of a GNN serving pipeline on one AMD MI355X (gfx950):
+ * batched multi-hop neighbour sampling over a CSR graph, dedup + relabel of the sampled ids,
+ * gather of the sampled nodes' feature rows into one dense tensor, and the two workload metrics
+ * that govern the path: the probabilistic sampled sub-graph size (PSGS) per node and the
+ * feature access probability (FAP) per node, which ranks feature rows for placement in HBM
+ * versus host memory.  Paper: "Quiver: Supporting GPUs for Low-Latency, High-Throughput GNN
+ * Serving with Workload Awareness", arXiv 2305.10863.
+ *
+ * General rules of this ABI
+ *   - Plain C.  Every pointer argument is marked [dev] (device memory of the context's GPU),
+ *     [host] (ordinary host memory) or [dev|host].  The caller owns every buffer it passes; the
+ *     library owns only its handles and the scratch memory inside a context.
+ *   - Every call returns a qv_status (0 = ok, negative = error) and never aborts or throws.
+ *     qv_last_error() gives the text of the last error of a context (or, with NULL, of the last
+ *     failed handle creation on this thread).
+ *   - Work is enqueued on the context's HIP stream and is asynchronous.  Sizes that only the
+ *     device knows (how many nodes, edges were produced) are written to device memory; the
+ *     caller copies them back after synchronising.  Conditions only the device can detect (an id
+ *     out of range, an output array too small) are recorded in a status word that qv_ctx_sync()
+ *     returns; kernels never write outside the capacities they were given.
+ *   - One context serves one stream; calls on one context must not overlap.  Use several
+ *     contexts (one per stream) to keep several batches in flight.
+ *   - ids are int32 (graphs of fewer than 2^31 nodes); rowptr is int32 or int64; offsets int64.
+ */
+#ifndef QV_H
+#define QV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct qv_ctx qv_ctx;    /* device, stream, scratch arena, status word            */
+typedef struct qv_csr qv_csr;    /* view of a device-resident CSR graph (borrowed arrays) */
+typedef struct qv_feat qv_feat;  /* feature table: HBM tier + host-pinned tier + lookup   */
+
+typedef enum {
+    QV_OK = 0,
+    QV_EINVAL = -1,     /* bad argument (null pointer, fanout < 1, too many hops, ...)        */
+    QV_ENOMEM = -2,     /* device or pinned-host allocation failed                           */
+    QV_EHIP = -3,       /* a HIP call failed; text in qv_last_error                          */
+    QV_ECAPACITY = -4,  /* an output array was too small; outputs are truncated, not overrun */
+    QV_ERANGE = -5      /* a node / row id outside [0, n)                                    */
+} qv_status;
+
+#define QV_MAX_HOPS 8
+#define QV_MAX_FANOUT 1024
+
+/* ---------------------------------------------------------------------------------------------
+ * Context
+ * ------------------------------------------------------------------------------------------ */
+
+/* Create a context on GPU `device` that enqueues on `hip_stream` (a hipStream_t; NULL = the
+ * default stream).  The stream is borrowed and must outlive the context. */
+qv_status qv_ctx_create(int device, void* hip_stream, qv_ctx** out);
+void qv_ctx_destroy(qv_ctx* ctx);
+const char* qv_last_error(const qv_ctx* ctx);
+
+/* Wait for the context's stream, then return and clear the deferred device status:
+ * QV_OK, QV_ERANGE or QV_ECAPACITY (or QV_EHIP if the stream reports a failure). */
+qv_status qv_ctx_sync(qv_ctx* ctx);
+
+/* Grow the scratch arena now so that later qv_sample / qv_reindex calls with at most `n_seeds`
+ * seeds and these fanouts on a graph of `n_nodes` nodes allocate nothing.  Optional. */
+qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts /*[host]*/,
+                         int32_t n_hops, int64_t n_nodes);
+
+/* A-priori output sizes of qv_sample (host arithmetic only): most distinct nodes, most edges
+ * over all hops, most frontier entries over hops 0..n_hops.  Outputs sized to these bounds can
+ * never report QV_ECAPACITY. */
+qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts /*[host]*/, int32_t n_hops,
+                           int64_t n_nodes, int64_t* max_nodes, int64_t* max_edges,
+                           int64_t* max_frontier);
+
+/* ---------------------------------------------------------------------------------------------
+ * Graph  (paper Section 3.2: the graph topology given at deployment)
+ * ------------------------------------------------------------------------------------------ */
+
+/* Wrap a CSR of OUT-edges: neighbours of v are col[rowptr[v] .. rowptr[v+1]).  rowptr [dev] has
+ * n_nodes+1 entries of rowptr_bits (32 or 64) bits; col [dev] has n_edges int32 entries.  The
+ * arrays are borrowed and must outlive the handle.  With validate != 0 the arrays are checked
+ * on the device (rowptr[0] == 0, non-decreasing, rowptr[n] == n_edges, 0 <= col < n_nodes) and
+ * a malformed graph returns QV_EINVAL; this synchronises once. */
+qv_status qv_csr_create(qv_ctx* ctx, int64_t n_nodes, int64_t n_edges, const void* rowptr,
+                        int32_t rowptr_bits, const int32_t* col, int32_t validate, qv_csr** out);
+void qv_csr_destroy(qv_csr* csr);
+
+/* ---------------------------------------------------------------------------------------------
+ * Sampling  (paper Section 2.1, overview figure: seed -> layer-1 neighbours -> layer-2 ...;
+ * Section 6: "k-hop neighbour sampling without replacement".  The paper prints no sampling
+ * algorithm; the random choices are fixed as follows so that results are reproducible.)
+ *
+ * For frontier node v (global id) in hop k (1-based) with out-degree d and fanout l:
+ *   d <= l : all d adjacency positions 0..d-1, in CSR order;
+ *   d >  l : Floyd's selection of l distinct positions: for slot s = 0..l-1, j = d-l+s,
+ *            t = rand_below(j+1), position = t unless an earlier slot already holds t, else j;
+ *            output in slot order.
+ *   rand_below(b) = high 64 bits of r64 * b, r64 = (x1 << 32) | x0 of Philox4x32-10 with
+ *            key (lo32(rng_seed), hi32(rng_seed)) and counter (v, k, s, 0).
+ * ------------------------------------------------------------------------------------------ */
+
+/* One hop.  frontier [dev] int32[n_frontier] (order matters; ids may repeat).
+ * off_out [dev] int64[n_frontier+1]: segment f of nbr_out starts at off_out[f];
+ * off_out[n_frontier] = number of sampled neighbours.  nbr_out [dev] int32[nbr_cap] receives the
+ * segments back to back; entries beyond nbr_cap are dropped and QV_ECAPACITY is deferred.
+ * A frontier id outside [0, n_nodes) contributes an empty segment and defers QV_ERANGE. */
+qv_status qv_sample_hop(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier,
+                        int64_t n_frontier, int32_t fanout, uint64_t rng_seed, int32_t hop,
+                        int32_t* nbr_out, int64_t nbr_cap, int64_t* off_out);
+
+/* Output block of qv_sample.  All arrays are caller-allocated [dev] memory. */
+typedef struct {
+    int32_t* n_id;           /* distinct sampled nodes (global ids), the distinct seeds first,  */
+    int64_t n_id_cap;        /*   then new nodes in order of first appearance; local id = index */
+    int32_t* row_local;      /* per sampled edge: local id of the expanded node                 */
+    int32_t* col_local;      /* per sampled edge: local id of the sampled neighbour             */
+    int32_t* nbr_global;     /* per sampled edge: global id of the neighbour (may be NULL)      */
+    int64_t edge_cap;        /* capacity of the three edge arrays                               */
+    int32_t* frontier;       /* F_0 | F_1 | .. | F_K back to back (may be NULL): F_0 = distinct */
+    int64_t frontier_cap;    /*   seeds, F_k = distinct neighbours produced by hop k            */
+    int64_t* node_off;       /* [n_hops+2] node_off[0]=0, node_off[k+1] = |n_id| after hop k    */
+    int64_t* edge_off;       /* [n_hops+1] hop k's edges are [edge_off[k-1], edge_off[k])       */
+    int64_t* frontier_off;   /* [n_hops+2] F_k = frontier[frontier_off[k] .. frontier_off[k+1]) */
+} qv_sample_out;
+
+/* Multi-hop sampling + reindex for one batch of seeds [dev] int32[n_seeds] (repeats allowed;
+ * they are merged, first occurrence first).  fanouts [host] int32[n_hops], each in
+ * [1, QV_MAX_FANOUT]; 1 <= n_hops <= QV_MAX_HOPS.  Hop k expands exactly F_{k-1}, the distinct
+ * nodes hop k-1 produced (layer frontiers: the process the PSGS / FAP recursions of Sections 4.1
+ * and 5.1 model).  Edges of a hop are ordered by frontier position, then slot.  No host
+ * synchronisation happens inside the call. */
+qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_t n_seeds,
+                    const int32_t* fanouts, int32_t n_hops, uint64_t rng_seed,
+                    const qv_sample_out* out);
+
+/* Dedup + relabel (Section 2.1: the sampled nodes are collected once each and the sub-graph is
+ * expressed over them).  known [dev] int32[n_known]: ids that already have local ids (local id
+ * = index; entries must be distinct, else QV_EINVAL is deferred).  nbr [dev] int32[n_nbr].
+ *   n_id_out     [dev] int32[n_id_cap]: known, then the ids of nbr not in known, in order of
+ *                first appearance;  *n_id_len [dev] = its length
+ *   local_out    [dev] int32[n_nbr]: local id of each nbr entry
+ *   frontier_out [dev] int32[n_nbr] (may be NULL): the distinct ids of nbr in order of first
+ *                appearance, whether known or not;  *frontier_len [dev] = its length */
+qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const int32_t* nbr,
+                     int64_t n_nbr, int64_t n_nodes /* ids must be < n_nodes; 0 = unchecked */,
+                     int32_t* n_id_out, int64_t n_id_cap, int64_t* n_id_len, int32_t* local_out,
+                     int32_t* frontier_out, int64_t* frontier_len);
+
+/* ---------------------------------------------------------------------------------------------
+ * Features  (Section 2.1: collect the features of all sampled nodes into one tensor;
+ * Section 5.2 step (i) and Section 5.3: rows ranked by access probability, the most popular
+ * placed in GPU memory, the rest in host memory read by the kernel itself (zero-copy), located
+ * through a feature lookup table)
+ * ------------------------------------------------------------------------------------------ */
+
+/* Build a feature table of n_rows x dim elements of elem_bytes (2 or 4) bytes.
+ *   table          [dev|host] (table_on_device says which) row-major, contiguous.
+ *   hbm_budget_bytes  bytes of HBM the table may occupy; < 0 or >= the table size = all in HBM.
+ *   rank           [dev] int32[n_rows] placement order (most popular first, e.g. from
+ *                  qv_place_rank); required when the budget is smaller than the table.
+ * All rows in HBM and table on device: the table is BORROWED (no copy) and must outlive the
+ * handle.  Otherwise the library copies: the first floor(budget / row bytes) rows of `rank` into
+ * an HBM tier it owns (hot row i = table[rank[i]]), the remaining rows, in ascending id order,
+ * into host-pinned memory it owns and maps into the GPU; the caller's table may be freed after
+ * the call returns (the call synchronises). */
+qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device, int64_t n_rows,
+                         int32_t dim, int32_t elem_bytes, int64_t hbm_budget_bytes,
+                         const int32_t* rank, qv_feat** out);
+void qv_feat_destroy(qv_feat* feat);
+/* Number of rows held in HBM (== n_rows when everything fits). */
+int64_t qv_feat_hot_rows(const qv_feat* feat);
+/* The lookup table [dev] int32[n_rows]: loc[id] >= 0 -> HBM row, < 0 -> host row ~loc[id];
+ * NULL when every row is in HBM in id order. */
+const int32_t* qv_feat_loc(const qv_feat* feat);
+
+/* out[r, :] = table[ids[r], :] for r < n_ids, as raw bytes.  ids [dev] int32[n_ids], any order,
+ * repeats allowed.  out [dev], row r at byte offset r * out_row_stride_bytes (>= row bytes, a
+ * multiple of elem_bytes).  An id outside [0, n_rows) leaves its output row untouched and
+ * defers QV_ERANGE.  `n_ids_dev` [dev] (may be NULL): if given, only min(*n_ids_dev, n_ids)
+ * rows are gathered, so a gather can follow qv_sample without a host round trip. */
+qv_status qv_gather(qv_ctx* ctx, const qv_feat* feat, const int32_t* ids, int64_t n_ids,
+                    const int64_t* n_ids_dev, void* out, int64_t out_row_stride_bytes);
+
+/* ---------------------------------------------------------------------------------------------
+ * Workload metrics
+ * ------------------------------------------------------------------------------------------ */
+
+/* PSGS, Section 4.1:  Q[i] = sum_{k=0..K} q_k[i],  q_0 = 1,
+ *   q_k[i] = sum_j delta_{k-1}(i,j) * min(deg(j), l_k),  delta_k = A_1 .. A_k,
+ *   A_m[i][j] = min(deg(i), l_m) / deg(i) on every out-edge i->j (the probability that the edge
+ *   is taken when min(deg, l_m) of deg neighbours are drawn without replacement).
+ * psgs_out [dev] float[n_nodes].  Sums are accumulated in fp64 and stored in fp32. */
+qv_status qv_psgs(qv_ctx* ctx, const qv_csr* csr, const int32_t* fanouts /*[host]*/,
+                  int32_t n_hops, float* psgs_out);
+
+/* Sum of PSGS over a batch of seeds (Section 4.2.2: the quantity compared with the chosen
+ * threshold to decide where a batch is sampled).  psgs [dev] float[n_nodes], seeds [dev],
+ * sum_out [dev] double[1]. */
+qv_status qv_psgs_batch_sum(qv_ctx* ctx, const float* psgs, int64_t n_nodes, const int32_t* seeds,
+                            int64_t n_seeds, double* sum_out);
+
+/* FAP, Section 5.1:  P[i] = sum_{k=0..K} p_k[i],  p_0 = seed distribution,
+ *   p_k[i] = sum_{j -> i} p_{k-1}[j] * A_k[j][i]   (A as above).
+ * p0 [dev] float[n_nodes] or NULL for the uniform 1/n_nodes.  prob_out [dev] float[n_nodes].
+ * Sums are accumulated in fp64 and stored in fp32. */
+qv_status qv_access_prob(qv_ctx* ctx, const qv_csr* csr, const int32_t* fanouts /*[host]*/,
+                         int32_t n_hops, const float* p0, float* prob_out);
+
+/* Placement order, Section 5.2 step (i): node ids sorted by prob descending, ties by smaller id.
+ * prob [dev] float[n] (no NaNs), rank_out [dev] int32[n]. */
+qv_status qv_place_rank(qv_ctx* ctx, const float* prob, int64_t n, int32_t* rank_out);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QV_H */

@@ -1,0 +1,178 @@
+// Context, scratch arena, deferred status, CSR handle and its validation kernel.
+#include "qv_internal.hpp"
+#include <cstring>
+#include <new>
+
+namespace qv {
+
+static thread_local std::string g_error;
+
+void set_global_error(const char* msg) { g_error = msg; }
+
+qv_status fail(qv_ctx* ctx, qv_status code, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx) ctx->err = buf;
+    else g_error = buf;
+    return code;
+}
+
+qv_status arena_begin(qv_ctx* ctx, size_t total_bytes) {
+    ctx->arena_used = 0;
+    if (total_bytes <= ctx->arena_bytes) return QV_OK;
+    // earlier calls may still be reading the old arena
+    QV_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->arena) QV_HIP(ctx, hipFree(ctx->arena));
+    ctx->arena = nullptr;
+    ctx->arena_bytes = 0;
+    size_t want = align_up(total_bytes + total_bytes / 8, 1 << 20);
+    QV_HIP(ctx, hipMalloc((void**)&ctx->arena, want));
+    ctx->arena_bytes = want;
+    return QV_OK;
+}
+
+void* arena_take(qv_ctx* ctx, size_t bytes) {
+    size_t at = align_up(ctx->arena_used);
+    if (at + bytes > ctx->arena_bytes) return nullptr;   // callers size the arena first
+    ctx->arena_used = at + bytes;
+    return ctx->arena + at;
+}
+
+// ---- CSR validation -----------------------------------------------------------------------
+template <typename RP>
+__global__ void k_validate_csr(int64_t n, int64_t n_edges, const RP* __restrict__ rowptr,
+                               const int32_t* __restrict__ col, int32_t* status) {
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    bool bad = false;
+    for (int64_t v = tid; v < n; v += stride) {
+        int64_t a = (int64_t)rowptr[v], b = (int64_t)rowptr[v + 1];
+        if (b < a || b - a >= (int64_t)0x7FFFFFFF) bad = true;
+    }
+    if (tid == 0 && ((int64_t)rowptr[0] != 0 || (int64_t)rowptr[n] != n_edges)) bad = true;
+    for (int64_t e = tid; e < n_edges; e += stride) {
+        int32_t c = col[e];
+        if (c < 0 || (int64_t)c >= n) bad = true;
+    }
+    if (bad) atomicOr(status, kStatInval);
+}
+
+}  // namespace qv
+
+using namespace qv;
+
+extern "C" {
+
+qv_status qv_ctx_create(int device, void* hip_stream, qv_ctx** out) {
+    if (!out) return fail(nullptr, QV_EINVAL, "qv_ctx_create: out is NULL");
+    *out = nullptr;
+    int n_dev = 0;
+    hipError_t e = hipGetDeviceCount(&n_dev);
+    if (e != hipSuccess || device < 0 || device >= n_dev)
+        return fail(nullptr, QV_EHIP, "qv_ctx_create: no GPU %d (%s, %d visible)", device,
+                    hipGetErrorString(e), n_dev);
+    qv_ctx* ctx = new (std::nothrow) qv_ctx();
+    if (!ctx) return fail(nullptr, QV_ENOMEM, "qv_ctx_create: out of host memory");
+    ctx->device = device;
+    ctx->stream = (hipStream_t)hip_stream;
+    hipDeviceProp_t prop;
+    if ((e = hipSetDevice(device)) != hipSuccess ||
+        (e = hipGetDeviceProperties(&prop, device)) != hipSuccess ||
+        (e = hipMalloc((void**)&ctx->d_status, 256)) != hipSuccess ||
+        (e = hipHostMalloc((void**)&ctx->h_status, 256, hipHostMallocDefault)) != hipSuccess ||
+        (e = hipMemsetAsync(ctx->d_status, 0, 256, ctx->stream)) != hipSuccess) {
+        qv_status rc = fail(nullptr, QV_EHIP, "qv_ctx_create: %s", hipGetErrorString(e));
+        qv_ctx_destroy(ctx);
+        return rc;
+    }
+    ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    *out = ctx;
+    return QV_OK;
+}
+
+void qv_ctx_destroy(qv_ctx* ctx) {
+    if (!ctx) return;
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->arena) (void)hipFree(ctx->arena);
+    if (ctx->d_status) (void)hipFree(ctx->d_status);
+    if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+    delete ctx;
+}
+
+const char* qv_last_error(const qv_ctx* ctx) { return ctx ? ctx->err.c_str() : g_error.c_str(); }
+
+qv_status qv_ctx_sync(qv_ctx* ctx) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_sync: ctx is NULL");
+    QV_HIP(ctx, hipMemcpyAsync(ctx->h_status, ctx->d_status, sizeof(int32_t), hipMemcpyDeviceToHost,
+                               ctx->stream));
+    QV_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    int32_t s = ctx->h_status[0];
+    if (s == 0) return QV_OK;
+    QV_HIP(ctx, hipMemsetAsync(ctx->d_status, 0, sizeof(int32_t), ctx->stream));
+    if (s & kStatInval) return fail(ctx, QV_EINVAL, "device check failed: malformed input (e.g. repeated known ids)");
+    if (s & kStatRange) return fail(ctx, QV_ERANGE, "device check failed: an id was outside [0, n)");
+    return fail(ctx, QV_ECAPACITY, "device check failed: an output array was too small; results are truncated");
+}
+
+qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes,
+                           int64_t* max_nodes, int64_t* max_edges, int64_t* max_frontier) {
+    if (n_seeds < 0 || n_hops < 1 || n_hops > QV_MAX_HOPS || !fanouts || n_nodes < 0)
+        return fail(nullptr, QV_EINVAL, "qv_sample_bounds: bad arguments");
+    int64_t f = n_seeds, nodes = n_seeds, edges = 0, front = n_seeds;
+    for (int k = 0; k < n_hops; ++k) {
+        if (fanouts[k] < 1 || fanouts[k] > QV_MAX_FANOUT)
+            return fail(nullptr, QV_EINVAL, "qv_sample_bounds: fanout %d outside [1, %d]", fanouts[k], QV_MAX_FANOUT);
+        int64_t e = f * (int64_t)fanouts[k];
+        if (e >= ((int64_t)1 << 31)) return fail(nullptr, QV_EINVAL, "qv_sample_bounds: a hop may exceed 2^31 edges");
+        f = e < n_nodes ? e : n_nodes;
+        edges += e;
+        front += f;
+        nodes += e;
+    }
+    if (nodes > n_nodes) nodes = n_nodes;
+    if (max_nodes) *max_nodes = nodes;
+    if (max_edges) *max_edges = edges;
+    if (max_frontier) *max_frontier = front;
+    return QV_OK;
+}
+
+qv_status qv_csr_create(qv_ctx* ctx, int64_t n_nodes, int64_t n_edges, const void* rowptr,
+                        int32_t rowptr_bits, const int32_t* col, int32_t validate, qv_csr** out) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_csr_create: ctx is NULL");
+    if (!out) return fail(ctx, QV_EINVAL, "qv_csr_create: out is NULL");
+    *out = nullptr;
+    if (n_nodes < 0 || n_nodes >= ((int64_t)1 << 31) || n_edges < 0 || !rowptr || (n_edges > 0 && !col))
+        return fail(ctx, QV_EINVAL, "qv_csr_create: need 0 <= n_nodes < 2^31, n_edges >= 0, non-null arrays");
+    if (rowptr_bits != 32 && rowptr_bits != 64)
+        return fail(ctx, QV_EINVAL, "qv_csr_create: rowptr_bits must be 32 or 64");
+    if (rowptr_bits == 32 && n_edges >= ((int64_t)1 << 31))
+        return fail(ctx, QV_EINVAL, "qv_csr_create: int32 rowptr cannot index %lld edges", (long long)n_edges);
+    if (validate) {
+        qv_status pending = qv_ctx_sync(ctx);       // do not mix with an earlier deferred error
+        if (pending != QV_OK) return pending;
+        int blocks = grid_for(n_edges > n_nodes ? n_edges : n_nodes, 256 * 8, ctx->n_cu * 8);
+        if (rowptr_bits == 32)
+            hipLaunchKernelGGL(k_validate_csr<int32_t>, dim3(blocks), dim3(256), 0, ctx->stream, n_nodes,
+                               n_edges, (const int32_t*)rowptr, col, ctx->d_status);
+        else
+            hipLaunchKernelGGL(k_validate_csr<int64_t>, dim3(blocks), dim3(256), 0, ctx->stream, n_nodes,
+                               n_edges, (const int64_t*)rowptr, col, ctx->d_status);
+        QV_LAUNCH_CHECK(ctx, "k_validate_csr");
+        qv_status rc = qv_ctx_sync(ctx);
+        if (rc == QV_EINVAL)
+            return fail(ctx, QV_EINVAL, "qv_csr_create: malformed CSR (rowptr not monotone from 0 to n_edges, a row "
+                                        "of 2^31 or more entries, or a column id outside [0, n_nodes))");
+        if (rc != QV_OK) return rc;
+    }
+    qv_csr* g = new (std::nothrow) qv_csr{ctx, n_nodes, n_edges, rowptr, rowptr_bits, col};
+    if (!g) return fail(ctx, QV_ENOMEM, "qv_csr_create: out of host memory");
+    *out = g;
+    return QV_OK;
+}
+
+void qv_csr_destroy(qv_csr* csr) { delete csr; }
+
+}  // extern "C"

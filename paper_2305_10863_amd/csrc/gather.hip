@@ -1,0 +1,240 @@
+// Feature table (HBM tier + host-pinned tier + lookup table) and the row gather.
+//
+// Gather kernel: a group of LPR lanes (a power of two, up to the whole wave) copies one row with
+// the widest vector the row size and the pointers allow (16, 8, 4 or 2 bytes per lane), several
+// rows in flight per group.  Rows of the host tier are read by the same loads through the
+// device mapping of pinned host memory (zero-copy), so placement never changes the result.
+#include "qv_internal.hpp"
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace qv {
+
+typedef uint32_t v4u __attribute__((ext_vector_type(4)));
+typedef uint32_t v2u __attribute__((ext_vector_type(2)));
+
+constexpr int kRowsInFlight = 4;
+
+struct GatherArgs {
+    const char* hot;
+    const char* cold;
+    const int32_t* loc;             // nullptr: row id == hot row
+    int64_t n_rows;                 // rows of the table (range check)
+    int64_t row_bytes;
+    const int32_t* ids;
+    int64_t n_ids;
+    const int64_t* n_ids_dev;       // nullable clamp
+    char* out;
+    int64_t out_stride;
+    int32_t vecs_per_row;
+    int32_t* status;
+};
+
+template <typename V, int LPR>
+__global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
+    int64_t n = a.n_ids;
+    if (a.n_ids_dev) { int64_t nd = *a.n_ids_dev; if (nd < n) n = nd; }
+    const int sub = threadIdx.x % LPR;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPR;
+    const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / LPR;
+    for (int64_t r0 = group; r0 < n; r0 += n_groups * kRowsInFlight) {
+        const V* src[kRowsInFlight];
+        V* dst[kRowsInFlight];
+#pragma unroll
+        for (int j = 0; j < kRowsInFlight; ++j) {
+            int64_t r = r0 + (int64_t)j * n_groups;
+            src[j] = nullptr; dst[j] = nullptr;
+            if (r < n) {
+                int32_t id = a.ids[r];
+                if (id < 0 || (int64_t)id >= a.n_rows) {
+                    if (sub == 0) atomicOr(a.status, kStatRange);
+                } else {
+                    const char* base = a.hot;
+                    int64_t row = id;
+                    if (a.loc) {
+                        int32_t l = a.loc[id];
+                        if (l < 0) { base = a.cold; row = (int64_t)(~l); } else row = l;
+                    }
+                    src[j] = reinterpret_cast<const V*>(base + row * a.row_bytes);
+                    dst[j] = reinterpret_cast<V*>(a.out + r * a.out_stride);
+                }
+            }
+        }
+        for (int i = sub; i < a.vecs_per_row; i += LPR) {
+            V tmp[kRowsInFlight];
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) if (src[j]) tmp[j] = src[j][i];
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j) if (src[j]) dst[j][i] = tmp[j];
+        }
+    }
+}
+
+template <typename V>
+static void launch_gather_v(qv_ctx* ctx, const GatherArgs& a, int lpr) {
+    int64_t threads = a.n_ids * lpr / kRowsInFlight + 256;
+    int blocks = grid_for(threads, 256, ctx->n_cu * 32);
+    switch (lpr) {
+        case 1: hipLaunchKernelGGL((k_gather<V, 1>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
+        case 2: hipLaunchKernelGGL((k_gather<V, 2>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
+        case 4: hipLaunchKernelGGL((k_gather<V, 4>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
+        case 8: hipLaunchKernelGGL((k_gather<V, 8>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
+        case 16: hipLaunchKernelGGL((k_gather<V, 16>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
+        case 32: hipLaunchKernelGGL((k_gather<V, 32>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
+        default: hipLaunchKernelGGL((k_gather<V, 64>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
+    }
+}
+
+qv_status launch_gather(qv_ctx* ctx, const char* hot, const char* cold, const int32_t* loc, int64_t n_rows,
+                        int64_t row_bytes, const int32_t* ids, int64_t n_ids, const int64_t* n_ids_dev, char* out,
+                        int64_t out_stride) {
+    if (n_ids == 0) return QV_OK;
+    // widest vector that divides every row start and the row length
+    uintptr_t bits = (uintptr_t)row_bytes | (uintptr_t)out_stride | (uintptr_t)hot | (uintptr_t)cold | (uintptr_t)out;
+    int vec = (bits % 16 == 0) ? 16 : (bits % 8 == 0) ? 8 : (bits % 4 == 0) ? 4 : 2;
+    if (bits % 2 != 0) return fail(ctx, QV_EINVAL, "gather: rows must be 2-byte aligned");
+    GatherArgs a{hot, cold, loc, n_rows, row_bytes, ids, n_ids, n_ids_dev, out, out_stride,
+                 (int32_t)(row_bytes / vec), ctx->d_status};
+    int lpr = 1;
+    while (lpr < 64 && lpr < a.vecs_per_row) lpr <<= 1;
+    switch (vec) {
+        case 16: launch_gather_v<v4u>(ctx, a, lpr); break;
+        case 8: launch_gather_v<v2u>(ctx, a, lpr); break;
+        case 4: launch_gather_v<uint32_t>(ctx, a, lpr); break;
+        default: launch_gather_v<uint16_t>(ctx, a, lpr); break;
+    }
+    QV_LAUNCH_CHECK(ctx, "k_gather");
+    return QV_OK;
+}
+
+}  // namespace qv
+
+using namespace qv;
+
+extern "C" {
+
+void qv_feat_destroy(qv_feat* f) {
+    if (!f) return;
+    if (f->ctx) (void)hipStreamSynchronize(f->ctx->stream);
+    if (f->hot_owned) (void)hipFree(f->hot_owned);
+    if (f->cold_host) (void)hipHostFree(f->cold_host);
+    if (f->loc) (void)hipFree(f->loc);
+    delete f;
+}
+
+int64_t qv_feat_hot_rows(const qv_feat* f) { return f ? f->n_hot : 0; }
+const int32_t* qv_feat_loc(const qv_feat* f) { return f ? f->loc : nullptr; }
+
+qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device, int64_t n_rows, int32_t dim,
+                         int32_t elem_bytes, int64_t hbm_budget_bytes, const int32_t* rank, qv_feat** out) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_feat_create: ctx is NULL");
+    if (!out) return fail(ctx, QV_EINVAL, "qv_feat_create: out is NULL");
+    *out = nullptr;
+    if (!table || n_rows < 0 || n_rows >= ((int64_t)1 << 31) || dim < 1 || (elem_bytes != 2 && elem_bytes != 4))
+        return fail(ctx, QV_EINVAL, "qv_feat_create: need a table, 0 <= n_rows < 2^31, dim >= 1, elem_bytes 2 or 4");
+    const int64_t row_bytes = (int64_t)dim * elem_bytes;
+    const int64_t table_bytes = n_rows * row_bytes;
+    const bool all_hot = hbm_budget_bytes < 0 || hbm_budget_bytes >= table_bytes;
+    if (!all_hot && !rank) return fail(ctx, QV_EINVAL, "qv_feat_create: a budget below the table size needs `rank`");
+    qv_feat* f = new (std::nothrow) qv_feat();
+    if (!f) return fail(ctx, QV_ENOMEM, "qv_feat_create: out of host memory");
+    f->ctx = ctx; f->n_rows = n_rows; f->dim = dim; f->elem_bytes = elem_bytes; f->row_bytes = row_bytes;
+    f->hot = nullptr; f->hot_owned = nullptr; f->cold_host = nullptr; f->cold_dev = nullptr; f->loc = nullptr;
+    f->n_hot = all_hot ? n_rows : hbm_budget_bytes / row_bytes;
+    qv_status rc = QV_OK;
+    hipError_t e = hipSuccess;
+#define FEAT_TRY(call)                                                                                   \
+    if (rc == QV_OK && (e = (call)) != hipSuccess)                                                        \
+        rc = fail(ctx, e == hipErrorOutOfMemory ? QV_ENOMEM : QV_EHIP, "qv_feat_create: %s failed: %s", #call, \
+                  hipGetErrorString(e));
+    if (all_hot) {
+        if (table_on_device) {
+            f->hot = (const char*)table;                               // borrowed
+        } else {
+            FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(table_bytes > 0 ? table_bytes : 256)));
+            FEAT_TRY(hipMemcpyAsync(f->hot_owned, table, (size_t)table_bytes, hipMemcpyHostToDevice, ctx->stream));
+            FEAT_TRY(hipStreamSynchronize(ctx->stream));
+            f->hot = f->hot_owned;
+        }
+    } else {
+        const int64_t n_hot = f->n_hot, n_cold = n_rows - n_hot;
+        std::vector<int32_t> h_rank, h_loc, cold_ids;
+        try {
+            h_rank.resize((size_t)n_rows); h_loc.assign((size_t)n_rows, -1); cold_ids.reserve((size_t)n_cold);
+        } catch (...) { rc = fail(ctx, QV_ENOMEM, "qv_feat_create: out of host memory"); }
+        FEAT_TRY(hipMemcpyAsync(h_rank.data(), rank, (size_t)n_rows * 4, hipMemcpyDeviceToHost, ctx->stream));
+        FEAT_TRY(hipStreamSynchronize(ctx->stream));
+        if (rc == QV_OK) {
+            // rank must be a permutation of the row ids
+            std::vector<char> seen((size_t)n_rows, 0);
+            for (int64_t i = 0; i < n_rows && rc == QV_OK; ++i) {
+                int32_t id = h_rank[i];
+                if (id < 0 || id >= n_rows || seen[id]) rc = fail(ctx, QV_EINVAL, "qv_feat_create: rank is not a permutation");
+                else seen[id] = 1;
+            }
+        }
+        if (rc == QV_OK) {
+            for (int64_t i = 0; i < n_hot; ++i) h_loc[h_rank[i]] = (int32_t)i;
+            int32_t c = 0;
+            for (int64_t id = 0; id < n_rows; ++id)
+                if (h_loc[id] < 0) { h_loc[id] = ~c; ++c; cold_ids.push_back((int32_t)id); }
+        }
+        FEAT_TRY(hipMalloc((void**)&f->loc, (size_t)n_rows * 4 + 256));
+        FEAT_TRY(hipMemcpyAsync(f->loc, h_loc.data(), (size_t)n_rows * 4, hipMemcpyHostToDevice, ctx->stream));
+        FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(n_hot * row_bytes + 256)));
+        FEAT_TRY(hipHostMalloc((void**)&f->cold_host, (size_t)(n_cold * row_bytes + 256), hipHostMallocMapped));
+        FEAT_TRY(hipHostGetDevicePointer((void**)&f->cold_dev, f->cold_host, 0));
+        f->hot = f->hot_owned;
+        if (rc == QV_OK && table_on_device) {
+            // both tiers are filled by the gather kernel itself (the cold tier through the mapping)
+            int32_t* d_cold_ids = nullptr;
+            FEAT_TRY(hipMalloc((void**)&d_cold_ids, (size_t)n_cold * 4 + 256));
+            FEAT_TRY(hipMemcpyAsync(d_cold_ids, cold_ids.data(), (size_t)n_cold * 4, hipMemcpyHostToDevice, ctx->stream));
+            if (rc == QV_OK)
+                rc = launch_gather(ctx, (const char*)table, nullptr, nullptr, n_rows, row_bytes, rank, n_hot, nullptr,
+                                   f->hot_owned, row_bytes);
+            if (rc == QV_OK)
+                rc = launch_gather(ctx, (const char*)table, nullptr, nullptr, n_rows, row_bytes, d_cold_ids, n_cold,
+                                   nullptr, (char*)f->cold_dev, row_bytes);
+            FEAT_TRY(hipStreamSynchronize(ctx->stream));
+            if (d_cold_ids) (void)hipFree(d_cold_ids);
+        } else if (rc == QV_OK) {
+            const char* src = (const char*)table;
+            for (int64_t c = 0; c < n_cold; ++c)
+                std::memcpy(f->cold_host + c * row_bytes, src + (int64_t)cold_ids[c] * row_bytes, (size_t)row_bytes);
+            // hot rows: stage through pinned memory in chunks
+            const int64_t chunk_rows = std::max<int64_t>(1, (64ll << 20) / row_bytes);
+            char* stage = nullptr;
+            FEAT_TRY(hipHostMalloc((void**)&stage, (size_t)(chunk_rows * row_bytes), hipHostMallocDefault));
+            for (int64_t i0 = 0; i0 < n_hot && rc == QV_OK; i0 += chunk_rows) {
+                int64_t cnt = std::min(chunk_rows, n_hot - i0);
+                for (int64_t i = 0; i < cnt; ++i)
+                    std::memcpy(stage + i * row_bytes, src + (int64_t)h_rank[i0 + i] * row_bytes, (size_t)row_bytes);
+                FEAT_TRY(hipMemcpyAsync(f->hot_owned + i0 * row_bytes, stage, (size_t)(cnt * row_bytes),
+                                        hipMemcpyHostToDevice, ctx->stream));
+                FEAT_TRY(hipStreamSynchronize(ctx->stream));
+            }
+            if (stage) (void)hipHostFree(stage);
+        }
+        FEAT_TRY(hipStreamSynchronize(ctx->stream));
+    }
+#undef FEAT_TRY
+    if (rc != QV_OK) { std::string keep = ctx->err; qv_feat_destroy(f); ctx->err = keep; return rc; }
+    *out = f;
+    return QV_OK;
+}
+
+qv_status qv_gather(qv_ctx* ctx, const qv_feat* f, const int32_t* ids, int64_t n_ids, const int64_t* n_ids_dev,
+                    void* out, int64_t out_row_stride_bytes) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_gather: ctx is NULL");
+    if (!f || n_ids < 0 || (n_ids > 0 && (!ids || !out))) return fail(ctx, QV_EINVAL, "qv_gather: null or negative argument");
+    if (out_row_stride_bytes < f->row_bytes || out_row_stride_bytes % f->elem_bytes != 0)
+        return fail(ctx, QV_EINVAL, "qv_gather: out_row_stride_bytes %lld must be >= %lld and a multiple of %d",
+                    (long long)out_row_stride_bytes, (long long)f->row_bytes, f->elem_bytes);
+    return launch_gather(ctx, f->hot, f->cold_dev, f->loc, f->n_rows, f->row_bytes, ids, n_ids, n_ids_dev, (char*)out,
+                         out_row_stride_bytes);
+}
+
+}  // extern "C"

@@ -1,0 +1,271 @@
+// Workload metrics over the whole graph: PSGS (pull sweeps over out-edges), feature access
+// probability (push sweeps with fp64 hardware atomics) and the placement order (radix sort).
+//
+// Both metrics are K sparse matrix-VECTOR sweeps, not a K-th matrix power: the sums the paper
+// defines re-associate so that only one value per node is carried between hops.
+//   PSGS:  S_m[i] = min(deg i, l_m) + (min(deg i, l_m)/deg i) * sum_{j in N+(i)} S_{m+1}[j],
+//          S_{K+1} = 0,  Q = 1 + S_1.
+//   FAP:   p_k[i] = sum_{j -> i} p_{k-1}[j] * min(deg j, l_k)/deg j,  P = sum_k p_k.
+// Row sums run to 10^5 terms and in-degree sums to 10^6 and more, so partial sums are kept in
+// fp64 (vector fp64 adds are far from the bottleneck next to the memory traffic); values carried
+// between PSGS sweeps and all outputs are fp32.
+#include "qv_internal.hpp"
+#include <cstring>
+#include <string.h>
+#include <rocprim/rocprim.hpp>
+
+namespace qv {
+
+template <int G>
+__device__ __forceinline__ double group_sum(double v) {
+#pragma unroll
+    for (int o = G / 2; o >= 1; o >>= 1) v += __shfl_xor(v, o, G);
+    return v;
+}
+
+// One PSGS sweep: group of G lanes per row.  s_next == nullptr is the innermost hop (no edges read).
+template <int G, typename RP>
+__global__ void __launch_bounds__(256) k_psgs_sweep(const RP* __restrict__ rowptr, const int32_t* __restrict__ col,
+                                                    int64_t n, int32_t fanout, const float* __restrict__ s_next,
+                                                    float* __restrict__ s_out, float add) {
+    const int sub = threadIdx.x % G;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G;
+    const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / G;
+    for (int64_t i = group; i < n; i += n_groups) {
+        const int64_t rs = (int64_t)rowptr[i], re = (int64_t)rowptr[i + 1];
+        const int64_t deg = re - rs;
+        const double m = (double)(deg < fanout ? deg : (int64_t)fanout);
+        double val = m;
+        if (s_next && deg > 0) {
+            double acc0 = 0.0, acc1 = 0.0;
+            int64_t e = rs + sub;
+            for (; e + G < re; e += 2 * G) {
+                float x0 = s_next[col[e]], x1 = s_next[col[e + G]];
+                acc0 += (double)x0; acc1 += (double)x1;
+            }
+            if (e < re) acc0 += (double)s_next[col[e]];
+            double acc = group_sum<G>(acc0 + acc1);
+            val = m + (m / (double)deg) * acc;
+        }
+        if (sub == 0) s_out[i] = (float)(val + (double)add);
+    }
+}
+
+__global__ void k_psgs_batch_sum(const float* __restrict__ psgs, int64_t n_nodes, const int32_t* __restrict__ seeds,
+                                 int64_t n_seeds, double* out, int32_t* status) {
+    __shared__ double part[256 / kWave];
+    double acc = 0.0;
+    for (int64_t i = threadIdx.x; i < n_seeds; i += blockDim.x) {
+        int32_t s = seeds[i];
+        if (s < 0 || (int64_t)s >= n_nodes) atomicOr(status, kStatRange);
+        else acc += (double)psgs[s];
+    }
+    acc = group_sum<kWave>(acc);
+    if (threadIdx.x % kWave == 0) part[threadIdx.x / kWave] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < (int)(blockDim.x / kWave); ++w) t += part[w];
+        *out = t;
+    }
+}
+
+// FAP ------------------------------------------------------------------------------------------
+__global__ void k_fap_init(int64_t n, const float* __restrict__ p0, double uniform, double* __restrict__ p_cur,
+                           double* __restrict__ p_nxt, double* __restrict__ p_tot) {
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = tid; i < n; i += stride) {
+        double v = p0 ? (double)p0[i] : uniform;
+        p_cur[i] = v; p_tot[i] = v; p_nxt[i] = 0.0;
+    }
+}
+
+// push: every out-edge j -> i adds p_cur[j] * w(j) to p_nxt[i]
+template <int G, typename RP>
+__global__ void __launch_bounds__(256) k_fap_push(const RP* __restrict__ rowptr, const int32_t* __restrict__ col,
+                                                  int64_t n, int32_t fanout, const double* __restrict__ p_cur,
+                                                  double* __restrict__ p_nxt) {
+    const int sub = threadIdx.x % G;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G;
+    const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / G;
+    for (int64_t j = group; j < n; j += n_groups) {
+        const int64_t rs = (int64_t)rowptr[j], re = (int64_t)rowptr[j + 1];
+        const int64_t deg = re - rs;
+        if (deg == 0) continue;
+        const double m = (double)(deg < fanout ? deg : (int64_t)fanout);
+        const double c = p_cur[j] * (m / (double)deg);
+        if (c == 0.0) continue;
+        for (int64_t e = rs + sub; e < re; e += G) unsafeAtomicAdd(&p_nxt[col[e]], c);
+    }
+}
+
+// fold the finished layer into the total, clear the buffer the next sweep will add into
+__global__ void k_fap_fold(int64_t n, const double* __restrict__ p_new, double* __restrict__ p_tot,
+                           double* __restrict__ p_old, float* __restrict__ out) {
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = tid; i < n; i += stride) {
+        double t = p_tot[i] + p_new[i];
+        p_tot[i] = t;
+        p_old[i] = 0.0;
+        if (out) out[i] = (float)t;
+    }
+}
+
+__global__ void k_to_float(int64_t n, const double* __restrict__ src, float* __restrict__ dst) {
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = tid; i < n; i += stride) dst[i] = (float)src[i];
+}
+
+// placement keys: ascending order of the key == descending prob, ties by ascending id
+__global__ void k_rank_keys(int64_t n, const float* __restrict__ prob, uint64_t* __restrict__ keys) {
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = tid; i < n; i += stride) {
+        float f = prob[i];
+        if (f == 0.0f) f = 0.0f;                                  // -0 and +0 compare equal
+        uint32_t b = __float_as_uint(f);
+        uint32_t asc = (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+        keys[i] = ((uint64_t)(~asc) << 32) | (uint64_t)(uint32_t)i;
+    }
+}
+__global__ void k_rank_ids(int64_t n, const uint64_t* __restrict__ keys, int32_t* __restrict__ rank) {
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = tid; i < n; i += stride) rank[i] = (int32_t)(uint32_t)keys[i];
+}
+
+static int group_width_for(int64_t n, int64_t e) {
+    double avg = n > 0 ? (double)e / (double)n : 0.0;
+    return avg < 6 ? 4 : avg < 12 ? 8 : avg < 24 ? 16 : avg < 48 ? 32 : 64;
+}
+
+template <typename RP>
+static void launch_psgs_sweep(qv_ctx* ctx, const qv_csr* g, int G, int32_t fanout, const float* s_next, float* s_out,
+                              float add) {
+    int blocks = grid_for(g->n_nodes * G, 256, ctx->n_cu * 32);
+    const RP* rp = (const RP*)g->rowptr;
+    switch (G) {
+        case 4: hipLaunchKernelGGL((k_psgs_sweep<4, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
+        case 8: hipLaunchKernelGGL((k_psgs_sweep<8, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
+        case 16: hipLaunchKernelGGL((k_psgs_sweep<16, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
+        case 32: hipLaunchKernelGGL((k_psgs_sweep<32, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
+        default: hipLaunchKernelGGL((k_psgs_sweep<64, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
+    }
+}
+
+template <typename RP>
+static void launch_fap_push(qv_ctx* ctx, const qv_csr* g, int G, int32_t fanout, const double* p_cur, double* p_nxt) {
+    int blocks = grid_for(g->n_nodes * G, 256, ctx->n_cu * 32);
+    const RP* rp = (const RP*)g->rowptr;
+    switch (G) {
+        case 4: hipLaunchKernelGGL((k_fap_push<4, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, p_cur, p_nxt); break;
+        case 8: hipLaunchKernelGGL((k_fap_push<8, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, p_cur, p_nxt); break;
+        case 16: hipLaunchKernelGGL((k_fap_push<16, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, p_cur, p_nxt); break;
+        case 32: hipLaunchKernelGGL((k_fap_push<32, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, p_cur, p_nxt); break;
+        default: hipLaunchKernelGGL((k_fap_push<64, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, p_cur, p_nxt); break;
+    }
+}
+
+static qv_status check_fanouts(qv_ctx* ctx, const char* who, const int32_t* fanouts, int n_hops) {
+    if (!fanouts || n_hops < 1 || n_hops > QV_MAX_HOPS) return fail(ctx, QV_EINVAL, "%s: need 1 <= n_hops <= %d and fanouts", who, QV_MAX_HOPS);
+    for (int k = 0; k < n_hops; ++k)
+        if (fanouts[k] < 1) return fail(ctx, QV_EINVAL, "%s: fanout %d < 1", who, fanouts[k]);
+    return QV_OK;
+}
+
+}  // namespace qv
+
+using namespace qv;
+
+extern "C" {
+
+qv_status qv_psgs(qv_ctx* ctx, const qv_csr* g, const int32_t* fanouts, int32_t n_hops, float* psgs_out) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_psgs: ctx is NULL");
+    if (!g || !psgs_out) return fail(ctx, QV_EINVAL, "qv_psgs: null argument");
+    qv_status rc = check_fanouts(ctx, "qv_psgs", fanouts, n_hops);
+    if (rc != QV_OK) return rc;
+    const int64_t n = g->n_nodes;
+    if (n == 0) return QV_OK;
+    rc = arena_begin(ctx, align_up((size_t)n * 4) + 4096);
+    if (rc != QV_OK) return rc;
+    float* tmp = (float*)arena_take(ctx, (size_t)n * 4);
+    const int G = group_width_for(n, g->n_edges);
+    const float* prev = nullptr;
+    for (int j = 0; j < n_hops; ++j) {                 // hop m = K - j
+        const int m = n_hops - j;
+        float* dst = ((n_hops - 1 - j) % 2 == 0) ? psgs_out : tmp;
+        const float add = (m == 1) ? 1.0f : 0.0f;
+        const int Gj = prev ? G : 4;                   // the innermost hop reads no edges
+        if (g->rowptr_bits == 32) launch_psgs_sweep<int32_t>(ctx, g, Gj, fanouts[m - 1], prev, dst, add);
+        else launch_psgs_sweep<int64_t>(ctx, g, Gj, fanouts[m - 1], prev, dst, add);
+        QV_LAUNCH_CHECK(ctx, "k_psgs_sweep");
+        prev = dst;
+    }
+    return QV_OK;
+}
+
+qv_status qv_psgs_batch_sum(qv_ctx* ctx, const float* psgs, int64_t n_nodes, const int32_t* seeds, int64_t n_seeds,
+                            double* sum_out) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_psgs_batch_sum: ctx is NULL");
+    if (!psgs || !sum_out || n_seeds < 0 || (n_seeds > 0 && !seeds)) return fail(ctx, QV_EINVAL, "qv_psgs_batch_sum: null or negative argument");
+    hipLaunchKernelGGL(k_psgs_batch_sum, dim3(1), dim3(256), 0, ctx->stream, psgs, n_nodes, seeds, n_seeds, sum_out, ctx->d_status);
+    QV_LAUNCH_CHECK(ctx, "k_psgs_batch_sum");
+    return QV_OK;
+}
+
+qv_status qv_access_prob(qv_ctx* ctx, const qv_csr* g, const int32_t* fanouts, int32_t n_hops, const float* p0,
+                         float* prob_out) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_access_prob: ctx is NULL");
+    if (!g || !prob_out) return fail(ctx, QV_EINVAL, "qv_access_prob: null argument");
+    qv_status rc = check_fanouts(ctx, "qv_access_prob", fanouts, n_hops);
+    if (rc != QV_OK) return rc;
+    const int64_t n = g->n_nodes;
+    if (n == 0) return QV_OK;
+    rc = arena_begin(ctx, 3 * align_up((size_t)n * 8) + 4096);
+    if (rc != QV_OK) return rc;
+    double* p_cur = (double*)arena_take(ctx, (size_t)n * 8);
+    double* p_nxt = (double*)arena_take(ctx, (size_t)n * 8);
+    double* p_tot = (double*)arena_take(ctx, (size_t)n * 8);
+    const int ew = grid_for(n, 256 * 4, ctx->n_cu * 16);
+    hipLaunchKernelGGL(k_fap_init, dim3(ew), dim3(256), 0, ctx->stream, n, p0, 1.0 / (double)n, p_cur, p_nxt, p_tot);
+    QV_LAUNCH_CHECK(ctx, "k_fap_init");
+    const int G = group_width_for(n, g->n_edges);
+    for (int k = 1; k <= n_hops; ++k) {
+        if (g->rowptr_bits == 32) launch_fap_push<int32_t>(ctx, g, G, fanouts[k - 1], p_cur, p_nxt);
+        else launch_fap_push<int64_t>(ctx, g, G, fanouts[k - 1], p_cur, p_nxt);
+        QV_LAUNCH_CHECK(ctx, "k_fap_push");
+        hipLaunchKernelGGL(k_fap_fold, dim3(ew), dim3(256), 0, ctx->stream, n, (const double*)p_nxt, p_tot, p_cur,
+                           k == n_hops ? prob_out : (float*)nullptr);
+        QV_LAUNCH_CHECK(ctx, "k_fap_fold");
+        double* t = p_cur; p_cur = p_nxt; p_nxt = t;
+    }
+    return QV_OK;
+}
+
+qv_status qv_place_rank(qv_ctx* ctx, const float* prob, int64_t n, int32_t* rank_out) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_place_rank: ctx is NULL");
+    if (n < 0 || n >= ((int64_t)1 << 31) || (n > 0 && (!prob || !rank_out))) return fail(ctx, QV_EINVAL, "qv_place_rank: bad argument");
+    if (n == 0) return QV_OK;
+    size_t temp_bytes = 0;
+    hipError_t e = rocprim::radix_sort_keys((void*)nullptr, temp_bytes, (uint64_t*)nullptr, (uint64_t*)nullptr, (size_t)n,
+                                            0, 64, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, QV_EHIP, "qv_place_rank: sort sizing failed: %s", hipGetErrorString(e));
+    qv_status rc = arena_begin(ctx, 2 * align_up((size_t)n * 8) + align_up(temp_bytes) + 4096);
+    if (rc != QV_OK) return rc;
+    uint64_t* keys_in = (uint64_t*)arena_take(ctx, (size_t)n * 8);
+    uint64_t* keys_out = (uint64_t*)arena_take(ctx, (size_t)n * 8);
+    void* temp = arena_take(ctx, temp_bytes);
+    const int ew = grid_for(n, 256 * 4, ctx->n_cu * 16);
+    hipLaunchKernelGGL(k_rank_keys, dim3(ew), dim3(256), 0, ctx->stream, n, prob, keys_in);
+    QV_LAUNCH_CHECK(ctx, "k_rank_keys");
+    e = rocprim::radix_sort_keys(temp, temp_bytes, keys_in, keys_out, (size_t)n, 0, 64, ctx->stream);
+    if (e != hipSuccess) return fail(ctx, QV_EHIP, "qv_place_rank: sort failed: %s", hipGetErrorString(e));
+    hipLaunchKernelGGL(k_rank_ids, dim3(ew), dim3(256), 0, ctx->stream, n, (const uint64_t*)keys_out, rank_out);
+    QV_LAUNCH_CHECK(ctx, "k_rank_ids");
+    return QV_OK;
+}
+
+}  // extern "C"

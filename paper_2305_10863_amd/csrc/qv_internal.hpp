@@ -1,0 +1,113 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+#include <cstdio>
+#include <cstdarg>
+#include <string>
+#include "../../include/qv.h"
+
+namespace qv {
+
+constexpr int kWave = 64;               // CDNA wavefront width
+constexpr int kMaxTiles = 1024;         // tiles per scan stage (one partial per thread of a block)
+constexpr int kScanBlock = 256;
+
+// deferred device status bits (qv_ctx::d_status[0])
+constexpr int kStatRange = 1;
+constexpr int kStatCapacity = 2;
+constexpr int kStatInval = 4;
+
+// One open-addressing table entry: 16 bytes, so one entry is one aligned 128-bit access.
+struct alignas(16) HashEntry {
+    uint32_t key;        // global id, kEmptyKey when free
+    int32_t lid;         // local id once assigned, -1 before
+    uint64_t minpos;     // smallest tagged position at which the key occurred in the newest stage
+};
+constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
+constexpr uint64_t kNoPos = ~0ull;
+
+// Sizes that only the device knows while a qv_sample call is in flight.
+struct SampleMeta {
+    int64_t node_off[QV_MAX_HOPS + 2];
+    int64_t edge_off[QV_MAX_HOPS + 1];
+    int64_t frontier_off[QV_MAX_HOPS + 2];
+    int64_t stage_range[2];            // [begin, end) of the flat id array of a reindex stage
+};
+
+}  // namespace qv
+
+struct qv_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    char* arena = nullptr;             // scratch; grown on demand, never shrunk
+    size_t arena_bytes = 0;
+    size_t arena_used = 0;             // bump pointer within one API call
+    int32_t* d_status = nullptr;       // device status word
+    int32_t* h_status = nullptr;       // pinned mirror
+    int n_cu = 256;
+    std::string err;
+};
+
+struct qv_csr {
+    qv_ctx* ctx;
+    int64_t n_nodes, n_edges;
+    const void* rowptr;
+    int rowptr_bits;
+    const int32_t* col;
+};
+
+struct qv_feat {
+    qv_ctx* ctx;
+    int64_t n_rows, n_hot;
+    int32_t dim, elem_bytes;
+    int64_t row_bytes;
+    const char* hot;                   // HBM tier (borrowed or owned)
+    char* hot_owned;
+    char* cold_host;                   // pinned host allocation (owned)
+    const char* cold_dev;              // the same memory as seen from the GPU
+    int32_t* loc;                      // lookup table (owned) or nullptr
+};
+
+namespace qv {
+
+qv_status fail(qv_ctx* ctx, qv_status code, const char* fmt, ...);
+void set_global_error(const char* msg);
+
+#define QV_HIP(ctx, call)                                                                   \
+    do {                                                                                    \
+        hipError_t e_ = (call);                                                             \
+        if (e_ != hipSuccess)                                                               \
+            return qv::fail((ctx), e_ == hipErrorOutOfMemory ? QV_ENOMEM : QV_EHIP,         \
+                            "%s failed: %s", #call, hipGetErrorString(e_));                 \
+    } while (0)
+
+#define QV_LAUNCH_CHECK(ctx, name)                                                          \
+    do {                                                                                    \
+        hipError_t e_ = hipGetLastError();                                                  \
+        if (e_ != hipSuccess)                                                               \
+            return qv::fail((ctx), QV_EHIP, "launch of %s failed: %s", name,                \
+                            hipGetErrorString(e_));                                         \
+    } while (0)
+
+// scratch arena ---------------------------------------------------------------------------
+qv_status arena_begin(qv_ctx* ctx, size_t total_bytes);     // ensure capacity, reset bump pointer
+void* arena_take(qv_ctx* ctx, size_t bytes);                // 256-byte aligned slice
+inline size_t align_up(size_t x, size_t a = 256) { return (x + a - 1) / a * a; }
+
+inline int grid_for(int64_t work_items, int per_block, int cap) {
+    int64_t b = (work_items + per_block - 1) / per_block;
+    if (b < 1) b = 1;
+    if (b > cap) b = cap;
+    return (int)b;
+}
+
+// sample.hip: table sizing shared by qv_sample / qv_reindex / qv_ctx_reserve
+size_t sample_scratch_bytes(int64_t n_seeds, const int32_t* fanouts, int n_hops, int64_t n_nodes);
+
+// gather.hip: raw row gather used by qv_gather and by tier construction
+qv_status launch_gather(qv_ctx* ctx, const char* hot, const char* cold, const int32_t* loc,
+                        int64_t n_rows, int64_t row_bytes, const int32_t* ids, int64_t n_ids,
+                        const int64_t* n_ids_dev, char* out, int64_t out_stride);
+
+}  // namespace qv

@@ -1,7 +1,7 @@
 // Device-side twin of the host feature generator: fills an n x dim feature table directly in
 // HBM so that tables of tens of GB never pass through host memory.  Pure data generation; the
-// integer part is exact and the single fp32 multiply (and the fp16 conversion, round to nearest
-// even) round identically on host and device, so both produce the same bits.
+// integer part is exact and the single fp32 multiply and the fp16 conversion (round to nearest
+// even, done with integer operations) round identically on host and device, so both produce the same bits.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
 #include <cstdint>
@@ -27,6 +27,28 @@ __device__ __forceinline__ float feature_value(uint64_t seed, uint64_t i, uint64
     return __fmul_rn((float)s, 2.6428998e-5f);
 }
 
+// fp32 -> fp16, round to nearest even, written out with integer operations (the same steps as
+// the host generator) so that the compiler cannot merge the multiply and the conversion into
+// one mixed-precision instruction with a single rounding.
+__device__ __forceinline__ uint16_t f32_to_f16_rne(float f) {
+    uint32_t x = __float_as_uint(f);
+    uint32_t sign = (x >> 16) & 0x8000u;
+    int32_t e = (int32_t)((x >> 23) & 0xFF) - 127 + 15;
+    uint32_t m = x & 0x7FFFFFu;
+    if (e >= 31) return (uint16_t)(sign | 0x7C00u);
+    if (e <= 0) {
+        if (e < -10) return (uint16_t)sign;
+        m |= 0x800000u;
+        int shift = 14 - e;
+        uint32_t half = m >> shift, rem = m & ((1u << shift) - 1), mid = 1u << (shift - 1);
+        if (rem > mid || (rem == mid && (half & 1))) ++half;
+        return (uint16_t)(sign | half);
+    }
+    uint32_t half = ((uint32_t)e << 10) | (m >> 13), rem = m & 0x1FFFu;
+    if (rem > 0x1000u || (rem == 0x1000u && (half & 1))) ++half;
+    return (uint16_t)(sign | half);
+}
+
 template <typename T>
 __global__ void fill_features(uint64_t seed, int64_t row_begin, int64_t n_rows, int64_t dim, T* out) {
     int64_t total = n_rows * dim;
@@ -35,7 +57,7 @@ __global__ void fill_features(uint64_t seed, int64_t row_begin, int64_t n_rows, 
         int64_t r = idx / dim, j = idx - r * dim;
         float v = feature_value(seed, (uint64_t)(row_begin + r), (uint64_t)j);
         if constexpr (sizeof(T) == 4) out[idx] = v;
-        else out[idx] = __float2half_rn(v);
+        else out[idx] = f32_to_f16_rne(v);
     }
 }
 
@@ -51,7 +73,7 @@ extern "C" int qg_features_device(uint64_t seed, int64_t row_begin, int64_t n_ro
     if (elem_bytes == 4)
         hipLaunchKernelGGL(fill_features<float>, dim3((unsigned)blocks), dim3(256), 0, s, seed, row_begin, n_rows, dim, (float*)out);
     else if (elem_bytes == 2)
-        hipLaunchKernelGGL(fill_features<__half>, dim3((unsigned)blocks), dim3(256), 0, s, seed, row_begin, n_rows, dim, (__half*)out);
+        hipLaunchKernelGGL(fill_features<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, s, seed, row_begin, n_rows, dim, (uint16_t*)out);
     else
         return -1;
     return (int)hipGetLastError();

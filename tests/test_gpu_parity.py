@@ -1,0 +1,304 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Integer outputs (sampled ids, offsets, local ids, gathered bytes, placement order) must be
+bit-exact.  PSGS / FAP are fp32 on the GPU against fp64 in the oracle: relative error <= 1e-4
+(the tolerance the benchmark spec states), and exactly zero where the oracle is zero.
+"""
+import numpy as np
+import pytest
+
+import oracle
+import qvgen
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+REL_TOL = 1e-4
+
+
+@pytest.fixture(scope="module")
+def qv():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    import paper_2305_10863_amd as m
+    m.lib()
+    return m
+
+
+@pytest.fixture(scope="module")
+def ctx(qv):
+    c = qv.Context(0)
+    yield c
+    c.close()
+
+
+def dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def make_graph(qv, ctx, rowptr, col):
+    return qv.Graph(ctx, dev(rowptr), dev(col))
+
+
+def assert_sample_equal(got, want):
+    for k in ("node_off", "edge_off", "frontier_off", "n_id", "row_local", "col_local", "nbr_global", "frontier"):
+        assert np.array_equal(got[k], want[k]), k
+
+
+def rel_err(g, o):
+    g = g.astype(np.float64)
+    nz = o != 0
+    assert np.all(g[~nz] == 0)
+    return np.max(np.abs(g[nz] - o[nz]) / np.abs(o[nz])) if nz.any() else 0.0
+
+
+# ------------------------------------------------------------------------------------------------
+@pytest.fixture(scope="module")
+def tiny(qv, ctx):
+    w = qvgen.workload("tiny")
+    rowptr, col = w.graph()
+    return w, rowptr, col, make_graph(qv, ctx, rowptr, col)
+
+
+@pytest.mark.parametrize("fanout", [1, 3, 8, 9, 16, 17, 32, 33, 64, 65, 128, 200, 1024])
+def test_sample_hop_matches_oracle(qv, ctx, tiny, fanout):
+    w, rowptr, col, g = tiny
+    rng = np.random.default_rng(fanout)
+    deg = np.diff(rowptr)
+    hubs = np.argsort(-deg)[:40]                                   # long rows: the drawing path
+    frontier = np.concatenate([rng.integers(0, w.n, 3000), hubs, hubs[:5]]).astype(np.int32)
+    rng.shuffle(frontier)
+    for hop in (1, 3):
+        nbr, off = qv.qv_sample_hop(ctx, g, dev(frontier), fanout, 0xC0FFEE1234567 + fanout, hop)
+        ctx.sync()
+        o_nbr, o_off = oracle.sample_hop(rowptr, col, frontier, fanout, 0xC0FFEE1234567 + fanout, hop)
+        off = off.cpu().numpy()
+        assert np.array_equal(off, o_off)
+        assert np.array_equal(nbr[:off[-1]].cpu().numpy(), o_nbr)
+
+
+def test_sample_hop_tight_rows_exercise_collisions(qv, ctx):
+    # rows only slightly longer than the fanout: nearly every draw collides
+    rng = np.random.default_rng(5)
+    n = 3000
+    deg = rng.integers(0, 90, n)
+    rowptr = np.zeros(n + 1, np.int64)
+    rowptr[1:] = np.cumsum(deg)
+    col = rng.integers(0, n, rowptr[-1]).astype(np.int32)
+    g = make_graph(qv, ctx, rowptr, col)
+    frontier = np.arange(n, dtype=np.int32)
+    for fanout in (2, 7, 15, 31, 50, 64, 70, 88):
+        for seed in (1, 2 ** 63 + 12345):
+            nbr, off = qv.qv_sample_hop(ctx, g, dev(frontier), fanout, seed, 2)
+            ctx.sync()
+            o_nbr, o_off = oracle.sample_hop(rowptr, col, frontier, fanout, seed, 2)
+            off = off.cpu().numpy()
+            assert np.array_equal(off, o_off)
+            assert np.array_equal(nbr[:off[-1]].cpu().numpy(), o_nbr), (fanout, seed)
+
+
+@pytest.mark.parametrize("n_known,n_nbr,universe", [(0, 0, 10), (0, 1, 10), (5, 0, 100), (64, 3000, 500),
+                                                     (1000, 100000, 30000), (3, 300000, 50), (70000, 200000, 10 ** 8)])
+def test_reindex_matches_oracle(qv, ctx, n_known, n_nbr, universe):
+    rng = np.random.default_rng(n_known + n_nbr)
+    known = rng.choice(universe, size=n_known, replace=False).astype(np.int32) if n_known else np.zeros(0, np.int32)
+    nbr = rng.integers(0, universe, n_nbr).astype(np.int32)
+    n_id, n_len, local, front, f_len = qv.qv_reindex(ctx, dev(known), dev(nbr), n_nodes=universe)
+    ctx.sync()
+    o_n_id, o_local, o_front = oracle.reindex(known, nbr)
+    assert int(n_len.item()) == len(o_n_id) and int(f_len.item()) == len(o_front)
+    assert np.array_equal(n_id[:len(o_n_id)].cpu().numpy(), o_n_id)
+    assert np.array_equal(local[:n_nbr].cpu().numpy(), o_local)
+    assert np.array_equal(front[:len(o_front)].cpu().numpy(), o_front)
+
+
+def test_sample_tiny_workload_all_batches(qv, ctx, tiny):
+    w, rowptr, col, g = tiny
+    for b in range(8):
+        seeds = w.seeds(b)
+        out = qv.qv_sample(ctx, g, dev(seeds), w.fanouts, w.rng_seed(b))
+        ctx.sync()
+        assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, w.fanouts, w.rng_seed(b)))
+
+
+@pytest.mark.parametrize("fanouts,n_seeds", [([10, 5], 1), ([15, 10, 5], 512), ([25, 10], 1000), ([3], 4096),
+                                             ([70, 2], 200), ([2, 2, 2, 2, 2, 2, 2, 2], 50), ([40, 33], 300)])
+def test_sample_shapes(qv, ctx, tiny, fanouts, n_seeds):
+    w, rowptr, col, g = tiny
+    seeds = w.seeds(100 + n_seeds, n_seeds)
+    out = qv.qv_sample(ctx, g, dev(seeds), fanouts, 77)
+    ctx.sync()
+    assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, fanouts, 77))
+
+
+def test_sample_int64_rowptr_and_in_degree_skew(qv, ctx):
+    w = qvgen.workload("citation", scale=0.003)
+    rowptr, col = w.graph()
+    assert rowptr.dtype == np.int64
+    g = make_graph(qv, ctx, rowptr, col)
+    for b in range(3):
+        seeds = w.seeds(b)
+        out = qv.qv_sample(ctx, g, dev(seeds), w.fanouts, w.rng_seed(b))
+        ctx.sync()
+        assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, w.fanouts, w.rng_seed(b)))
+
+
+def test_sample_degenerate_inputs(qv, ctx):
+    rowptr = np.array([0, 0, 2, 2], dtype=np.int64)
+    col = np.array([0, 2], dtype=np.int32)
+    g = make_graph(qv, ctx, rowptr, col)
+    for seeds, fanouts in (([0, 0, 2], [3, 3]), ([1], [1, 4]), ([], [2]), ([1, 1, 1], [5])):
+        s = np.array(seeds, dtype=np.int32)
+        out = qv.qv_sample(ctx, g, dev(s) if len(s) else torch.zeros(0, dtype=torch.int32, device="cuda"), fanouts, 5)
+        ctx.sync()
+        assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, s, fanouts, 5))
+
+
+def test_errors_are_reported_not_fatal(qv, ctx, tiny):
+    w, rowptr, col, g = tiny
+    seeds = w.seeds(0)
+    # id out of range -> deferred QV_ERANGE, the rest of the batch still sampled
+    bad = seeds.copy()
+    bad[3] = w.n + 5
+    qv.qv_sample(ctx, g, dev(bad), w.fanouts, 1)
+    with pytest.raises(qv.QvError) as e:
+        ctx.sync()
+    assert e.value.status == qv.QV_ERANGE
+    ctx.sync()                                           # status was cleared
+    # output arrays too small -> deferred QV_ECAPACITY, nothing written past the capacity
+    buf = qv.SampleBuffers(ctx, len(seeds), w.fanouts, w.n, caps=(100, 150, 80))
+    guard = torch.full((1000,), -7, dtype=torch.int32, device="cuda")
+    qv.qv_sample(ctx, g, dev(seeds), w.fanouts, 1, out=buf)
+    with pytest.raises(qv.QvError) as e:
+        ctx.sync()
+    assert e.value.status == qv.QV_ECAPACITY
+    assert bool((guard == -7).all())
+    # host-side argument checks
+    for fan in ([0, 5], [5] * 9, [2000]):
+        with pytest.raises(qv.QvError) as e:
+            qv.qv_sample(ctx, g, dev(seeds), fan, 1)
+        assert e.value.status == qv.QV_EINVAL
+    # malformed graphs are refused at creation
+    rp = rowptr.copy().astype(np.int64)
+    rp[5], rp[6] = rp[6] + 1, rp[5]
+    with pytest.raises(qv.QvError) as e:
+        make_graph(qv, ctx, rp, col)
+    assert e.value.status == qv.QV_EINVAL
+    c2 = col.copy()
+    c2[17] = w.n
+    with pytest.raises(qv.QvError):
+        make_graph(qv, ctx, rowptr, c2)
+    # repeated known ids in the stand-alone reindex
+    qv.qv_reindex(ctx, dev(np.array([4, 4], np.int32)), dev(np.array([1], np.int32)))
+    with pytest.raises(qv.QvError) as e:
+        ctx.sync()
+    assert e.value.status == qv.QV_EINVAL
+    ctx.sync()
+
+
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,dim", [(np.float32, 64), (np.float16, 128), (np.float32, 602), (np.float32, 100),
+                                       (np.float32, 1024), (np.float16, 7), (np.float32, 1), (np.float16, 1)])
+def test_gather_matches_oracle(qv, ctx, dtype, dim):
+    n = 5000
+    table = qvgen.features_host(42, n, dim, dtype)
+    rng = np.random.default_rng(dim)
+    ids = rng.integers(0, n, 12345).astype(np.int32)
+    tdtype = torch.float32 if dtype == np.float32 else torch.float16
+    t_dev = qvgen.features_device(42, n, dim, tdtype)
+    assert t_dev.cpu().numpy().tobytes() == table.tobytes()          # host and device generators agree
+    feat = qv.Features(ctx, t_dev)
+    out = qv.qv_gather(ctx, feat, dev(ids))
+    ctx.sync()
+    want = oracle.gather(table, ids)
+    assert out.cpu().numpy().tobytes() == want.tobytes()
+    # a host table (copied into HBM by the library) and a device-side row count
+    feat_h = qv.Features(ctx, torch.from_numpy(table))
+    n_dev = torch.tensor([777], dtype=torch.int64, device="cuda")
+    out2 = torch.zeros((len(ids), dim), dtype=tdtype, device="cuda")
+    qv.qv_gather(ctx, feat_h, dev(ids), n_ids_dev=n_dev, out=out2)
+    ctx.sync()
+    got = out2.cpu().numpy()
+    assert got[:777].tobytes() == want[:777].tobytes() and not got[777:].any()
+    # empty gather, out-of-range id
+    qv.qv_gather(ctx, feat, torch.zeros(0, dtype=torch.int32, device="cuda"))
+    ctx.sync()
+    qv.qv_gather(ctx, feat, dev(np.array([1, n], np.int32)))
+    with pytest.raises(qv.QvError) as e:
+        ctx.sync()
+    assert e.value.status == qv.QV_ERANGE
+    feat.close()
+    feat_h.close()
+
+
+@pytest.mark.parametrize("on_device", [True, False])
+def test_tiered_gather_and_placement(qv, ctx, on_device):
+    n, dim = 20000, 96
+    table = qvgen.features_host(9, n, dim, np.float32)
+    rng = np.random.default_rng(3)
+    prob = rng.random(n).astype(np.float32)
+    prob[rng.integers(0, n, 4000)] = np.float32(0.5)                 # ties
+    rank = qv.qv_place_rank(ctx, dev(prob))
+    ctx.sync()
+    budget = 3000 * dim * 4 + 100                                    # floor -> 3000 hot rows
+    o_rank, o_loc = oracle.place(prob, 3000)
+    assert np.array_equal(rank.cpu().numpy(), o_rank)
+    src = qvgen.features_device(9, n, dim, torch.float32) if on_device else torch.from_numpy(table)
+    feat = qv.Features(ctx, src, hbm_budget_bytes=budget, rank=rank)
+    assert feat.n_hot == 3000
+    loc_ptr = qv.lib().qv_feat_loc(feat.h)
+    assert loc_ptr
+    ids = rng.integers(0, n, 50000).astype(np.int32)
+    out = qv.qv_gather(ctx, feat, dev(ids))
+    ctx.sync()
+    assert out.cpu().numpy().tobytes() == oracle.gather(table, ids).tobytes()
+    cold_frac = (o_loc[ids] < 0).mean()
+    assert 0.7 < cold_frac < 0.95                                    # both tiers were exercised
+    feat.close()
+
+
+# ------------------------------------------------------------------------------------------------
+def metric_graphs():
+    yield "tiny", qvgen.workload("tiny")
+    yield "co_purchase_1pct", qvgen.workload("co_purchase", scale=0.01)
+    yield "citation_0.3pct", qvgen.workload("citation", scale=0.003)
+    yield "dense_social_2pct", qvgen.workload("dense_social", scale=0.02)
+
+
+@pytest.mark.parametrize("name,w", list(metric_graphs()), ids=[n for n, _ in metric_graphs()])
+def test_psgs_and_access_prob_match_oracle(qv, ctx, name, w):
+    rowptr, col = w.graph()
+    g = make_graph(qv, ctx, rowptr, col)
+    rng = np.random.default_rng(1)
+    p0 = (rng.random(w.n) ** 4).astype(np.float32)
+    p0 /= p0.sum(dtype=np.float64)
+    p0 = p0.astype(np.float32)
+    for fanouts in (w.fanouts, [15, 10, 5], [7], [3, 1000]):
+        Q = qv.qv_psgs(ctx, g, fanouts)
+        P = qv.qv_access_prob(ctx, g, fanouts)
+        P2 = qv.qv_access_prob(ctx, g, fanouts, p0=dev(p0))
+        ctx.sync()
+        oQ = oracle.psgs(rowptr, col, fanouts)
+        assert rel_err(Q.cpu().numpy(), oQ) <= REL_TOL
+        assert rel_err(P.cpu().numpy(), oracle.access_prob(rowptr, col, fanouts)) <= REL_TOL
+        assert rel_err(P2.cpu().numpy(), oracle.access_prob(rowptr, col, fanouts, p0=p0.astype(np.float64))) <= REL_TOL
+        # accesses per request == expected sample size, on the GPU's own numbers
+        assert abs(P.double().sum().item() - Q.double().mean().item()) <= 1e-4 * oQ.mean()
+    seeds = w.seeds(0)
+    Q = qv.qv_psgs(ctx, g, w.fanouts)
+    s = qv.qv_psgs_batch_sum(ctx, Q, dev(seeds))
+    ctx.sync()
+    assert abs(s.item() - oracle.psgs(rowptr, col, w.fanouts)[seeds].sum()) <= 1e-4 * s.item()
+
+
+def test_place_rank_large_with_ties(qv, ctx):
+    rng = np.random.default_rng(8)
+    prob = rng.random(1_000_003).astype(np.float32)
+    prob[rng.integers(0, len(prob), 300000)] = np.float32(0.125)
+    prob[rng.integers(0, len(prob), 1000)] = 0.0
+    rank = qv.qv_place_rank(ctx, dev(prob))
+    ctx.sync()
+    assert np.array_equal(rank.cpu().numpy(), oracle.place(prob, 0)[0])
