@@ -43,6 +43,8 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-metrics", action="store_true", help="skip the PSGS / FAP whole-graph passes")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB copy kernel (copy_bytes) so that hardware byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no collectives, no sharding); --gpus %d is not supported. "
@@ -72,6 +74,14 @@ def main():
     table = qvgen.features_device(w.seed, w.n, w.dim, tdtype)
     torch.cuda.synchronize()
     log("graph uploaded, %.1f GB feature table filled in HBM in %.1fs" % (w.n * w.row_bytes / 1e9, time.time() - t0))
+
+    if args.calibrate_copy:
+        a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+        b = torch.empty_like(a)
+        for _ in range(3):
+            qvgen.copy_device(a, b)
+        torch.cuda.synchronize()
+        del a, b
 
     ctx0 = qv.Context(0)
     g = qv.Graph(ctx0, d_rowptr, d_col, validate=True)

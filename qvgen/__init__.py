@@ -80,6 +80,8 @@ def dev():
         _dev.qg_features_device.restype = C.c_int
         _dev.qg_features_device.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_int64, C.c_int,
                                             C.c_void_p, C.c_void_p]
+        _dev.qg_copy_device.restype = C.c_int
+        _dev.qg_copy_device.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     return _dev
 
 
@@ -136,6 +138,16 @@ def features_device(seed, n_rows, dim, torch_dtype, device="cuda:0"):
     if rc != 0:
         raise RuntimeError("qg_features_device failed: hip error %d" % rc)
     return out
+
+
+def copy_device(src, dst):
+    """Plain device copy kernel of src.nbytes bytes (counter calibration yardstick)."""
+    import torch
+    n = src.numel() * src.element_size()
+    rc = dev().qg_copy_device(src.data_ptr(), dst.data_ptr(), n, torch.cuda.current_stream().cuda_stream)
+    if rc != 0:
+        raise RuntimeError("qg_copy_device failed: hip error %d" % rc)
+    return n
 
 
 def seeds(seed, n_nodes, batch, n_seeds, mode=0):

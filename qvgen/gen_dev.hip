@@ -61,7 +61,23 @@ __global__ void fill_features(uint64_t seed, int64_t row_begin, int64_t n_rows, 
     }
 }
 
+// Plain 16-byte-per-lane copy of a known size: the yardstick that hardware byte counters
+// (FETCH_SIZE / WRITE_SIZE) are scaled by when the library's kernels are profiled.
+__global__ void copy_bytes(const uint4* __restrict__ src, uint4* __restrict__ dst, int64_t n_vec) {
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_vec; i += (int64_t)gridDim.x * blockDim.x)
+        dst[i] = src[i];
+}
+
 }  // namespace
+
+extern "C" int qg_copy_device(const void* src, void* dst, int64_t n_bytes, void* stream) {
+    int64_t n_vec = n_bytes / 16;
+    if (n_vec <= 0) return 0;
+    int64_t blocks = (n_vec + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipLaunchKernelGGL(copy_bytes, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)stream, (const uint4*)src, (uint4*)dst, n_vec);
+    return (int)hipGetLastError();
+}
 
 extern "C" int qg_features_device(uint64_t seed, int64_t row_begin, int64_t n_rows, int64_t dim,
                                   int elem_bytes, void* out, void* stream) {
