@@ -47,6 +47,7 @@ typedef enum {
 
 #define QV_MAX_HOPS 8
 #define QV_MAX_FANOUT 1024
+#define QV_MAX_BATCHES 8     /* batches per qv_sample_many / qv_gather_many call */
 
 /* ---------------------------------------------------------------------------------------------
  * Context
@@ -66,6 +67,11 @@ qv_status qv_ctx_sync(qv_ctx* ctx);
  * seeds and these fanouts on a graph of `n_nodes` nodes allocate nothing.  Optional. */
 qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts /*[host]*/,
                          int32_t n_hops, int64_t n_nodes);
+
+/* Testing aid.  The dedup tables are never cleared between calls: every call stamps its entries
+ * with a fresh epoch number, and only when the counter is exhausted (about 10^6 calls) are the
+ * tables cleared once.  This sets the counter so that a test can cross that point quickly. */
+qv_status qv_ctx_set_epoch(qv_ctx* ctx, uint32_t epoch);
 
 /* A-priori output sizes of qv_sample (host arithmetic only): most distinct nodes, most edges
  * over all hops, most frontier entries over hops 0..n_hops.  Outputs sized to these bounds can
@@ -135,6 +141,17 @@ qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_
                     const int32_t* fanouts, int32_t n_hops, uint64_t rng_seed,
                     const qv_sample_out* out);
 
+/* Several independent batches through one set of kernel launches (Section 4.3 (1): several
+ * pipelines are multiplexed on one processor so that small requests still fill it).  Batch b is
+ * sampled exactly as qv_sample(seeds[b], n_seeds[b], rng_seeds[b], &outs[b]) would sample it; the
+ * batches share nothing but the launches.  seeds: [host] array of n_batches [dev] pointers;
+ * n_seeds, rng_seeds: [host] arrays; outs: [host] array of output blocks ([dev] arrays inside).
+ * 1 <= n_batches <= QV_MAX_BATCHES. */
+qv_status qv_sample_many(qv_ctx* ctx, const qv_csr* csr, int32_t n_batches,
+                         const int32_t* const* seeds, const int64_t* n_seeds,
+                         const int32_t* fanouts, int32_t n_hops, const uint64_t* rng_seeds,
+                         const qv_sample_out* outs);
+
 /* Dedup + relabel (Section 2.1: the sampled nodes are collected once each and the sub-graph is
  * expressed over them).  known [dev] int32[n_known]: ids that already have local ids (local id
  * = index; entries must be distinct, else QV_EINVAL is deferred).  nbr [dev] int32[n_nbr].
@@ -182,6 +199,14 @@ const int32_t* qv_feat_loc(const qv_feat* feat);
  * rows are gathered, so a gather can follow qv_sample without a host round trip. */
 qv_status qv_gather(qv_ctx* ctx, const qv_feat* feat, const int32_t* ids, int64_t n_ids,
                     const int64_t* n_ids_dev, void* out, int64_t out_row_stride_bytes);
+
+/* qv_gather for several id lists in one launch: ids, n_ids_dev, outs are [host] arrays of
+ * n_batches [dev] pointers (n_ids_dev may be NULL, or hold NULL entries), n_ids a [host] array.
+ * All outputs share out_row_stride_bytes.  1 <= n_batches <= QV_MAX_BATCHES. */
+qv_status qv_gather_many(qv_ctx* ctx, const qv_feat* feat, int32_t n_batches,
+                         const int32_t* const* ids, const int64_t* n_ids,
+                         const int64_t* const* n_ids_dev, void* const* outs,
+                         int64_t out_row_stride_bytes);
 
 /* ---------------------------------------------------------------------------------------------
  * Workload metrics

@@ -14,13 +14,13 @@ LIB_PATH = os.path.join(_HERE, "libqv.so")
 _lib = None
 
 QV_OK, QV_EINVAL, QV_ENOMEM, QV_EHIP, QV_ECAPACITY, QV_ERANGE = 0, -1, -2, -3, -4, -5
-QV_MAX_HOPS, QV_MAX_FANOUT = 8, 1024
+QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 8
 
 EXPORTS = [
-    "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve",
-    "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_sample_hop", "qv_sample",
+    "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch",
+    "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_sample_hop", "qv_sample", "qv_sample_many",
     "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc",
-    "qv_gather", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
+    "qv_gather", "qv_gather_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
 ]
 
 
@@ -54,12 +54,16 @@ def lib():
         L.qv_last_error.restype = C.c_char_p
         L.qv_ctx_sync.argtypes = [vp]
         L.qv_ctx_reserve.argtypes = [vp, i64, C.POINTER(i32), i32, i64]
+        L.qv_ctx_set_epoch.argtypes = [vp, C.c_uint32]
         L.qv_sample_bounds.argtypes = [i64, C.POINTER(i32), i32, i64, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
         L.qv_csr_create.argtypes = [vp, i64, i64, vp, i32, vp, i32, C.POINTER(vp)]
         L.qv_csr_destroy.argtypes = [vp]
         L.qv_csr_destroy.restype = None
         L.qv_sample_hop.argtypes = [vp, vp, vp, i64, i32, u64, i32, vp, i64, vp]
         L.qv_sample.argtypes = [vp, vp, vp, i64, C.POINTER(i32), i32, u64, C.POINTER(_SampleOut)]
+        L.qv_sample_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i32), i32,
+                                     C.POINTER(u64), C.POINTER(_SampleOut)]
+        L.qv_gather_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), i64]
         L.qv_reindex.argtypes = [vp, vp, i64, vp, i64, i64, vp, i64, vp, vp, vp, vp]
         L.qv_feat_create.argtypes = [vp, vp, i32, i64, i32, i32, i64, vp, C.POINTER(vp)]
         L.qv_feat_destroy.argtypes = [vp]
@@ -239,6 +243,72 @@ def qv_sample(ctx, graph, seeds, fanouts, rng_seed, out=None):
     st = out.struct()
     ctx.check(lib().qv_sample(ctx.h, graph.h, _ptr(seeds), seeds.numel(), arr, k, C.c_uint64(rng_seed), C.byref(st)))
     return out
+
+
+class ManyPlan:
+    """Pre-marshalled argument arrays for qv_sample_many + qv_gather_many over fixed buffers, so
+    that a serving loop only swaps seed pointers and rng seeds."""
+
+    def __init__(self, ctx, graph, feat, bufs, rows, fanouts):
+        n = len(bufs)
+        self.ctx, self.graph, self.feat, self.bufs, self.rows, self.n = ctx, graph, feat, bufs, rows, n
+        self.fan, self.k = _fan(fanouts)
+        self.seed_ptrs = (C.c_void_p * n)()
+        self.n_seeds = (C.c_int64 * n)()
+        self.rng = (C.c_uint64 * n)()
+        self.outs = (_SampleOut * n)(*[b.struct() for b in bufs])
+        if feat is not None:
+            K = bufs[0].n_hops
+            self.ids = (C.c_void_p * n)(*[b.n_id.data_ptr() for b in bufs])
+            self.n_ids = (C.c_int64 * n)(*[b.caps[0] for b in bufs])
+            self.n_dev = (C.c_void_p * n)(*[b.node_off.data_ptr() + 8 * (K + 1) for b in bufs])
+            self.out_ptrs = (C.c_void_p * n)(*[r.data_ptr() for r in rows])
+            self.stride = rows[0].stride(0) * rows[0].element_size()
+
+    def refresh_outputs(self):
+        """Call after swapping a buffer's offset tensors."""
+        K = self.bufs[0].n_hops
+        for i, b in enumerate(self.bufs):
+            self.outs[i] = b.struct()
+            if self.feat is not None:
+                self.n_dev[i] = b.node_off.data_ptr() + 8 * (K + 1)
+
+    def run(self, seeds, rng_seeds, n_batches=None):
+        n = len(seeds) if n_batches is None else n_batches
+        for i in range(n):
+            self.seed_ptrs[i] = seeds[i].data_ptr()
+            self.n_seeds[i] = seeds[i].numel()
+            self.rng[i] = rng_seeds[i]
+        L, c = lib(), self.ctx
+        c.check(L.qv_sample_many(c.h, self.graph.h, n, self.seed_ptrs, self.n_seeds, self.fan, self.k, self.rng, self.outs))
+        if self.feat is not None:
+            c.check(L.qv_gather_many(c.h, self.feat.h, n, self.ids, self.n_ids, self.n_dev, self.out_ptrs, self.stride))
+
+
+def qv_sample_many(ctx, graph, seeds_list, fanouts, rng_seeds, outs=None):
+    """Several independent batches through one set of launches.  Returns the SampleBuffers list."""
+    n = len(seeds_list)
+    for s in seeds_list:
+        _dev_i32(s, "seeds")
+    if outs is None:
+        outs = [SampleBuffers(ctx, s.numel(), fanouts, graph.n_nodes) for s in seeds_list]
+    plan = ManyPlan(ctx, graph, None, outs, None, fanouts)
+    plan.run(seeds_list, rng_seeds, n)
+    return outs
+
+
+def qv_gather_many(ctx, feat, ids_list, n_ids_dev_list=None, outs=None):
+    n = len(ids_list)
+    if outs is None:
+        outs = [torch.empty((max(t.numel(), 1), feat.dim), dtype=feat.dtype, device=ctx.device) for t in ids_list]
+    ids = (C.c_void_p * n)(*[_dev_i32(t, "ids").data_ptr() for t in ids_list])
+    cnt = (C.c_int64 * n)(*[t.numel() for t in ids_list])
+    ndev = None
+    if n_ids_dev_list is not None:
+        ndev = (C.c_void_p * n)(*[None if t is None else t.data_ptr() for t in n_ids_dev_list])
+    optr = (C.c_void_p * n)(*[o.data_ptr() for o in outs])
+    ctx.check(lib().qv_gather_many(ctx.h, feat.h, n, ids, cnt, ndev, optr, outs[0].stride(0) * outs[0].element_size()))
+    return outs
 
 
 def qv_sample_hop(ctx, graph, frontier, fanout, rng_seed, hop, nbr_cap=None):

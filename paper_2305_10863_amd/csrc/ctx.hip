@@ -97,6 +97,8 @@ void qv_ctx_destroy(qv_ctx* ctx) {
     if (!ctx) return;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->arena) (void)hipFree(ctx->arena);
+    if (ctx->table_slots) (void)hipFree(ctx->table_slots);
+    if (ctx->table_lid) (void)hipFree(ctx->table_lid);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
     delete ctx;
@@ -115,6 +117,13 @@ qv_status qv_ctx_sync(qv_ctx* ctx) {
     if (s & kStatInval) return fail(ctx, QV_EINVAL, "device check failed: malformed input (e.g. repeated known ids)");
     if (s & kStatRange) return fail(ctx, QV_ERANGE, "device check failed: an id was outside [0, n)");
     return fail(ctx, QV_ECAPACITY, "device check failed: an output array was too small; results are truncated");
+}
+
+qv_status qv_ctx_set_epoch(qv_ctx* ctx, uint32_t epoch) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_set_epoch: ctx is NULL");
+    if (epoch < ctx->epoch) return fail(ctx, QV_EINVAL, "qv_ctx_set_epoch: the epoch counter only moves forward");
+    ctx->epoch = epoch > kEpochLimit ? kEpochLimit : epoch;
+    return QV_OK;
 }
 
 qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes,

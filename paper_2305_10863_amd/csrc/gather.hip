@@ -23,19 +23,17 @@ struct GatherArgs {
     const int32_t* loc;             // nullptr: row id == hot row
     int64_t n_rows;                 // rows of the table (range check)
     int64_t row_bytes;
-    const int32_t* ids;
-    int64_t n_ids;
-    const int64_t* n_ids_dev;       // nullable clamp
-    char* out;
     int64_t out_stride;
     int32_t vecs_per_row;
     int32_t* status;
+    GatherJob jobs[kMaxBatch];      // one id list / output per blockIdx.y
 };
 
 template <typename V, int LPR>
 __global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
-    int64_t n = a.n_ids;
-    if (a.n_ids_dev) { int64_t nd = *a.n_ids_dev; if (nd < n) n = nd; }
+    const GatherJob& job = a.jobs[blockIdx.y];
+    int64_t n = job.n_ids;
+    if (job.n_ids_dev) { int64_t nd = *job.n_ids_dev; if (nd < n) n = nd; }
     const int sub = threadIdx.x % LPR;
     const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / LPR;
     const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / LPR;
@@ -47,7 +45,7 @@ __global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
             int64_t r = r0 + (int64_t)j * n_groups;
             src[j] = nullptr; dst[j] = nullptr;
             if (r < n) {
-                int32_t id = a.ids[r];
+                int32_t id = job.ids[r];
                 if (id < 0 || (int64_t)id >= a.n_rows) {
                     if (sub == 0) atomicOr(a.status, kStatRange);
                 } else {
@@ -58,7 +56,7 @@ __global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
                         if (l < 0) { base = a.cold; row = (int64_t)(~l); } else row = l;
                     }
                     src[j] = reinterpret_cast<const V*>(base + row * a.row_bytes);
-                    dst[j] = reinterpret_cast<V*>(a.out + r * a.out_stride);
+                    dst[j] = reinterpret_cast<V*>(job.out + r * a.out_stride);
                 }
             }
         }
@@ -73,37 +71,42 @@ __global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
 }
 
 template <typename V>
-static void launch_gather_v(qv_ctx* ctx, const GatherArgs& a, int lpr) {
-    int64_t threads = a.n_ids * lpr / kRowsInFlight + 256;
-    int blocks = grid_for(threads, 256, ctx->n_cu * 32);
+static void launch_gather_v(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t max_ids, int n_jobs) {
+    int64_t threads = max_ids * lpr / kRowsInFlight + 256;
+    dim3 grid((unsigned)grid_for(threads, 256, ctx->n_cu * 8), (unsigned)n_jobs);
     switch (lpr) {
-        case 1: hipLaunchKernelGGL((k_gather<V, 1>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        case 2: hipLaunchKernelGGL((k_gather<V, 2>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        case 4: hipLaunchKernelGGL((k_gather<V, 4>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        case 8: hipLaunchKernelGGL((k_gather<V, 8>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        case 16: hipLaunchKernelGGL((k_gather<V, 16>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        case 32: hipLaunchKernelGGL((k_gather<V, 32>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        default: hipLaunchKernelGGL((k_gather<V, 64>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
+        case 1: hipLaunchKernelGGL((k_gather<V, 1>), grid, dim3(256), 0, ctx->stream, a); break;
+        case 2: hipLaunchKernelGGL((k_gather<V, 2>), grid, dim3(256), 0, ctx->stream, a); break;
+        case 4: hipLaunchKernelGGL((k_gather<V, 4>), grid, dim3(256), 0, ctx->stream, a); break;
+        case 8: hipLaunchKernelGGL((k_gather<V, 8>), grid, dim3(256), 0, ctx->stream, a); break;
+        case 16: hipLaunchKernelGGL((k_gather<V, 16>), grid, dim3(256), 0, ctx->stream, a); break;
+        case 32: hipLaunchKernelGGL((k_gather<V, 32>), grid, dim3(256), 0, ctx->stream, a); break;
+        default: hipLaunchKernelGGL((k_gather<V, 64>), grid, dim3(256), 0, ctx->stream, a); break;
     }
 }
 
 qv_status launch_gather(qv_ctx* ctx, const char* hot, const char* cold, const int32_t* loc, int64_t n_rows,
-                        int64_t row_bytes, const int32_t* ids, int64_t n_ids, const int64_t* n_ids_dev, char* out,
-                        int64_t out_stride) {
-    if (n_ids == 0) return QV_OK;
+                        int64_t row_bytes, const GatherJob* jobs, int n_jobs, int64_t out_stride) {
     // widest vector that divides every row start and the row length
-    uintptr_t bits = (uintptr_t)row_bytes | (uintptr_t)out_stride | (uintptr_t)hot | (uintptr_t)cold | (uintptr_t)out;
-    int vec = (bits % 16 == 0) ? 16 : (bits % 8 == 0) ? 8 : (bits % 4 == 0) ? 4 : 2;
+    uintptr_t bits = (uintptr_t)row_bytes | (uintptr_t)out_stride | (uintptr_t)hot | (uintptr_t)cold;
+    int64_t max_ids = 0;
+    GatherArgs a{hot, cold, loc, n_rows, row_bytes, out_stride, 0, ctx->d_status, {}};
+    for (int i = 0; i < n_jobs; ++i) {
+        a.jobs[i] = jobs[i];
+        if (jobs[i].n_ids > 0) bits |= (uintptr_t)jobs[i].out;
+        if (jobs[i].n_ids > max_ids) max_ids = jobs[i].n_ids;
+    }
+    if (max_ids == 0) return QV_OK;
     if (bits % 2 != 0) return fail(ctx, QV_EINVAL, "gather: rows must be 2-byte aligned");
-    GatherArgs a{hot, cold, loc, n_rows, row_bytes, ids, n_ids, n_ids_dev, out, out_stride,
-                 (int32_t)(row_bytes / vec), ctx->d_status};
+    int vec = (bits % 16 == 0) ? 16 : (bits % 8 == 0) ? 8 : (bits % 4 == 0) ? 4 : 2;
+    a.vecs_per_row = (int32_t)(row_bytes / vec);
     int lpr = 1;
     while (lpr < 64 && lpr < a.vecs_per_row) lpr <<= 1;
     switch (vec) {
-        case 16: launch_gather_v<v4u>(ctx, a, lpr); break;
-        case 8: launch_gather_v<v2u>(ctx, a, lpr); break;
-        case 4: launch_gather_v<uint32_t>(ctx, a, lpr); break;
-        default: launch_gather_v<uint16_t>(ctx, a, lpr); break;
+        case 16: launch_gather_v<v4u>(ctx, a, lpr, max_ids, n_jobs); break;
+        case 8: launch_gather_v<v2u>(ctx, a, lpr, max_ids, n_jobs); break;
+        case 4: launch_gather_v<uint32_t>(ctx, a, lpr, max_ids, n_jobs); break;
+        default: launch_gather_v<uint16_t>(ctx, a, lpr, max_ids, n_jobs); break;
     }
     QV_LAUNCH_CHECK(ctx, "k_gather");
     return QV_OK;
@@ -192,12 +195,14 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
             int32_t* d_cold_ids = nullptr;
             FEAT_TRY(hipMalloc((void**)&d_cold_ids, (size_t)n_cold * 4 + 256));
             FEAT_TRY(hipMemcpyAsync(d_cold_ids, cold_ids.data(), (size_t)n_cold * 4, hipMemcpyHostToDevice, ctx->stream));
-            if (rc == QV_OK)
-                rc = launch_gather(ctx, (const char*)table, nullptr, nullptr, n_rows, row_bytes, rank, n_hot, nullptr,
-                                   f->hot_owned, row_bytes);
-            if (rc == QV_OK)
-                rc = launch_gather(ctx, (const char*)table, nullptr, nullptr, n_rows, row_bytes, d_cold_ids, n_cold,
-                                   nullptr, (char*)f->cold_dev, row_bytes);
+            if (rc == QV_OK) {
+                GatherJob job{rank, n_hot, nullptr, f->hot_owned};
+                rc = launch_gather(ctx, (const char*)table, nullptr, nullptr, n_rows, row_bytes, &job, 1, row_bytes);
+            }
+            if (rc == QV_OK) {
+                GatherJob job{d_cold_ids, n_cold, nullptr, (char*)f->cold_dev};
+                rc = launch_gather(ctx, (const char*)table, nullptr, nullptr, n_rows, row_bytes, &job, 1, row_bytes);
+            }
             FEAT_TRY(hipStreamSynchronize(ctx->stream));
             if (d_cold_ids) (void)hipFree(d_cold_ids);
         } else if (rc == QV_OK) {
@@ -233,8 +238,24 @@ qv_status qv_gather(qv_ctx* ctx, const qv_feat* f, const int32_t* ids, int64_t n
     if (out_row_stride_bytes < f->row_bytes || out_row_stride_bytes % f->elem_bytes != 0)
         return fail(ctx, QV_EINVAL, "qv_gather: out_row_stride_bytes %lld must be >= %lld and a multiple of %d",
                     (long long)out_row_stride_bytes, (long long)f->row_bytes, f->elem_bytes);
-    return launch_gather(ctx, f->hot, f->cold_dev, f->loc, f->n_rows, f->row_bytes, ids, n_ids, n_ids_dev, (char*)out,
-                         out_row_stride_bytes);
+    GatherJob job{ids, n_ids, n_ids_dev, (char*)out};
+    return launch_gather(ctx, f->hot, f->cold_dev, f->loc, f->n_rows, f->row_bytes, &job, 1, out_row_stride_bytes);
+}
+
+qv_status qv_gather_many(qv_ctx* ctx, const qv_feat* f, int32_t n_batches, const int32_t* const* ids, const int64_t* n_ids,
+                         const int64_t* const* n_ids_dev, void* const* outs, int64_t out_row_stride_bytes) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_gather_many: ctx is NULL");
+    if (!f || !ids || !n_ids || !outs) return fail(ctx, QV_EINVAL, "qv_gather_many: null argument");
+    if (n_batches < 1 || n_batches > kMaxBatch) return fail(ctx, QV_EINVAL, "qv_gather_many: n_batches %d outside [1, %d]", n_batches, kMaxBatch);
+    if (out_row_stride_bytes < f->row_bytes || out_row_stride_bytes % f->elem_bytes != 0)
+        return fail(ctx, QV_EINVAL, "qv_gather_many: out_row_stride_bytes %lld must be >= %lld and a multiple of %d",
+                    (long long)out_row_stride_bytes, (long long)f->row_bytes, f->elem_bytes);
+    GatherJob jobs[kMaxBatch];
+    for (int i = 0; i < n_batches; ++i) {
+        if (n_ids[i] < 0 || (n_ids[i] > 0 && (!ids[i] || !outs[i]))) return fail(ctx, QV_EINVAL, "qv_gather_many: batch %d: null or negative argument", i);
+        jobs[i] = GatherJob{ids[i], n_ids[i], n_ids_dev ? n_ids_dev[i] : nullptr, (char*)outs[i]};
+    }
+    return launch_gather(ctx, f->hot, f->cold_dev, f->loc, f->n_rows, f->row_bytes, jobs, n_batches, out_row_stride_bytes);
 }
 
 }  // extern "C"

@@ -10,29 +10,42 @@
 namespace qv {
 
 constexpr int kWave = 64;               // CDNA wavefront width
-constexpr int kMaxTiles = 1024;         // tiles per scan stage (one partial per thread of a block)
 constexpr int kScanBlock = 256;
+constexpr int kItemsPerThread = 4;
+constexpr int kTileItems = kScanBlock * kItemsPerThread;   // positions per dedup tile
+constexpr int kMaxBatch = QV_MAX_BATCHES;
 
 // deferred device status bits (qv_ctx::d_status[0])
 constexpr int kStatRange = 1;
 constexpr int kStatCapacity = 2;
 constexpr int kStatInval = 4;
 
-// One open-addressing table entry: 16 bytes, so one entry is one aligned 128-bit access.
-struct alignas(16) HashEntry {
-    uint32_t key;        // global id, kEmptyKey when free
-    int32_t lid;         // local id once assigned, -1 before
-    uint64_t minpos;     // smallest tagged position at which the key occurred in the newest stage
+// Open-addressing table keyed by global node id.  One 16-byte slot per key plus a separate
+// array of local ids (the relabel pass touches only the latter).
+//   keyw   = epoch << 32 | key.  A slot whose epoch differs from the call's epoch is free, so the
+//            table is never cleared between calls.
+//   minpos = smallest tagged position at which the key occurred in the newest stage of the
+//            newest call: tag = (~epoch & 0xFFFFF) << 44 | (15 - stage) << 40 | position, so a
+//            newer call or stage always wins an atomicMin and stale values need no reset.
+struct alignas(16) TableSlot {
+    uint64_t keyw;
+    uint64_t minpos;
 };
-constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
-constexpr uint64_t kNoPos = ~0ull;
+constexpr uint32_t kEpochLimit = 0xFFFFEu;          // epochs 1 .. kEpochLimit, then a full clear
+
+struct TableRef {
+    TableSlot* slots;
+    int32_t* lid;
+    uint32_t mask;
+    int32_t shift;
+};
 
 // Sizes that only the device knows while a qv_sample call is in flight.
 struct SampleMeta {
     int64_t node_off[QV_MAX_HOPS + 2];
     int64_t edge_off[QV_MAX_HOPS + 1];
     int64_t frontier_off[QV_MAX_HOPS + 2];
-    int64_t stage_range[2];            // [begin, end) of the flat id array of a reindex stage
+    int64_t stage_range[2];            // [begin, end) of the flat id array of stage 0
 };
 
 }  // namespace qv
@@ -43,6 +56,11 @@ struct qv_ctx {
     char* arena = nullptr;             // scratch; grown on demand, never shrunk
     size_t arena_bytes = 0;
     size_t arena_used = 0;             // bump pointer within one API call
+    // hash tables live apart from the arena: their contents carry over between calls
+    qv::TableSlot* table_slots = nullptr;
+    int32_t* table_lid = nullptr;
+    size_t table_entries = 0;          // total slots allocated (all batches of a call together)
+    uint32_t epoch = 0;
     int32_t* d_status = nullptr;       // device status word
     int32_t* h_status = nullptr;       // pinned mirror
     int n_cu = 256;
@@ -102,12 +120,15 @@ inline int grid_for(int64_t work_items, int per_block, int cap) {
     return (int)b;
 }
 
-// sample.hip: table sizing shared by qv_sample / qv_reindex / qv_ctx_reserve
-size_t sample_scratch_bytes(int64_t n_seeds, const int32_t* fanouts, int n_hops, int64_t n_nodes);
-
 // gather.hip: raw row gather used by qv_gather and by tier construction
+struct GatherJob {
+    const int32_t* ids;
+    int64_t n_ids;
+    const int64_t* n_ids_dev;
+    char* out;
+};
 qv_status launch_gather(qv_ctx* ctx, const char* hot, const char* cold, const int32_t* loc,
-                        int64_t n_rows, int64_t row_bytes, const int32_t* ids, int64_t n_ids,
-                        const int64_t* n_ids_dev, char* out, int64_t out_stride);
+                        int64_t n_rows, int64_t row_bytes, const GatherJob* jobs, int n_jobs,
+                        int64_t out_stride);
 
 }  // namespace qv

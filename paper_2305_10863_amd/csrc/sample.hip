@@ -1,14 +1,15 @@
 // Neighbour sampling (one sub-wave group per frontier node, Philox4x32-10 + Floyd's selection)
-// and dedup / relabel (open-addressing hash in HBM keyed by global id, first-occurrence order
+// and dedup / relabel (open-addressing hash in HBM keyed by global id; first-occurrence order
 // recovered from the smallest position at which each id occurs).
 //
-// Stage structure of one qv_sample call (no host synchronisation anywhere):
-//   k_init        clear the table, initialise the device-side size block
-//   k_insert_ids  seeds -> table                                  (stage 0)
-//   k_flag / k_assign  first occurrences -> F_0, n_id, local ids, segment offsets of hop 1
-//   per hop k:   k_sample (pick neighbours, write edges, insert into the table)
-//                k_flag / k_assign  -> F_k, n_id growth, segment offsets of hop k+1
-//   k_relabel     col_local for all edges, export of the size block
+// Launches of one qv_sample / qv_sample_many call (no host synchronisation anywhere; every
+// kernel takes up to QV_MAX_BATCHES independent batches along blockIdx.y):
+//   k_insert_ids  seeds -> table (stage 0); also clears the call's scan state
+//   k_dedup       stage 0: first occurrences -> F_0, n_id, local ids, row extents and segment
+//                 offsets of hop 1 (single pass: tile scan with decoupled look-back)
+//   per hop k:    k_sample (pick neighbours, write the hop's edges, insert into the table)
+//                 k_dedup  -> F_k, n_id growth, local ids, row extents / offsets of hop k+1
+//   k_relabel     col_local of every edge, export of the sizes
 #include "qv_internal.hpp"
 #include <new>
 
@@ -76,65 +77,137 @@ __device__ __forceinline__ uint32_t floyd_resolve(uint32_t t, bool active, bool 
 // ---------------------------------------------------------------------------------------------
 // hash table
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t table_home(uint32_t key, int shift) { return (key * 0x9E3779B1u) >> shift; }
+struct TableView {
+    TableSlot* slots;
+    int32_t* lid;
+    uint32_t mask;
+    int32_t shift;
+    uint32_t epoch;
+};
+
+__device__ __forceinline__ uint64_t pos_tag(uint32_t epoch, int stage) {
+    return ((uint64_t)((~epoch) & 0xFFFFFu) << 44) | ((uint64_t)(15 - stage) << 40);
+}
 
 // Returns the slot of `key`, inserting it if absent; 0xFFFFFFFF if the table is full.
-__device__ __forceinline__ uint32_t table_insert(HashEntry* table, uint32_t mask, int shift, uint32_t key) {
-    uint32_t h = table_home(key, shift) & mask;
-    for (uint32_t probes = 0; probes <= mask; ++probes) {
-        uint32_t k = __hip_atomic_load(&table[h].key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (k == key) return h;
-        if (k == kEmptyKey) {
-            uint32_t old = atomicCAS(&table[h].key, kEmptyKey, key);
-            if (old == kEmptyKey || old == key) return h;
+// A slot is free when its epoch is not the call's epoch; whoever claims it resets its local id.
+__device__ __forceinline__ uint32_t table_insert(const TableView& t, uint32_t key) {
+    const uint64_t mine = ((uint64_t)t.epoch << 32) | key;
+    uint32_t h = ((key * 0x9E3779B1u) >> t.shift) & t.mask;
+    for (uint32_t probes = 0; probes <= t.mask; ++probes) {
+        unsigned long long* kw = reinterpret_cast<unsigned long long*>(&t.slots[h].keyw);
+        uint64_t cur = __hip_atomic_load(kw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (;;) {
+            if (cur == mine) return h;
+            if ((uint32_t)(cur >> 32) == t.epoch) break;             // another key of this call
+            uint64_t old = atomicCAS(kw, (unsigned long long)cur, (unsigned long long)mine);
+            if (old == cur) { t.lid[h] = -1; return h; }             // claimed a free slot
+            cur = old;                                               // lost a race: look again
         }
-        h = (h + 1) & mask;
+        h = (h + 1) & t.mask;
     }
     return 0xFFFFFFFFu;
 }
 
-struct TableRef {
-    HashEntry* entries;
-    uint32_t mask;
-    int shift;
-};
+__device__ __forceinline__ void table_note_position(const TableView& t, uint32_t slot, uint64_t tagged_pos) {
+    atomicMin(reinterpret_cast<unsigned long long*>(&t.slots[slot].minpos), (unsigned long long)tagged_pos);
+}
 
-// ---------------------------------------------------------------------------------------------
-// k_init: clear the table and write the initial size block
-// ---------------------------------------------------------------------------------------------
-__global__ void k_init(TableRef tab, SampleMeta* meta, int64_t stage0_len, int64_t edge1_len) {
+// full clear: after (re)allocation and when the epoch counter wraps
+__global__ void k_table_clear(TableSlot* slots, int32_t* lid, int64_t n) {
     int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    uint4 empty;
-    empty.x = kEmptyKey; empty.y = 0xFFFFFFFFu; empty.z = 0xFFFFFFFFu; empty.w = 0xFFFFFFFFu;
-    uint4* e = reinterpret_cast<uint4*>(tab.entries);
-    for (int64_t i = tid; i <= (int64_t)tab.mask; i += stride) e[i] = empty;
-    if (tid == 0) {
-        for (int i = 0; i < QV_MAX_HOPS + 2; ++i) { meta->node_off[i] = 0; meta->frontier_off[i] = 0; }
-        for (int i = 0; i < QV_MAX_HOPS + 1; ++i) meta->edge_off[i] = 0;
-        meta->edge_off[1] = edge1_len;           // used by the stand-alone reindex only
-        meta->stage_range[0] = 0;
-        meta->stage_range[1] = stage0_len;
-    }
+    uint4 z;
+    z.x = 0u; z.y = 0u; z.z = 0xFFFFFFFFu; z.w = 0xFFFFFFFFu;       // epoch 0 = never used; minpos = max
+    uint4* e = reinterpret_cast<uint4*>(slots);
+    for (int64_t i = tid; i < n; i += stride) { e[i] = z; lid[i] = -1; }
 }
 
 // ---------------------------------------------------------------------------------------------
-// k_insert_ids: a flat id array -> table, recording the smallest position of every id
+// per-batch state and per-launch arguments
 // ---------------------------------------------------------------------------------------------
-__global__ void k_insert_ids(const int32_t* __restrict__ ids, int64_t n, int64_t n_nodes, TableRef tab,
-                             uint64_t tag, uint32_t* __restrict__ slot_of, int32_t* status) {
-    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+struct BatchArgs {
+    const int32_t* seeds;           // stage-0 ids
+    int64_t n_seeds;
+    uint64_t rng_seed;
+    TableSlot* slots; int32_t* lid; // this batch's table region
+    SampleMeta* meta;
+    uint32_t* seed_slot;            // table slot of each stage-0 id
+    uint32_t* slot_of;              // table slot of each edge's neighbour
+    int32_t* nbr;                   // global id per edge (caller's array or scratch)
+    int32_t* row_local; int32_t* col_local;
+    int64_t edge_cap;
+    int32_t* n_id; int64_t n_id_cap;
+    // working frontier F_0 | F_1 | .. (scratch, structure of arrays)
+    int32_t* fr_id; int32_t* fr_lid; int64_t* fr_rs; uint32_t* fr_deg; uint32_t* fr_seg; int64_t fr_cap;
+    int32_t* fr_user; int64_t fr_user_cap;
+    uint64_t* tile_state;           // look-back state, two words per tile, all stages back to back
+    uint32_t* tickets;              // one per stage
+    int64_t* node_off_out; int64_t* edge_off_out; int64_t* frontier_off_out;
+    int64_t* n_id_len_out; int64_t* frontier_len_out;      // stand-alone reindex
+};
+
+struct CallArgs {
+    // graph
+    const void* rowptr; const int32_t* col; int64_t n_nodes;
+    // table geometry (same for every batch of the call)
+    uint32_t mask; int32_t shift; uint32_t epoch;
+    // stage being run
+    int32_t stage;                  // 0 = seeds / known ids, k >= 1 = hop k
+    int32_t hop;                    // k_sample: hop number fed to the random stream (== stage in qv_sample)
+    int32_t fanout;                 // k_sample: this hop's fanout
+    int32_t next_fanout;            // k_dedup: fanout of the following hop, 0 = none
+    int32_t n_hops;
+    int64_t tile_base;              // first tile-state index of this stage
+    int32_t frontier_restart;       // stand-alone reindex: number this stage's frontier from 0
+    int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
+    int32_t state_words;            // k_insert_ids of stage 0: tile-state words to clear per batch
+    int32_t n_stages;               //   ... and tickets to clear
+    int32_t* status;
+    BatchArgs b[kMaxBatch];
+};
+
+__device__ __forceinline__ TableView table_of(const CallArgs& c, const BatchArgs& b) {
+    return TableView{b.slots, b.lid, c.mask, c.shift, c.epoch};
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_insert_ids: a flat id array -> table, recording the smallest position of every id.
+// The stage-0 launch is the first kernel of a call and also resets the scan state.
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(256) k_insert_ids(CallArgs c) {
+    const BatchArgs& b = c.b[blockIdx.y];
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int32_t* ids;
+    uint32_t* slot_of;
+    int64_t n;
+    if (c.stage == 0) {
+        ids = b.seeds; slot_of = b.seed_slot; n = b.n_seeds;
+        for (int64_t i = tid; i < c.state_words; i += stride) b.tile_state[i] = 0ull;
+        if (tid < c.n_stages) b.tickets[tid] = 0u;
+        if (tid == 0) {
+            SampleMeta* m = b.meta;
+            for (int i = 0; i < QV_MAX_HOPS + 2; ++i) { m->node_off[i] = 0; m->frontier_off[i] = 0; }
+            for (int i = 0; i < QV_MAX_HOPS + 1; ++i) m->edge_off[i] = 0;
+            m->edge_off[1] = b.edge_cap;        // stand-alone reindex: stage 1 is the flat nbr array
+            m->stage_range[0] = 0;
+            m->stage_range[1] = b.n_seeds;
+        }
+    } else {                                    // stand-alone reindex, stage 1
+        ids = b.nbr; slot_of = b.slot_of; n = b.edge_cap;
+    }
+    const TableView t = table_of(c, b);
+    const uint64_t tag = pos_tag(c.epoch, c.stage);
     for (int64_t i = tid; i < n; i += stride) {
         int32_t id = ids[i];
         uint32_t slot = 0xFFFFFFFFu;
-        if (id < 0 || (n_nodes >= 0 && (int64_t)id >= n_nodes)) {
-            atomicOr(status, kStatRange);
+        if (id < 0 || (c.n_nodes >= 0 && (int64_t)id >= c.n_nodes)) {
+            atomicOr(c.status, kStatRange);
         } else {
-            slot = table_insert(tab.entries, tab.mask, tab.shift, (uint32_t)id);
-            if (slot == 0xFFFFFFFFu) atomicOr(status, kStatCapacity);
-            else atomicMin(reinterpret_cast<unsigned long long*>(&tab.entries[slot].minpos),
-                           (unsigned long long)(tag | (uint64_t)i));
+            slot = table_insert(t, (uint32_t)id);
+            if (slot == 0xFFFFFFFFu) atomicOr(c.status, kStatCapacity);
+            else table_note_position(t, slot, tag | (uint64_t)i);
         }
         slot_of[i] = slot;
     }
@@ -143,153 +216,113 @@ __global__ void k_insert_ids(const int32_t* __restrict__ ids, int64_t n, int64_t
 // ---------------------------------------------------------------------------------------------
 // k_sample: one group of G lanes per frontier node, fanout <= G
 // ---------------------------------------------------------------------------------------------
-struct SampleArgs {
-    const void* rowptr;
-    const int32_t* col;
-    int64_t n_nodes;
-    const int32_t* frontier;        // global ids
-    const int32_t* frontier_lid;    // local ids of the frontier entries (nullable)
-    const int64_t* seg_off;         // start of each frontier entry's segment, relative to the hop's base
-    const int64_t* fr_range;        // device [begin, end) into the three arrays above; NULL = [0, n_frontier)
-    int64_t n_frontier;
-    const int64_t* edge_base;       // device: first edge index of this hop; NULL = 0
-    int32_t fanout, hop;
-    uint64_t seed;
-    int32_t* nbr_out;               // global id per edge
-    int32_t* row_local;             // nullable
-    int64_t cap;
-    TableRef tab;                   // entries == nullptr: no dedup bookkeeping
-    uint32_t* slot_of;
-    uint64_t tag;
-    int32_t* status;
-};
+__device__ __forceinline__ void emit_edge(const CallArgs& c, const BatchArgs& b, const TableView& t, uint64_t tag,
+                                          int64_t p, int32_t g, int32_t vl) {
+    if (p < b.edge_cap) {
+        b.nbr[p] = g;
+        if (b.row_local) b.row_local[p] = vl;
+        if (b.slot_of) {
+            uint32_t slot = 0xFFFFFFFFu;
+            if (g < 0 || (int64_t)g >= c.n_nodes) {
+                atomicOr(c.status, kStatRange);
+            } else {
+                slot = table_insert(t, (uint32_t)g);
+                if (slot == 0xFFFFFFFFu) atomicOr(c.status, kStatCapacity);
+                else table_note_position(t, slot, tag | (uint64_t)p);
+            }
+            b.slot_of[p] = slot;
+        }
+    } else {
+        atomicOr(c.status, kStatCapacity);
+    }
+}
 
-template <int G, typename RP>
-__global__ void __launch_bounds__(256) k_sample(SampleArgs a) {
-    const RP* __restrict__ rowptr = static_cast<const RP*>(a.rowptr);
+template <int G>
+__global__ void __launch_bounds__(256) k_sample(CallArgs c) {
+    const BatchArgs& b = c.b[blockIdx.y];
     const int sub = threadIdx.x % G;
-    const int groups_per_block = 256 / G;
-    int64_t fbeg = 0, F = a.n_frontier;
-    if (a.fr_range) { fbeg = a.fr_range[0]; F = a.fr_range[1] - fbeg; }
-    const int64_t ebase = a.edge_base ? *a.edge_base : 0;
+    constexpr int groups_per_block = 256 / G;
+    const SampleMeta* m = b.meta;
+    const int64_t fbeg = m->frontier_off[c.stage - 1];
+    const int64_t F = m->frontier_off[c.stage] - fbeg;
+    const int64_t ebase = m->edge_off[c.stage - 1];
     const int64_t stride = (int64_t)gridDim.x * groups_per_block;
     const int group_in_wave = (threadIdx.x % kWave) / G;
+    const TableView t = table_of(c, b);
+    const uint64_t tag = pos_tag(c.epoch, c.stage);
+    const uint32_t l = (uint32_t)c.fanout;
     // the loop is uniform over the wave: every lane runs the same number of iterations
     int64_t f0 = (int64_t)blockIdx.x * groups_per_block + (threadIdx.x / kWave) * (kWave / G);
     for (; f0 < F; f0 += stride) {
-        int64_t f = f0 + group_in_wave;
-        uint32_t d = 0;
-        int64_t rs = 0, off = 0;
-        int32_t v = -1, vl = -1;
+        const int64_t f = f0 + group_in_wave;
+        uint32_t d = 0, off = 0;
+        int64_t rs = 0;
+        int32_t v = 0, vl = -1;
         if (f < F) {
-            v = a.frontier[fbeg + f];
-            if (v < 0 || (int64_t)v >= a.n_nodes) {
-                if (sub == 0) atomicOr(a.status, kStatRange);
-                v = -1;
-            } else {
-                rs = (int64_t)rowptr[v];
-                d = (uint32_t)((int64_t)rowptr[v + 1] - rs);
-                off = a.seg_off[fbeg + f];
-                if (a.frontier_lid) vl = a.frontier_lid[fbeg + f];
-            }
+            v = b.fr_id[fbeg + f];
+            rs = b.fr_rs[fbeg + f];
+            d = b.fr_deg[fbeg + f];
+            off = b.fr_seg[fbeg + f];
+            vl = b.fr_lid[fbeg + f];
         }
-        const uint32_t l = (uint32_t)a.fanout;
         const bool draw = d > l;
-        const uint32_t m = draw ? l : d;
+        const uint32_t mcount = draw ? l : d;
         uint32_t pos = (uint32_t)sub;
         if (__any(draw)) {
-            bool active = draw && (uint32_t)sub < l;
-            uint32_t base = d - l;                      // meaningful only where draw
-            uint32_t t = 0xFFFFFFFFu;
-            if (active) t = rand_below(a.seed, (uint32_t)v, (uint32_t)a.hop, (uint32_t)sub, base + (uint32_t)sub + 1u);
-            uint32_t pick = floyd_resolve<G>(t, active, false, base, sub, 0, (int)l);
+            const bool active = draw && (uint32_t)sub < l;
+            const uint32_t base = d - l;                      // meaningful only where draw
+            uint32_t tdraw = 0xFFFFFFFFu;
+            if (active) tdraw = rand_below(b.rng_seed, (uint32_t)v, (uint32_t)c.hop, (uint32_t)sub, base + (uint32_t)sub + 1u);
+            const uint32_t pick = floyd_resolve<G>(tdraw, active, false, base, sub, 0, (int)l);
             if (draw) pos = pick;
         }
-        if ((uint32_t)sub < m) {
-            int64_t p = ebase + off + sub;
-            if (p < a.cap) {
-                int32_t g = a.col[rs + pos];
-                a.nbr_out[p] = g;
-                if (a.row_local) a.row_local[p] = vl;
-                if (a.tab.entries) {
-                    uint32_t slot = 0xFFFFFFFFu;
-                    if (g < 0 || (int64_t)g >= a.n_nodes) {
-                        atomicOr(a.status, kStatRange);
-                    } else {
-                        slot = table_insert(a.tab.entries, a.tab.mask, a.tab.shift, (uint32_t)g);
-                        if (slot == 0xFFFFFFFFu) atomicOr(a.status, kStatCapacity);
-                        else atomicMin(reinterpret_cast<unsigned long long*>(&a.tab.entries[slot].minpos),
-                                       (unsigned long long)(a.tag | (uint64_t)p));
-                    }
-                    a.slot_of[p] = slot;
-                }
-            } else {
-                atomicOr(a.status, kStatCapacity);
-            }
+        if ((uint32_t)sub < mcount) {
+            const int32_t g = c.col[rs + pos];
+            emit_edge(c, b, t, tag, ebase + off + sub, g, vl);
         }
     }
 }
 
 // Fanouts above 64: one wave (= one block) per frontier node, slots processed 64 at a time,
 // earlier picks kept in LDS.
-template <typename RP>
-__global__ void __launch_bounds__(64) k_sample_wide(SampleArgs a) {
+__global__ void __launch_bounds__(64) k_sample_wide(CallArgs c) {
     __shared__ uint32_t picks[QV_MAX_FANOUT];
-    const RP* __restrict__ rowptr = static_cast<const RP*>(a.rowptr);
+    const BatchArgs& b = c.b[blockIdx.y];
     const int lane = threadIdx.x;
-    int64_t fbeg = 0, F = a.n_frontier;
-    if (a.fr_range) { fbeg = a.fr_range[0]; F = a.fr_range[1] - fbeg; }
-    const int64_t ebase = a.edge_base ? *a.edge_base : 0;
-    const uint32_t l = (uint32_t)a.fanout;
+    const SampleMeta* m = b.meta;
+    const int64_t fbeg = m->frontier_off[c.stage - 1];
+    const int64_t F = m->frontier_off[c.stage] - fbeg;
+    const int64_t ebase = m->edge_off[c.stage - 1];
+    const TableView t = table_of(c, b);
+    const uint64_t tag = pos_tag(c.epoch, c.stage);
+    const uint32_t l = (uint32_t)c.fanout;
     for (int64_t f = blockIdx.x; f < F; f += gridDim.x) {
-        int32_t v = a.frontier[fbeg + f];
-        if (v < 0 || (int64_t)v >= a.n_nodes) {
-            if (lane == 0) atomicOr(a.status, kStatRange);
-            continue;
-        }
-        const int64_t rs = (int64_t)rowptr[v];
-        const uint32_t d = (uint32_t)((int64_t)rowptr[v + 1] - rs);
-        const int64_t off = a.seg_off[fbeg + f];
-        const int32_t vl = a.frontier_lid ? a.frontier_lid[fbeg + f] : -1;
+        const int32_t v = b.fr_id[fbeg + f];
+        const int64_t rs = b.fr_rs[fbeg + f];
+        const uint32_t d = b.fr_deg[fbeg + f];
+        const uint32_t off = b.fr_seg[fbeg + f];
+        const int32_t vl = b.fr_lid[fbeg + f];
         const bool draw = d > l;
-        const uint32_t m = draw ? l : d;
+        const uint32_t mcount = draw ? l : d;
         const uint32_t base = d - l;
-        for (uint32_t c0 = 0; c0 < m; c0 += kWave) {
-            uint32_t s = c0 + (uint32_t)lane;
+        for (uint32_t c0 = 0; c0 < mcount; c0 += kWave) {
+            const uint32_t s = c0 + (uint32_t)lane;
             uint32_t pos = s;
             if (draw) {
-                bool active = s < l;
-                uint32_t t = 0xFFFFFFFFu;
-                if (active) t = rand_below(a.seed, (uint32_t)v, (uint32_t)a.hop, s, base + s + 1u);
-                bool pre = false;                       // t already chosen by a slot of an earlier round?
-                for (uint32_t r = 0; r < c0; ++r) pre |= (picks[r] == t);
-                int n_active = (int)((l - c0) < (uint32_t)kWave ? (l - c0) : (uint32_t)kWave);
-                pos = floyd_resolve<kWave>(t, active, active && pre, base, lane, (int)c0, n_active);
+                const bool active = s < l;
+                uint32_t tdraw = 0xFFFFFFFFu;
+                if (active) tdraw = rand_below(b.rng_seed, (uint32_t)v, (uint32_t)c.hop, s, base + s + 1u);
+                bool pre = false;                       // already chosen by a slot of an earlier round?
+                for (uint32_t r = 0; r < c0; ++r) pre |= (picks[r] == tdraw);
+                const int n_active = (int)((l - c0) < (uint32_t)kWave ? (l - c0) : (uint32_t)kWave);
+                pos = floyd_resolve<kWave>(tdraw, active, active && pre, base, lane, (int)c0, n_active);
                 __syncthreads();
                 if (active) picks[s] = pos;
                 __syncthreads();
             }
-            if (s < m) {
-                int64_t p = ebase + off + s;
-                if (p < a.cap) {
-                    int32_t g = a.col[rs + pos];
-                    a.nbr_out[p] = g;
-                    if (a.row_local) a.row_local[p] = vl;
-                    if (a.tab.entries) {
-                        uint32_t slot = 0xFFFFFFFFu;
-                        if (g < 0 || (int64_t)g >= a.n_nodes) {
-                            atomicOr(a.status, kStatRange);
-                        } else {
-                            slot = table_insert(a.tab.entries, a.tab.mask, a.tab.shift, (uint32_t)g);
-                            if (slot == 0xFFFFFFFFu) atomicOr(a.status, kStatCapacity);
-                            else atomicMin(reinterpret_cast<unsigned long long*>(&a.tab.entries[slot].minpos),
-                                           (unsigned long long)(a.tag | (uint64_t)p));
-                        }
-                        a.slot_of[p] = slot;
-                    }
-                } else {
-                    atomicOr(a.status, kStatCapacity);
-                }
+            if (s < mcount) {
+                const int32_t g = c.col[rs + pos];
+                emit_edge(c, b, t, tag, ebase + off + s, g, vl);
             }
         }
         __syncthreads();                                // picks are reused by the next node
@@ -323,176 +356,212 @@ __device__ __forceinline__ Tri block_scan3(Tri v, Tri& total, uint32_t (*lds)[3]
 }
 
 // ---------------------------------------------------------------------------------------------
-// k_flag / k_assign: first occurrences of a stage's ids -> frontier, n_id, local ids, offsets
+// Decoupled look-back over tiles.  Each tile publishes the sum over its own items, then walks
+// back over its predecessors until it meets one whose inclusive prefix is known.  Tiles are
+// numbered by a ticket taken when the block starts, so every predecessor of a tile is already
+// running: the wait always ends, whatever the order in which the hardware starts blocks.
+// Two independent 62-bit payloads per tile: word 0 = (first occurrences << 31 | new nodes),
+// word 1 = next-hop segment sizes.  Top two bits: 0 not ready, 1 tile sum, 2 inclusive prefix.
 // ---------------------------------------------------------------------------------------------
-struct StageArgs {
-    const void* rowptr;             // for the degree of first occurrences (next hop's segment sizes)
-    int64_t n_nodes;
-    const int32_t* ids;             // the stage's id array (seeds, or global neighbour ids)
-    const uint32_t* slot_of;
-    uint16_t* flags;
-    uint32_t* partial;              // [kMaxTiles][3]
-    SampleMeta* meta;
-    int32_t stage;                  // 0 = seeds / known ids, k >= 1 = hop k
-    int32_t next_fanout;            // 0: no further hop
-    int32_t items_per_thread;
-    int32_t frontier_restart;       // stand-alone reindex: number the stage's frontier from 0
-    int32_t expect_all_first;       // stand-alone reindex stage 0: known ids must be distinct
-    int64_t ids_cap;                // positions at or above this were dropped
-    HashEntry* table;
-    uint64_t tag;
-    int32_t* n_id; int64_t n_id_cap;
-    int32_t* fr_ids; int32_t* fr_lid; int64_t* fr_seg; int64_t fr_cap;      // working frontier (scratch)
-    int32_t* fr_user; int64_t fr_user_cap;                                  // caller's copy (nullable)
-    int32_t* status;
-};
+constexpr uint64_t kStMask = 3ull << 62, kStSum = 1ull << 62, kStIncl = 2ull << 62;
 
-__device__ __forceinline__ void stage_range(const StageArgs& a, int64_t& begin, int64_t& end) {
-    if (a.stage == 0) { begin = a.meta->stage_range[0]; end = a.meta->stage_range[1]; }
-    else { begin = a.meta->edge_off[a.stage - 1]; end = a.meta->edge_off[a.stage]; }
-    if (end > a.ids_cap) end = a.ids_cap;
-    if (end < begin) end = begin;
+__device__ __forceinline__ uint64_t wave_sum64(uint64_t v) {
+#pragma unroll
+    for (int o = kWave / 2; o >= 1; o >>= 1) {
+        uint32_t lo = __shfl_xor((uint32_t)v, o), hi = __shfl_xor((uint32_t)(v >> 32), o);
+        v += ((uint64_t)hi << 32) | lo;
+    }
+    return v;
 }
 
+// Called by the 64 lanes of wave 0.  Returns the exclusive prefixes of both payloads.
+__device__ __forceinline__ void tile_lookback(uint64_t* state, int64_t tile, uint64_t sum0, uint64_t sum1,
+                                              uint64_t& ex0, uint64_t& ex1) {
+    const int lane = threadIdx.x;
+    unsigned long long* st = reinterpret_cast<unsigned long long*>(state);
+    if (lane == 0) {
+        const uint64_t flag = tile == 0 ? kStIncl : kStSum;
+        __hip_atomic_store(&st[tile * 2 + 0], (unsigned long long)(flag | sum0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&st[tile * 2 + 1], (unsigned long long)(flag | sum1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    ex0 = 0; ex1 = 0;
+    if (tile == 0) return;
+    bool done0 = false, done1 = false;
+    for (int64_t idx = tile - 1; !(done0 && done1); idx -= kWave) {
+        const int64_t my = idx - lane;
+        uint64_t w0 = kStIncl, w1 = kStIncl;            // before tile 0: inclusive prefix 0
+        if (my >= 0) {
+            if (!done0) {
+                do { w0 = __hip_atomic_load(&st[my * 2 + 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                     if ((w0 & kStMask) == 0) __builtin_amdgcn_s_sleep(1); } while ((w0 & kStMask) == 0);
+            }
+            if (!done1) {
+                do { w1 = __hip_atomic_load(&st[my * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                     if ((w1 & kStMask) == 0) __builtin_amdgcn_s_sleep(1); } while ((w1 & kStMask) == 0);
+            }
+        }
+        if (!done0) {
+            const uint64_t incl = __ballot((w0 & kStMask) == kStIncl);
+            const int first = incl ? (int)__ffsll((unsigned long long)incl) - 1 : kWave;   // nearest predecessor
+            ex0 += wave_sum64(lane <= first ? (w0 & ~kStMask) : 0ull);
+            done0 = first < kWave;
+        }
+        if (!done1) {
+            const uint64_t incl = __ballot((w1 & kStMask) == kStIncl);
+            const int first = incl ? (int)__ffsll((unsigned long long)incl) - 1 : kWave;
+            ex1 += wave_sum64(lane <= first ? (w1 & ~kStMask) : 0ull);
+            done1 = first < kWave;
+        }
+    }
+    if (lane == 0) {
+        __hip_atomic_store(&st[tile * 2 + 0], (unsigned long long)(kStIncl | (ex0 + sum0)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&st[tile * 2 + 1], (unsigned long long)(kStIncl | (ex1 + sum1)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_dedup: first occurrences of a stage's ids -> frontier, n_id, local ids, next-hop extents.
+// Position p of the stage is a first occurrence iff the table's smallest tagged position for
+// its id is p itself; it is a new node iff that id has no local id yet.
+// ---------------------------------------------------------------------------------------------
 template <typename RP>
-__global__ void __launch_bounds__(kScanBlock) k_flag(StageArgs a) {
+__global__ void __launch_bounds__(kScanBlock) k_dedup(CallArgs c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const RP* __restrict__ rowptr = static_cast<const RP*>(a.rowptr);
+    __shared__ int64_t sh_tile;
+    __shared__ uint64_t sh_ex[2];
+    const BatchArgs& b = c.b[blockIdx.y];
+    const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
+    SampleMeta* m = b.meta;
+    const int stage = c.stage;
     int64_t begin, end;
-    stage_range(a, begin, end);
-    const int64_t tile_size = (int64_t)kScanBlock * a.items_per_thread;
-    const int64_t t0 = begin + (int64_t)blockIdx.x * tile_size;
-    if (t0 >= end) return;
-    Tri sum = {0, 0, 0};
-    for (int it = 0; it < a.items_per_thread; ++it) {
-        int64_t p = t0 + (int64_t)it * kScanBlock + threadIdx.x;
+    const int32_t* ids;
+    const uint32_t* slot_of;
+    if (stage == 0) { begin = m->stage_range[0]; end = m->stage_range[1]; ids = b.seeds; slot_of = b.seed_slot; }
+    else {
+        begin = m->edge_off[stage - 1]; end = m->edge_off[stage];
+        if (end > b.edge_cap) end = b.edge_cap;
+        ids = b.nbr; slot_of = b.slot_of;
+    }
+    if (end < begin) end = begin;
+    if (threadIdx.x == 0) sh_tile = (int64_t)atomicAdd(&b.tickets[stage], 1u);
+    __syncthreads();
+    const int64_t tile = sh_tile;
+    const int64_t n_tiles = (end - begin + kTileItems - 1) / kTileItems;
+    if (tile >= n_tiles && !(n_tiles == 0 && tile == 0)) return;
+    const int64_t p0 = begin + tile * kTileItems + (int64_t)threadIdx.x * kItemsPerThread;
+    const uint64_t tag = pos_tag(c.epoch, stage);
+
+    uint32_t first[kItemsPerThread], isnew[kItemsPerThread], seg[kItemsPerThread], slot[kItemsPerThread];
+    int32_t id[kItemsPerThread], oldlid[kItemsPerThread];
+    int64_t rs[kItemsPerThread];
+    uint32_t deg[kItemsPerThread];
+    Tri mine = {0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < kItemsPerThread; ++i) {
+        const int64_t p = p0 + i;
+        first[i] = 0; isnew[i] = 0; seg[i] = 0; slot[i] = 0xFFFFFFFFu; id[i] = 0; oldlid[i] = -1; rs[i] = 0; deg[i] = 0;
         if (p < end) {
-            uint32_t slot = a.slot_of[p];
-            uint32_t first = 0, isnew = 0, m = 0;
-            if (slot != 0xFFFFFFFFu) {
-                HashEntry e = a.table[slot];
-                first = (e.minpos == (a.tag | (uint64_t)p)) ? 1u : 0u;
-                isnew = (first && e.lid < 0) ? 1u : 0u;
-                if (first && a.next_fanout > 0) {
-                    int32_t g = a.ids[p];
-                    uint32_t d = (uint32_t)((int64_t)rowptr[g + 1] - (int64_t)rowptr[g]);
-                    m = d < (uint32_t)a.next_fanout ? d : (uint32_t)a.next_fanout;
+            slot[i] = slot_of[p];
+            if (slot[i] != 0xFFFFFFFFu && b.slots[slot[i]].minpos == (tag | (uint64_t)p)) {
+                first[i] = 1;
+                oldlid[i] = b.lid[slot[i]];
+                isnew[i] = oldlid[i] < 0 ? 1u : 0u;
+                id[i] = ids[p];
+                if (c.next_fanout > 0) {
+                    rs[i] = (int64_t)rowptr[id[i]];
+                    deg[i] = (uint32_t)((int64_t)rowptr[id[i] + 1] - rs[i]);
+                    seg[i] = deg[i] < (uint32_t)c.next_fanout ? deg[i] : (uint32_t)c.next_fanout;
                 }
             }
-            a.flags[p] = (uint16_t)(first | (isnew << 1) | (m << 2));
-            sum.a += first; sum.b += isnew; sum.c += m;
         }
+        mine.a += first[i]; mine.b += isnew[i]; mine.c += seg[i];
     }
     Tri total;
-    block_scan3(sum, total, lds);
-    if (threadIdx.x == 0) {
-        a.partial[blockIdx.x * 3 + 0] = total.a;
-        a.partial[blockIdx.x * 3 + 1] = total.b;
-        a.partial[blockIdx.x * 3 + 2] = total.c;
+    Tri ex = block_scan3(mine, total, lds);
+    if (threadIdx.x < kWave) {
+        uint64_t e0, e1;
+        tile_lookback(b.tile_state + c.tile_base * 2, tile, ((uint64_t)total.a << 31) | total.b, (uint64_t)total.c, e0, e1);
+        if (threadIdx.x == 0) { sh_ex[0] = e0; sh_ex[1] = e1; }
     }
-}
-
-__global__ void __launch_bounds__(kScanBlock) k_assign(StageArgs a) {
-    __shared__ uint32_t lds[kScanBlock / kWave][3];
-    int64_t begin, end;
-    stage_range(a, begin, end);
-    const int64_t tile_size = (int64_t)kScanBlock * a.items_per_thread;
-    const int64_t t0 = begin + (int64_t)blockIdx.x * tile_size;
-    const bool empty_stage = end <= begin;
-    if (t0 >= end && !(empty_stage && blockIdx.x == 0)) return;
-    // totals of all earlier tiles
-    Tri pre = {0, 0, 0};
-    for (int i = threadIdx.x; i < (int)blockIdx.x; i += kScanBlock) {
-        pre.a += a.partial[i * 3 + 0]; pre.b += a.partial[i * 3 + 1]; pre.c += a.partial[i * 3 + 2];
-    }
-    Tri run;
-    block_scan3(pre, run, lds);
-    const int64_t node_base = a.meta->node_off[a.stage];
-    const int64_t fr_base = a.meta->frontier_off[a.stage];
-    const int64_t fr_user_base = a.frontier_restart ? 0 : fr_base;
-    for (int it = 0; it < a.items_per_thread; ++it) {
-        int64_t p = t0 + (int64_t)it * kScanBlock + threadIdx.x;
-        uint32_t f = (p < end) ? a.flags[p] : 0u;
-        Tri v = {f & 1u, (f >> 1) & 1u, f >> 2};
-        Tri tot;
-        Tri ex = block_scan3(v, tot, lds);
-        if (v.a) {
-            uint32_t slot = a.slot_of[p];
-            int32_t id = a.ids[p];
-            int64_t u = node_base + run.b + ex.b;
-            int32_t lid;
-            if (v.b) {
+    __syncthreads();
+    const int64_t pre_first = (int64_t)(sh_ex[0] >> 31), pre_new = (int64_t)(sh_ex[0] & 0x7FFFFFFFull);
+    const int64_t pre_seg = (int64_t)sh_ex[1];
+    const int64_t node_base = m->node_off[stage];
+    const int64_t fr_base = m->frontier_off[stage];
+    const int64_t fr_user_base = c.frontier_restart ? 0 : fr_base;
+    int64_t j = pre_first + ex.a, u = node_base + pre_new + ex.b, so = pre_seg + ex.c;
+#pragma unroll
+    for (int i = 0; i < kItemsPerThread; ++i) {
+        if (first[i]) {
+            int32_t lid = oldlid[i];
+            if (isnew[i]) {
                 lid = (int32_t)u;
-                a.table[slot].lid = lid;
-                if (u < a.n_id_cap) a.n_id[u] = id;
-                else atomicOr(a.status, kStatCapacity);
-            } else {
-                lid = a.table[slot].lid;
+                b.lid[slot[i]] = lid;
+                if (u < b.n_id_cap) b.n_id[u] = id[i];
+                else atomicOr(c.status, kStatCapacity);
+                ++u;
             }
-            int64_t j = (int64_t)run.a + ex.a;
-            if (fr_base + j < a.fr_cap) {
-                a.fr_ids[fr_base + j] = id;
-                a.fr_lid[fr_base + j] = lid;
-                a.fr_seg[fr_base + j] = (int64_t)run.c + ex.c;
-            } else {
-                atomicOr(a.status, kStatCapacity);
+            if (c.next_fanout > 0) {                 // the next hop expands this entry
+                if (fr_base + j < b.fr_cap) {
+                    b.fr_id[fr_base + j] = id[i];
+                    b.fr_lid[fr_base + j] = lid;
+                    b.fr_rs[fr_base + j] = rs[i];
+                    b.fr_deg[fr_base + j] = deg[i];
+                    b.fr_seg[fr_base + j] = (uint32_t)so;
+                } else {
+                    atomicOr(c.status, kStatCapacity);
+                }
             }
-            if (a.fr_user) {
-                if (fr_user_base + j < a.fr_user_cap) a.fr_user[fr_user_base + j] = id;
-                else atomicOr(a.status, kStatCapacity);
+            if (b.fr_user) {
+                if (fr_user_base + j < b.fr_user_cap) b.fr_user[fr_user_base + j] = id[i];
+                else atomicOr(c.status, kStatCapacity);
             }
+            ++j;
+            so += seg[i];
         }
-        run.a += tot.a; run.b += tot.b; run.c += tot.c;
     }
-    const bool last = empty_stage || (t0 + tile_size >= end);
-    if (last && threadIdx.x == 0) {
-        a.meta->node_off[a.stage + 1] = node_base + run.b;
-        a.meta->frontier_off[a.stage + 1] = fr_base + run.a;
-        if (a.next_fanout > 0) a.meta->edge_off[a.stage + 1] = a.meta->edge_off[a.stage] + run.c;
-        if (a.expect_all_first && (int64_t)run.a != end - begin) atomicOr(a.status, kStatInval);
+    const bool last = (n_tiles == 0) || (tile == n_tiles - 1);
+    if (last && threadIdx.x == kScanBlock - 1) {       // the last thread's running values are the totals
+        m->node_off[stage + 1] = u;
+        m->frontier_off[stage + 1] = fr_base + j;
+        if (c.next_fanout > 0) m->edge_off[stage + 1] = m->edge_off[stage] + so;
+        if (c.expect_all_first && j != end - begin) atomicOr(c.status, kStatInval);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
 // k_relabel: local id of every edge's neighbour; export of the sizes
 // ---------------------------------------------------------------------------------------------
-struct RelabelArgs {
-    const uint32_t* slot_of;
-    const HashEntry* table;
-    const SampleMeta* meta;
-    int32_t last_stage;             // edges are [edge_off[first_stage-1].. edge_off[last_stage])
-    int64_t cap;
-    int32_t* col_local;
-    // exports (all nullable)
-    int64_t* node_off; int64_t* edge_off; int64_t* frontier_off; int32_t n_hops;
-    int64_t* n_id_len; int64_t* frontier_len;      // stand-alone reindex
-};
-
-__global__ void k_relabel(RelabelArgs a) {
-    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    int64_t end = a.meta->edge_off[a.last_stage];
-    if (end > a.cap) end = a.cap;
+__global__ void __launch_bounds__(256) k_relabel(CallArgs c) {
+    const BatchArgs& b = c.b[blockIdx.y];
+    const SampleMeta* m = b.meta;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t end = m->edge_off[c.stage];                // c.stage = last stage
+    if (end > b.edge_cap) end = b.edge_cap;
     for (int64_t p = tid; p < end; p += stride) {
-        uint32_t slot = a.slot_of[p];
-        a.col_local[p] = slot == 0xFFFFFFFFu ? -1 : a.table[slot].lid;
+        uint32_t slot = b.slot_of[p];
+        b.col_local[p] = slot == 0xFFFFFFFFu ? -1 : b.lid[slot];
     }
     if (tid == 0) {
-        if (a.node_off) for (int i = 0; i < a.n_hops + 2; ++i) a.node_off[i] = a.meta->node_off[i];
-        if (a.edge_off) for (int i = 0; i < a.n_hops + 1; ++i) a.edge_off[i] = a.meta->edge_off[i];
-        if (a.frontier_off) for (int i = 0; i < a.n_hops + 2; ++i) a.frontier_off[i] = a.meta->frontier_off[i];
-        if (a.n_id_len) *a.n_id_len = a.meta->node_off[2];
-        if (a.frontier_len) *a.frontier_len = a.meta->frontier_off[2] - (a.meta->frontier_off[1]);
+        if (b.node_off_out) for (int i = 0; i < c.n_hops + 2; ++i) b.node_off_out[i] = m->node_off[i];
+        if (b.edge_off_out) for (int i = 0; i < c.n_hops + 1; ++i) b.edge_off_out[i] = m->edge_off[i];
+        if (b.frontier_off_out) for (int i = 0; i < c.n_hops + 2; ++i) b.frontier_off_out[i] = m->frontier_off[i];
+        if (b.n_id_len_out) *b.n_id_len_out = m->node_off[2];
+        if (b.frontier_len_out) *b.frontier_len_out = m->frontier_off[2] - m->frontier_off[1];
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// stand-alone hop: segment sizes -> offsets (two-kernel tile scan)
+// stand-alone hop: row extents and segment offsets of a caller-given frontier (two-kernel scan)
 // ---------------------------------------------------------------------------------------------
+constexpr int kMaxDegTiles = 1024;
+
 template <typename RP>
 __global__ void __launch_bounds__(kScanBlock) k_deg_partial(const RP* __restrict__ rowptr, int64_t n_nodes,
                                                             const int32_t* __restrict__ frontier, int64_t F,
-                                                            int32_t fanout, int32_t ipt, uint32_t* partial) {
+                                                            int32_t fanout, int32_t ipt, uint32_t* partial,
+                                                            int32_t* status) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
     const int64_t t0 = (int64_t)blockIdx.x * kScanBlock * ipt;
     if (t0 >= F) return;
@@ -504,6 +573,8 @@ __global__ void __launch_bounds__(kScanBlock) k_deg_partial(const RP* __restrict
             if (v >= 0 && (int64_t)v < n_nodes) {
                 uint32_t d = (uint32_t)((int64_t)rowptr[v + 1] - (int64_t)rowptr[v]);
                 sum.a += d < (uint32_t)fanout ? d : (uint32_t)fanout;
+            } else {
+                atomicOr(status, kStatRange);
             }
         }
     }
@@ -516,7 +587,8 @@ template <typename RP>
 __global__ void __launch_bounds__(kScanBlock) k_deg_scan(const RP* __restrict__ rowptr, int64_t n_nodes,
                                                          const int32_t* __restrict__ frontier, int64_t F,
                                                          int32_t fanout, int32_t ipt, const uint32_t* partial,
-                                                         int64_t* off_out) {
+                                                         int64_t* off_out, int64_t* fr_rs, uint32_t* fr_deg,
+                                                         uint32_t* fr_seg, SampleMeta* meta) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
     const int64_t t0 = (int64_t)blockIdx.x * kScanBlock * ipt;
     if (t0 >= F && !(F == 0 && blockIdx.x == 0)) return;
@@ -527,18 +599,28 @@ __global__ void __launch_bounds__(kScanBlock) k_deg_scan(const RP* __restrict__ 
     for (int it = 0; it < ipt; ++it) {
         int64_t f = t0 + (int64_t)it * kScanBlock + threadIdx.x;
         Tri v = {0, 0, 0}, tot;
+        int64_t rs = 0;
+        uint32_t d = 0;
         if (f < F) {
             int32_t x = frontier[f];
             if (x >= 0 && (int64_t)x < n_nodes) {
-                uint32_t d = (uint32_t)((int64_t)rowptr[x + 1] - (int64_t)rowptr[x]);
+                rs = (int64_t)rowptr[x];
+                d = (uint32_t)((int64_t)rowptr[x + 1] - rs);
                 v.a = d < (uint32_t)fanout ? d : (uint32_t)fanout;
             }
         }
         Tri ex = block_scan3(v, tot, lds);
-        if (f < F) off_out[f] = (int64_t)(running + ex.a);
+        if (f < F) {
+            off_out[f] = (int64_t)(running + ex.a);
+            fr_rs[f] = rs; fr_deg[f] = d; fr_seg[f] = (uint32_t)(running + ex.a);
+        }
         running += tot.a;
     }
-    if (threadIdx.x == 0 && (F == 0 || t0 + (int64_t)kScanBlock * ipt >= F)) off_out[F] = (int64_t)running;
+    if (threadIdx.x == 0 && (F == 0 || t0 + (int64_t)kScanBlock * ipt >= F)) {
+        off_out[F] = (int64_t)running;
+        meta->frontier_off[0] = 0; meta->frontier_off[1] = F;      // read by k_sample as stage 1
+        meta->edge_off[0] = 0; meta->edge_off[1] = (int64_t)running;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -578,104 +660,166 @@ static void table_geometry(int64_t max_keys, uint32_t* mask, int* shift) {
     *shift = 32 - bits;
 }
 
-struct Scratch {
-    TableRef tab;
-    SampleMeta* meta;
-    uint32_t *seed_slot, *slot_of, *partial;
-    uint16_t *seed_flags, *flags;
-    int32_t *nbr, *fr_ids, *fr_lid;
-    int64_t* fr_seg;
-    int64_t edge_room, fr_room;
+// Make sure the context owns n_tables tables of (mask + 1) slots and start a new epoch.
+static qv_status table_prepare(qv_ctx* ctx, int n_tables, uint32_t mask) {
+    const size_t need = (size_t)n_tables * ((size_t)mask + 1);
+    bool clear = false;
+    if (need > ctx->table_entries) {
+        QV_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (ctx->table_slots) QV_HIP(ctx, hipFree(ctx->table_slots));
+        if (ctx->table_lid) QV_HIP(ctx, hipFree(ctx->table_lid));
+        ctx->table_slots = nullptr; ctx->table_lid = nullptr; ctx->table_entries = 0;
+        QV_HIP(ctx, hipMalloc((void**)&ctx->table_slots, need * sizeof(TableSlot)));
+        QV_HIP(ctx, hipMalloc((void**)&ctx->table_lid, need * sizeof(int32_t)));
+        ctx->table_entries = need;
+        clear = true;
+    }
+    if (ctx->epoch >= kEpochLimit) clear = true;
+    if (clear) {
+        hipLaunchKernelGGL(k_table_clear, dim3(grid_for((int64_t)ctx->table_entries, 1024, ctx->n_cu * 16)), dim3(256), 0,
+                           ctx->stream, ctx->table_slots, ctx->table_lid, (int64_t)ctx->table_entries);
+        QV_LAUNCH_CHECK(ctx, "k_table_clear");
+        ctx->epoch = 0;
+    }
+    ++ctx->epoch;
+    return QV_OK;
+}
+
+struct Layout {                     // per-batch scratch sizes (bytes) and stage tile offsets
+    int64_t stage0, edges, frontier;
+    int64_t tile_base[QV_MAX_HOPS + 2];     // first tile index of each stage; [n_stages] = total
+    int n_stages;
 };
 
-static size_t scratch_bytes(int64_t stage0, int64_t edges, int64_t frontier, int64_t max_keys) {
-    uint32_t mask; int shift;
-    table_geometry(max_keys, &mask, &shift);
+static int64_t tiles_for(int64_t items) { return items > 0 ? (items + kTileItems - 1) / kTileItems : 1; }
+
+static size_t per_batch_bytes(const Layout& L) {
     size_t t = 0;
-    t += align_up(((size_t)mask + 1) * sizeof(HashEntry));
     t += align_up(sizeof(SampleMeta));
-    t += align_up((size_t)stage0 * 4) + align_up((size_t)stage0 * 2);
-    t += align_up((size_t)edges * 4) * 2 + align_up((size_t)edges * 2);
-    t += align_up((size_t)frontier * 4) * 2 + align_up((size_t)frontier * 8);
-    t += align_up((size_t)kMaxTiles * 3 * 4);
-    return t + 4096;
+    t += align_up((size_t)L.stage0 * 4);                                    // seed_slot
+    t += 2 * align_up((size_t)L.edges * 4);                                 // slot_of, nbr
+    t += 2 * align_up((size_t)L.frontier * 4) + align_up((size_t)L.frontier * 8) +
+         2 * align_up((size_t)L.frontier * 4);                              // fr_id, fr_lid, fr_rs, fr_deg, fr_seg
+    t += align_up((size_t)L.tile_base[L.n_stages] * 16);                    // tile_state
+    t += align_up((size_t)(QV_MAX_HOPS + 2) * 4);                           // tickets
+    return t + 2048;
 }
 
-size_t sample_scratch_bytes(int64_t n_seeds, const int32_t* fanouts, int n_hops, int64_t n_nodes) {
-    Bounds b;
-    if (compute_bounds(nullptr, n_seeds, fanouts, n_hops, n_nodes, &b) != QV_OK) return 0;
-    return scratch_bytes(n_seeds, b.edges, b.frontier, b.nodes);
+static bool carve(qv_ctx* ctx, const Layout& L, BatchArgs* b) {
+    b->meta = (SampleMeta*)arena_take(ctx, sizeof(SampleMeta));
+    b->seed_slot = (uint32_t*)arena_take(ctx, (size_t)L.stage0 * 4);
+    b->slot_of = (uint32_t*)arena_take(ctx, (size_t)L.edges * 4);
+    b->nbr = (int32_t*)arena_take(ctx, (size_t)L.edges * 4);
+    b->fr_id = (int32_t*)arena_take(ctx, (size_t)L.frontier * 4);
+    b->fr_lid = (int32_t*)arena_take(ctx, (size_t)L.frontier * 4);
+    b->fr_rs = (int64_t*)arena_take(ctx, (size_t)L.frontier * 8);
+    b->fr_deg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
+    b->fr_seg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
+    b->tile_state = (uint64_t*)arena_take(ctx, (size_t)L.tile_base[L.n_stages] * 16);
+    b->tickets = (uint32_t*)arena_take(ctx, (size_t)(QV_MAX_HOPS + 2) * 4);
+    b->fr_cap = L.frontier;
+    return b->meta && b->seed_slot && b->slot_of && b->nbr && b->fr_id && b->fr_lid && b->fr_rs && b->fr_deg &&
+           b->fr_seg && b->tile_state && b->tickets;
 }
 
-static qv_status take_scratch(qv_ctx* ctx, int64_t stage0, int64_t edges, int64_t frontier, int64_t max_keys,
-                              Scratch* s) {
-    qv_status rc = arena_begin(ctx, scratch_bytes(stage0, edges, frontier, max_keys));
-    if (rc != QV_OK) return rc;
-    table_geometry(max_keys, &s->tab.mask, &s->tab.shift);
-    s->tab.entries = (HashEntry*)arena_take(ctx, ((size_t)s->tab.mask + 1) * sizeof(HashEntry));
-    s->meta = (SampleMeta*)arena_take(ctx, sizeof(SampleMeta));
-    s->seed_slot = (uint32_t*)arena_take(ctx, (size_t)stage0 * 4);
-    s->seed_flags = (uint16_t*)arena_take(ctx, (size_t)stage0 * 2);
-    s->slot_of = (uint32_t*)arena_take(ctx, (size_t)edges * 4);
-    s->nbr = (int32_t*)arena_take(ctx, (size_t)edges * 4);
-    s->flags = (uint16_t*)arena_take(ctx, (size_t)edges * 2);
-    s->fr_ids = (int32_t*)arena_take(ctx, (size_t)frontier * 4);
-    s->fr_lid = (int32_t*)arena_take(ctx, (size_t)frontier * 4);
-    s->fr_seg = (int64_t*)arena_take(ctx, (size_t)frontier * 8);
-    s->partial = (uint32_t*)arena_take(ctx, (size_t)kMaxTiles * 3 * 4);
-    s->edge_room = edges; s->fr_room = frontier;
-    if (!s->tab.entries || !s->meta || !s->seed_slot || !s->seed_flags || !s->slot_of || !s->nbr || !s->flags ||
-        !s->fr_ids || !s->fr_lid || !s->fr_seg || !s->partial)
-        return fail(ctx, QV_ENOMEM, "scratch arena too small (internal sizing error)");
+static qv_status launch_dedup(qv_ctx* ctx, const CallArgs& c, int rowptr_bits, int64_t max_items, int n_batches) {
+    dim3 grid((unsigned)tiles_for(max_items), (unsigned)n_batches);
+    if (rowptr_bits == 32) hipLaunchKernelGGL(k_dedup<int32_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
+    else hipLaunchKernelGGL(k_dedup<int64_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
+    QV_LAUNCH_CHECK(ctx, "k_dedup");
     return QV_OK;
 }
 
-static void tile_shape(int64_t max_items, int* ipt, int* tiles) {
-    int64_t per = (max_items + (int64_t)kScanBlock * kMaxTiles - 1) / ((int64_t)kScanBlock * kMaxTiles);
-    if (per < 1) per = 1;
-    int64_t t = (max_items + kScanBlock * per - 1) / (kScanBlock * per);
-    if (t < 1) t = 1;
-    *ipt = (int)per; *tiles = (int)t;
-}
-
-static qv_status run_stage(qv_ctx* ctx, StageArgs a, int rowptr_bits, int64_t max_items) {
-    int ipt, tiles;
-    tile_shape(max_items, &ipt, &tiles);
-    a.items_per_thread = ipt;
-    if (rowptr_bits == 32) hipLaunchKernelGGL(k_flag<int32_t>, dim3(tiles), dim3(kScanBlock), 0, ctx->stream, a);
-    else hipLaunchKernelGGL(k_flag<int64_t>, dim3(tiles), dim3(kScanBlock), 0, ctx->stream, a);
-    QV_LAUNCH_CHECK(ctx, "k_flag");
-    hipLaunchKernelGGL(k_assign, dim3(tiles), dim3(kScanBlock), 0, ctx->stream, a);
-    QV_LAUNCH_CHECK(ctx, "k_assign");
-    return QV_OK;
-}
-
-template <typename RP>
-static void launch_sample_rp(qv_ctx* ctx, const SampleArgs& a, int64_t max_frontier) {
-    int l = a.fanout;
+static qv_status launch_sample(qv_ctx* ctx, const CallArgs& c, int64_t max_frontier, int n_batches) {
+    const int l = c.fanout;
     if (l > 64) {
-        int blocks = grid_for(max_frontier, 1, ctx->n_cu * 32);
-        hipLaunchKernelGGL(k_sample_wide<RP>, dim3(blocks), dim3(64), 0, ctx->stream, a);
-        return;
+        dim3 grid((unsigned)grid_for(max_frontier, 1, ctx->n_cu * 32), (unsigned)n_batches);
+        hipLaunchKernelGGL(k_sample_wide, grid, dim3(64), 0, ctx->stream, c);
+    } else {
+        const int G = l <= 8 ? 8 : l <= 16 ? 16 : l <= 32 ? 32 : 64;
+        dim3 grid((unsigned)grid_for(max_frontier, 256 / G, ctx->n_cu * 8), (unsigned)n_batches);
+        switch (G) {
+            case 8: hipLaunchKernelGGL(k_sample<8>, grid, dim3(256), 0, ctx->stream, c); break;
+            case 16: hipLaunchKernelGGL(k_sample<16>, grid, dim3(256), 0, ctx->stream, c); break;
+            case 32: hipLaunchKernelGGL(k_sample<32>, grid, dim3(256), 0, ctx->stream, c); break;
+            default: hipLaunchKernelGGL(k_sample<64>, grid, dim3(256), 0, ctx->stream, c); break;
+        }
     }
-    int G = l <= 8 ? 8 : l <= 16 ? 16 : l <= 32 ? 32 : 64;
-    int blocks = grid_for(max_frontier, 256 / G, ctx->n_cu * 16);
-    switch (G) {
-        case 8: hipLaunchKernelGGL((k_sample<8, RP>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        case 16: hipLaunchKernelGGL((k_sample<16, RP>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        case 32: hipLaunchKernelGGL((k_sample<32, RP>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-        default: hipLaunchKernelGGL((k_sample<64, RP>), dim3(blocks), dim3(256), 0, ctx->stream, a); break;
-    }
-}
-
-static qv_status launch_sample(qv_ctx* ctx, const SampleArgs& a, int rowptr_bits, int64_t max_frontier) {
-    if (rowptr_bits == 32) launch_sample_rp<int32_t>(ctx, a, max_frontier);
-    else launch_sample_rp<int64_t>(ctx, a, max_frontier);
     QV_LAUNCH_CHECK(ctx, "k_sample");
     return QV_OK;
 }
 
-static inline uint64_t stage_tag(int stage) { return (uint64_t)(255 - stage) << 48; }   // newer stage = smaller tag
+static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, const int32_t* const* seeds,
+                             const int64_t* n_seeds, const int32_t* fanouts, int n_hops, const uint64_t* rng_seeds,
+                             const qv_sample_out* outs, const char* who) {
+    if (!csr || !outs || !seeds || !n_seeds || !rng_seeds) return fail(ctx, QV_EINVAL, "%s: null argument", who);
+    if (n_batches < 1 || n_batches > kMaxBatch) return fail(ctx, QV_EINVAL, "%s: n_batches %d outside [1, %d]", who, n_batches, kMaxBatch);
+    int64_t max_seeds = 0;
+    for (int i = 0; i < n_batches; ++i) {
+        const qv_sample_out& o = outs[i];
+        if (n_seeds[i] < 0 || (n_seeds[i] > 0 && !seeds[i])) return fail(ctx, QV_EINVAL, "%s: batch %d has no seeds array", who, i);
+        if (!o.n_id || !o.row_local || !o.col_local || !o.node_off || !o.edge_off || !o.frontier_off)
+            return fail(ctx, QV_EINVAL, "%s: n_id, row_local, col_local and the three offset arrays are required", who);
+        if (o.n_id_cap < 0 || o.edge_cap < 0 || (o.frontier && o.frontier_cap < 0)) return fail(ctx, QV_EINVAL, "%s: negative capacity", who);
+        if (n_seeds[i] > max_seeds) max_seeds = n_seeds[i];
+    }
+    Bounds bd;
+    qv_status rc = compute_bounds(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, &bd);
+    if (rc != QV_OK) return rc;
+    Layout L;
+    L.stage0 = max_seeds; L.edges = bd.edges; L.frontier = bd.frontier; L.n_stages = n_hops + 1;
+    L.tile_base[0] = 0;
+    L.tile_base[1] = tiles_for(max_seeds);
+    for (int k = 1; k <= n_hops; ++k) L.tile_base[k + 1] = L.tile_base[k] + tiles_for(bd.hop_edges[k]);
+    rc = arena_begin(ctx, per_batch_bytes(L) * n_batches);
+    if (rc != QV_OK) return rc;
+    CallArgs c{};
+    c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
+    table_geometry(bd.nodes, &c.mask, &c.shift);
+    rc = table_prepare(ctx, n_batches, c.mask);
+    if (rc != QV_OK) return rc;
+    c.epoch = ctx->epoch; c.n_hops = n_hops; c.status = ctx->d_status;
+    c.state_words = (int32_t)(L.tile_base[L.n_stages] * 2); c.n_stages = L.n_stages;
+    for (int i = 0; i < n_batches; ++i) {
+        BatchArgs& b = c.b[i];
+        if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "%s: scratch arena too small (internal sizing error)", who);
+        const qv_sample_out& o = outs[i];
+        b.seeds = seeds[i]; b.n_seeds = n_seeds[i]; b.rng_seed = rng_seeds[i];
+        b.slots = ctx->table_slots + (size_t)i * ((size_t)c.mask + 1);
+        b.lid = ctx->table_lid + (size_t)i * ((size_t)c.mask + 1);
+        if (o.nbr_global) b.nbr = o.nbr_global;
+        b.row_local = o.row_local; b.col_local = o.col_local;
+        b.edge_cap = bd.edges < o.edge_cap ? bd.edges : o.edge_cap;
+        b.n_id = o.n_id; b.n_id_cap = o.n_id_cap;
+        b.fr_user = o.frontier; b.fr_user_cap = o.frontier ? o.frontier_cap : 0;
+        b.node_off_out = o.node_off; b.edge_off_out = o.edge_off; b.frontier_off_out = o.frontier_off;
+        b.n_id_len_out = nullptr; b.frontier_len_out = nullptr;
+    }
+    // stage 0: the seeds
+    c.stage = 0; c.next_fanout = fanouts[0]; c.tile_base = L.tile_base[0];
+    {
+        int64_t work = max_seeds > c.state_words ? max_seeds : c.state_words;
+        dim3 grid((unsigned)grid_for(work, 256, ctx->n_cu * 4), (unsigned)n_batches);
+        hipLaunchKernelGGL(k_insert_ids, grid, dim3(256), 0, ctx->stream, c);
+        QV_LAUNCH_CHECK(ctx, "k_insert_ids");
+    }
+    // edge_off[1] is preset by k_insert_ids for the stand-alone reindex; stage 0 overwrites it here
+    rc = launch_dedup(ctx, c, csr->rowptr_bits, max_seeds, n_batches);
+    if (rc != QV_OK) return rc;
+    for (int k = 1; k <= n_hops; ++k) {
+        c.stage = k; c.hop = k; c.fanout = fanouts[k - 1]; c.next_fanout = k < n_hops ? fanouts[k] : 0;
+        c.tile_base = L.tile_base[k];
+        rc = launch_sample(ctx, c, bd.hop_front[k - 1], n_batches);
+        if (rc != QV_OK) return rc;
+        rc = launch_dedup(ctx, c, csr->rowptr_bits, bd.hop_edges[k], n_batches);
+        if (rc != QV_OK) return rc;
+    }
+    c.stage = n_hops;
+    dim3 grid((unsigned)grid_for(bd.edges, 256 * 4, ctx->n_cu * 4), (unsigned)n_batches);
+    hipLaunchKernelGGL(k_relabel, grid, dim3(256), 0, ctx->stream, c);
+    QV_LAUNCH_CHECK(ctx, "k_relabel");
+    return QV_OK;
+}
 
 }  // namespace qv
 
@@ -685,10 +829,22 @@ extern "C" {
 
 qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_reserve: ctx is NULL");
-    Bounds b;
-    qv_status rc = compute_bounds(ctx, n_seeds, fanouts, n_hops, n_nodes, &b);
+    Bounds bd;
+    qv_status rc = compute_bounds(ctx, n_seeds, fanouts, n_hops, n_nodes, &bd);
     if (rc != QV_OK) return rc;
-    return arena_begin(ctx, scratch_bytes(n_seeds, b.edges, b.frontier, b.nodes));
+    Layout L;
+    L.stage0 = n_seeds; L.edges = bd.edges; L.frontier = bd.frontier; L.n_stages = n_hops + 1;
+    L.tile_base[0] = 0;
+    L.tile_base[1] = tiles_for(n_seeds);
+    for (int k = 1; k <= n_hops; ++k) L.tile_base[k + 1] = L.tile_base[k] + tiles_for(bd.hop_edges[k]);
+    const size_t want = per_batch_bytes(L) * kMaxBatch;
+    if (want > ctx->arena_bytes) {
+        rc = arena_begin(ctx, want);
+        if (rc != QV_OK) return rc;
+    }
+    uint32_t mask; int shift;
+    table_geometry(bd.nodes, &mask, &shift);
+    return table_prepare(ctx, kMaxBatch, mask);
 }
 
 qv_status qv_sample_hop(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier, int64_t n_frontier,
@@ -700,94 +856,55 @@ qv_status qv_sample_hop(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier,
     if (fanout < 1 || fanout > QV_MAX_FANOUT) return fail(ctx, QV_EINVAL, "qv_sample_hop: fanout %d outside [1, %d]", fanout, QV_MAX_FANOUT);
     if (hop < 1) return fail(ctx, QV_EINVAL, "qv_sample_hop: hop is 1-based");
     if (n_frontier * (int64_t)fanout >= ((int64_t)1 << 31)) return fail(ctx, QV_EINVAL, "qv_sample_hop: 2^31 or more edges possible");
-    qv_status rc = arena_begin(ctx, align_up((size_t)kMaxTiles * 4) + 4096);
+    const size_t F = (size_t)n_frontier;
+    qv_status rc = arena_begin(ctx, align_up(sizeof(SampleMeta)) + align_up(kMaxDegTiles * 4) + align_up(F * 8) + 2 * align_up(F * 4) + 4096);
     if (rc != QV_OK) return rc;
-    uint32_t* partial = (uint32_t*)arena_take(ctx, (size_t)kMaxTiles * 4);
-    int ipt, tiles;
-    tile_shape(n_frontier, &ipt, &tiles);
+    SampleMeta* meta = (SampleMeta*)arena_take(ctx, sizeof(SampleMeta));
+    uint32_t* partial = (uint32_t*)arena_take(ctx, kMaxDegTiles * 4);
+    int64_t* fr_rs = (int64_t*)arena_take(ctx, F * 8);
+    uint32_t* fr_deg = (uint32_t*)arena_take(ctx, F * 4);
+    uint32_t* fr_seg = (uint32_t*)arena_take(ctx, F * 4);
+    int64_t per = (n_frontier + (int64_t)kScanBlock * kMaxDegTiles - 1) / ((int64_t)kScanBlock * kMaxDegTiles);
+    if (per < 1) per = 1;
+    int64_t tiles = (n_frontier + kScanBlock * per - 1) / (kScanBlock * per);
+    if (tiles < 1) tiles = 1;
+    const int ipt = (int)per;
     if (csr->rowptr_bits == 32) {
-        hipLaunchKernelGGL(k_deg_partial<int32_t>, dim3(tiles), dim3(kScanBlock), 0, ctx->stream, (const int32_t*)csr->rowptr,
-                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial);
-        hipLaunchKernelGGL(k_deg_scan<int32_t>, dim3(tiles), dim3(kScanBlock), 0, ctx->stream, (const int32_t*)csr->rowptr,
-                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, off_out);
+        hipLaunchKernelGGL(k_deg_partial<int32_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int32_t*)csr->rowptr,
+                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, ctx->d_status);
+        hipLaunchKernelGGL(k_deg_scan<int32_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int32_t*)csr->rowptr,
+                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, off_out, fr_rs, fr_deg, fr_seg, meta);
     } else {
-        hipLaunchKernelGGL(k_deg_partial<int64_t>, dim3(tiles), dim3(kScanBlock), 0, ctx->stream, (const int64_t*)csr->rowptr,
-                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial);
-        hipLaunchKernelGGL(k_deg_scan<int64_t>, dim3(tiles), dim3(kScanBlock), 0, ctx->stream, (const int64_t*)csr->rowptr,
-                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, off_out);
+        hipLaunchKernelGGL(k_deg_partial<int64_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int64_t*)csr->rowptr,
+                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, ctx->d_status);
+        hipLaunchKernelGGL(k_deg_scan<int64_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int64_t*)csr->rowptr,
+                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, off_out, fr_rs, fr_deg, fr_seg, meta);
     }
     QV_LAUNCH_CHECK(ctx, "k_deg_scan");
     if (n_frontier == 0) return QV_OK;
-    SampleArgs a{};
-    a.rowptr = csr->rowptr; a.col = csr->col; a.n_nodes = csr->n_nodes;
-    a.frontier = frontier; a.frontier_lid = nullptr; a.seg_off = off_out; a.fr_range = nullptr;
-    a.n_frontier = n_frontier; a.edge_base = nullptr; a.fanout = fanout; a.hop = hop; a.seed = rng_seed;
-    a.nbr_out = nbr_out; a.row_local = nullptr; a.cap = nbr_cap;
-    a.tab.entries = nullptr; a.tab.mask = 0; a.tab.shift = 0; a.slot_of = nullptr; a.tag = 0; a.status = ctx->d_status;
-    return launch_sample(ctx, a, csr->rowptr_bits, n_frontier);
+    CallArgs c{};
+    c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
+    c.stage = 1; c.hop = hop; c.fanout = fanout; c.status = ctx->d_status;
+    BatchArgs& b = c.b[0];
+    b.rng_seed = rng_seed; b.meta = meta;
+    b.fr_id = const_cast<int32_t*>(frontier); b.fr_lid = const_cast<int32_t*>(frontier);   // local ids unused (row_local == NULL)
+    b.fr_rs = fr_rs; b.fr_deg = fr_deg; b.fr_seg = fr_seg;
+    b.nbr = nbr_out; b.row_local = nullptr; b.slot_of = nullptr; b.edge_cap = nbr_cap;
+    return launch_sample(ctx, c, n_frontier, 1);
 }
 
 qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts,
                     int32_t n_hops, uint64_t rng_seed, const qv_sample_out* out) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_sample: ctx is NULL");
-    if (!csr || !out || (n_seeds > 0 && !seeds)) return fail(ctx, QV_EINVAL, "qv_sample: null argument");
-    if (!out->n_id || !out->row_local || !out->col_local || !out->node_off || !out->edge_off || !out->frontier_off)
-        return fail(ctx, QV_EINVAL, "qv_sample: n_id, row_local, col_local and the three offset arrays are required");
-    if (out->n_id_cap < 0 || out->edge_cap < 0 || (out->frontier && out->frontier_cap < 0))
-        return fail(ctx, QV_EINVAL, "qv_sample: negative capacity");
-    Bounds b;
-    qv_status rc = compute_bounds(ctx, n_seeds, fanouts, n_hops, csr->n_nodes, &b);
-    if (rc != QV_OK) return rc;
-    const int64_t edge_room = b.edges < out->edge_cap ? b.edges : out->edge_cap;
-    Scratch s;
-    rc = take_scratch(ctx, n_seeds, edge_room, b.frontier, b.nodes, &s);
-    if (rc != QV_OK) return rc;
-    int32_t* nbr = out->nbr_global ? out->nbr_global : s.nbr;
+    if (!out) return fail(ctx, QV_EINVAL, "qv_sample: null argument");
+    return sample_many(ctx, csr, 1, &seeds, &n_seeds, fanouts, n_hops, &rng_seed, out, "qv_sample");
+}
 
-    int init_blocks = grid_for((int64_t)s.tab.mask + 1, 256 * 4, ctx->n_cu * 8);
-    hipLaunchKernelGGL(k_init, dim3(init_blocks), dim3(256), 0, ctx->stream, s.tab, s.meta, n_seeds, (int64_t)0);
-    QV_LAUNCH_CHECK(ctx, "k_init");
-    if (n_seeds > 0) {
-        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(n_seeds, 256, ctx->n_cu * 8)), dim3(256), 0, ctx->stream, seeds,
-                           n_seeds, csr->n_nodes, s.tab, stage_tag(0), s.seed_slot, ctx->d_status);
-        QV_LAUNCH_CHECK(ctx, "k_insert_ids");
-    }
-    StageArgs st{};
-    st.rowptr = csr->rowptr; st.n_nodes = csr->n_nodes; st.partial = s.partial; st.meta = s.meta;
-    st.table = s.tab.entries; st.n_id = out->n_id; st.n_id_cap = out->n_id_cap;
-    st.fr_ids = s.fr_ids; st.fr_lid = s.fr_lid; st.fr_seg = s.fr_seg; st.fr_cap = s.fr_room;
-    st.fr_user = out->frontier; st.fr_user_cap = out->frontier ? out->frontier_cap : 0;
-    st.status = ctx->d_status; st.frontier_restart = 0; st.expect_all_first = 0;
-    // stage 0: the seeds
-    st.ids = seeds; st.slot_of = s.seed_slot; st.flags = s.seed_flags; st.stage = 0; st.next_fanout = fanouts[0];
-    st.ids_cap = n_seeds; st.tag = stage_tag(0);
-    rc = run_stage(ctx, st, csr->rowptr_bits, n_seeds);
-    if (rc != QV_OK) return rc;
-    for (int k = 1; k <= n_hops; ++k) {
-        SampleArgs a{};
-        a.rowptr = csr->rowptr; a.col = csr->col; a.n_nodes = csr->n_nodes;
-        a.frontier = s.fr_ids; a.frontier_lid = s.fr_lid; a.seg_off = s.fr_seg;
-        a.fr_range = &s.meta->frontier_off[k - 1]; a.n_frontier = 0; a.edge_base = &s.meta->edge_off[k - 1];
-        a.fanout = fanouts[k - 1]; a.hop = k; a.seed = rng_seed;
-        a.nbr_out = nbr; a.row_local = out->row_local; a.cap = edge_room;
-        a.tab = s.tab; a.slot_of = s.slot_of; a.tag = stage_tag(k); a.status = ctx->d_status;
-        rc = launch_sample(ctx, a, csr->rowptr_bits, b.hop_front[k - 1]);
-        if (rc != QV_OK) return rc;
-        st.ids = nbr; st.slot_of = s.slot_of; st.flags = s.flags; st.stage = k;
-        st.next_fanout = k < n_hops ? fanouts[k] : 0; st.ids_cap = edge_room; st.tag = stage_tag(k);
-        rc = run_stage(ctx, st, csr->rowptr_bits, b.hop_edges[k]);
-        if (rc != QV_OK) return rc;
-    }
-    RelabelArgs r{};
-    r.slot_of = s.slot_of; r.table = s.tab.entries; r.meta = s.meta; r.last_stage = n_hops; r.cap = edge_room;
-    r.col_local = out->col_local; r.node_off = out->node_off; r.edge_off = out->edge_off;
-    r.frontier_off = out->frontier_off; r.n_hops = n_hops; r.n_id_len = nullptr; r.frontier_len = nullptr;
-    hipLaunchKernelGGL(k_relabel, dim3(grid_for(b.edges, 256 * 4, ctx->n_cu * 8)), dim3(256), 0, ctx->stream, r);
-    QV_LAUNCH_CHECK(ctx, "k_relabel");
-    if (b.edges > out->edge_cap) {
-        // the device flags an overflow only if it happens; nothing to do here
-    }
-    return QV_OK;
+qv_status qv_sample_many(qv_ctx* ctx, const qv_csr* csr, int32_t n_batches, const int32_t* const* seeds,
+                         const int64_t* n_seeds, const int32_t* fanouts, int32_t n_hops, const uint64_t* rng_seeds,
+                         const qv_sample_out* outs) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_sample_many: ctx is NULL");
+    return sample_many(ctx, csr, n_batches, seeds, n_seeds, fanouts, n_hops, rng_seeds, outs, "qv_sample_many");
 }
 
 qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const int32_t* nbr, int64_t n_nbr,
@@ -798,42 +915,48 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
         !n_id_out || !n_id_len || (frontier_out && !frontier_len))
         return fail(ctx, QV_EINVAL, "qv_reindex: null or negative argument");
     if (n_known >= ((int64_t)1 << 31) || n_nbr >= ((int64_t)1 << 31)) return fail(ctx, QV_EINVAL, "qv_reindex: too many ids");
-    if (n_nodes <= 0) n_nodes = -1;                     // unchecked
-    Scratch s;
-    int64_t keys = n_known + n_nbr;
-    qv_status rc = take_scratch(ctx, n_known, n_nbr, n_known + n_nbr, keys, &s);
+    Layout L;
+    L.stage0 = n_known; L.edges = n_nbr; L.frontier = 1; L.n_stages = 2;
+    L.tile_base[0] = 0; L.tile_base[1] = tiles_for(n_known); L.tile_base[2] = L.tile_base[1] + tiles_for(n_nbr);
+    qv_status rc = arena_begin(ctx, per_batch_bytes(L));
     if (rc != QV_OK) return rc;
-    int init_blocks = grid_for((int64_t)s.tab.mask + 1, 256 * 4, ctx->n_cu * 8);
-    hipLaunchKernelGGL(k_init, dim3(init_blocks), dim3(256), 0, ctx->stream, s.tab, s.meta, n_known, n_nbr);
-    QV_LAUNCH_CHECK(ctx, "k_init");
-    StageArgs st{};
-    st.rowptr = nullptr; st.n_nodes = n_nodes; st.partial = s.partial; st.meta = s.meta; st.table = s.tab.entries;
-    st.n_id = n_id_out; st.n_id_cap = n_id_cap;
-    st.fr_ids = s.fr_ids; st.fr_lid = s.fr_lid; st.fr_seg = s.fr_seg; st.fr_cap = s.fr_room;
-    st.status = ctx->d_status; st.next_fanout = 0;
-    if (n_known > 0) {
-        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(n_known, 256, ctx->n_cu * 8)), dim3(256), 0, ctx->stream, known,
-                           n_known, n_nodes, s.tab, stage_tag(0), s.seed_slot, ctx->d_status);
+    CallArgs c{};
+    c.rowptr = nullptr; c.col = nullptr; c.n_nodes = n_nodes > 0 ? n_nodes : -1;
+    table_geometry(n_known + n_nbr, &c.mask, &c.shift);
+    rc = table_prepare(ctx, 1, c.mask);
+    if (rc != QV_OK) return rc;
+    c.epoch = ctx->epoch; c.n_hops = 1; c.status = ctx->d_status;
+    c.state_words = (int32_t)(L.tile_base[2] * 2); c.n_stages = 2;
+    BatchArgs& b = c.b[0];
+    if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "qv_reindex: scratch arena too small (internal sizing error)");
+    b.seeds = known; b.n_seeds = n_known; b.rng_seed = 0;
+    b.slots = ctx->table_slots; b.lid = ctx->table_lid;
+    b.nbr = const_cast<int32_t*>(nbr);                   // read only on this path
+    b.row_local = nullptr; b.col_local = local_out; b.edge_cap = n_nbr;
+    b.n_id = n_id_out; b.n_id_cap = n_id_cap;
+    b.fr_user = nullptr; b.fr_user_cap = 0;
+    b.node_off_out = nullptr; b.edge_off_out = nullptr; b.frontier_off_out = nullptr;
+    b.n_id_len_out = n_id_len; b.frontier_len_out = frontier_len;
+    // stage 0: the known ids
+    c.stage = 0; c.next_fanout = 0; c.tile_base = 0; c.frontier_restart = 0; c.expect_all_first = 1;
+    {
+        int64_t work = n_known > c.state_words ? n_known : c.state_words;
+        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(work, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);
         QV_LAUNCH_CHECK(ctx, "k_insert_ids");
     }
-    st.ids = known; st.slot_of = s.seed_slot; st.flags = s.seed_flags; st.stage = 0; st.ids_cap = n_known;
-    st.tag = stage_tag(0); st.fr_user = nullptr; st.fr_user_cap = 0; st.frontier_restart = 0; st.expect_all_first = 1;
-    rc = run_stage(ctx, st, 32, n_known);
+    rc = launch_dedup(ctx, c, 32, n_known, 1);
     if (rc != QV_OK) return rc;
+    // stage 1: the neighbour ids
+    c.stage = 1; c.tile_base = L.tile_base[1]; c.frontier_restart = 1; c.expect_all_first = 0;
+    c.state_words = 0; c.n_stages = 0;
+    b.fr_user = frontier_out; b.fr_user_cap = frontier_out ? n_nbr : 0;
     if (n_nbr > 0) {
-        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(n_nbr, 256, ctx->n_cu * 8)), dim3(256), 0, ctx->stream, nbr, n_nbr,
-                           n_nodes, s.tab, stage_tag(1), s.slot_of, ctx->d_status);
+        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(n_nbr, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);
         QV_LAUNCH_CHECK(ctx, "k_insert_ids");
     }
-    st.ids = nbr; st.slot_of = s.slot_of; st.flags = s.flags; st.stage = 1; st.ids_cap = n_nbr; st.tag = stage_tag(1);
-    st.fr_user = frontier_out; st.fr_user_cap = n_nbr; st.frontier_restart = 1; st.expect_all_first = 0;
-    rc = run_stage(ctx, st, 32, n_nbr);
+    rc = launch_dedup(ctx, c, 32, n_nbr, 1);
     if (rc != QV_OK) return rc;
-    RelabelArgs r{};
-    r.slot_of = s.slot_of; r.table = s.tab.entries; r.meta = s.meta; r.last_stage = 1; r.cap = n_nbr;
-    r.col_local = local_out; r.node_off = nullptr; r.edge_off = nullptr; r.frontier_off = nullptr; r.n_hops = 0;
-    r.n_id_len = n_id_len; r.frontier_len = frontier_len;
-    hipLaunchKernelGGL(k_relabel, dim3(grid_for(n_nbr, 256 * 4, ctx->n_cu * 8)), dim3(256), 0, ctx->stream, r);
+    hipLaunchKernelGGL(k_relabel, dim3(grid_for(n_nbr, 256 * 4, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);
     QV_LAUNCH_CHECK(ctx, "k_relabel");
     return QV_OK;
 }

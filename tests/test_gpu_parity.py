@@ -146,6 +146,50 @@ def test_sample_int64_rowptr_and_in_degree_skew(qv, ctx):
         assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, w.fanouts, w.rng_seed(b)))
 
 
+@pytest.mark.parametrize("n_batches", [1, 3, 8])
+def test_sample_many_and_gather_many(qv, ctx, tiny, n_batches):
+    w, rowptr, col, g = tiny
+    sizes = [64, 1, 500, 0, 2000, 64, 7, 300][:n_batches]
+    fanouts = [15, 10, 5]
+    seeds = [w.seeds(200 + i, n) if n else np.zeros(0, np.int32) for i, n in enumerate(sizes)]
+    rngs = [w.rng_seed(200 + i) for i in range(n_batches)]
+    d_seeds = [dev(s) if len(s) else torch.zeros(0, dtype=torch.int32, device="cuda") for s in seeds]
+    outs = qv.qv_sample_many(ctx, g, d_seeds, fanouts, rngs)
+    table = qvgen.features_host(w.seed, w.n, w.dim, w.feat_dtype)
+    feat = qv.Features(ctx, torch.from_numpy(table).cuda())
+    rows = qv.qv_gather_many(ctx, feat, [o.n_id for o in outs], [o.node_off[-1:] for o in outs])
+    ctx.sync()
+    for i in range(n_batches):
+        want = oracle.sample(rowptr, col, seeds[i], fanouts, rngs[i])
+        assert_sample_equal(outs[i].to_host(), want)
+        U = len(want["n_id"])
+        assert rows[i][:U].cpu().numpy().tobytes() == oracle.gather(table, want["n_id"]).tobytes()
+    feat.close()
+
+
+def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
+    # the dedup tables are not cleared between calls; results must not depend on what earlier
+    # calls (of other sizes, other batch counts) left behind, nor on the counter wrapping
+    w, rowptr, col, g0 = tiny
+    c = qv.Context(0)
+    g = make_graph(qv, c, rowptr, col)
+    plan = [(64, [10, 5]), (2000, [15, 10, 5]), (3, [3]), (700, [25, 10]), (64, [10, 5])]
+    for rnd in range(3):
+        if rnd == 2:
+            c.check(qv.lib().qv_ctx_set_epoch(c.h, 0xFFFFE - 3))       # cross the wrap point
+        for i, (n, fan) in enumerate(plan * 2):
+            seeds = w.seeds(300 + i, n)
+            out = qv.qv_sample(c, g, dev(seeds), fan, 1000 + i)
+            c.sync()
+            assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, fan, 1000 + i))
+        many = [w.seeds(400 + j, 100 + 50 * j) for j in range(4)]
+        outs = qv.qv_sample_many(c, g, [dev(s) for s in many], [10, 5], [7, 8, 9, 10])
+        c.sync()
+        for j in range(4):
+            assert_sample_equal(outs[j].to_host(), oracle.sample(rowptr, col, many[j], [10, 5], 7 + j))
+    c.close()
+
+
 def test_sample_degenerate_inputs(qv, ctx):
     rowptr = np.array([0, 0, 2, 2], dtype=np.int64)
     col = np.array([0, 2], dtype=np.int32)
