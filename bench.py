@@ -40,6 +40,10 @@ def main():
     ap.add_argument("--workload", default="citation")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--streams", type=int, default=1, help="batches in flight (one context per stream)")
+    ap.add_argument("--batches-per-call", type=int, default=1,
+                    help="independent batches per qv_sample_many / qv_gather_many call (1..8)")
+    ap.add_argument("--table-budget-gib", type=float, default=-1.0,
+                    help="dedup table budget per context in GiB (0 = always hash; default: the library's)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-metrics", action="store_true", help="skip the PSGS / FAP whole-graph passes")
@@ -126,6 +130,8 @@ def main():
         feat = qv.Features(ctx0, table)
 
     # ---- batches, contexts, buffers -------------------------------------------------------------
+    import copy
+    B = max(1, min(args.batches_per_call, qv.QV_MAX_BATCHES))
     n_batches = K + W
     seeds_host = [w.seeds(b, batch) for b in range(n_batches)]
     seeds_dev = [torch.from_numpy(s).cuda() for s in seeds_host]
@@ -134,32 +140,54 @@ def main():
     nb, eb, fb = qv.qv_sample_bounds(batch, w.fanouts, w.n)
     bufs, rows = [], []
     for c in ctxs:
+        if args.table_budget_gib >= 0:
+            c.set_table_budget(int(args.table_budget_gib * 2 ** 30))
         c.reserve(batch, w.fanouts, w.n)
-        bufs.append(qv.SampleBuffers(c, batch, w.fanouts, w.n))
-        rows.append(torch.empty((nb, w.dim), dtype=tdtype, device="cuda"))
+        bufs.append([qv.SampleBuffers(c, batch, w.fanouts, w.n) for _ in range(B)])
+        rows.append([torch.empty((nb, w.dim), dtype=tdtype, device="cuda") for _ in range(B)])
     Kh = len(w.fanouts)
     # per-step size blocks so that counts can be read after the timed region
     offs = [(torch.zeros(Kh + 2, dtype=torch.int64, device="cuda"), torch.zeros(Kh + 1, dtype=torch.int64, device="cuda"),
              torch.zeros(Kh + 2, dtype=torch.int64, device="cuda")) for _ in range(n_batches)]
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(n_batches)]
 
-    def step(i):
-        c, b = ctxs[i % S], bufs[i % S]
-        b.node_off, b.edge_off, b.frontier_off = offs[i]
-        ev[i][0].record(c.stream)
-        qv.qv_sample(c, g, seeds_dev[i], w.fanouts, rng_seeds[i], out=b)
-        ev[i][1].record(c.stream)
-        qv.qv_gather(c, feat, b.n_id, n_ids_dev=b.node_off[Kh + 1:], out=rows[i % S], n_ids=nb)
-        ev[i][2].record(c.stream)
+    # calls: (first batch, count); warm-up and timed batches are never mixed in one call
+    def split(lo, hi):
+        return [(i, min(B, hi - i)) for i in range(lo, hi, B)]
+    calls = split(0, W) + split(W, W + K)
+    n_warm_calls = len(split(0, W))
+    plans, ev = [], []
+    for j, (first, cnt) in enumerate(calls):
+        c = ctxs[j % S]
+        views = []
+        for t in range(cnt):
+            v = copy.copy(bufs[j % S][t])
+            v.node_off, v.edge_off, v.frontier_off = offs[first + t]
+            views.append(v)
+        plans.append(qv.ManyPlan(c, g, feat, views, rows[j % S][:cnt], w.fanouts))
+        ev.append([torch.cuda.Event(enable_timing=True) for _ in range(3)])
+    L = qv.lib()
 
-    for i in range(W):
-        step(i)
+    def call(j):
+        first, cnt = calls[j]
+        p, c = plans[j], ctxs[j % S]
+        for t in range(cnt):
+            p.seed_ptrs[t] = seeds_dev[first + t].data_ptr()
+            p.n_seeds[t] = batch
+            p.rng[t] = rng_seeds[first + t]
+        ev[j][0].record(c.stream)
+        c.check(L.qv_sample_many(c.h, g.h, cnt, p.seed_ptrs, p.n_seeds, p.fan, p.k, p.rng, p.outs))
+        ev[j][1].record(c.stream)
+        c.check(L.qv_gather_many(c.h, feat.h, cnt, p.ids, p.n_ids, p.n_dev, p.out_ptrs, p.stride))
+        ev[j][2].record(c.stream)
+
+    for j in range(n_warm_calls):
+        call(j)
     torch.cuda.synchronize()
     for c in ctxs:
         c.sync()
     t_start = time.perf_counter()
-    for i in range(W, W + K):
-        step(i)
+    for j in range(n_warm_calls, len(calls)):
+        call(j)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
     for c in ctxs:
@@ -168,7 +196,6 @@ def main():
     # ---- accounting -------------------------------------------------------------------------
     tot_edges = tot_unique = tot_front = 0
     samp_b = reidx_b = gath_b = 0
-    gather_ms, sample_ms, batch_ms = [], [], []
     for i in range(W, W + K):
         no, eo, fo = (t.cpu().numpy() for t in offs[i])
         U, E, F = int(no[-1]), int(eo[-1]), int(fo[Kh])        # frontier entries expanded = F_0..F_{K-1}
@@ -179,12 +206,14 @@ def main():
         samp_b += sb
         reidx_b += rb
         gath_b += gb
-        sample_ms.append(ev[i][0].elapsed_time(ev[i][1]))
-        gather_ms.append(ev[i][1].elapsed_time(ev[i][2]))
-        batch_ms.append(ev[i][0].elapsed_time(ev[i][2]))
+    timed = range(n_warm_calls, len(calls))
+    sample_ms = [ev[j][0].elapsed_time(ev[j][1]) for j in timed]
+    gather_ms = [ev[j][1].elapsed_time(ev[j][2]) for j in timed]
+    batch_ms = [ev[j][0].elapsed_time(ev[j][2]) for j in timed]
+    n_launch = len(timed)
     ms_per_step = elapsed * 1e3 / K
     gather_avg_ms = float(np.mean(gather_ms))
-    gather_bytes_per_launch = gath_b / K
+    gather_bytes_per_launch = gath_b / n_launch
     achieved = gather_bytes_per_launch / (gather_avg_ms * 1e-3) / 1e9
     path_bytes = samp_b + reidx_b + gath_b
 
@@ -200,15 +229,15 @@ def main():
         "config": {"workload": "%s: %d nodes, %d edges, %s x %d features, fanouts %s, batch %d%s" %
                    (w.name, w.n, n_edges_graph, "fp16" if tdtype == torch.float16 else "fp32", w.dim, w.fanouts,
                     batch, ", %d rows in HBM / rest host-pinned" % feat.n_hot if tiered else ", features all in HBM"),
-                   "streams": S, "scale": args.scale},
+                   "streams": S, "batches_per_call": B, "scale": args.scale},
         "sampled_edges_per_batch": round(tot_edges / K, 1),
         "unique_nodes_per_batch": round(tot_unique / K, 1),
         "gathered_feature_GBps": round(tot_unique * w.row_bytes / (sum(gather_ms) * 1e-3) / 1e9, 2),
         "gather_frac_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
         "path_algorithmic_GBps": round(path_bytes / elapsed / 1e9, 2),
         "path_frac_hbm_peak": round(path_bytes / elapsed / 1e9 / HBM_PEAK_GBPS, 4),
-        "p50_batch_latency_ms": round(float(np.percentile(batch_ms, 50)), 4),
-        "p99_batch_latency_ms": round(float(np.percentile(batch_ms, 99)), 4),
+        "p50_call_latency_ms": round(float(np.percentile(batch_ms, 50)), 4),
+        "p99_call_latency_ms": round(float(np.percentile(batch_ms, 99)), 4),
         "sample_ms_avg": round(float(np.mean(sample_ms)), 4),
         "gather_ms_avg": round(gather_avg_ms, 4),
         "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,

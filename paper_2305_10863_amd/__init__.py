@@ -17,7 +17,7 @@ QV_OK, QV_EINVAL, QV_ENOMEM, QV_EHIP, QV_ECAPACITY, QV_ERANGE = 0, -1, -2, -3, -
 QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 8
 
 EXPORTS = [
-    "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch",
+    "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget",
     "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_sample_hop", "qv_sample", "qv_sample_many",
     "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc",
     "qv_gather", "qv_gather_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
@@ -55,6 +55,7 @@ def lib():
         L.qv_ctx_sync.argtypes = [vp]
         L.qv_ctx_reserve.argtypes = [vp, i64, C.POINTER(i32), i32, i64]
         L.qv_ctx_set_epoch.argtypes = [vp, C.c_uint32]
+        L.qv_ctx_set_table_budget.argtypes = [vp, i64]
         L.qv_sample_bounds.argtypes = [i64, C.POINTER(i32), i32, i64, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
         L.qv_csr_create.argtypes = [vp, i64, i64, vp, i32, vp, i32, C.POINTER(vp)]
         L.qv_csr_destroy.argtypes = [vp]
@@ -115,6 +116,10 @@ class Context:
     def sync(self):
         """Wait for the stream and raise on a deferred device-side error."""
         self.check(lib().qv_ctx_sync(self.h))
+
+    def set_table_budget(self, n_bytes):
+        """0 forces the hashed dedup table; see qv_ctx_set_table_budget."""
+        self.check(lib().qv_ctx_set_table_budget(self.h, n_bytes))
 
     def reserve(self, n_seeds, fanouts, n_nodes):
         arr, k = _fan(fanouts)

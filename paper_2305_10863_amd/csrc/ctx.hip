@@ -97,7 +97,8 @@ void qv_ctx_destroy(qv_ctx* ctx) {
     if (!ctx) return;
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->arena) (void)hipFree(ctx->arena);
-    if (ctx->table_slots) (void)hipFree(ctx->table_slots);
+    if (ctx->table_keyw) (void)hipFree(ctx->table_keyw);
+    if (ctx->table_minpos) (void)hipFree(ctx->table_minpos);
     if (ctx->table_lid) (void)hipFree(ctx->table_lid);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
@@ -123,6 +124,13 @@ qv_status qv_ctx_set_epoch(qv_ctx* ctx, uint32_t epoch) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_set_epoch: ctx is NULL");
     if (epoch < ctx->epoch) return fail(ctx, QV_EINVAL, "qv_ctx_set_epoch: the epoch counter only moves forward");
     ctx->epoch = epoch > kEpochLimit ? kEpochLimit : epoch;
+    return QV_OK;
+}
+
+qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_set_table_budget: ctx is NULL");
+    if (bytes < 0) return fail(ctx, QV_EINVAL, "qv_ctx_set_table_budget: negative budget");
+    ctx->direct_budget_bytes = bytes;
     return QV_OK;
 }
 

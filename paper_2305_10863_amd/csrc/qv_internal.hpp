@@ -20,25 +20,18 @@ constexpr int kStatRange = 1;
 constexpr int kStatCapacity = 2;
 constexpr int kStatInval = 4;
 
-// Open-addressing table keyed by global node id.  One 16-byte slot per key plus a separate
-// array of local ids (the relabel pass touches only the latter).
-//   keyw   = epoch << 32 | key.  A slot whose epoch differs from the call's epoch is free, so the
-//            table is never cleared between calls.
-//   minpos = smallest tagged position at which the key occurred in the newest stage of the
-//            newest call: tag = (~epoch & 0xFFFFF) << 44 | (15 - stage) << 40 | position, so a
-//            newer call or stage always wins an atomicMin and stale values need no reset.
-struct alignas(16) TableSlot {
-    uint64_t keyw;
-    uint64_t minpos;
-};
+// Dedup table keyed by global node id, structure of arrays, in one of two forms:
+//   direct  slot == node id (arrays of n_nodes entries): no probing, one atomic per sampled edge.
+//           Used when n_nodes x 12 bytes x batches fits the context's table budget.
+//   hashed  open addressing with linear probing over a power-of-two number of slots; keyw[slot]
+//           = epoch << 32 | key, and a slot whose epoch differs from the call's is free.
+// Common to both:
+//   minpos[slot] = smallest tagged position at which the key occurred in the newest stage of the
+//           newest call: tag = (~epoch & 0xFFFFF) << 44 | (15 - stage) << 40 | position, so a newer
+//           call or stage always wins an atomicMin and stale values never need a reset.
+//   lid[slot]    = local id, -1 until assigned; reset by whoever first touches the key in a call.
+// Nothing is cleared between calls; only when the epoch counter is exhausted.
 constexpr uint32_t kEpochLimit = 0xFFFFEu;          // epochs 1 .. kEpochLimit, then a full clear
-
-struct TableRef {
-    TableSlot* slots;
-    int32_t* lid;
-    uint32_t mask;
-    int32_t shift;
-};
 
 // Sizes that only the device knows while a qv_sample call is in flight.
 struct SampleMeta {
@@ -57,9 +50,12 @@ struct qv_ctx {
     size_t arena_bytes = 0;
     size_t arena_used = 0;             // bump pointer within one API call
     // hash tables live apart from the arena: their contents carry over between calls
-    qv::TableSlot* table_slots = nullptr;
+    uint64_t* table_keyw = nullptr;    // hashed form only
+    uint64_t* table_minpos = nullptr;
     int32_t* table_lid = nullptr;
-    size_t table_entries = 0;          // total slots allocated (all batches of a call together)
+    size_t table_entries = 0;          // slots allocated in minpos / lid (all batches of a call together)
+    size_t table_keyw_entries = 0;     // slots allocated in keyw
+    int64_t direct_budget_bytes = (int64_t)12 << 30;
     uint32_t epoch = 0;
     int32_t* d_status = nullptr;       // device status word
     int32_t* h_status = nullptr;       // pinned mirror

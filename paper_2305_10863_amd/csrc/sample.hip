@@ -4,12 +4,17 @@
 //
 // Launches of one qv_sample / qv_sample_many call (no host synchronisation anywhere; every
 // kernel takes up to QV_MAX_BATCHES independent batches along blockIdx.y):
-//   k_insert_ids  seeds -> table (stage 0); also clears the call's scan state
-//   k_dedup       stage 0: first occurrences -> F_0, n_id, local ids, row extents and segment
-//                 offsets of hop 1 (single pass: tile scan with decoupled look-back)
-//   per hop k:    k_sample (pick neighbours, write the hop's edges, insert into the table)
-//                 k_dedup  -> F_k, n_id growth, local ids, row extents / offsets of hop k+1
+//   k_insert_ids  seeds -> table (stage 0); also initialises the device-side size block
+//   k_flag        stage 0: which positions are first occurrences / new nodes, per-tile counts
+//   k_assign      stage 0: scan of the counts -> F_0, n_id, local ids, row extents and segment
+//                 offsets of hop 1
+//   per hop k:    k_sample (pick neighbours, write the hop's edges, register them in the table)
+//                 k_flag / k_assign -> F_k, n_id growth, local ids, extents / offsets of hop k+1
 //   k_relabel     col_local of every edge, export of the sizes
+// A single-pass variant of k_flag + k_assign (tile scan with decoupled look-back) was measured
+// and dropped: agent-scope atomics across the eight XCDs cost 1.5-2 us per dependent step, so
+// the ticket + publish + look-back chain was slower (12-17 us per stage) than two short kernels
+// (4-5 us each).
 #include "qv_internal.hpp"
 #include <new>
 
@@ -78,24 +83,28 @@ __device__ __forceinline__ uint32_t floyd_resolve(uint32_t t, bool active, bool 
 // hash table
 // ---------------------------------------------------------------------------------------------
 struct TableView {
-    TableSlot* slots;
+    uint64_t* keyw;                 // hashed form only
+    uint64_t* minpos;
     int32_t* lid;
     uint32_t mask;
     int32_t shift;
     uint32_t epoch;
+    int32_t direct;
 };
 
 __device__ __forceinline__ uint64_t pos_tag(uint32_t epoch, int stage) {
     return ((uint64_t)((~epoch) & 0xFFFFFu) << 44) | ((uint64_t)(15 - stage) << 40);
 }
 
-// Returns the slot of `key`, inserting it if absent; 0xFFFFFFFF if the table is full.
-// A slot is free when its epoch is not the call's epoch; whoever claims it resets its local id.
+// Hashed form: returns the slot of `key`, inserting it if absent; 0xFFFFFFFF if the table is
+// full.  A slot is free when its epoch is not the call's epoch; whoever claims it resets its
+// local id.  The first look at a slot is an ordinary load: a stale value can only make the
+// compare-and-swap fail, and that returns the current value.
 __device__ __forceinline__ uint32_t table_insert(const TableView& t, uint32_t key) {
     const uint64_t mine = ((uint64_t)t.epoch << 32) | key;
     uint32_t h = ((key * 0x9E3779B1u) >> t.shift) & t.mask;
     for (uint32_t probes = 0; probes <= t.mask; ++probes) {
-        unsigned long long* kw = reinterpret_cast<unsigned long long*>(&t.slots[h].keyw);
+        unsigned long long* kw = reinterpret_cast<unsigned long long*>(&t.keyw[h]);
         uint64_t cur = __hip_atomic_load(kw, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         for (;;) {
             if (cur == mine) return h;
@@ -109,18 +118,27 @@ __device__ __forceinline__ uint32_t table_insert(const TableView& t, uint32_t ke
     return 0xFFFFFFFFu;
 }
 
-__device__ __forceinline__ void table_note_position(const TableView& t, uint32_t slot, uint64_t tagged_pos) {
-    atomicMin(reinterpret_cast<unsigned long long*>(&t.slots[slot].minpos), (unsigned long long)tagged_pos);
+// Register that `key` occurs at tagged position `tp`; returns the key's slot (0xFFFFFFFF: table
+// full).  Direct form: the slot is the key itself and this is the only atomic; the returned old
+// value tells whether this is the key's first touch in this call, in which case its local id is
+// reset here.
+__device__ __forceinline__ uint32_t table_touch(const TableView& t, uint32_t key, uint64_t tp) {
+    if (t.direct) {
+        const uint64_t old = atomicMin(reinterpret_cast<unsigned long long*>(&t.minpos[key]), (unsigned long long)tp);
+        if ((old >> 44) != (tp >> 44)) t.lid[key] = -1;
+        return key;
+    }
+    const uint32_t slot = table_insert(t, key);
+    if (slot != 0xFFFFFFFFu) atomicMin(reinterpret_cast<unsigned long long*>(&t.minpos[slot]), (unsigned long long)tp);
+    return slot;
 }
 
 // full clear: after (re)allocation and when the epoch counter wraps
-__global__ void k_table_clear(TableSlot* slots, int32_t* lid, int64_t n) {
+__global__ void k_table_clear(uint64_t* keyw, int64_t n_keyw, uint64_t* minpos, int32_t* lid, int64_t n) {
     int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    uint4 z;
-    z.x = 0u; z.y = 0u; z.z = 0xFFFFFFFFu; z.w = 0xFFFFFFFFu;       // epoch 0 = never used; minpos = max
-    uint4* e = reinterpret_cast<uint4*>(slots);
-    for (int64_t i = tid; i < n; i += stride) { e[i] = z; lid[i] = -1; }
+    for (int64_t i = tid; i < n_keyw; i += stride) keyw[i] = 0ull;            // epoch 0 = never used
+    for (int64_t i = tid; i < n; i += stride) { minpos[i] = ~0ull; lid[i] = -1; }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -130,7 +148,7 @@ struct BatchArgs {
     const int32_t* seeds;           // stage-0 ids
     int64_t n_seeds;
     uint64_t rng_seed;
-    TableSlot* slots; int32_t* lid; // this batch's table region
+    uint64_t* keyw; uint64_t* minpos; int32_t* lid;    // this batch's table region (minpos == NULL: no dedup)
     SampleMeta* meta;
     uint32_t* seed_slot;            // table slot of each stage-0 id
     uint32_t* slot_of;              // table slot of each edge's neighbour
@@ -141,8 +159,9 @@ struct BatchArgs {
     // working frontier F_0 | F_1 | .. (scratch, structure of arrays)
     int32_t* fr_id; int32_t* fr_lid; int64_t* fr_rs; uint32_t* fr_deg; uint32_t* fr_seg; int64_t fr_cap;
     int32_t* fr_user; int64_t fr_user_cap;
-    uint64_t* tile_state;           // look-back state, two words per tile, all stages back to back
-    uint32_t* tickets;              // one per stage
+    uint16_t* seed_flags;           // stage-0 flags
+    uint16_t* flags;                // per edge: first occurrence | new node << 1 | next-hop segment size << 2
+    uint32_t* partial;              // [kMaxTiles][3] per-tile counts of the stage being run
     int64_t* node_off_out; int64_t* edge_off_out; int64_t* frontier_off_out;
     int64_t* n_id_len_out; int64_t* frontier_len_out;      // stand-alone reindex
 };
@@ -151,24 +170,22 @@ struct CallArgs {
     // graph
     const void* rowptr; const int32_t* col; int64_t n_nodes;
     // table geometry (same for every batch of the call)
-    uint32_t mask; int32_t shift; uint32_t epoch;
+    uint32_t mask; int32_t shift; uint32_t epoch; int32_t direct;
     // stage being run
     int32_t stage;                  // 0 = seeds / known ids, k >= 1 = hop k
     int32_t hop;                    // k_sample: hop number fed to the random stream (== stage in qv_sample)
     int32_t fanout;                 // k_sample: this hop's fanout
     int32_t next_fanout;            // k_dedup: fanout of the following hop, 0 = none
     int32_t n_hops;
-    int64_t tile_base;              // first tile-state index of this stage
+    int32_t items_per_thread;       // k_flag / k_assign: tile = kScanBlock * items_per_thread positions
     int32_t frontier_restart;       // stand-alone reindex: number this stage's frontier from 0
     int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
-    int32_t state_words;            // k_insert_ids of stage 0: tile-state words to clear per batch
-    int32_t n_stages;               //   ... and tickets to clear
     int32_t* status;
     BatchArgs b[kMaxBatch];
 };
 
 __device__ __forceinline__ TableView table_of(const CallArgs& c, const BatchArgs& b) {
-    return TableView{b.slots, b.lid, c.mask, c.shift, c.epoch};
+    return TableView{b.keyw, b.minpos, b.lid, c.mask, c.shift, c.epoch, c.direct};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -184,8 +201,6 @@ __global__ void __launch_bounds__(256) k_insert_ids(CallArgs c) {
     int64_t n;
     if (c.stage == 0) {
         ids = b.seeds; slot_of = b.seed_slot; n = b.n_seeds;
-        for (int64_t i = tid; i < c.state_words; i += stride) b.tile_state[i] = 0ull;
-        if (tid < c.n_stages) b.tickets[tid] = 0u;
         if (tid == 0) {
             SampleMeta* m = b.meta;
             for (int i = 0; i < QV_MAX_HOPS + 2; ++i) { m->node_off[i] = 0; m->frontier_off[i] = 0; }
@@ -205,11 +220,10 @@ __global__ void __launch_bounds__(256) k_insert_ids(CallArgs c) {
         if (id < 0 || (c.n_nodes >= 0 && (int64_t)id >= c.n_nodes)) {
             atomicOr(c.status, kStatRange);
         } else {
-            slot = table_insert(t, (uint32_t)id);
+            slot = table_touch(t, (uint32_t)id, tag | (uint64_t)i);
             if (slot == 0xFFFFFFFFu) atomicOr(c.status, kStatCapacity);
-            else table_note_position(t, slot, tag | (uint64_t)i);
         }
-        slot_of[i] = slot;
+        if (!c.direct) slot_of[i] = slot;
     }
 }
 
@@ -221,16 +235,15 @@ __device__ __forceinline__ void emit_edge(const CallArgs& c, const BatchArgs& b,
     if (p < b.edge_cap) {
         b.nbr[p] = g;
         if (b.row_local) b.row_local[p] = vl;
-        if (b.slot_of) {
+        if (b.minpos) {
             uint32_t slot = 0xFFFFFFFFu;
             if (g < 0 || (int64_t)g >= c.n_nodes) {
                 atomicOr(c.status, kStatRange);
             } else {
-                slot = table_insert(t, (uint32_t)g);
+                slot = table_touch(t, (uint32_t)g, tag | (uint64_t)p);
                 if (slot == 0xFFFFFFFFu) atomicOr(c.status, kStatCapacity);
-                else table_note_position(t, slot, tag | (uint64_t)p);
             }
-            b.slot_of[p] = slot;
+            if (!c.direct) b.slot_of[p] = slot;
         }
     } else {
         atomicOr(c.status, kStatCapacity);
@@ -356,176 +369,154 @@ __device__ __forceinline__ Tri block_scan3(Tri v, Tri& total, uint32_t (*lds)[3]
 }
 
 // ---------------------------------------------------------------------------------------------
-// Decoupled look-back over tiles.  Each tile publishes the sum over its own items, then walks
-// back over its predecessors until it meets one whose inclusive prefix is known.  Tiles are
-// numbered by a ticket taken when the block starts, so every predecessor of a tile is already
-// running: the wait always ends, whatever the order in which the hardware starts blocks.
-// Two independent 62-bit payloads per tile: word 0 = (first occurrences << 31 | new nodes),
-// word 1 = next-hop segment sizes.  Top two bits: 0 not ready, 1 tile sum, 2 inclusive prefix.
-// ---------------------------------------------------------------------------------------------
-constexpr uint64_t kStMask = 3ull << 62, kStSum = 1ull << 62, kStIncl = 2ull << 62;
-
-__device__ __forceinline__ uint64_t wave_sum64(uint64_t v) {
-#pragma unroll
-    for (int o = kWave / 2; o >= 1; o >>= 1) {
-        uint32_t lo = __shfl_xor((uint32_t)v, o), hi = __shfl_xor((uint32_t)(v >> 32), o);
-        v += ((uint64_t)hi << 32) | lo;
-    }
-    return v;
-}
-
-// Called by the 64 lanes of wave 0.  Returns the exclusive prefixes of both payloads.
-__device__ __forceinline__ void tile_lookback(uint64_t* state, int64_t tile, uint64_t sum0, uint64_t sum1,
-                                              uint64_t& ex0, uint64_t& ex1) {
-    const int lane = threadIdx.x;
-    unsigned long long* st = reinterpret_cast<unsigned long long*>(state);
-    if (lane == 0) {
-        const uint64_t flag = tile == 0 ? kStIncl : kStSum;
-        __hip_atomic_store(&st[tile * 2 + 0], (unsigned long long)(flag | sum0), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&st[tile * 2 + 1], (unsigned long long)(flag | sum1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    ex0 = 0; ex1 = 0;
-    if (tile == 0) return;
-    bool done0 = false, done1 = false;
-    for (int64_t idx = tile - 1; !(done0 && done1); idx -= kWave) {
-        const int64_t my = idx - lane;
-        uint64_t w0 = kStIncl, w1 = kStIncl;            // before tile 0: inclusive prefix 0
-        if (my >= 0) {
-            if (!done0) {
-                do { w0 = __hip_atomic_load(&st[my * 2 + 0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                     if ((w0 & kStMask) == 0) __builtin_amdgcn_s_sleep(1); } while ((w0 & kStMask) == 0);
-            }
-            if (!done1) {
-                do { w1 = __hip_atomic_load(&st[my * 2 + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                     if ((w1 & kStMask) == 0) __builtin_amdgcn_s_sleep(1); } while ((w1 & kStMask) == 0);
-            }
-        }
-        if (!done0) {
-            const uint64_t incl = __ballot((w0 & kStMask) == kStIncl);
-            const int first = incl ? (int)__ffsll((unsigned long long)incl) - 1 : kWave;   // nearest predecessor
-            ex0 += wave_sum64(lane <= first ? (w0 & ~kStMask) : 0ull);
-            done0 = first < kWave;
-        }
-        if (!done1) {
-            const uint64_t incl = __ballot((w1 & kStMask) == kStIncl);
-            const int first = incl ? (int)__ffsll((unsigned long long)incl) - 1 : kWave;
-            ex1 += wave_sum64(lane <= first ? (w1 & ~kStMask) : 0ull);
-            done1 = first < kWave;
-        }
-    }
-    if (lane == 0) {
-        __hip_atomic_store(&st[tile * 2 + 0], (unsigned long long)(kStIncl | (ex0 + sum0)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(&st[tile * 2 + 1], (unsigned long long)(kStIncl | (ex1 + sum1)), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// k_dedup: first occurrences of a stage's ids -> frontier, n_id, local ids, next-hop extents.
+// k_flag / k_assign: first occurrences of a stage's ids -> frontier, n_id, local ids, extents.
 // Position p of the stage is a first occurrence iff the table's smallest tagged position for
 // its id is p itself; it is a new node iff that id has no local id yet.
 // ---------------------------------------------------------------------------------------------
-template <typename RP>
-__global__ void __launch_bounds__(kScanBlock) k_dedup(CallArgs c) {
-    __shared__ uint32_t lds[kScanBlock / kWave][3];
-    __shared__ int64_t sh_tile;
-    __shared__ uint64_t sh_ex[2];
-    const BatchArgs& b = c.b[blockIdx.y];
-    const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
-    SampleMeta* m = b.meta;
-    const int stage = c.stage;
+constexpr int kMaxTiles = 1024;         // tiles per stage (k_assign sums the counts of earlier tiles itself)
+
+struct StageView {
     int64_t begin, end;
     const int32_t* ids;
     const uint32_t* slot_of;
-    if (stage == 0) { begin = m->stage_range[0]; end = m->stage_range[1]; ids = b.seeds; slot_of = b.seed_slot; }
-    else {
-        begin = m->edge_off[stage - 1]; end = m->edge_off[stage];
-        if (end > b.edge_cap) end = b.edge_cap;
-        ids = b.nbr; slot_of = b.slot_of;
-    }
-    if (end < begin) end = begin;
-    if (threadIdx.x == 0) sh_tile = (int64_t)atomicAdd(&b.tickets[stage], 1u);
-    __syncthreads();
-    const int64_t tile = sh_tile;
-    const int64_t n_tiles = (end - begin + kTileItems - 1) / kTileItems;
-    if (tile >= n_tiles && !(n_tiles == 0 && tile == 0)) return;
-    const int64_t p0 = begin + tile * kTileItems + (int64_t)threadIdx.x * kItemsPerThread;
-    const uint64_t tag = pos_tag(c.epoch, stage);
+    uint16_t* flags;
+};
 
-    uint32_t first[kItemsPerThread], isnew[kItemsPerThread], seg[kItemsPerThread], slot[kItemsPerThread];
-    int32_t id[kItemsPerThread], oldlid[kItemsPerThread];
-    int64_t rs[kItemsPerThread];
-    uint32_t deg[kItemsPerThread];
-    Tri mine = {0, 0, 0};
-#pragma unroll
-    for (int i = 0; i < kItemsPerThread; ++i) {
-        const int64_t p = p0 + i;
-        first[i] = 0; isnew[i] = 0; seg[i] = 0; slot[i] = 0xFFFFFFFFu; id[i] = 0; oldlid[i] = -1; rs[i] = 0; deg[i] = 0;
-        if (p < end) {
-            slot[i] = slot_of[p];
-            if (slot[i] != 0xFFFFFFFFu && b.slots[slot[i]].minpos == (tag | (uint64_t)p)) {
-                first[i] = 1;
-                oldlid[i] = b.lid[slot[i]];
-                isnew[i] = oldlid[i] < 0 ? 1u : 0u;
-                id[i] = ids[p];
-                if (c.next_fanout > 0) {
-                    rs[i] = (int64_t)rowptr[id[i]];
-                    deg[i] = (uint32_t)((int64_t)rowptr[id[i] + 1] - rs[i]);
-                    seg[i] = deg[i] < (uint32_t)c.next_fanout ? deg[i] : (uint32_t)c.next_fanout;
+__device__ __forceinline__ StageView stage_view(const CallArgs& c, const BatchArgs& b) {
+    StageView v;
+    const SampleMeta* m = b.meta;
+    if (c.stage == 0) {
+        v.begin = m->stage_range[0]; v.end = m->stage_range[1];
+        v.ids = b.seeds; v.slot_of = b.seed_slot; v.flags = b.seed_flags;
+    } else {
+        v.begin = m->edge_off[c.stage - 1]; v.end = m->edge_off[c.stage];
+        if (v.end > b.edge_cap) v.end = b.edge_cap;
+        v.ids = b.nbr; v.slot_of = b.slot_of; v.flags = b.flags;
+    }
+    if (v.end < v.begin) v.end = v.begin;
+    return v;
+}
+
+// slot of the id at position p (0xFFFFFFFF: the id was out of range or the table was full)
+__device__ __forceinline__ uint32_t slot_at(const CallArgs& c, const StageView& v, int64_t p, int32_t id) {
+    if (!c.direct) return v.slot_of[p];
+    return (id >= 0 && (c.n_nodes < 0 || (int64_t)id < c.n_nodes)) ? (uint32_t)id : 0xFFFFFFFFu;
+}
+
+template <typename RP>
+__global__ void __launch_bounds__(kScanBlock) k_flag(CallArgs c) {
+    __shared__ uint32_t lds[kScanBlock / kWave][3];
+    const BatchArgs& b = c.b[blockIdx.y];
+    const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
+    const StageView v = stage_view(c, b);
+    const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
+    const int64_t t0 = v.begin + (int64_t)blockIdx.x * tile_size;
+    if (t0 >= v.end) return;
+    const uint64_t tag = pos_tag(c.epoch, c.stage);
+    Tri sum = {0, 0, 0};
+    for (int it = 0; it < c.items_per_thread; ++it) {
+        const int64_t p = t0 + (int64_t)it * kScanBlock + threadIdx.x;
+        if (p < v.end) {
+            const int32_t id = v.ids[p];
+            const uint32_t slot = slot_at(c, v, p, id);
+            uint32_t first = 0, isnew = 0, seg = 0;
+            if (slot != 0xFFFFFFFFu) {
+                // independent loads, issued together
+                const uint64_t mp = b.minpos[slot];
+                const int32_t lid = b.lid[slot];
+                int64_t rs = 0, re = 0;
+                if (c.next_fanout > 0) { rs = (int64_t)rowptr[id]; re = (int64_t)rowptr[id + 1]; }
+                first = (mp == (tag | (uint64_t)p)) ? 1u : 0u;
+                isnew = (first && lid < 0) ? 1u : 0u;
+                if (first) {
+                    const uint32_t d = (uint32_t)(re - rs);
+                    seg = d < (uint32_t)c.next_fanout ? d : (uint32_t)c.next_fanout;
                 }
             }
+            v.flags[p] = (uint16_t)(first | (isnew << 1) | (seg << 2));
+            sum.a += first; sum.b += isnew; sum.c += seg;
         }
-        mine.a += first[i]; mine.b += isnew[i]; mine.c += seg[i];
     }
     Tri total;
-    Tri ex = block_scan3(mine, total, lds);
-    if (threadIdx.x < kWave) {
-        uint64_t e0, e1;
-        tile_lookback(b.tile_state + c.tile_base * 2, tile, ((uint64_t)total.a << 31) | total.b, (uint64_t)total.c, e0, e1);
-        if (threadIdx.x == 0) { sh_ex[0] = e0; sh_ex[1] = e1; }
+    block_scan3(sum, total, lds);
+    if (threadIdx.x == 0) {
+        b.partial[blockIdx.x * 3 + 0] = total.a;
+        b.partial[blockIdx.x * 3 + 1] = total.b;
+        b.partial[blockIdx.x * 3 + 2] = total.c;
     }
-    __syncthreads();
-    const int64_t pre_first = (int64_t)(sh_ex[0] >> 31), pre_new = (int64_t)(sh_ex[0] & 0x7FFFFFFFull);
-    const int64_t pre_seg = (int64_t)sh_ex[1];
-    const int64_t node_base = m->node_off[stage];
-    const int64_t fr_base = m->frontier_off[stage];
+}
+
+template <typename RP>
+__global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
+    __shared__ uint32_t lds[kScanBlock / kWave][3];
+    const BatchArgs& b = c.b[blockIdx.y];
+    const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
+    SampleMeta* m = b.meta;
+    const StageView v = stage_view(c, b);
+    const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
+    const int64_t t0 = v.begin + (int64_t)blockIdx.x * tile_size;
+    const bool empty_stage = v.end <= v.begin;
+    if (t0 >= v.end && !(empty_stage && blockIdx.x == 0)) return;
+    const int64_t node_base = m->node_off[c.stage];
+    const int64_t fr_base = m->frontier_off[c.stage];
+    const int64_t edge_base = m->edge_off[c.stage];
     const int64_t fr_user_base = c.frontier_restart ? 0 : fr_base;
-    int64_t j = pre_first + ex.a, u = node_base + pre_new + ex.b, so = pre_seg + ex.c;
-#pragma unroll
-    for (int i = 0; i < kItemsPerThread; ++i) {
-        if (first[i]) {
-            int32_t lid = oldlid[i];
-            if (isnew[i]) {
+    // counts of all earlier tiles
+    Tri pre = {0, 0, 0};
+    for (int i = threadIdx.x; i < (int)blockIdx.x; i += kScanBlock) {
+        pre.a += b.partial[i * 3 + 0]; pre.b += b.partial[i * 3 + 1]; pre.c += b.partial[i * 3 + 2];
+    }
+    Tri run;
+    block_scan3(pre, run, lds);
+    for (int it = 0; it < c.items_per_thread; ++it) {
+        const int64_t p = t0 + (int64_t)it * kScanBlock + threadIdx.x;
+        const uint32_t f = (p < v.end) ? v.flags[p] : 0u;
+        const Tri x = {f & 1u, (f >> 1) & 1u, f >> 2};
+        // loads a first occurrence needs, issued before the scan's barriers
+        int32_t id = 0, lid = -1;
+        uint32_t slot = 0xFFFFFFFFu, deg = 0;
+        int64_t rs = 0;
+        if (x.a) {
+            id = v.ids[p];
+            slot = slot_at(c, v, p, id);
+            if (!x.b) lid = b.lid[slot];
+            if (c.next_fanout > 0) { rs = (int64_t)rowptr[id]; deg = (uint32_t)((int64_t)rowptr[id + 1] - rs); }
+        }
+        Tri tot;
+        const Tri ex = block_scan3(x, tot, lds);
+        if (x.a) {
+            const int64_t u = node_base + run.b + ex.b;
+            if (x.b) {
                 lid = (int32_t)u;
-                b.lid[slot[i]] = lid;
-                if (u < b.n_id_cap) b.n_id[u] = id[i];
+                b.lid[slot] = lid;
+                if (u < b.n_id_cap) b.n_id[u] = id;
                 else atomicOr(c.status, kStatCapacity);
-                ++u;
             }
+            const int64_t j = (int64_t)run.a + ex.a;
             if (c.next_fanout > 0) {                 // the next hop expands this entry
                 if (fr_base + j < b.fr_cap) {
-                    b.fr_id[fr_base + j] = id[i];
+                    b.fr_id[fr_base + j] = id;
                     b.fr_lid[fr_base + j] = lid;
-                    b.fr_rs[fr_base + j] = rs[i];
-                    b.fr_deg[fr_base + j] = deg[i];
-                    b.fr_seg[fr_base + j] = (uint32_t)so;
+                    b.fr_rs[fr_base + j] = rs;
+                    b.fr_deg[fr_base + j] = deg;
+                    b.fr_seg[fr_base + j] = run.c + ex.c;
                 } else {
                     atomicOr(c.status, kStatCapacity);
                 }
             }
             if (b.fr_user) {
-                if (fr_user_base + j < b.fr_user_cap) b.fr_user[fr_user_base + j] = id[i];
+                if (fr_user_base + j < b.fr_user_cap) b.fr_user[fr_user_base + j] = id;
                 else atomicOr(c.status, kStatCapacity);
             }
-            ++j;
-            so += seg[i];
         }
+        run.a += tot.a; run.b += tot.b; run.c += tot.c;
     }
-    const bool last = (n_tiles == 0) || (tile == n_tiles - 1);
-    if (last && threadIdx.x == kScanBlock - 1) {       // the last thread's running values are the totals
-        m->node_off[stage + 1] = u;
-        m->frontier_off[stage + 1] = fr_base + j;
-        if (c.next_fanout > 0) m->edge_off[stage + 1] = m->edge_off[stage] + so;
-        if (c.expect_all_first && j != end - begin) atomicOr(c.status, kStatInval);
+    const bool last = empty_stage || (t0 + tile_size >= v.end);
+    if (last && threadIdx.x == 0) {
+        m->node_off[c.stage + 1] = node_base + run.b;
+        m->frontier_off[c.stage + 1] = fr_base + run.a;
+        if (c.next_fanout > 0) m->edge_off[c.stage + 1] = edge_base + run.c;
+        if (c.expect_all_first && (int64_t)run.a != v.end - v.begin) atomicOr(c.status, kStatInval);
     }
 }
 
@@ -540,7 +531,13 @@ __global__ void __launch_bounds__(256) k_relabel(CallArgs c) {
     int64_t end = m->edge_off[c.stage];                // c.stage = last stage
     if (end > b.edge_cap) end = b.edge_cap;
     for (int64_t p = tid; p < end; p += stride) {
-        uint32_t slot = b.slot_of[p];
+        uint32_t slot;
+        if (c.direct) {
+            const int32_t g = b.nbr[p];
+            slot = (g >= 0 && (c.n_nodes < 0 || (int64_t)g < c.n_nodes)) ? (uint32_t)g : 0xFFFFFFFFu;
+        } else {
+            slot = b.slot_of[p];
+        }
         b.col_local[p] = slot == 0xFFFFFFFFu ? -1 : b.lid[slot];
     }
     if (tid == 0) {
@@ -660,24 +657,36 @@ static void table_geometry(int64_t max_keys, uint32_t* mask, int* shift) {
     *shift = 32 - bits;
 }
 
-// Make sure the context owns n_tables tables of (mask + 1) slots and start a new epoch.
-static qv_status table_prepare(qv_ctx* ctx, int n_tables, uint32_t mask) {
-    const size_t need = (size_t)n_tables * ((size_t)mask + 1);
+// Make sure the context owns n_tables tables of `slots` entries (with key words if hashed) and
+// start a new epoch.
+static qv_status table_prepare(qv_ctx* ctx, int n_tables, size_t slots, bool hashed) {
+    const size_t need = (size_t)n_tables * slots;
+    const size_t need_keyw = hashed ? need : 0;
     bool clear = false;
-    if (need > ctx->table_entries) {
+    if (need > ctx->table_entries || need_keyw > ctx->table_keyw_entries) {
         QV_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        if (ctx->table_slots) QV_HIP(ctx, hipFree(ctx->table_slots));
-        if (ctx->table_lid) QV_HIP(ctx, hipFree(ctx->table_lid));
-        ctx->table_slots = nullptr; ctx->table_lid = nullptr; ctx->table_entries = 0;
-        QV_HIP(ctx, hipMalloc((void**)&ctx->table_slots, need * sizeof(TableSlot)));
-        QV_HIP(ctx, hipMalloc((void**)&ctx->table_lid, need * sizeof(int32_t)));
-        ctx->table_entries = need;
+        if (need > ctx->table_entries) {
+            if (ctx->table_minpos) QV_HIP(ctx, hipFree(ctx->table_minpos));
+            if (ctx->table_lid) QV_HIP(ctx, hipFree(ctx->table_lid));
+            ctx->table_minpos = nullptr; ctx->table_lid = nullptr; ctx->table_entries = 0;
+            QV_HIP(ctx, hipMalloc((void**)&ctx->table_minpos, need * sizeof(uint64_t)));
+            QV_HIP(ctx, hipMalloc((void**)&ctx->table_lid, need * sizeof(int32_t)));
+            ctx->table_entries = need;
+        }
+        if (need_keyw > ctx->table_keyw_entries) {
+            if (ctx->table_keyw) QV_HIP(ctx, hipFree(ctx->table_keyw));
+            ctx->table_keyw = nullptr; ctx->table_keyw_entries = 0;
+            QV_HIP(ctx, hipMalloc((void**)&ctx->table_keyw, need_keyw * sizeof(uint64_t)));
+            ctx->table_keyw_entries = need_keyw;
+        }
         clear = true;
     }
     if (ctx->epoch >= kEpochLimit) clear = true;
     if (clear) {
-        hipLaunchKernelGGL(k_table_clear, dim3(grid_for((int64_t)ctx->table_entries, 1024, ctx->n_cu * 16)), dim3(256), 0,
-                           ctx->stream, ctx->table_slots, ctx->table_lid, (int64_t)ctx->table_entries);
+        const int64_t n_max = (int64_t)(ctx->table_entries > ctx->table_keyw_entries ? ctx->table_entries : ctx->table_keyw_entries);
+        hipLaunchKernelGGL(k_table_clear, dim3(grid_for(n_max, 1024, ctx->n_cu * 16)), dim3(256), 0, ctx->stream,
+                           ctx->table_keyw, (int64_t)ctx->table_keyw_entries, ctx->table_minpos, ctx->table_lid,
+                           (int64_t)ctx->table_entries);
         QV_LAUNCH_CHECK(ctx, "k_table_clear");
         ctx->epoch = 0;
     }
@@ -685,48 +694,64 @@ static qv_status table_prepare(qv_ctx* ctx, int n_tables, uint32_t mask) {
     return QV_OK;
 }
 
-struct Layout {                     // per-batch scratch sizes (bytes) and stage tile offsets
+// direct (slot == node id) when the arrays for all batches fit the context's budget
+static bool use_direct(const qv_ctx* ctx, int64_t n_nodes, int n_tables) {
+    return n_nodes > 0 && n_nodes * 12 * (int64_t)n_tables <= ctx->direct_budget_bytes;
+}
+
+struct Layout {                     // per-batch scratch sizes (elements)
     int64_t stage0, edges, frontier;
-    int64_t tile_base[QV_MAX_HOPS + 2];     // first tile index of each stage; [n_stages] = total
-    int n_stages;
 };
 
-static int64_t tiles_for(int64_t items) { return items > 0 ? (items + kTileItems - 1) / kTileItems : 1; }
+static void tile_shape(int64_t max_items, int* ipt, int* tiles) {
+    int64_t per = (max_items + (int64_t)kScanBlock * kMaxTiles - 1) / ((int64_t)kScanBlock * kMaxTiles);
+    if (per < 1) per = 1;
+    int64_t t = (max_items + kScanBlock * per - 1) / (kScanBlock * per);
+    if (t < 1) t = 1;
+    *ipt = (int)per; *tiles = (int)t;
+}
 
 static size_t per_batch_bytes(const Layout& L) {
     size_t t = 0;
     t += align_up(sizeof(SampleMeta));
-    t += align_up((size_t)L.stage0 * 4);                                    // seed_slot
-    t += 2 * align_up((size_t)L.edges * 4);                                 // slot_of, nbr
-    t += 2 * align_up((size_t)L.frontier * 4) + align_up((size_t)L.frontier * 8) +
-         2 * align_up((size_t)L.frontier * 4);                              // fr_id, fr_lid, fr_rs, fr_deg, fr_seg
-    t += align_up((size_t)L.tile_base[L.n_stages] * 16);                    // tile_state
-    t += align_up((size_t)(QV_MAX_HOPS + 2) * 4);                           // tickets
+    t += align_up((size_t)L.stage0 * 4) + align_up((size_t)L.stage0 * 2);   // seed_slot, seed_flags
+    t += 2 * align_up((size_t)L.edges * 4) + align_up((size_t)L.edges * 2); // slot_of, nbr, flags
+    t += 4 * align_up((size_t)L.frontier * 4) + align_up((size_t)L.frontier * 8);   // fr_id, fr_lid, fr_deg, fr_seg, fr_rs
+    t += align_up((size_t)kMaxTiles * 3 * 4);                               // partial
     return t + 2048;
 }
 
 static bool carve(qv_ctx* ctx, const Layout& L, BatchArgs* b) {
     b->meta = (SampleMeta*)arena_take(ctx, sizeof(SampleMeta));
     b->seed_slot = (uint32_t*)arena_take(ctx, (size_t)L.stage0 * 4);
+    b->seed_flags = (uint16_t*)arena_take(ctx, (size_t)L.stage0 * 2);
     b->slot_of = (uint32_t*)arena_take(ctx, (size_t)L.edges * 4);
     b->nbr = (int32_t*)arena_take(ctx, (size_t)L.edges * 4);
+    b->flags = (uint16_t*)arena_take(ctx, (size_t)L.edges * 2);
     b->fr_id = (int32_t*)arena_take(ctx, (size_t)L.frontier * 4);
     b->fr_lid = (int32_t*)arena_take(ctx, (size_t)L.frontier * 4);
     b->fr_rs = (int64_t*)arena_take(ctx, (size_t)L.frontier * 8);
     b->fr_deg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
     b->fr_seg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
-    b->tile_state = (uint64_t*)arena_take(ctx, (size_t)L.tile_base[L.n_stages] * 16);
-    b->tickets = (uint32_t*)arena_take(ctx, (size_t)(QV_MAX_HOPS + 2) * 4);
+    b->partial = (uint32_t*)arena_take(ctx, (size_t)kMaxTiles * 3 * 4);
     b->fr_cap = L.frontier;
-    return b->meta && b->seed_slot && b->slot_of && b->nbr && b->fr_id && b->fr_lid && b->fr_rs && b->fr_deg &&
-           b->fr_seg && b->tile_state && b->tickets;
+    return b->meta && b->seed_slot && b->seed_flags && b->slot_of && b->nbr && b->flags && b->fr_id && b->fr_lid &&
+           b->fr_rs && b->fr_deg && b->fr_seg && b->partial;
 }
 
-static qv_status launch_dedup(qv_ctx* ctx, const CallArgs& c, int rowptr_bits, int64_t max_items, int n_batches) {
-    dim3 grid((unsigned)tiles_for(max_items), (unsigned)n_batches);
-    if (rowptr_bits == 32) hipLaunchKernelGGL(k_dedup<int32_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
-    else hipLaunchKernelGGL(k_dedup<int64_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
-    QV_LAUNCH_CHECK(ctx, "k_dedup");
+static qv_status launch_dedup(qv_ctx* ctx, CallArgs& c, int rowptr_bits, int64_t max_items, int n_batches) {
+    int ipt, tiles;
+    tile_shape(max_items, &ipt, &tiles);
+    c.items_per_thread = ipt;
+    dim3 grid((unsigned)tiles, (unsigned)n_batches);
+    if (rowptr_bits == 32) {
+        hipLaunchKernelGGL(k_flag<int32_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
+        hipLaunchKernelGGL(k_assign<int32_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
+    } else {
+        hipLaunchKernelGGL(k_flag<int64_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
+        hipLaunchKernelGGL(k_assign<int64_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
+    }
+    QV_LAUNCH_CHECK(ctx, "k_flag / k_assign");
     return QV_OK;
 }
 
@@ -767,26 +792,25 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     qv_status rc = compute_bounds(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, &bd);
     if (rc != QV_OK) return rc;
     Layout L;
-    L.stage0 = max_seeds; L.edges = bd.edges; L.frontier = bd.frontier; L.n_stages = n_hops + 1;
-    L.tile_base[0] = 0;
-    L.tile_base[1] = tiles_for(max_seeds);
-    for (int k = 1; k <= n_hops; ++k) L.tile_base[k + 1] = L.tile_base[k] + tiles_for(bd.hop_edges[k]);
+    L.stage0 = max_seeds; L.edges = bd.edges; L.frontier = bd.frontier;
     rc = arena_begin(ctx, per_batch_bytes(L) * n_batches);
     if (rc != QV_OK) return rc;
     CallArgs c{};
     c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
     table_geometry(bd.nodes, &c.mask, &c.shift);
-    rc = table_prepare(ctx, n_batches, c.mask);
+    c.direct = use_direct(ctx, csr->n_nodes, n_batches) ? 1 : 0;
+    const size_t table_slots = c.direct ? (size_t)csr->n_nodes : (size_t)c.mask + 1;
+    rc = table_prepare(ctx, n_batches, table_slots, !c.direct);
     if (rc != QV_OK) return rc;
     c.epoch = ctx->epoch; c.n_hops = n_hops; c.status = ctx->d_status;
-    c.state_words = (int32_t)(L.tile_base[L.n_stages] * 2); c.n_stages = L.n_stages;
     for (int i = 0; i < n_batches; ++i) {
         BatchArgs& b = c.b[i];
         if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "%s: scratch arena too small (internal sizing error)", who);
         const qv_sample_out& o = outs[i];
         b.seeds = seeds[i]; b.n_seeds = n_seeds[i]; b.rng_seed = rng_seeds[i];
-        b.slots = ctx->table_slots + (size_t)i * ((size_t)c.mask + 1);
-        b.lid = ctx->table_lid + (size_t)i * ((size_t)c.mask + 1);
+        b.keyw = c.direct ? nullptr : ctx->table_keyw + (size_t)i * table_slots;
+        b.minpos = ctx->table_minpos + (size_t)i * table_slots;
+        b.lid = ctx->table_lid + (size_t)i * table_slots;
         if (o.nbr_global) b.nbr = o.nbr_global;
         b.row_local = o.row_local; b.col_local = o.col_local;
         b.edge_cap = bd.edges < o.edge_cap ? bd.edges : o.edge_cap;
@@ -796,10 +820,9 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
         b.n_id_len_out = nullptr; b.frontier_len_out = nullptr;
     }
     // stage 0: the seeds
-    c.stage = 0; c.next_fanout = fanouts[0]; c.tile_base = L.tile_base[0];
+    c.stage = 0; c.next_fanout = fanouts[0];
     {
-        int64_t work = max_seeds > c.state_words ? max_seeds : c.state_words;
-        dim3 grid((unsigned)grid_for(work, 256, ctx->n_cu * 4), (unsigned)n_batches);
+        dim3 grid((unsigned)grid_for(max_seeds, 256, ctx->n_cu * 4), (unsigned)n_batches);
         hipLaunchKernelGGL(k_insert_ids, grid, dim3(256), 0, ctx->stream, c);
         QV_LAUNCH_CHECK(ctx, "k_insert_ids");
     }
@@ -808,7 +831,6 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     if (rc != QV_OK) return rc;
     for (int k = 1; k <= n_hops; ++k) {
         c.stage = k; c.hop = k; c.fanout = fanouts[k - 1]; c.next_fanout = k < n_hops ? fanouts[k] : 0;
-        c.tile_base = L.tile_base[k];
         rc = launch_sample(ctx, c, bd.hop_front[k - 1], n_batches);
         if (rc != QV_OK) return rc;
         rc = launch_dedup(ctx, c, csr->rowptr_bits, bd.hop_edges[k], n_batches);
@@ -833,10 +855,7 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, i
     qv_status rc = compute_bounds(ctx, n_seeds, fanouts, n_hops, n_nodes, &bd);
     if (rc != QV_OK) return rc;
     Layout L;
-    L.stage0 = n_seeds; L.edges = bd.edges; L.frontier = bd.frontier; L.n_stages = n_hops + 1;
-    L.tile_base[0] = 0;
-    L.tile_base[1] = tiles_for(n_seeds);
-    for (int k = 1; k <= n_hops; ++k) L.tile_base[k + 1] = L.tile_base[k] + tiles_for(bd.hop_edges[k]);
+    L.stage0 = n_seeds; L.edges = bd.edges; L.frontier = bd.frontier;
     const size_t want = per_batch_bytes(L) * kMaxBatch;
     if (want > ctx->arena_bytes) {
         rc = arena_begin(ctx, want);
@@ -844,7 +863,8 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, i
     }
     uint32_t mask; int shift;
     table_geometry(bd.nodes, &mask, &shift);
-    return table_prepare(ctx, kMaxBatch, mask);
+    const bool direct = use_direct(ctx, n_nodes, kMaxBatch);
+    return table_prepare(ctx, kMaxBatch, direct ? (size_t)n_nodes : (size_t)mask + 1, !direct);
 }
 
 qv_status qv_sample_hop(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier, int64_t n_frontier,
@@ -916,21 +936,20 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
         return fail(ctx, QV_EINVAL, "qv_reindex: null or negative argument");
     if (n_known >= ((int64_t)1 << 31) || n_nbr >= ((int64_t)1 << 31)) return fail(ctx, QV_EINVAL, "qv_reindex: too many ids");
     Layout L;
-    L.stage0 = n_known; L.edges = n_nbr; L.frontier = 1; L.n_stages = 2;
-    L.tile_base[0] = 0; L.tile_base[1] = tiles_for(n_known); L.tile_base[2] = L.tile_base[1] + tiles_for(n_nbr);
+    L.stage0 = n_known; L.edges = n_nbr; L.frontier = 1;
     qv_status rc = arena_begin(ctx, per_batch_bytes(L));
     if (rc != QV_OK) return rc;
     CallArgs c{};
     c.rowptr = nullptr; c.col = nullptr; c.n_nodes = n_nodes > 0 ? n_nodes : -1;
     table_geometry(n_known + n_nbr, &c.mask, &c.shift);
-    rc = table_prepare(ctx, 1, c.mask);
+    c.direct = use_direct(ctx, n_nodes, 1) ? 1 : 0;
+    rc = table_prepare(ctx, 1, c.direct ? (size_t)n_nodes : (size_t)c.mask + 1, !c.direct);
     if (rc != QV_OK) return rc;
     c.epoch = ctx->epoch; c.n_hops = 1; c.status = ctx->d_status;
-    c.state_words = (int32_t)(L.tile_base[2] * 2); c.n_stages = 2;
     BatchArgs& b = c.b[0];
     if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "qv_reindex: scratch arena too small (internal sizing error)");
     b.seeds = known; b.n_seeds = n_known; b.rng_seed = 0;
-    b.slots = ctx->table_slots; b.lid = ctx->table_lid;
+    b.keyw = c.direct ? nullptr : ctx->table_keyw; b.minpos = ctx->table_minpos; b.lid = ctx->table_lid;
     b.nbr = const_cast<int32_t*>(nbr);                   // read only on this path
     b.row_local = nullptr; b.col_local = local_out; b.edge_cap = n_nbr;
     b.n_id = n_id_out; b.n_id_cap = n_id_cap;
@@ -938,17 +957,15 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
     b.node_off_out = nullptr; b.edge_off_out = nullptr; b.frontier_off_out = nullptr;
     b.n_id_len_out = n_id_len; b.frontier_len_out = frontier_len;
     // stage 0: the known ids
-    c.stage = 0; c.next_fanout = 0; c.tile_base = 0; c.frontier_restart = 0; c.expect_all_first = 1;
+    c.stage = 0; c.next_fanout = 0; c.frontier_restart = 0; c.expect_all_first = 1;
     {
-        int64_t work = n_known > c.state_words ? n_known : c.state_words;
-        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(work, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);
+        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(n_known, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);
         QV_LAUNCH_CHECK(ctx, "k_insert_ids");
     }
     rc = launch_dedup(ctx, c, 32, n_known, 1);
     if (rc != QV_OK) return rc;
     // stage 1: the neighbour ids
-    c.stage = 1; c.tile_base = L.tile_base[1]; c.frontier_restart = 1; c.expect_all_first = 0;
-    c.state_words = 0; c.n_stages = 0;
+    c.stage = 1; c.frontier_restart = 1; c.expect_all_first = 0;
     b.fr_user = frontier_out; b.fr_user_cap = frontier_out ? n_nbr : 0;
     if (n_nbr > 0) {
         hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(n_nbr, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);

@@ -25,9 +25,13 @@ def qv():
     return m
 
 
-@pytest.fixture(scope="module")
-def ctx(qv):
+@pytest.fixture(scope="module", params=["direct", "hashed"])
+def ctx(qv, request):
+    """Every test runs with both forms of the dedup table (addressed by node id / open-addressing hash)."""
     c = qv.Context(0)
+    if request.param == "hashed":
+        c.set_table_budget(0)
+        c._budget = 0
     yield c
     c.close()
 
@@ -172,6 +176,7 @@ def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
     # calls (of other sizes, other batch counts) left behind, nor on the counter wrapping
     w, rowptr, col, g0 = tiny
     c = qv.Context(0)
+    c.set_table_budget(g0.ctx.__dict__.get("_budget", 12 << 30))
     g = make_graph(qv, c, rowptr, col)
     plan = [(64, [10, 5]), (2000, [15, 10, 5]), (3, [3]), (700, [25, 10]), (64, [10, 5])]
     for rnd in range(3):
