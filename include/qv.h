@@ -68,10 +68,10 @@ qv_status qv_ctx_sync(qv_ctx* ctx);
 qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts /*[host]*/,
                          int32_t n_hops, int64_t n_nodes);
 
-/* Dedup tables come in two forms.  When n_nodes x 12 bytes x (batches in the call) is at most
+/* Dedup tables come in two forms.  When n_nodes x 16 bytes x (batches in the call) is at most
  * `bytes`, the table is addressed directly by node id (no probing, one atomic per sampled
  * edge; the memory is held by the context).  Otherwise an open-addressing hash sized by the
- * batch is used.  Default 12 GiB; 0 selects the hash always.  Results are identical. */
+ * batch is used.  Default 16 GiB; 0 selects the hash always.  Results are identical. */
 qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes);
 
 /* Testing aid.  The dedup tables are never cleared between calls: every call stamps its entries

@@ -98,8 +98,7 @@ void qv_ctx_destroy(qv_ctx* ctx) {
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->arena) (void)hipFree(ctx->arena);
     if (ctx->table_keyw) (void)hipFree(ctx->table_keyw);
-    if (ctx->table_minpos) (void)hipFree(ctx->table_minpos);
-    if (ctx->table_lid) (void)hipFree(ctx->table_lid);
+    if (ctx->table_slots) (void)hipFree(ctx->table_slots);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
     delete ctx;

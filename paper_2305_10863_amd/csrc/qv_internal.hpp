@@ -20,17 +20,23 @@ constexpr int kStatRange = 1;
 constexpr int kStatCapacity = 2;
 constexpr int kStatInval = 4;
 
-// Dedup table keyed by global node id, structure of arrays, in one of two forms:
-//   direct  slot == node id (arrays of n_nodes entries): no probing, one atomic per sampled edge.
-//           Used when n_nodes x 12 bytes x batches fits the context's table budget.
-//   hashed  open addressing with linear probing over a power-of-two number of slots; keyw[slot]
-//           = epoch << 32 | key, and a slot whose epoch differs from the call's is free.
-// Common to both:
-//   minpos[slot] = smallest tagged position at which the key occurred in the newest stage of the
-//           newest call: tag = (~epoch & 0xFFFFF) << 44 | (15 - stage) << 40 | position, so a newer
-//           call or stage always wins an atomicMin and stale values never need a reset.
-//   lid[slot]    = local id, -1 until assigned; reset by whoever first touches the key in a call.
+// Dedup table keyed by global node id: 16-byte slots {minpos, lid, lid_epoch}, in one of two forms:
+//   direct  slot == node id (n_nodes slots): no probing, one fire-and-forget atomic per sampled
+//           edge.  Used when n_nodes x 16 bytes x batches fits the context's table budget.
+//   hashed  open addressing with linear probing over a power-of-two number of slots, with a
+//           parallel array keyw[slot] = epoch << 32 | key; a slot whose epoch differs from the
+//           call's is free.
+// Fields:
+//   minpos     smallest tagged position at which the key occurred in the newest stage of the
+//              newest call: tag = (~epoch & 0xFFFFF) << 44 | (15 - stage) << 40 | position, so a
+//              newer call or stage always wins an atomicMin and stale values never need a reset.
+//   lid        local id of the key, meaningful only while lid_epoch equals the call's epoch.
 // Nothing is cleared between calls; only when the epoch counter is exhausted.
+struct alignas(16) TableSlot {
+    uint64_t minpos;
+    int32_t lid;
+    uint32_t lid_epoch;
+};
 constexpr uint32_t kEpochLimit = 0xFFFFEu;          // epochs 1 .. kEpochLimit, then a full clear
 
 // Sizes that only the device knows while a qv_sample call is in flight.
@@ -51,11 +57,10 @@ struct qv_ctx {
     size_t arena_used = 0;             // bump pointer within one API call
     // hash tables live apart from the arena: their contents carry over between calls
     uint64_t* table_keyw = nullptr;    // hashed form only
-    uint64_t* table_minpos = nullptr;
-    int32_t* table_lid = nullptr;
-    size_t table_entries = 0;          // slots allocated in minpos / lid (all batches of a call together)
-    size_t table_keyw_entries = 0;     // slots allocated in keyw
-    int64_t direct_budget_bytes = (int64_t)12 << 30;
+    qv::TableSlot* table_slots = nullptr;
+    size_t table_entries = 0;          // slots allocated (all batches of a call together)
+    size_t table_keyw_entries = 0;     // entries allocated in keyw
+    int64_t direct_budget_bytes = (int64_t)16 << 30;
     uint32_t epoch = 0;
     int32_t* d_status = nullptr;       // device status word
     int32_t* h_status = nullptr;       // pinned mirror

@@ -84,8 +84,7 @@ __device__ __forceinline__ uint32_t floyd_resolve(uint32_t t, bool active, bool 
 // ---------------------------------------------------------------------------------------------
 struct TableView {
     uint64_t* keyw;                 // hashed form only
-    uint64_t* minpos;
-    int32_t* lid;
+    TableSlot* slots;
     uint32_t mask;
     int32_t shift;
     uint32_t epoch;
@@ -97,9 +96,7 @@ __device__ __forceinline__ uint64_t pos_tag(uint32_t epoch, int stage) {
 }
 
 // Hashed form: returns the slot of `key`, inserting it if absent; 0xFFFFFFFF if the table is
-// full.  A slot is free when its epoch is not the call's epoch; whoever claims it resets its
-// local id.  The first look at a slot is an ordinary load: a stale value can only make the
-// compare-and-swap fail, and that returns the current value.
+// full.  A slot is free when the epoch in its key word is not the call's epoch.
 __device__ __forceinline__ uint32_t table_insert(const TableView& t, uint32_t key) {
     const uint64_t mine = ((uint64_t)t.epoch << 32) | key;
     uint32_t h = ((key * 0x9E3779B1u) >> t.shift) & t.mask;
@@ -110,7 +107,7 @@ __device__ __forceinline__ uint32_t table_insert(const TableView& t, uint32_t ke
             if (cur == mine) return h;
             if ((uint32_t)(cur >> 32) == t.epoch) break;             // another key of this call
             uint64_t old = atomicCAS(kw, (unsigned long long)cur, (unsigned long long)mine);
-            if (old == cur) { t.lid[h] = -1; return h; }             // claimed a free slot
+            if (old == cur) return h;                                // claimed a free slot
             cur = old;                                               // lost a race: look again
         }
         h = (h + 1) & t.mask;
@@ -119,26 +116,23 @@ __device__ __forceinline__ uint32_t table_insert(const TableView& t, uint32_t ke
 }
 
 // Register that `key` occurs at tagged position `tp`; returns the key's slot (0xFFFFFFFF: table
-// full).  Direct form: the slot is the key itself and this is the only atomic; the returned old
-// value tells whether this is the key's first touch in this call, in which case its local id is
-// reset here.
+// full).  Direct form: the slot is the key itself and the atomicMin (result unused, so the wave
+// does not wait for it) is the only table access per sampled edge.
 __device__ __forceinline__ uint32_t table_touch(const TableView& t, uint32_t key, uint64_t tp) {
-    if (t.direct) {
-        const uint64_t old = atomicMin(reinterpret_cast<unsigned long long*>(&t.minpos[key]), (unsigned long long)tp);
-        if ((old >> 44) != (tp >> 44)) t.lid[key] = -1;
-        return key;
-    }
-    const uint32_t slot = table_insert(t, key);
-    if (slot != 0xFFFFFFFFu) atomicMin(reinterpret_cast<unsigned long long*>(&t.minpos[slot]), (unsigned long long)tp);
+    const uint32_t slot = t.direct ? key : table_insert(t, key);
+    if (slot != 0xFFFFFFFFu) atomicMin(reinterpret_cast<unsigned long long*>(&t.slots[slot].minpos), (unsigned long long)tp);
     return slot;
 }
 
 // full clear: after (re)allocation and when the epoch counter wraps
-__global__ void k_table_clear(uint64_t* keyw, int64_t n_keyw, uint64_t* minpos, int32_t* lid, int64_t n) {
+__global__ void k_table_clear(uint64_t* keyw, int64_t n_keyw, TableSlot* slots, int64_t n) {
     int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
     for (int64_t i = tid; i < n_keyw; i += stride) keyw[i] = 0ull;            // epoch 0 = never used
-    for (int64_t i = tid; i < n; i += stride) { minpos[i] = ~0ull; lid[i] = -1; }
+    uint4 z;
+    z.x = 0xFFFFFFFFu; z.y = 0xFFFFFFFFu; z.z = 0xFFFFFFFFu; z.w = 0u;        // minpos = max, lid = -1, lid_epoch = 0
+    uint4* e = reinterpret_cast<uint4*>(slots);
+    for (int64_t i = tid; i < n; i += stride) e[i] = z;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -148,7 +142,7 @@ struct BatchArgs {
     const int32_t* seeds;           // stage-0 ids
     int64_t n_seeds;
     uint64_t rng_seed;
-    uint64_t* keyw; uint64_t* minpos; int32_t* lid;    // this batch's table region (minpos == NULL: no dedup)
+    uint64_t* keyw; TableSlot* slots;                  // this batch's table region (slots == NULL: no dedup)
     SampleMeta* meta;
     uint32_t* seed_slot;            // table slot of each stage-0 id
     uint32_t* slot_of;              // table slot of each edge's neighbour
@@ -185,7 +179,7 @@ struct CallArgs {
 };
 
 __device__ __forceinline__ TableView table_of(const CallArgs& c, const BatchArgs& b) {
-    return TableView{b.keyw, b.minpos, b.lid, c.mask, c.shift, c.epoch, c.direct};
+    return TableView{b.keyw, b.slots, c.mask, c.shift, c.epoch, c.direct};
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -235,7 +229,7 @@ __device__ __forceinline__ void emit_edge(const CallArgs& c, const BatchArgs& b,
     if (p < b.edge_cap) {
         b.nbr[p] = g;
         if (b.row_local) b.row_local[p] = vl;
-        if (b.minpos) {
+        if (b.slots) {
             uint32_t slot = 0xFFFFFFFFu;
             if (g < 0 || (int64_t)g >= c.n_nodes) {
                 atomicOr(c.status, kStatRange);
@@ -421,13 +415,13 @@ __global__ void __launch_bounds__(kScanBlock) k_flag(CallArgs c) {
             const uint32_t slot = slot_at(c, v, p, id);
             uint32_t first = 0, isnew = 0, seg = 0;
             if (slot != 0xFFFFFFFFu) {
-                // independent loads, issued together
-                const uint64_t mp = b.minpos[slot];
-                const int32_t lid = b.lid[slot];
+                // independent loads, issued together: one 16-byte slot, the row extent
+                const uint4 sl = *reinterpret_cast<const uint4*>(&b.slots[slot]);
                 int64_t rs = 0, re = 0;
                 if (c.next_fanout > 0) { rs = (int64_t)rowptr[id]; re = (int64_t)rowptr[id + 1]; }
+                const uint64_t mp = ((uint64_t)sl.y << 32) | sl.x;
                 first = (mp == (tag | (uint64_t)p)) ? 1u : 0u;
-                isnew = (first && lid < 0) ? 1u : 0u;
+                isnew = (first && sl.w != c.epoch) ? 1u : 0u;          // no local id in this call yet
                 if (first) {
                     const uint32_t d = (uint32_t)(re - rs);
                     seg = d < (uint32_t)c.next_fanout ? d : (uint32_t)c.next_fanout;
@@ -479,7 +473,7 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
         if (x.a) {
             id = v.ids[p];
             slot = slot_at(c, v, p, id);
-            if (!x.b) lid = b.lid[slot];
+            if (!x.b) lid = b.slots[slot].lid;
             if (c.next_fanout > 0) { rs = (int64_t)rowptr[id]; deg = (uint32_t)((int64_t)rowptr[id + 1] - rs); }
         }
         Tri tot;
@@ -488,7 +482,8 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
             const int64_t u = node_base + run.b + ex.b;
             if (x.b) {
                 lid = (int32_t)u;
-                b.lid[slot] = lid;
+                *reinterpret_cast<unsigned long long*>(&b.slots[slot].lid) =
+                    ((unsigned long long)c.epoch << 32) | (unsigned long long)(uint32_t)lid;   // lid + lid_epoch, one store
                 if (u < b.n_id_cap) b.n_id[u] = id;
                 else atomicOr(c.status, kStatCapacity);
             }
@@ -538,7 +533,7 @@ __global__ void __launch_bounds__(256) k_relabel(CallArgs c) {
         } else {
             slot = b.slot_of[p];
         }
-        b.col_local[p] = slot == 0xFFFFFFFFu ? -1 : b.lid[slot];
+        b.col_local[p] = slot == 0xFFFFFFFFu ? -1 : b.slots[slot].lid;
     }
     if (tid == 0) {
         if (b.node_off_out) for (int i = 0; i < c.n_hops + 2; ++i) b.node_off_out[i] = m->node_off[i];
@@ -666,11 +661,9 @@ static qv_status table_prepare(qv_ctx* ctx, int n_tables, size_t slots, bool has
     if (need > ctx->table_entries || need_keyw > ctx->table_keyw_entries) {
         QV_HIP(ctx, hipStreamSynchronize(ctx->stream));
         if (need > ctx->table_entries) {
-            if (ctx->table_minpos) QV_HIP(ctx, hipFree(ctx->table_minpos));
-            if (ctx->table_lid) QV_HIP(ctx, hipFree(ctx->table_lid));
-            ctx->table_minpos = nullptr; ctx->table_lid = nullptr; ctx->table_entries = 0;
-            QV_HIP(ctx, hipMalloc((void**)&ctx->table_minpos, need * sizeof(uint64_t)));
-            QV_HIP(ctx, hipMalloc((void**)&ctx->table_lid, need * sizeof(int32_t)));
+            if (ctx->table_slots) QV_HIP(ctx, hipFree(ctx->table_slots));
+            ctx->table_slots = nullptr; ctx->table_entries = 0;
+            QV_HIP(ctx, hipMalloc((void**)&ctx->table_slots, need * sizeof(TableSlot)));
             ctx->table_entries = need;
         }
         if (need_keyw > ctx->table_keyw_entries) {
@@ -685,8 +678,7 @@ static qv_status table_prepare(qv_ctx* ctx, int n_tables, size_t slots, bool has
     if (clear) {
         const int64_t n_max = (int64_t)(ctx->table_entries > ctx->table_keyw_entries ? ctx->table_entries : ctx->table_keyw_entries);
         hipLaunchKernelGGL(k_table_clear, dim3(grid_for(n_max, 1024, ctx->n_cu * 16)), dim3(256), 0, ctx->stream,
-                           ctx->table_keyw, (int64_t)ctx->table_keyw_entries, ctx->table_minpos, ctx->table_lid,
-                           (int64_t)ctx->table_entries);
+                           ctx->table_keyw, (int64_t)ctx->table_keyw_entries, ctx->table_slots, (int64_t)ctx->table_entries);
         QV_LAUNCH_CHECK(ctx, "k_table_clear");
         ctx->epoch = 0;
     }
@@ -696,7 +688,7 @@ static qv_status table_prepare(qv_ctx* ctx, int n_tables, size_t slots, bool has
 
 // direct (slot == node id) when the arrays for all batches fit the context's budget
 static bool use_direct(const qv_ctx* ctx, int64_t n_nodes, int n_tables) {
-    return n_nodes > 0 && n_nodes * 12 * (int64_t)n_tables <= ctx->direct_budget_bytes;
+    return n_nodes > 0 && n_nodes * (int64_t)sizeof(TableSlot) * (int64_t)n_tables <= ctx->direct_budget_bytes;
 }
 
 struct Layout {                     // per-batch scratch sizes (elements)
@@ -809,8 +801,7 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
         const qv_sample_out& o = outs[i];
         b.seeds = seeds[i]; b.n_seeds = n_seeds[i]; b.rng_seed = rng_seeds[i];
         b.keyw = c.direct ? nullptr : ctx->table_keyw + (size_t)i * table_slots;
-        b.minpos = ctx->table_minpos + (size_t)i * table_slots;
-        b.lid = ctx->table_lid + (size_t)i * table_slots;
+        b.slots = ctx->table_slots + (size_t)i * table_slots;
         if (o.nbr_global) b.nbr = o.nbr_global;
         b.row_local = o.row_local; b.col_local = o.col_local;
         b.edge_cap = bd.edges < o.edge_cap ? bd.edges : o.edge_cap;
@@ -949,7 +940,7 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
     BatchArgs& b = c.b[0];
     if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "qv_reindex: scratch arena too small (internal sizing error)");
     b.seeds = known; b.n_seeds = n_known; b.rng_seed = 0;
-    b.keyw = c.direct ? nullptr : ctx->table_keyw; b.minpos = ctx->table_minpos; b.lid = ctx->table_lid;
+    b.keyw = c.direct ? nullptr : ctx->table_keyw; b.slots = ctx->table_slots;
     b.nbr = const_cast<int32_t*>(nbr);                   // read only on this path
     b.row_local = nullptr; b.col_local = local_out; b.edge_cap = n_nbr;
     b.n_id = n_id_out; b.n_id_cap = n_id_cap;
