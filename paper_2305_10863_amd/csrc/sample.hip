@@ -154,7 +154,7 @@ struct BatchArgs {
     int32_t* fr_id; int32_t* fr_lid; int64_t* fr_rs; uint32_t* fr_deg; uint32_t* fr_seg; int64_t fr_cap;
     int32_t* fr_user; int64_t fr_user_cap;
     uint16_t* seed_flags;           // stage-0 flags
-    uint16_t* flags;                // per edge: first occurrence | new node << 1 | next-hop segment size << 2
+    uint16_t* flags;                // per edge: first occurrence | new node << 1 | next-hop segment size << 2 | col_local written << 15
     uint32_t* partial;              // [kMaxTiles][3] per-tile counts of the stage being run
     int64_t* node_off_out; int64_t* edge_off_out; int64_t* frontier_off_out;
     int64_t* n_id_len_out; int64_t* frontier_len_out;      // stand-alone reindex
@@ -413,8 +413,11 @@ __global__ void __launch_bounds__(kScanBlock) k_flag(CallArgs c) {
         if (p < v.end) {
             const int32_t id = v.ids[p];
             const uint32_t slot = slot_at(c, v, p, id);
-            uint32_t first = 0, isnew = 0, seg = 0;
-            if (slot != 0xFFFFFFFFu) {
+            uint32_t first = 0, isnew = 0, seg = 0, resolved = 0;
+            int32_t known_lid = -1;
+            if (slot == 0xFFFFFFFFu) {
+                resolved = 1;                                          // bad id: local id -1
+            } else {
                 // independent loads, issued together: one 16-byte slot, the row extent
                 const uint4 sl = *reinterpret_cast<const uint4*>(&b.slots[slot]);
                 int64_t rs = 0, re = 0;
@@ -422,12 +425,14 @@ __global__ void __launch_bounds__(kScanBlock) k_flag(CallArgs c) {
                 const uint64_t mp = ((uint64_t)sl.y << 32) | sl.x;
                 first = (mp == (tag | (uint64_t)p)) ? 1u : 0u;
                 isnew = (first && sl.w != c.epoch) ? 1u : 0u;          // no local id in this call yet
+                if (sl.w == c.epoch) { resolved = 1; known_lid = (int32_t)sl.z; }   // numbered by an earlier stage
                 if (first) {
                     const uint32_t d = (uint32_t)(re - rs);
                     seg = d < (uint32_t)c.next_fanout ? d : (uint32_t)c.next_fanout;
                 }
             }
-            v.flags[p] = (uint16_t)(first | (isnew << 1) | (seg << 2));
+            if (resolved && c.stage > 0) b.col_local[p] = known_lid;
+            v.flags[p] = (uint16_t)(first | (isnew << 1) | (seg << 2) | (resolved << 15));
             sum.a += first; sum.b += isnew; sum.c += seg;
         }
     }
@@ -465,7 +470,7 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
     for (int it = 0; it < c.items_per_thread; ++it) {
         const int64_t p = t0 + (int64_t)it * kScanBlock + threadIdx.x;
         const uint32_t f = (p < v.end) ? v.flags[p] : 0u;
-        const Tri x = {f & 1u, (f >> 1) & 1u, f >> 2};
+        const Tri x = {f & 1u, (f >> 1) & 1u, (f >> 2) & 0x7FFu};
         // loads a first occurrence needs, issued before the scan's barriers
         int32_t id = 0, lid = -1;
         uint32_t slot = 0xFFFFFFFFu, deg = 0;
@@ -486,6 +491,7 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
                     ((unsigned long long)c.epoch << 32) | (unsigned long long)(uint32_t)lid;   // lid + lid_epoch, one store
                 if (u < b.n_id_cap) b.n_id[u] = id;
                 else atomicOr(c.status, kStatCapacity);
+                if (c.stage > 0) b.col_local[p] = lid;
             }
             const int64_t j = (int64_t)run.a + ex.a;
             if (c.next_fanout > 0) {                 // the next hop expands this entry
@@ -526,6 +532,10 @@ __global__ void __launch_bounds__(256) k_relabel(CallArgs c) {
     int64_t end = m->edge_off[c.stage];                // c.stage = last stage
     if (end > b.edge_cap) end = b.edge_cap;
     for (int64_t p = tid; p < end; p += stride) {
+        // only repeats of nodes that are new in their hop are still open: positions whose node was
+        // numbered by an earlier stage were written by k_flag, first occurrences by k_assign
+        const uint32_t f = b.flags[p];
+        if ((f & 0x8000u) || (f & 3u) == 3u) continue;
         uint32_t slot;
         if (c.direct) {
             const int32_t g = b.nbr[p];
