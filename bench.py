@@ -21,6 +21,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
+# Measured HBM bytes of k_gather over its algorithmic bytes (rocprofv3 FETCH_SIZE + WRITE_SIZE,
+# each scaled by a 1 GiB plain copy kernel; profiles/citation_k_gather_and_sampling_kernels.md).
+# Only quoted for the configuration that was profiled.
+GATHER_TRAFFIC_RATIO = {("citation", 1.0, 8): 0.992}
 
 
 def log(msg):
@@ -256,7 +260,9 @@ def main():
         "sample_ms_avg": round(float(np.mean(sample_ms)), 4),
         "gather_ms_avg": round(gather_avg_ms, 4),
         "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": (round(GATHER_TRAFFIC_RATIO[(w.name, args.scale, B)] * gather_bytes_per_launch)
+                                 if (w.name, args.scale, B) in GATHER_TRAFFIC_RATIO else None),
                      "bytes_per_launch": round(gather_bytes_per_launch), "avg_launch_ms": round(gather_avg_ms, 5)},
     }
     result.update(extra)
