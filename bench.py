@@ -100,7 +100,7 @@ def main():
 
     # ---- whole-graph metrics (deployment-time passes; not part of a step) ---------------------
     extra = {}
-    Pdev = None
+    Pdev = Qdev = None
     if not args.no_metrics:
         p0 = None
         if w.seed_mode == 1:
@@ -122,6 +122,8 @@ def main():
             extra[name + "_algorithmic_GBps"] = round(max(sweeps, 1) * per_sweep / ms / 1e6, 1)
             if name == "access_prob":
                 Pdev = res
+            else:
+                Qdev = res.clone()
         log("psgs %.2f ms, access_prob %.2f ms over the whole graph" % (extra["psgs_ms"], extra["access_prob_ms"]))
 
     if tiered:
@@ -133,8 +135,23 @@ def main():
         del table
         torch.cuda.empty_cache()
         log("tiered features: %d of %d rows in HBM" % (feat.n_hot, w.n))
+        hot_mask = torch.zeros(w.n, dtype=torch.bool, device="cuda")
+        hot_mask[rank[:feat.n_hot].long()] = True
+        # ceiling of the host link: pinned host -> device copy of 1 GiB
+        pin = torch.empty(1 << 28, dtype=torch.int32, pin_memory=True)
+        dst = torch.empty(1 << 28, dtype=torch.int32, device="cuda")
+        dst.copy_(pin, non_blocking=True)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            dst.copy_(pin, non_blocking=True)
+        e1.record()
+        torch.cuda.synchronize()
+        extra["host_link_pinned_copy_GBps"] = round(3 * pin.numel() * 4 / e0.elapsed_time(e1) / 1e6, 2)
+        del pin, dst
     else:
-        feat = qv.Features(ctx0, table)
+        feat = qv.Features(ctx0, table, own_copy=True)     # rows re-laid on 128-byte boundaries where cheap
 
     # ---- batches, contexts, buffers -------------------------------------------------------------
     import copy
@@ -151,7 +168,7 @@ def main():
             c.set_table_budget(int(args.table_budget_gib * 2 ** 30))
         c.reserve(batch, w.fanouts, w.n)
         bufs.append([qv.SampleBuffers(c, batch, w.fanouts, w.n) for _ in range(B)])
-        rows.append([torch.empty((nb, w.dim), dtype=tdtype, device="cuda") for _ in range(B)])
+        rows.append([feat.empty_rows(nb, "cuda") for _ in range(B)])
     Kh = len(w.fanouts)
     # per-step size blocks so that counts can be read after the timed region
     offs = [(torch.zeros(Kh + 2, dtype=torch.int64, device="cuda"), torch.zeros(Kh + 1, dtype=torch.int64, device="cuda"),
@@ -214,6 +231,10 @@ def main():
     # ---- accounting -------------------------------------------------------------------------
     tot_edges = tot_unique = tot_front = 0
     samp_b = reidx_b = gath_b = 0
+    if Qdev is not None:        # PSGS summed over a batch's seeds: the predicted size of its sampled tree
+        sums = [qv.qv_psgs_batch_sum(ctx0, Qdev, seeds_dev[i]) for i in range(W, W + min(K, 32))]
+        ctx0.sync()
+        extra["psgs_sum_per_batch"] = round(float(np.mean([x.item() for x in sums])), 1)
     for i in range(W, W + K):
         no, eo, fo = (t.cpu().numpy() for t in offs[i])
         U, E, F = int(no[-1]), int(eo[-1]), int(fo[Kh])        # frontier entries expanded = F_0..F_{K-1}
@@ -224,6 +245,15 @@ def main():
         samp_b += sb
         reidx_b += rb
         gath_b += gb
+    if tiered:                  # rows of the last call's batches that came over the host link
+        first, cnt = calls[-1]
+        cold = tot = 0
+        for t in range(cnt):
+            U = int(offs[first + t][0][-1].item())
+            ids = plans[-1].bufs[t].n_id[:U].long()
+            cold += int((~hot_mask[ids]).sum().item())
+            tot += U
+        extra["cold_row_fraction"] = round(cold / max(tot, 1), 4)
     timed = range(n_warm_calls, len(calls))
     sample_ms = [ev[j][0].elapsed_time(ev[j][1]) for j in timed]
     gather_ms = [ev[j][1].elapsed_time(ev[j][2]) for j in timed]
@@ -265,6 +295,11 @@ def main():
                                  if (w.name, args.scale, B) in GATHER_TRAFFIC_RATIO else None),
                      "bytes_per_launch": round(gather_bytes_per_launch), "avg_launch_ms": round(gather_avg_ms, 5)},
     }
+    if tiered:
+        cold_bytes = extra["cold_row_fraction"] * tot_unique * w.row_bytes
+        extra["cold_tier_GBps"] = round(cold_bytes / (sum(gather_ms) * 1e-3) / 1e9, 2)
+        result["roofline"]["note"] = ("tiered: %.0f%% of the rows come over the host link, which bounds this "
+                                      "kernel, not HBM" % (100 * extra["cold_row_fraction"]))
     result.update(extra)
 
     # ---- the oracle on this machine's host cores (a reported baseline, not the target) ------------

@@ -183,17 +183,25 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
  *   hbm_budget_bytes  bytes of HBM the table may occupy; < 0 or >= the table size = all in HBM.
  *   rank           [dev] int32[n_rows] placement order (most popular first, e.g. from
  *                  qv_place_rank); required when the budget is smaller than the table.
- * All rows in HBM and table on device: the table is BORROWED (no copy) and must outlive the
- * handle.  Otherwise the library copies: the first floor(budget / row bytes) rows of `rank` into
- * an HBM tier it owns (hot row i = table[rank[i]]), the remaining rows, in ascending id order,
- * into host-pinned memory it owns and maps into the GPU; the caller's table may be freed after
- * the call returns (the call synchronises). */
+ *   flags          0, or QV_FEAT_OWN_COPY.
+ * All rows in HBM, table on device, no QV_FEAT_OWN_COPY: the table is BORROWED (no copy) and
+ * must outlive the handle.  Otherwise the library copies: the first floor(budget / row bytes)
+ * rows of `rank` into an HBM tier it owns (hot row i = table[rank[i]]), the remaining rows, in
+ * ascending id order, into host-pinned memory it owns and maps into the GPU; the caller's table
+ * may be freed after the call returns (the call synchronises).  Tiers the library owns are laid
+ * out with their rows starting on 128-byte boundaries when that costs at most 1/32 more memory
+ * (e.g. 2,408-byte rows at a 2,432-byte stride), which the gather kernel rewards with wider
+ * loads; QV_FEAT_OWN_COPY asks for such a private copy even where borrowing would do. */
+#define QV_FEAT_OWN_COPY 1
 qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device, int64_t n_rows,
                          int32_t dim, int32_t elem_bytes, int64_t hbm_budget_bytes,
-                         const int32_t* rank, qv_feat** out);
+                         const int32_t* rank, int32_t flags, qv_feat** out);
 void qv_feat_destroy(qv_feat* feat);
 /* Number of rows held in HBM (== n_rows when everything fits). */
 int64_t qv_feat_hot_rows(const qv_feat* feat);
+/* Row stride in bytes of the HBM tier (== row bytes for a borrowed table): a good choice for
+ * out_row_stride_bytes of the gather calls as well. */
+int64_t qv_feat_row_stride(const qv_feat* feat);
 /* The lookup table [dev] int32[n_rows]: loc[id] >= 0 -> HBM row, < 0 -> host row ~loc[id];
  * NULL when every row is in HBM in id order. */
 const int32_t* qv_feat_loc(const qv_feat* feat);

@@ -19,7 +19,7 @@ QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 8
 EXPORTS = [
     "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget",
     "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_sample_hop", "qv_sample", "qv_sample_many",
-    "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc",
+    "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc", "qv_feat_row_stride",
     "qv_gather", "qv_gather_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
 ]
 
@@ -66,13 +66,15 @@ def lib():
                                      C.POINTER(u64), C.POINTER(_SampleOut)]
         L.qv_gather_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), i64]
         L.qv_reindex.argtypes = [vp, vp, i64, vp, i64, i64, vp, i64, vp, vp, vp, vp]
-        L.qv_feat_create.argtypes = [vp, vp, i32, i64, i32, i32, i64, vp, C.POINTER(vp)]
+        L.qv_feat_create.argtypes = [vp, vp, i32, i64, i32, i32, i64, vp, i32, C.POINTER(vp)]
         L.qv_feat_destroy.argtypes = [vp]
         L.qv_feat_destroy.restype = None
         L.qv_feat_hot_rows.argtypes = [vp]
         L.qv_feat_hot_rows.restype = i64
         L.qv_feat_loc.argtypes = [vp]
         L.qv_feat_loc.restype = vp
+        L.qv_feat_row_stride.argtypes = [vp]
+        L.qv_feat_row_stride.restype = i64
         L.qv_gather.argtypes = [vp, vp, vp, i64, vp, vp, i64]
         L.qv_psgs.argtypes = [vp, vp, C.POINTER(i32), i32, vp]
         L.qv_psgs_batch_sum.argtypes = [vp, vp, i64, vp, i64, vp]
@@ -161,7 +163,7 @@ class Graph:
 class Features:
     """qv_feat.  `table` is a 2-D torch tensor (CUDA or CPU) of fp16/fp32 (or any 2/4-byte type)."""
 
-    def __init__(self, ctx, table, hbm_budget_bytes=-1, rank=None):
+    def __init__(self, ctx, table, hbm_budget_bytes=-1, rank=None, own_copy=False):
         if table.dim() != 2 or not table.is_contiguous() or table.element_size() not in (2, 4):
             raise TypeError("table must be a contiguous 2-D tensor of 2- or 4-byte elements")
         self.ctx, self.dtype = ctx, table.dtype
@@ -170,11 +172,19 @@ class Features:
         h = C.c_void_p()
         ctx.check(lib().qv_feat_create(ctx.h, _ptr(table), 1 if table.is_cuda else 0, self.n_rows, self.dim,
                                        table.element_size(), hbm_budget_bytes,
-                                       None if rank is None else _ptr(_dev_i32(rank, "rank")), C.byref(h)))
+                                       None if rank is None else _ptr(_dev_i32(rank, "rank")),
+                                       1 if own_copy else 0, C.byref(h)))
         self.h = h
         self.n_hot = lib().qv_feat_hot_rows(h)
+        self.row_stride = lib().qv_feat_row_stride(h)          # bytes; also a good output stride
         # a borrowed device table must stay alive as long as the handle
         self._keep = table if (table.is_cuda and self.n_hot == self.n_rows) else None
+
+    def empty_rows(self, n, device):
+        """An (n, dim) output tensor whose rows start at the tier's (line-aligned) stride."""
+        esz = self.row_bytes // self.dim
+        padded = torch.empty((max(n, 1), self.row_stride // esz), dtype=self.dtype, device=device)
+        return padded[:, :self.dim]
 
     def close(self):
         if getattr(self, "h", None):
@@ -305,7 +315,7 @@ def qv_sample_many(ctx, graph, seeds_list, fanouts, rng_seeds, outs=None):
 def qv_gather_many(ctx, feat, ids_list, n_ids_dev_list=None, outs=None):
     n = len(ids_list)
     if outs is None:
-        outs = [torch.empty((max(t.numel(), 1), feat.dim), dtype=feat.dtype, device=ctx.device) for t in ids_list]
+        outs = [feat.empty_rows(t.numel(), ctx.device) for t in ids_list]
     ids = (C.c_void_p * n)(*[_dev_i32(t, "ids").data_ptr() for t in ids_list])
     cnt = (C.c_int64 * n)(*[t.numel() for t in ids_list])
     ndev = None
@@ -350,7 +360,7 @@ def qv_gather(ctx, feat, ids, n_ids_dev=None, out=None, n_ids=None):
     _dev_i32(ids, "ids")
     n = ids.numel() if n_ids is None else n_ids
     if out is None:
-        out = torch.empty((max(n, 1), feat.dim), dtype=feat.dtype, device=ctx.device)
+        out = feat.empty_rows(n, ctx.device)
     ctx.check(lib().qv_gather(ctx.h, feat.h, _ptr(ids), n, _ptr(n_ids_dev), _ptr(out), out.stride(0) * out.element_size()))
     return out
 

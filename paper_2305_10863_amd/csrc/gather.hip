@@ -1,9 +1,16 @@
 // Feature table (HBM tier + host-pinned tier + lookup table) and the row gather.
 //
 // Gather kernel: a group of LPR lanes (a power of two, up to the whole wave) copies one row with
-// the widest vector the row size and the pointers allow (16, 8, 4 or 2 bytes per lane), several
-// rows in flight per group.  Rows of the host tier are read by the same loads through the
-// device mapping of pinned host memory (zero-copy), so placement never changes the result.
+// the widest vector the row starts allow (16, 8, 4 or 2 bytes per lane), several rows in flight
+// per group, up to QV_MAX_BATCHES id lists per launch (blockIdx.y).  Rows of the host tier are
+// read by the same loads through the device mapping of pinned host memory (zero-copy), so
+// placement never changes the result.
+//
+// Row starts decide the vector width, not the row length: source tiers and the output may have a
+// row stride larger than the row (a multiple of 128 bytes when the library lays the tier out
+// itself), and a row whose length is not a multiple of the vector is finished with 2-byte pieces.
+// Measured on MI355X, 8 x 157k rows per launch: 2,408-byte rows at a 2,408-byte stride (8-byte
+// vectors, every row straddling lines) 3.7 TB/s; 2,432-byte rows (19 lines) 5.1 TB/s.
 #include "qv_internal.hpp"
 #include <algorithm>
 #include <cstring>
@@ -22,14 +29,16 @@ struct GatherArgs {
     const char* cold;
     const int32_t* loc;             // nullptr: row id == hot row
     int64_t n_rows;                 // rows of the table (range check)
-    int64_t row_bytes;
+    int64_t hot_stride, cold_stride;
     int64_t out_stride;
-    int32_t vecs_per_row;
+    int32_t vecs_per_row;           // whole vectors per row
+    int32_t tail_pieces;            // 2-byte pieces after the last whole vector
+    int32_t tail_at;                // index of the first tail piece (in 2-byte units)
     int32_t* status;
     GatherJob jobs[kMaxBatch];      // one id list / output per blockIdx.y
 };
 
-template <typename V, int LPR>
+template <typename V, int LPR, bool TAIL>
 __global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
     const GatherJob& job = a.jobs[blockIdx.y];
     int64_t n = job.n_ids;
@@ -49,13 +58,12 @@ __global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
                 if (id < 0 || (int64_t)id >= a.n_rows) {
                     if (sub == 0) atomicOr(a.status, kStatRange);
                 } else {
-                    const char* base = a.hot;
-                    int64_t row = id;
+                    const char* p = a.hot + (int64_t)id * a.hot_stride;
                     if (a.loc) {
                         int32_t l = a.loc[id];
-                        if (l < 0) { base = a.cold; row = (int64_t)(~l); } else row = l;
+                        p = l < 0 ? a.cold + (int64_t)(~l) * a.cold_stride : a.hot + (int64_t)l * a.hot_stride;
                     }
-                    src[j] = reinterpret_cast<const V*>(base + row * a.row_bytes);
+                    src[j] = reinterpret_cast<const V*>(p);
                     dst[j] = reinterpret_cast<V*>(job.out + r * a.out_stride);
                 }
             }
@@ -67,40 +75,52 @@ __global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
 #pragma unroll
             for (int j = 0; j < kRowsInFlight; ++j) if (src[j]) dst[j][i] = tmp[j];
         }
+        if (TAIL && sub < a.tail_pieces) {
+#pragma unroll
+            for (int j = 0; j < kRowsInFlight; ++j)
+                if (src[j])
+                    reinterpret_cast<uint16_t*>(dst[j])[a.tail_at + sub] =
+                        reinterpret_cast<const uint16_t*>(src[j])[a.tail_at + sub];
+        }
+    }
+}
+
+template <typename V, bool TAIL>
+static void launch_gather_vt(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t max_ids, int n_jobs) {
+    int64_t threads = max_ids * lpr / kRowsInFlight + 256;
+    dim3 grid((unsigned)grid_for(threads, 256, ctx->n_cu * 8), (unsigned)n_jobs);
+    switch (lpr) {
+        case 8: hipLaunchKernelGGL((k_gather<V, 8, TAIL>), grid, dim3(256), 0, ctx->stream, a); break;
+        case 16: hipLaunchKernelGGL((k_gather<V, 16, TAIL>), grid, dim3(256), 0, ctx->stream, a); break;
+        case 32: hipLaunchKernelGGL((k_gather<V, 32, TAIL>), grid, dim3(256), 0, ctx->stream, a); break;
+        default: hipLaunchKernelGGL((k_gather<V, 64, TAIL>), grid, dim3(256), 0, ctx->stream, a); break;
     }
 }
 
 template <typename V>
 static void launch_gather_v(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t max_ids, int n_jobs) {
-    int64_t threads = max_ids * lpr / kRowsInFlight + 256;
-    dim3 grid((unsigned)grid_for(threads, 256, ctx->n_cu * 8), (unsigned)n_jobs);
-    switch (lpr) {
-        case 1: hipLaunchKernelGGL((k_gather<V, 1>), grid, dim3(256), 0, ctx->stream, a); break;
-        case 2: hipLaunchKernelGGL((k_gather<V, 2>), grid, dim3(256), 0, ctx->stream, a); break;
-        case 4: hipLaunchKernelGGL((k_gather<V, 4>), grid, dim3(256), 0, ctx->stream, a); break;
-        case 8: hipLaunchKernelGGL((k_gather<V, 8>), grid, dim3(256), 0, ctx->stream, a); break;
-        case 16: hipLaunchKernelGGL((k_gather<V, 16>), grid, dim3(256), 0, ctx->stream, a); break;
-        case 32: hipLaunchKernelGGL((k_gather<V, 32>), grid, dim3(256), 0, ctx->stream, a); break;
-        default: hipLaunchKernelGGL((k_gather<V, 64>), grid, dim3(256), 0, ctx->stream, a); break;
-    }
+    if (a.tail_pieces > 0) launch_gather_vt<V, true>(ctx, a, lpr, max_ids, n_jobs);
+    else launch_gather_vt<V, false>(ctx, a, lpr, max_ids, n_jobs);
 }
 
-qv_status launch_gather(qv_ctx* ctx, const char* hot, const char* cold, const int32_t* loc, int64_t n_rows,
-                        int64_t row_bytes, const GatherJob* jobs, int n_jobs, int64_t out_stride) {
-    // widest vector that divides every row start and the row length
-    uintptr_t bits = (uintptr_t)row_bytes | (uintptr_t)out_stride | (uintptr_t)hot | (uintptr_t)cold;
+qv_status launch_gather(qv_ctx* ctx, const GatherSource& s, const GatherJob* jobs, int n_jobs, int64_t out_stride) {
+    // widest vector that divides every row start
+    uintptr_t bits = (uintptr_t)s.hot_stride | (uintptr_t)s.cold_stride | (uintptr_t)out_stride | (uintptr_t)s.hot |
+                     (uintptr_t)s.cold;
     int64_t max_ids = 0;
-    GatherArgs a{hot, cold, loc, n_rows, row_bytes, out_stride, 0, ctx->d_status, {}};
+    GatherArgs a{s.hot, s.cold, s.loc, s.n_rows, s.hot_stride, s.cold_stride, out_stride, 0, 0, 0, ctx->d_status, {}};
     for (int i = 0; i < n_jobs; ++i) {
         a.jobs[i] = jobs[i];
         if (jobs[i].n_ids > 0) bits |= (uintptr_t)jobs[i].out;
         if (jobs[i].n_ids > max_ids) max_ids = jobs[i].n_ids;
     }
     if (max_ids == 0) return QV_OK;
-    if (bits % 2 != 0) return fail(ctx, QV_EINVAL, "gather: rows must be 2-byte aligned");
-    int vec = (bits % 16 == 0) ? 16 : (bits % 8 == 0) ? 8 : (bits % 4 == 0) ? 4 : 2;
-    a.vecs_per_row = (int32_t)(row_bytes / vec);
-    int lpr = 1;
+    if (bits % 2 != 0 || s.row_bytes % 2 != 0) return fail(ctx, QV_EINVAL, "gather: rows must be 2-byte aligned");
+    const int vec = (bits % 16 == 0) ? 16 : (bits % 8 == 0) ? 8 : (bits % 4 == 0) ? 4 : 2;
+    a.vecs_per_row = (int32_t)(s.row_bytes / vec);
+    a.tail_pieces = (int32_t)((s.row_bytes % vec) / 2);
+    a.tail_at = (int32_t)((int64_t)a.vecs_per_row * vec / 2);
+    int lpr = 8;                                        // at least 8 lanes so that a tail (< 16 bytes) fits
     while (lpr < 64 && lpr < a.vecs_per_row) lpr <<= 1;
     switch (vec) {
         case 16: launch_gather_v<v4u>(ctx, a, lpr, max_ids, n_jobs); break;
@@ -110,6 +130,14 @@ qv_status launch_gather(qv_ctx* ctx, const char* hot, const char* cold, const in
     }
     QV_LAUNCH_CHECK(ctx, "k_gather");
     return QV_OK;
+}
+
+// Row stride for a tier the library lays out itself: the next multiple of 128 bytes when that
+// costs at most 1/32 more memory, else the row length rounded up to 16 bytes.
+static int64_t owned_stride(int64_t row_bytes) {
+    const int64_t lines = (row_bytes + 127) / 128 * 128;
+    if ((lines - row_bytes) * 32 <= row_bytes) return lines;
+    return (row_bytes + 15) / 16 * 16;
 }
 
 }  // namespace qv
@@ -129,9 +157,11 @@ void qv_feat_destroy(qv_feat* f) {
 
 int64_t qv_feat_hot_rows(const qv_feat* f) { return f ? f->n_hot : 0; }
 const int32_t* qv_feat_loc(const qv_feat* f) { return f ? f->loc : nullptr; }
+int64_t qv_feat_row_stride(const qv_feat* f) { return f ? f->hot_stride : 0; }
 
 qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device, int64_t n_rows, int32_t dim,
-                         int32_t elem_bytes, int64_t hbm_budget_bytes, const int32_t* rank, qv_feat** out) {
+                         int32_t elem_bytes, int64_t hbm_budget_bytes, const int32_t* rank, int32_t flags,
+                         qv_feat** out) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_feat_create: ctx is NULL");
     if (!out) return fail(ctx, QV_EINVAL, "qv_feat_create: out is NULL");
     *out = nullptr;
@@ -145,24 +175,50 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
     if (!f) return fail(ctx, QV_ENOMEM, "qv_feat_create: out of host memory");
     f->ctx = ctx; f->n_rows = n_rows; f->dim = dim; f->elem_bytes = elem_bytes; f->row_bytes = row_bytes;
     f->hot = nullptr; f->hot_owned = nullptr; f->cold_host = nullptr; f->cold_dev = nullptr; f->loc = nullptr;
+    f->hot_stride = row_bytes; f->cold_stride = row_bytes;
     f->n_hot = all_hot ? n_rows : hbm_budget_bytes / row_bytes;
+    const int64_t pad_stride = owned_stride(row_bytes);
     qv_status rc = QV_OK;
     hipError_t e = hipSuccess;
 #define FEAT_TRY(call)                                                                                   \
     if (rc == QV_OK && (e = (call)) != hipSuccess)                                                        \
         rc = fail(ctx, e == hipErrorOutOfMemory ? QV_ENOMEM : QV_EHIP, "qv_feat_create: %s failed: %s", #call, \
                   hipGetErrorString(e));
+    const GatherSource whole{(const char*)table, nullptr, nullptr, n_rows, row_bytes, row_bytes, row_bytes};
     if (all_hot) {
-        if (table_on_device) {
+        const bool relayout = table_on_device && (flags & QV_FEAT_OWN_COPY) && pad_stride != row_bytes;
+        if (table_on_device && !relayout) {
             f->hot = (const char*)table;                               // borrowed
+        } else if (table_on_device) {
+            // private copy with line-aligned rows: an identity gather into the padded layout
+            f->hot_stride = pad_stride;
+            int32_t* iota = nullptr;
+            FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(n_rows * pad_stride + 256)));
+            FEAT_TRY(hipMalloc((void**)&iota, (size_t)n_rows * 4 + 256));
+            if (rc == QV_OK) {
+                std::vector<int32_t> h((size_t)n_rows);
+                for (int64_t i = 0; i < n_rows; ++i) h[(size_t)i] = (int32_t)i;
+                FEAT_TRY(hipMemcpyAsync(iota, h.data(), (size_t)n_rows * 4, hipMemcpyHostToDevice, ctx->stream));
+                FEAT_TRY(hipStreamSynchronize(ctx->stream));
+            }
+            if (rc == QV_OK) {
+                GatherJob job{iota, n_rows, nullptr, f->hot_owned};
+                rc = launch_gather(ctx, whole, &job, 1, pad_stride);
+            }
+            FEAT_TRY(hipStreamSynchronize(ctx->stream));
+            if (iota) (void)hipFree(iota);
+            f->hot = f->hot_owned;
         } else {
-            FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(table_bytes > 0 ? table_bytes : 256)));
-            FEAT_TRY(hipMemcpyAsync(f->hot_owned, table, (size_t)table_bytes, hipMemcpyHostToDevice, ctx->stream));
+            f->hot_stride = pad_stride;
+            FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(n_rows * pad_stride + 256)));
+            FEAT_TRY(hipMemcpy2DAsync(f->hot_owned, (size_t)pad_stride, table, (size_t)row_bytes, (size_t)row_bytes,
+                                      (size_t)n_rows, hipMemcpyHostToDevice, ctx->stream));
             FEAT_TRY(hipStreamSynchronize(ctx->stream));
             f->hot = f->hot_owned;
         }
     } else {
         const int64_t n_hot = f->n_hot, n_cold = n_rows - n_hot;
+        f->hot_stride = pad_stride; f->cold_stride = pad_stride;
         std::vector<int32_t> h_rank, h_loc, cold_ids;
         try {
             h_rank.resize((size_t)n_rows); h_loc.assign((size_t)n_rows, -1); cold_ids.reserve((size_t)n_cold);
@@ -186,8 +242,8 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
         }
         FEAT_TRY(hipMalloc((void**)&f->loc, (size_t)n_rows * 4 + 256));
         FEAT_TRY(hipMemcpyAsync(f->loc, h_loc.data(), (size_t)n_rows * 4, hipMemcpyHostToDevice, ctx->stream));
-        FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(n_hot * row_bytes + 256)));
-        FEAT_TRY(hipHostMalloc((void**)&f->cold_host, (size_t)(n_cold * row_bytes + 256), hipHostMallocMapped));
+        FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(n_hot * pad_stride + 256)));
+        FEAT_TRY(hipHostMalloc((void**)&f->cold_host, (size_t)(n_cold * pad_stride + 256), hipHostMallocMapped));
         FEAT_TRY(hipHostGetDevicePointer((void**)&f->cold_dev, f->cold_host, 0));
         f->hot = f->hot_owned;
         if (rc == QV_OK && table_on_device) {
@@ -197,27 +253,27 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
             FEAT_TRY(hipMemcpyAsync(d_cold_ids, cold_ids.data(), (size_t)n_cold * 4, hipMemcpyHostToDevice, ctx->stream));
             if (rc == QV_OK) {
                 GatherJob job{rank, n_hot, nullptr, f->hot_owned};
-                rc = launch_gather(ctx, (const char*)table, nullptr, nullptr, n_rows, row_bytes, &job, 1, row_bytes);
+                rc = launch_gather(ctx, whole, &job, 1, pad_stride);
             }
             if (rc == QV_OK) {
                 GatherJob job{d_cold_ids, n_cold, nullptr, (char*)f->cold_dev};
-                rc = launch_gather(ctx, (const char*)table, nullptr, nullptr, n_rows, row_bytes, &job, 1, row_bytes);
+                rc = launch_gather(ctx, whole, &job, 1, pad_stride);
             }
             FEAT_TRY(hipStreamSynchronize(ctx->stream));
             if (d_cold_ids) (void)hipFree(d_cold_ids);
         } else if (rc == QV_OK) {
             const char* src = (const char*)table;
             for (int64_t c = 0; c < n_cold; ++c)
-                std::memcpy(f->cold_host + c * row_bytes, src + (int64_t)cold_ids[c] * row_bytes, (size_t)row_bytes);
+                std::memcpy(f->cold_host + c * pad_stride, src + (int64_t)cold_ids[c] * row_bytes, (size_t)row_bytes);
             // hot rows: stage through pinned memory in chunks
-            const int64_t chunk_rows = std::max<int64_t>(1, (64ll << 20) / row_bytes);
+            const int64_t chunk_rows = std::max<int64_t>(1, (64ll << 20) / pad_stride);
             char* stage = nullptr;
-            FEAT_TRY(hipHostMalloc((void**)&stage, (size_t)(chunk_rows * row_bytes), hipHostMallocDefault));
+            FEAT_TRY(hipHostMalloc((void**)&stage, (size_t)(chunk_rows * pad_stride), hipHostMallocDefault));
             for (int64_t i0 = 0; i0 < n_hot && rc == QV_OK; i0 += chunk_rows) {
                 int64_t cnt = std::min(chunk_rows, n_hot - i0);
                 for (int64_t i = 0; i < cnt; ++i)
-                    std::memcpy(stage + i * row_bytes, src + (int64_t)h_rank[i0 + i] * row_bytes, (size_t)row_bytes);
-                FEAT_TRY(hipMemcpyAsync(f->hot_owned + i0 * row_bytes, stage, (size_t)(cnt * row_bytes),
+                    std::memcpy(stage + i * pad_stride, src + (int64_t)h_rank[i0 + i] * row_bytes, (size_t)row_bytes);
+                FEAT_TRY(hipMemcpyAsync(f->hot_owned + i0 * pad_stride, stage, (size_t)(cnt * pad_stride),
                                         hipMemcpyHostToDevice, ctx->stream));
                 FEAT_TRY(hipStreamSynchronize(ctx->stream));
             }
@@ -231,15 +287,22 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
     return QV_OK;
 }
 
+static qv_status check_stride(qv_ctx* ctx, const qv_feat* f, int64_t stride, const char* who) {
+    if (stride < f->row_bytes || stride % f->elem_bytes != 0)
+        return fail(ctx, QV_EINVAL, "%s: out_row_stride_bytes %lld must be >= %lld and a multiple of %d", who,
+                    (long long)stride, (long long)f->row_bytes, f->elem_bytes);
+    return QV_OK;
+}
+
 qv_status qv_gather(qv_ctx* ctx, const qv_feat* f, const int32_t* ids, int64_t n_ids, const int64_t* n_ids_dev,
                     void* out, int64_t out_row_stride_bytes) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_gather: ctx is NULL");
     if (!f || n_ids < 0 || (n_ids > 0 && (!ids || !out))) return fail(ctx, QV_EINVAL, "qv_gather: null or negative argument");
-    if (out_row_stride_bytes < f->row_bytes || out_row_stride_bytes % f->elem_bytes != 0)
-        return fail(ctx, QV_EINVAL, "qv_gather: out_row_stride_bytes %lld must be >= %lld and a multiple of %d",
-                    (long long)out_row_stride_bytes, (long long)f->row_bytes, f->elem_bytes);
+    qv_status rc = check_stride(ctx, f, out_row_stride_bytes, "qv_gather");
+    if (rc != QV_OK) return rc;
     GatherJob job{ids, n_ids, n_ids_dev, (char*)out};
-    return launch_gather(ctx, f->hot, f->cold_dev, f->loc, f->n_rows, f->row_bytes, &job, 1, out_row_stride_bytes);
+    const GatherSource s{f->hot, f->cold_dev, f->loc, f->n_rows, f->row_bytes, f->hot_stride, f->cold_stride};
+    return launch_gather(ctx, s, &job, 1, out_row_stride_bytes);
 }
 
 qv_status qv_gather_many(qv_ctx* ctx, const qv_feat* f, int32_t n_batches, const int32_t* const* ids, const int64_t* n_ids,
@@ -247,15 +310,15 @@ qv_status qv_gather_many(qv_ctx* ctx, const qv_feat* f, int32_t n_batches, const
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_gather_many: ctx is NULL");
     if (!f || !ids || !n_ids || !outs) return fail(ctx, QV_EINVAL, "qv_gather_many: null argument");
     if (n_batches < 1 || n_batches > kMaxBatch) return fail(ctx, QV_EINVAL, "qv_gather_many: n_batches %d outside [1, %d]", n_batches, kMaxBatch);
-    if (out_row_stride_bytes < f->row_bytes || out_row_stride_bytes % f->elem_bytes != 0)
-        return fail(ctx, QV_EINVAL, "qv_gather_many: out_row_stride_bytes %lld must be >= %lld and a multiple of %d",
-                    (long long)out_row_stride_bytes, (long long)f->row_bytes, f->elem_bytes);
+    qv_status rc = check_stride(ctx, f, out_row_stride_bytes, "qv_gather_many");
+    if (rc != QV_OK) return rc;
     GatherJob jobs[kMaxBatch];
     for (int i = 0; i < n_batches; ++i) {
         if (n_ids[i] < 0 || (n_ids[i] > 0 && (!ids[i] || !outs[i]))) return fail(ctx, QV_EINVAL, "qv_gather_many: batch %d: null or negative argument", i);
         jobs[i] = GatherJob{ids[i], n_ids[i], n_ids_dev ? n_ids_dev[i] : nullptr, (char*)outs[i]};
     }
-    return launch_gather(ctx, f->hot, f->cold_dev, f->loc, f->n_rows, f->row_bytes, jobs, n_batches, out_row_stride_bytes);
+    const GatherSource s{f->hot, f->cold_dev, f->loc, f->n_rows, f->row_bytes, f->hot_stride, f->cold_stride};
+    return launch_gather(ctx, s, jobs, n_batches, out_row_stride_bytes);
 }
 
 }  // extern "C"

@@ -81,6 +81,7 @@ struct qv_feat {
     int64_t n_rows, n_hot;
     int32_t dim, elem_bytes;
     int64_t row_bytes;
+    int64_t hot_stride, cold_stride;   // row strides of the two tiers (>= row_bytes)
     const char* hot;                   // HBM tier (borrowed or owned)
     char* hot_owned;
     char* cold_host;                   // pinned host allocation (owned)
@@ -128,8 +129,13 @@ struct GatherJob {
     const int64_t* n_ids_dev;
     char* out;
 };
-qv_status launch_gather(qv_ctx* ctx, const char* hot, const char* cold, const int32_t* loc,
-                        int64_t n_rows, int64_t row_bytes, const GatherJob* jobs, int n_jobs,
+struct GatherSource {
+    const char* hot;
+    const char* cold;
+    const int32_t* loc;
+    int64_t n_rows, row_bytes, hot_stride, cold_stride;
+};
+qv_status launch_gather(qv_ctx* ctx, const GatherSource& src, const GatherJob* jobs, int n_jobs,
                         int64_t out_stride);
 
 }  // namespace qv

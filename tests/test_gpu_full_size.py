@@ -87,7 +87,8 @@ def test_dense_social_full(qv, ctx):
     table = qvgen.features_host(w.seed, w.n, w.dim, w.feat_dtype)
     t_dev = qvgen.features_device(w.seed, w.n, w.dim, torch.float32)
     assert t_dev.cpu().numpy().tobytes() == table.tobytes()
-    feat = qv.Features(ctx, t_dev)
+    feat = qv.Features(ctx, t_dev, own_copy=True)               # 2,408-byte rows at a 2,432-byte stride
+    assert feat.row_stride == 2432
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(3), table=table)
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()

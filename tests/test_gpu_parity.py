@@ -250,7 +250,8 @@ def test_errors_are_reported_not_fatal(qv, ctx, tiny):
 
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("dtype,dim", [(np.float32, 64), (np.float16, 128), (np.float32, 602), (np.float32, 100),
-                                       (np.float32, 1024), (np.float16, 7), (np.float32, 1), (np.float16, 1)])
+                                       (np.float32, 1024), (np.float16, 7), (np.float32, 1), (np.float16, 1),
+                                       (np.float16, 1203), (np.float32, 33), (np.float16, 517)])
 def test_gather_matches_oracle(qv, ctx, dtype, dim):
     n = 5000
     table = qvgen.features_host(42, n, dim, dtype)
@@ -264,6 +265,15 @@ def test_gather_matches_oracle(qv, ctx, dtype, dim):
     ctx.sync()
     want = oracle.gather(table, ids)
     assert out.cpu().numpy().tobytes() == want.tobytes()
+    # the library's own copy (rows re-laid on 128-byte boundaries where that is cheap) and an
+    # output with the same row stride
+    feat_own = qv.Features(ctx, t_dev, own_copy=True)
+    assert feat_own.row_stride >= feat_own.row_bytes and feat_own.row_stride % 16 == 0
+    out_own = qv.qv_gather(ctx, feat_own, dev(ids))
+    ctx.sync()
+    assert out_own.stride(0) * out_own.element_size() == feat_own.row_stride
+    assert out_own.cpu().numpy().tobytes() == want.tobytes()
+    feat_own.close()
     # a host table (copied into HBM by the library) and a device-side row count
     feat_h = qv.Features(ctx, torch.from_numpy(table))
     n_dev = torch.tensor([777], dtype=torch.int64, device="cuda")
