@@ -272,7 +272,7 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": W,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int32 ids, %s rows copied bit for bit" % ("f16" if tdtype == torch.float16 else "f32"),
+        "dtype": "int32",       # ids, offsets and counters; feature rows are copied bit for bit
         "data": "synthetic",
         "config": {"workload": "%s: %d nodes, %d edges, %s x %d features, fanouts %s, batch %d%s" %
                    (w.name, w.n, n_edges_graph, "fp16" if tdtype == torch.float16 else "fp32", w.dim, w.fanouts,

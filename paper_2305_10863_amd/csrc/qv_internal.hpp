@@ -10,9 +10,7 @@
 namespace qv {
 
 constexpr int kWave = 64;               // CDNA wavefront width
-constexpr int kScanBlock = 256;
-constexpr int kItemsPerThread = 4;
-constexpr int kTileItems = kScanBlock * kItemsPerThread;   // positions per dedup tile
+constexpr int kScanBlock = 256;         // threads per block of the scan kernels
 constexpr int kMaxBatch = QV_MAX_BATCHES;
 
 // deferred device status bits (qv_ctx::d_status[0])
