@@ -39,6 +39,88 @@ def algorithmic_bytes(n_frontier_entries, n_edges, n_unique, n_rows, row_bytes, 
     return sample, reindex, gather
 
 
+def psgs_curve(qv, qvgen, w, ctx, g, feat, Q, rowptr, col, tdtype):
+    """One batch at a time: PSGS summed over the seeds (the paper's dispatch signal) against the
+    measured latency of sample + gather on the GPU and of the oracle on one host core."""
+    import numpy as np
+    import torch
+    import oracle
+    assert Q is not None, "--psgs-curve needs the PSGS pass (do not pass --no-metrics)"
+    sub_rows = min(w.n, 4_000_000)
+    host_table = qvgen.features_host(w.seed, sub_rows, w.dim, w.feat_dtype)
+    points = []
+    for bs in (1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1024, 2048, 4096):
+        buf = qv.SampleBuffers(ctx, bs, w.fanouts, w.n)
+        rows = feat.empty_rows(buf.caps[0], "cuda")
+        plan = qv.ManyPlan(ctx, g, feat, [buf], [rows], w.fanouts)
+        gpu_ms, cpu_ms, psgs, edges = [], [], [], []
+        for rep in range(12):
+            seeds = w.seeds(10_000 + rep, bs)
+            d_seeds = torch.from_numpy(seeds).cuda()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(ctx.stream)
+            plan.run([d_seeds], [w.rng_seed(rep)])
+            e1.record(ctx.stream)
+            ctx.sync()
+            s = qv.qv_psgs_batch_sum(ctx, Q, d_seeds)
+            ctx.sync()
+            t1 = time.perf_counter()
+            o = oracle.sample(rowptr, col, seeds, w.fanouts, w.rng_seed(rep))
+            oracle.gather(host_table, o["n_id"] % sub_rows)
+            t2 = time.perf_counter()
+            if rep >= 2:                                   # the first runs size the scratch arena
+                gpu_ms.append(e0.elapsed_time(e1)); cpu_ms.append((t2 - t1) * 1e3)
+                psgs.append(s.item()); edges.append(int(o["edge_off"][-1]) + len(o["n_id"]))
+        points.append({"batch": bs, "psgs_sum": round(float(np.mean(psgs)), 1),
+                       "sampled_nodes_plus_edges": round(float(np.mean(edges)), 1),
+                       "gpu_ms_avg": round(float(np.mean(gpu_ms)), 4), "gpu_ms_max": round(float(np.max(gpu_ms)), 4),
+                       "cpu_oracle_ms_avg": round(float(np.mean(cpu_ms)), 4), "cpu_oracle_ms_max": round(float(np.max(cpu_ms)), 4)})
+        log(str(points[-1]))
+    print(json.dumps({"metric": "latency_vs_psgs", "workload": w.name, "cpu": "oracle, 1 core", "points": points}), flush=True)
+
+
+def placement_ablation(qv, qvgen, w, ctx, g, table, P_pop, rowptr, col, tdtype):
+    """Hot sets of the same size chosen by four rankings; HBM hit rate over Zipf-popular batches."""
+    import numpy as np
+    import torch
+    assert w.hbm_budget is not None and P_pop is not None, "--placement-ablation needs the tiered workload and the FAP pass"
+    deg_out = torch.from_numpy(np.diff(rowptr).astype(np.float32)).cuda()
+    deg_in = torch.from_numpy(np.bincount(col, minlength=w.n).astype(np.float32)).cuda()
+    rankings = {"fap_seed_popularity": P_pop, "fap_uniform_seeds": qv.qv_access_prob(ctx, g, w.fanouts),
+                "in_degree": deg_in, "out_degree": deg_out}
+    ctx.sync()
+    n_hot = w.hbm_budget // w.row_bytes
+    batches = []
+    for b in range(16):
+        seeds = torch.from_numpy(w.seeds(b)).cuda()
+        out = qv.qv_sample(ctx, g, seeds, w.fanouts, w.rng_seed(b))
+        ctx.sync()
+        U = int(out.node_off[-1].item())
+        batches.append(out.n_id[:U].clone())
+    res = {}
+    for name, score in rankings.items():
+        rank = qv.qv_place_rank(ctx, score)
+        ctx.sync()
+        hot = torch.zeros(w.n, dtype=torch.bool, device="cuda")
+        hot[rank[:n_hot].long()] = True
+        hit = float(np.mean([hot[ids.long()].float().mean().item() for ids in batches]))
+        feat = qv.Features(ctx, table, hbm_budget_bytes=w.hbm_budget, rank=rank)
+        outs = [feat.empty_rows(ids.numel(), "cuda") for ids in batches[:8]]
+        qv.qv_gather_many(ctx, feat, batches[:8], None, outs)
+        ctx.sync()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(ctx.stream)
+        qv.qv_gather_many(ctx, feat, batches[:8], None, outs)
+        e1.record(ctx.stream)
+        ctx.sync()
+        rows = sum(ids.numel() for ids in batches[:8])
+        res[name] = {"hbm_hit_rate": round(hit, 4), "gather_ms_8_batches": round(e0.elapsed_time(e1), 3),
+                     "host_link_GBps": round((1 - hit) * rows * w.row_bytes / e0.elapsed_time(e1) / 1e6, 2)}
+        log("%s: %s" % (name, res[name]))
+        feat.close()
+    print(json.dumps({"metric": "placement_ablation", "workload": w.name, "hot_rows": int(n_hot), "rankings": res}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -54,6 +136,14 @@ def main():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-metrics", action="store_true", help="skip the PSGS / FAP whole-graph passes")
+    ap.add_argument("--psgs-curve", action="store_true",
+                    help="instead of the benchmark: latency of one batch against the PSGS summed over its seeds "
+                         "(Section 4.2.1), for batch sizes 1..4096, GPU path and CPU oracle side by side")
+    ap.add_argument("--placement-ablation", action="store_true",
+                    help="instead of the benchmark (tiered workload): HBM hit rate and gather time for hot sets "
+                         "ranked by FAP under the seed popularity, FAP under uniform seeds, in-degree, out-degree")
+    ap.add_argument("--graph-in-host-memory", action="store_true",
+                    help="keep rowptr / col in pinned host memory and sample through the host link (Section 4.3 (3))")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB copy kernel (copy_bytes) so that hardware byte counters can be scaled")
     args = ap.parse_args()
@@ -80,7 +170,10 @@ def main():
     n_edges_graph = len(col)
     log("graph %s: %d nodes, %d edges generated in %.1fs" % (w.name, w.n, n_edges_graph, time.time() - t0))
     t0 = time.time()
-    d_rowptr, d_col = torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda()
+    if args.graph_in_host_memory:      # zero-copy topology: the kernels read it over the host link
+        d_rowptr, d_col = torch.from_numpy(rowptr).pin_memory(), torch.from_numpy(col).pin_memory()
+    else:
+        d_rowptr, d_col = torch.from_numpy(rowptr).cuda(), torch.from_numpy(col).cuda()
     tdtype = torch.float16 if w.feat_dtype == np.float16 else torch.float32
     table = qvgen.features_device(w.seed, w.n, w.dim, tdtype)
     torch.cuda.synchronize()
@@ -126,7 +219,8 @@ def main():
                 Qdev = res.clone()
         log("psgs %.2f ms, access_prob %.2f ms over the whole graph" % (extra["psgs_ms"], extra["access_prob_ms"]))
 
-    if tiered:
+    table_for_ablation = table if args.placement_ablation else None
+    if tiered and not args.placement_ablation:
         if Pdev is None:
             Pdev = qv.qv_access_prob(ctx0, g, w.fanouts)
         rank = qv.qv_place_rank(ctx0, Pdev)
@@ -150,8 +244,15 @@ def main():
         torch.cuda.synchronize()
         extra["host_link_pinned_copy_GBps"] = round(3 * pin.numel() * 4 / e0.elapsed_time(e1) / 1e6, 2)
         del pin, dst
-    else:
+    elif not args.placement_ablation:
         feat = qv.Features(ctx0, table, own_copy=True)     # rows re-laid on 128-byte boundaries where cheap
+    else:
+        feat = None
+
+    if args.psgs_curve:
+        return psgs_curve(qv, qvgen, w, ctx0, g, feat, Qdev, rowptr, col, tdtype)
+    if args.placement_ablation:
+        return placement_ablation(qv, qvgen, w, ctx0, g, table_for_ablation, Pdev, rowptr, col, tdtype)
 
     # ---- batches, contexts, buffers -------------------------------------------------------------
     import copy

@@ -92,7 +92,9 @@ qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts /*[host]*/, i
 
 /* Wrap a CSR of OUT-edges: neighbours of v are col[rowptr[v] .. rowptr[v+1]).  rowptr [dev] has
  * n_nodes+1 entries of rowptr_bits (32 or 64) bits; col [dev] has n_edges int32 entries.  The
- * arrays are borrowed and must outlive the handle.  With validate != 0 the arrays are checked
+ * arrays are borrowed and must outlive the handle.  Either array may instead live in pinned host
+ * memory (hipHostMalloc): the kernels then read the topology over the host link, zero-copy
+ * (Section 4.3 (3): a graph shared from pinned host memory, for graphs larger than HBM).  With validate != 0 the arrays are checked
  * on the device (rowptr[0] == 0, non-decreasing, rowptr[n] == n_edges, 0 <= col < n_nodes) and
  * a malformed graph returns QV_EINVAL; this synchronises once. */
 qv_status qv_csr_create(qv_ctx* ctx, int64_t n_nodes, int64_t n_edges, const void* rowptr,

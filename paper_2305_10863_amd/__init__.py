@@ -140,12 +140,15 @@ class Context:
 
 
 class Graph:
-    """qv_csr over two device tensors (kept alive here)."""
+    """qv_csr over two tensors (kept alive here): CUDA tensors, or pinned CPU tensors for a graph
+    that is read zero-copy over the host link."""
 
     def __init__(self, ctx, rowptr, col, validate=True):
-        if rowptr.dtype not in (torch.int32, torch.int64) or not rowptr.is_cuda or not rowptr.is_contiguous():
-            raise TypeError("rowptr must be a contiguous int32/int64 CUDA tensor")
-        _dev_i32(col, "col")
+        for t, name in ((rowptr, "rowptr"), (col, "col")):
+            if not t.is_contiguous() or not (t.is_cuda or t.is_pinned()):
+                raise TypeError("%s must be a contiguous CUDA tensor or a pinned CPU tensor" % name)
+        if rowptr.dtype not in (torch.int32, torch.int64) or col.dtype != torch.int32:
+            raise TypeError("rowptr must be int32/int64 and col int32")
         self.ctx, self.rowptr, self.col = ctx, rowptr, col
         self.n_nodes, self.n_edges = rowptr.numel() - 1, col.numel()
         h = C.c_void_p()

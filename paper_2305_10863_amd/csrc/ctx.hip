@@ -166,6 +166,22 @@ qv_status qv_csr_create(qv_ctx* ctx, int64_t n_nodes, int64_t n_edges, const voi
         return fail(ctx, QV_EINVAL, "qv_csr_create: rowptr_bits must be 32 or 64");
     if (rowptr_bits == 32 && n_edges >= ((int64_t)1 << 31))
         return fail(ctx, QV_EINVAL, "qv_csr_create: int32 rowptr cannot index %lld edges", (long long)n_edges);
+    // The arrays may live in pinned host memory mapped into the GPU (graphs beyond HBM): kernels
+    // then read them over the host link.  Translate such pointers to their device view.
+    for (const void** pp : {&rowptr, reinterpret_cast<const void**>(&col)}) {
+        if (!*pp) continue;
+        hipPointerAttribute_t attr;
+        hipError_t pe = hipPointerGetAttributes(&attr, *pp);
+        if (pe != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(ctx, QV_EINVAL, "qv_csr_create: an array is neither device memory nor pinned host memory (%s)",
+                        hipGetErrorString(pe));
+        }
+        if (attr.type == hipMemoryTypeHost) {
+            if (!attr.devicePointer) return fail(ctx, QV_EINVAL, "qv_csr_create: pinned host array is not mapped into the device");
+            *pp = attr.devicePointer;
+        }
+    }
     if (validate) {
         qv_status pending = qv_ctx_sync(ctx);       // do not mix with an earlier deferred error
         if (pending != QV_OK) return pending;

@@ -195,6 +195,20 @@ def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
     c.close()
 
 
+def test_graph_in_pinned_host_memory(qv, ctx, tiny):
+    # topology read zero-copy over the host link: same results
+    w, rowptr, col, _ = tiny
+    g = qv.Graph(ctx, torch.from_numpy(rowptr).pin_memory(), torch.from_numpy(col).pin_memory())
+    seeds = w.seeds(5)
+    out = qv.qv_sample(ctx, g, dev(seeds), w.fanouts, 99)
+    Q = qv.qv_psgs(ctx, g, w.fanouts)
+    ctx.sync()
+    assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, w.fanouts, 99))
+    assert rel_err(Q.cpu().numpy(), oracle.psgs(rowptr, col, w.fanouts)) <= REL_TOL
+    with pytest.raises(TypeError):
+        qv.Graph(ctx, torch.from_numpy(rowptr), torch.from_numpy(col))       # pageable host memory
+
+
 def test_sample_degenerate_inputs(qv, ctx):
     rowptr = np.array([0, 0, 2, 2], dtype=np.int64)
     col = np.array([0, 2], dtype=np.int32)
