@@ -300,7 +300,7 @@ def main():
             p.n_seeds[t] = batch
             p.rng[t] = rng_seeds[first + t]
         ev[j][0].record(c.stream)
-        c.check(L.qv_sample_many(c.h, g.h, cnt, p.seed_ptrs, p.n_seeds, p.fan, p.k, p.rng, p.outs))
+        c.check(L.qv_sample_many(c.h, g.h, cnt, p.seed_ptrs, p.n_seeds, p.fan, p.k, p.rng, 0, p.outs))
         ev[j][1].record(c.stream)
         c.check(L.qv_gather_many(c.h, feat.h, cnt, p.ids, p.n_ids, p.n_dev, p.out_ptrs, p.stride))
         ev[j][2].record(c.stream)

@@ -66,7 +66,7 @@ qv_status qv_ctx_sync(qv_ctx* ctx);
 /* Grow the scratch arena now so that later qv_sample / qv_reindex calls with at most `n_seeds`
  * seeds and these fanouts on a graph of `n_nodes` nodes allocate nothing.  Optional. */
 qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts /*[host]*/,
-                         int32_t n_hops, int64_t n_nodes);
+                         int32_t n_hops, int64_t n_nodes, uint32_t flags /* as for qv_sample */);
 
 /* Dedup tables come in two forms.  When n_nodes x 16 bytes x (batches in the call) is at most
  * `bytes`, the table is addressed directly by node id (no probing, one atomic per sampled
@@ -83,8 +83,8 @@ qv_status qv_ctx_set_epoch(qv_ctx* ctx, uint32_t epoch);
  * over all hops, most frontier entries over hops 0..n_hops.  Outputs sized to these bounds can
  * never report QV_ECAPACITY. */
 qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts /*[host]*/, int32_t n_hops,
-                           int64_t n_nodes, int64_t* max_nodes, int64_t* max_edges,
-                           int64_t* max_frontier);
+                           int64_t n_nodes, uint32_t flags /* as for qv_sample */,
+                           int64_t* max_nodes, int64_t* max_edges, int64_t* max_frontier);
 
 /* ---------------------------------------------------------------------------------------------
  * Graph  (paper Section 3.2: the graph topology given at deployment)
@@ -141,12 +141,18 @@ typedef struct {
 
 /* Multi-hop sampling + reindex for one batch of seeds [dev] int32[n_seeds] (repeats allowed;
  * they are merged, first occurrence first).  fanouts [host] int32[n_hops], each in
- * [1, QV_MAX_FANOUT]; 1 <= n_hops <= QV_MAX_HOPS.  Hop k expands exactly F_{k-1}, the distinct
- * nodes hop k-1 produced (layer frontiers: the process the PSGS / FAP recursions of Sections 4.1
- * and 5.1 model).  Edges of a hop are ordered by frontier position, then slot.  No host
- * synchronisation happens inside the call. */
+ * [1, QV_MAX_FANOUT]; 1 <= n_hops <= QV_MAX_HOPS.  Edges of a hop are ordered by the position
+ * of the expanded node, then slot.  No host synchronisation happens inside the call.
+ * flags = 0: hop k expands exactly F_{k-1}, the distinct nodes hop k-1 produced (layer
+ *   frontiers: the process the PSGS / FAP recursions of Sections 4.1 and 5.1 model).
+ * flags = QV_SAMPLE_CUMULATIVE: hop k expands every node sampled so far (n_id after hop k-1, in
+ *   local-id order), which yields the nested bipartite blocks consumed by the GraphSAGE / GAT
+ *   layers of the libraries whose samplers the paper adopts (Section 6).  A node expanded again
+ *   in a later hop draws afresh (the hop number is part of the random stream).  `frontier` still
+ *   receives the distinct neighbours of each hop. */
+#define QV_SAMPLE_CUMULATIVE 1u
 qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_t n_seeds,
-                    const int32_t* fanouts, int32_t n_hops, uint64_t rng_seed,
+                    const int32_t* fanouts, int32_t n_hops, uint64_t rng_seed, uint32_t flags,
                     const qv_sample_out* out);
 
 /* Several independent batches through one set of kernel launches (Section 4.3 (1): several
@@ -158,7 +164,7 @@ qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_
 qv_status qv_sample_many(qv_ctx* ctx, const qv_csr* csr, int32_t n_batches,
                          const int32_t* const* seeds, const int64_t* n_seeds,
                          const int32_t* fanouts, int32_t n_hops, const uint64_t* rng_seeds,
-                         const qv_sample_out* outs);
+                         uint32_t flags, const qv_sample_out* outs);
 
 /* Dedup + relabel (Section 2.1: the sampled nodes are collected once each and the sub-graph is
  * expressed over them).  known [dev] int32[n_known]: ids that already have local ids (local id

@@ -100,24 +100,24 @@ def reindex(known, nbr):
     return n_id[:n1.value].copy(), local[:len(nbr)].copy(), front[:n2.value].copy()
 
 
-def sample_bounds(n_seeds, fanouts, n_nodes):
+def sample_bounds(n_seeds, fanouts, n_nodes, cumulative=False):
     """A-priori output sizes: (nodes, edges, frontier entries)."""
     f, nodes, edges, front = n_seeds, n_seeds, 0, n_seeds
     for l in fanouts:
         e = f * int(l)
-        f = min(e, n_nodes)
         edges += e
-        front += f
-        nodes += e
+        front += min(e, n_nodes)
+        nodes = min(nodes + e, n_nodes)
+        f = nodes if cumulative else min(e, n_nodes)
     return min(nodes, n_nodes), edges, front
 
 
-def sample(rowptr, col, seeds, fanouts, rng_seed):
+def sample(rowptr, col, seeds, fanouts, rng_seed, cumulative=False):
     """Multi-hop sampling + reindex.  Returns a dict of numpy arrays."""
     rowptr, col, seeds, fanouts = _i64(rowptr), _i32(col), _i32(seeds), _i32(fanouts)
     n = len(rowptr) - 1
     K = len(fanouts)
-    nb, eb, fb = sample_bounds(len(seeds), fanouts, n)
+    nb, eb, fb = sample_bounds(len(seeds), fanouts, n, cumulative)
     n_id = np.zeros(max(1, nb), dtype=np.int32)
     row = np.zeros(max(1, eb), dtype=np.int32)
     cl = np.zeros(max(1, eb), dtype=np.int32)
@@ -128,7 +128,7 @@ def sample(rowptr, col, seeds, fanouts, rng_seed):
     fr_off = np.zeros(K + 2, dtype=np.int64)
     rc = lib().o_sample(C.c_int64(n), _p(rowptr, C.c_int64), _p(col, C.c_int32),
                         _p(seeds, C.c_int32), C.c_int64(len(seeds)), _p(fanouts, C.c_int32),
-                        C.c_int32(K), C.c_uint64(rng_seed), _p(n_id, C.c_int32),
+                        C.c_int32(K), C.c_uint64(rng_seed), C.c_int32(1 if cumulative else 0), _p(n_id, C.c_int32),
                         _p(row, C.c_int32), _p(cl, C.c_int32), _p(ng, C.c_int32),
                         _p(fr, C.c_int32), _p(node_off, C.c_int64), _p(edge_off, C.c_int64),
                         _p(fr_off, C.c_int64))

@@ -168,9 +168,13 @@ int o_reindex(const int32_t* known, int64_t n_known, const int32_t* nbr, int64_t
     return 0;
 }
 
-// Multi-hop sampling with layer frontiers: hop k expands exactly the distinct nodes that hop k-1
-// produced (hop 0 = the distinct seeds), which is the process the PSGS and FAP recursions model
-// (q_k is driven by the hop k-1 set; p_k by p_{k-1}).
+// Multi-hop sampling.  cumulative == 0 (layer frontiers): hop k expands exactly the distinct nodes
+// that hop k-1 produced (hop 0 = the distinct seeds), which is the process the PSGS and FAP
+// recursions model (q_k is driven by the hop k-1 set; p_k by p_{k-1}).  cumulative != 0: hop k
+// expands every node sampled so far (n_id after hop k-1, in local-id order), which yields the
+// nested bipartite blocks that GraphSAGE / GAT layers consume in the libraries whose samplers the
+// paper adopts (Section 6); a node expanded again in a later hop draws afresh (the hop number is
+// part of the random stream).  `frontier` holds the distinct neighbours of each hop either way.
 //   n_id          all distinct sampled nodes, seeds first, in order of first appearance
 //   row/col_local per edge: local id of the expanded node / of the sampled neighbour
 //   nbr_global    per edge: global id of the sampled neighbour
@@ -180,7 +184,7 @@ int o_reindex(const int32_t* known, int64_t n_known, const int32_t* nbr, int64_t
 // Output arrays must be large enough (bounds: see the binding).  Returns 0, -1 on a bad id.
 int o_sample(int64_t n_nodes, const int64_t* rowptr, const int32_t* col, const int32_t* seeds,
              int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, uint64_t rng_seed,
-             int32_t* n_id, int32_t* row_local, int32_t* col_local, int32_t* nbr_global,
+             int32_t cumulative, int32_t* n_id, int32_t* row_local, int32_t* col_local, int32_t* nbr_global,
              int32_t* frontier, int64_t* node_off, int64_t* edge_off, int64_t* frontier_off) {
     std::unordered_map<int32_t, int32_t> local;
     std::vector<int32_t> cur;                       // F_{k-1}
@@ -200,6 +204,7 @@ int o_sample(int64_t n_nodes, const int64_t* rowptr, const int32_t* col, const i
     for (int32_t k = 1; k <= n_hops; ++k) {
         std::vector<int32_t> next;
         std::unordered_set<int32_t> seen_here;
+        if (cumulative) cur.assign(n_id, n_id + n_nodes_out);       // everything sampled so far
         for (int32_t v : cur) {
             int64_t start = rowptr[v], deg = rowptr[v + 1] - rowptr[v];
             sample_positions(rng_seed, v, k, deg, fanouts[k - 1], pos);
@@ -222,7 +227,7 @@ int o_sample(int64_t n_nodes, const int64_t* rowptr, const int32_t* col, const i
         node_off[k + 1] = n_nodes_out;
         edge_off[k] = n_edges;
         frontier_off[k + 1] = n_front;
-        cur.swap(next);
+        if (!cumulative) cur.swap(next);
     }
     return 0;
 }

@@ -15,6 +15,7 @@ _lib = None
 
 QV_OK, QV_EINVAL, QV_ENOMEM, QV_EHIP, QV_ECAPACITY, QV_ERANGE = 0, -1, -2, -3, -4, -5
 QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 8
+QV_SAMPLE_CUMULATIVE, QV_FEAT_OWN_COPY = 1, 1
 
 EXPORTS = [
     "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget",
@@ -53,17 +54,17 @@ def lib():
         L.qv_last_error.argtypes = [vp]
         L.qv_last_error.restype = C.c_char_p
         L.qv_ctx_sync.argtypes = [vp]
-        L.qv_ctx_reserve.argtypes = [vp, i64, C.POINTER(i32), i32, i64]
+        L.qv_ctx_reserve.argtypes = [vp, i64, C.POINTER(i32), i32, i64, C.c_uint32]
         L.qv_ctx_set_epoch.argtypes = [vp, C.c_uint32]
         L.qv_ctx_set_table_budget.argtypes = [vp, i64]
-        L.qv_sample_bounds.argtypes = [i64, C.POINTER(i32), i32, i64, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+        L.qv_sample_bounds.argtypes = [i64, C.POINTER(i32), i32, i64, C.c_uint32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
         L.qv_csr_create.argtypes = [vp, i64, i64, vp, i32, vp, i32, C.POINTER(vp)]
         L.qv_csr_destroy.argtypes = [vp]
         L.qv_csr_destroy.restype = None
         L.qv_sample_hop.argtypes = [vp, vp, vp, i64, i32, u64, i32, vp, i64, vp]
-        L.qv_sample.argtypes = [vp, vp, vp, i64, C.POINTER(i32), i32, u64, C.POINTER(_SampleOut)]
+        L.qv_sample.argtypes = [vp, vp, vp, i64, C.POINTER(i32), i32, u64, C.c_uint32, C.POINTER(_SampleOut)]
         L.qv_sample_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i32), i32,
-                                     C.POINTER(u64), C.POINTER(_SampleOut)]
+                                     C.POINTER(u64), C.c_uint32, C.POINTER(_SampleOut)]
         L.qv_gather_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), i64]
         L.qv_reindex.argtypes = [vp, vp, i64, vp, i64, i64, vp, i64, vp, vp, vp, vp]
         L.qv_feat_create.argtypes = [vp, vp, i32, i64, i32, i32, i64, vp, i32, C.POINTER(vp)]
@@ -123,9 +124,9 @@ class Context:
         """0 forces the hashed dedup table; see qv_ctx_set_table_budget."""
         self.check(lib().qv_ctx_set_table_budget(self.h, n_bytes))
 
-    def reserve(self, n_seeds, fanouts, n_nodes):
+    def reserve(self, n_seeds, fanouts, n_nodes, cumulative=False):
         arr, k = _fan(fanouts)
-        self.check(lib().qv_ctx_reserve(self.h, n_seeds, arr, k, n_nodes))
+        self.check(lib().qv_ctx_reserve(self.h, n_seeds, arr, k, n_nodes, 1 if cumulative else 0))
 
     def close(self):
         if getattr(self, "h", None):
@@ -201,10 +202,10 @@ class Features:
             pass
 
 
-def qv_sample_bounds(n_seeds, fanouts, n_nodes):
+def qv_sample_bounds(n_seeds, fanouts, n_nodes, cumulative=False):
     arr, k = _fan(fanouts)
     a, b, c = C.c_int64(), C.c_int64(), C.c_int64()
-    rc = lib().qv_sample_bounds(n_seeds, arr, k, n_nodes, C.byref(a), C.byref(b), C.byref(c))
+    rc = lib().qv_sample_bounds(n_seeds, arr, k, n_nodes, 1 if cumulative else 0, C.byref(a), C.byref(b), C.byref(c))
     if rc != QV_OK:
         raise QvError(rc, lib().qv_last_error(None).decode())
     return a.value, b.value, c.value
@@ -213,8 +214,9 @@ def qv_sample_bounds(n_seeds, fanouts, n_nodes):
 class SampleBuffers:
     """Caller-side output arrays of qv_sample, sized to the a-priori bounds (or given caps)."""
 
-    def __init__(self, ctx, n_seeds, fanouts, n_nodes, caps=None, want_frontier=True, want_nbr_global=True):
-        nb, eb, fb = qv_sample_bounds(n_seeds, fanouts, n_nodes)
+    def __init__(self, ctx, n_seeds, fanouts, n_nodes, caps=None, want_frontier=True, want_nbr_global=True,
+                 cumulative=False):
+        nb, eb, fb = qv_sample_bounds(n_seeds, fanouts, n_nodes, cumulative)
         if caps is not None:
             nb, eb, fb = caps
         dev, K = ctx.device, len(fanouts)
@@ -252,14 +254,16 @@ class SampleBuffers:
         return out
 
 
-def qv_sample(ctx, graph, seeds, fanouts, rng_seed, out=None):
-    """Multi-hop sampling + reindex of one batch; asynchronous.  Returns the SampleBuffers."""
+def qv_sample(ctx, graph, seeds, fanouts, rng_seed, out=None, cumulative=False):
+    """Multi-hop sampling + reindex of one batch; asynchronous.  Returns the SampleBuffers.
+    cumulative=True: every hop expands all nodes sampled so far (nested blocks)."""
     _dev_i32(seeds, "seeds")
     if out is None:
-        out = SampleBuffers(ctx, seeds.numel(), fanouts, graph.n_nodes)
+        out = SampleBuffers(ctx, seeds.numel(), fanouts, graph.n_nodes, cumulative=cumulative)
     arr, k = _fan(fanouts)
     st = out.struct()
-    ctx.check(lib().qv_sample(ctx.h, graph.h, _ptr(seeds), seeds.numel(), arr, k, C.c_uint64(rng_seed), C.byref(st)))
+    ctx.check(lib().qv_sample(ctx.h, graph.h, _ptr(seeds), seeds.numel(), arr, k, C.c_uint64(rng_seed),
+                              1 if cumulative else 0, C.byref(st)))
     return out
 
 
@@ -267,9 +271,10 @@ class ManyPlan:
     """Pre-marshalled argument arrays for qv_sample_many + qv_gather_many over fixed buffers, so
     that a serving loop only swaps seed pointers and rng seeds."""
 
-    def __init__(self, ctx, graph, feat, bufs, rows, fanouts):
+    def __init__(self, ctx, graph, feat, bufs, rows, fanouts, cumulative=False):
         n = len(bufs)
         self.ctx, self.graph, self.feat, self.bufs, self.rows, self.n = ctx, graph, feat, bufs, rows, n
+        self.flags = 1 if cumulative else 0
         self.fan, self.k = _fan(fanouts)
         self.seed_ptrs = (C.c_void_p * n)()
         self.n_seeds = (C.c_int64 * n)()
@@ -298,19 +303,20 @@ class ManyPlan:
             self.n_seeds[i] = seeds[i].numel()
             self.rng[i] = rng_seeds[i]
         L, c = lib(), self.ctx
-        c.check(L.qv_sample_many(c.h, self.graph.h, n, self.seed_ptrs, self.n_seeds, self.fan, self.k, self.rng, self.outs))
+        c.check(L.qv_sample_many(c.h, self.graph.h, n, self.seed_ptrs, self.n_seeds, self.fan, self.k, self.rng,
+                                 self.flags, self.outs))
         if self.feat is not None:
             c.check(L.qv_gather_many(c.h, self.feat.h, n, self.ids, self.n_ids, self.n_dev, self.out_ptrs, self.stride))
 
 
-def qv_sample_many(ctx, graph, seeds_list, fanouts, rng_seeds, outs=None):
+def qv_sample_many(ctx, graph, seeds_list, fanouts, rng_seeds, outs=None, cumulative=False):
     """Several independent batches through one set of launches.  Returns the SampleBuffers list."""
     n = len(seeds_list)
     for s in seeds_list:
         _dev_i32(s, "seeds")
     if outs is None:
-        outs = [SampleBuffers(ctx, s.numel(), fanouts, graph.n_nodes) for s in seeds_list]
-    plan = ManyPlan(ctx, graph, None, outs, None, fanouts)
+        outs = [SampleBuffers(ctx, s.numel(), fanouts, graph.n_nodes, cumulative=cumulative) for s in seeds_list]
+    plan = ManyPlan(ctx, graph, None, outs, None, fanouts, cumulative=cumulative)
     plan.run(seeds_list, rng_seeds, n)
     return outs
 

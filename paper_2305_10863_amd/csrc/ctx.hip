@@ -133,22 +133,22 @@ qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes) {
     return QV_OK;
 }
 
-qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes,
+qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes, uint32_t flags,
                            int64_t* max_nodes, int64_t* max_edges, int64_t* max_frontier) {
     if (n_seeds < 0 || n_hops < 1 || n_hops > QV_MAX_HOPS || !fanouts || n_nodes < 0)
         return fail(nullptr, QV_EINVAL, "qv_sample_bounds: bad arguments");
-    int64_t f = n_seeds, nodes = n_seeds, edges = 0, front = n_seeds;
+    const bool cumulative = (flags & QV_SAMPLE_CUMULATIVE) != 0;
+    int64_t f = n_seeds, nodes = n_seeds < n_nodes ? n_seeds : n_nodes, edges = 0, front = n_seeds;
     for (int k = 0; k < n_hops; ++k) {
         if (fanouts[k] < 1 || fanouts[k] > QV_MAX_FANOUT)
             return fail(nullptr, QV_EINVAL, "qv_sample_bounds: fanout %d outside [1, %d]", fanouts[k], QV_MAX_FANOUT);
         int64_t e = f * (int64_t)fanouts[k];
         if (e >= ((int64_t)1 << 31)) return fail(nullptr, QV_EINVAL, "qv_sample_bounds: a hop may exceed 2^31 edges");
-        f = e < n_nodes ? e : n_nodes;
         edges += e;
-        front += f;
-        nodes += e;
+        front += e < n_nodes ? e : n_nodes;
+        nodes = nodes + e < n_nodes ? nodes + e : n_nodes;
+        f = cumulative ? nodes : (e < n_nodes ? e : n_nodes);
     }
-    if (nodes > n_nodes) nodes = n_nodes;
     if (max_nodes) *max_nodes = nodes;
     if (max_edges) *max_edges = edges;
     if (max_frontier) *max_frontier = front;

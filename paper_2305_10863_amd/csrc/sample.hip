@@ -172,6 +172,7 @@ struct CallArgs {
     int32_t next_fanout;            // k_dedup: fanout of the following hop, 0 = none
     int32_t n_hops;
     int32_t items_per_thread;       // k_flag / k_assign: tile = kScanBlock * items_per_thread positions
+    int32_t cumulative;             // hop k expands every node sampled so far, not only F_{k-1}
     int32_t frontier_restart;       // stand-alone reindex: number this stage's frontier from 0
     int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
     int32_t* status;
@@ -250,8 +251,8 @@ __global__ void __launch_bounds__(256) k_sample(CallArgs c) {
     const int sub = threadIdx.x % G;
     constexpr int groups_per_block = 256 / G;
     const SampleMeta* m = b.meta;
-    const int64_t fbeg = m->frontier_off[c.stage - 1];
-    const int64_t F = m->frontier_off[c.stage] - fbeg;
+    const int64_t fbeg = c.cumulative ? 0 : m->frontier_off[c.stage - 1];
+    const int64_t F = c.cumulative ? m->node_off[c.stage] : m->frontier_off[c.stage] - fbeg;
     const int64_t ebase = m->edge_off[c.stage - 1];
     const int64_t stride = (int64_t)gridDim.x * groups_per_block;
     const int group_in_wave = (threadIdx.x % kWave) / G;
@@ -297,8 +298,8 @@ __global__ void __launch_bounds__(64) k_sample_wide(CallArgs c) {
     const BatchArgs& b = c.b[blockIdx.y];
     const int lane = threadIdx.x;
     const SampleMeta* m = b.meta;
-    const int64_t fbeg = m->frontier_off[c.stage - 1];
-    const int64_t F = m->frontier_off[c.stage] - fbeg;
+    const int64_t fbeg = c.cumulative ? 0 : m->frontier_off[c.stage - 1];
+    const int64_t F = c.cumulative ? m->node_off[c.stage] : m->frontier_off[c.stage] - fbeg;
     const int64_t ebase = m->edge_off[c.stage - 1];
     const TableView t = table_of(c, b);
     const uint64_t tag = pos_tag(c.epoch, c.stage);
@@ -421,12 +422,12 @@ __global__ void __launch_bounds__(kScanBlock) k_flag(CallArgs c) {
                 // independent loads, issued together: one 16-byte slot, the row extent
                 const uint4 sl = *reinterpret_cast<const uint4*>(&b.slots[slot]);
                 int64_t rs = 0, re = 0;
-                if (c.next_fanout > 0) { rs = (int64_t)rowptr[id]; re = (int64_t)rowptr[id + 1]; }
+                if (c.next_fanout > 0 && !c.cumulative) { rs = (int64_t)rowptr[id]; re = (int64_t)rowptr[id + 1]; }
                 const uint64_t mp = ((uint64_t)sl.y << 32) | sl.x;
                 first = (mp == (tag | (uint64_t)p)) ? 1u : 0u;
                 isnew = (first && sl.w != c.epoch) ? 1u : 0u;          // no local id in this call yet
                 if (sl.w == c.epoch) { resolved = 1; known_lid = (int32_t)sl.z; }   // numbered by an earlier stage
-                if (first) {
+                if (first && !c.cumulative) {
                     const uint32_t d = (uint32_t)(re - rs);
                     seg = d < (uint32_t)c.next_fanout ? d : (uint32_t)c.next_fanout;
                 }
@@ -479,7 +480,9 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
             id = v.ids[p];
             slot = slot_at(c, v, p, id);
             if (!x.b) lid = b.slots[slot].lid;
-            if (c.next_fanout > 0) { rs = (int64_t)rowptr[id]; deg = (uint32_t)((int64_t)rowptr[id + 1] - rs); }
+            if (c.next_fanout > 0 && (!c.cumulative || x.b)) {
+                rs = (int64_t)rowptr[id]; deg = (uint32_t)((int64_t)rowptr[id + 1] - rs);
+            }
         }
         Tri tot;
         const Tri ex = block_scan3(x, tot, lds);
@@ -494,7 +497,16 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
                 if (c.stage > 0) b.col_local[p] = lid;
             }
             const int64_t j = (int64_t)run.a + ex.a;
-            if (c.next_fanout > 0) {                 // the next hop expands this entry
+            if (c.cumulative) {
+                if (x.b && c.next_fanout > 0) {      // later hops expand every node: entry at its local id
+                    const int64_t u = node_base + run.b + ex.b;
+                    if (u < b.fr_cap) {
+                        b.fr_id[u] = id; b.fr_lid[u] = lid; b.fr_rs[u] = rs; b.fr_deg[u] = deg;
+                    } else {
+                        atomicOr(c.status, kStatCapacity);
+                    }
+                }
+            } else if (c.next_fanout > 0) {          // the next hop expands this entry
                 if (fr_base + j < b.fr_cap) {
                     b.fr_id[fr_base + j] = id;
                     b.fr_lid[fr_base + j] = lid;
@@ -516,9 +528,59 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
     if (last && threadIdx.x == 0) {
         m->node_off[c.stage + 1] = node_base + run.b;
         m->frontier_off[c.stage + 1] = fr_base + run.a;
-        if (c.next_fanout > 0) m->edge_off[c.stage + 1] = edge_base + run.c;
+        if (c.next_fanout > 0 && !c.cumulative) m->edge_off[c.stage + 1] = edge_base + run.c;
         if (c.expect_all_first && (int64_t)run.a != v.end - v.begin) atomicOr(c.status, kStatInval);
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// cumulative frontiers: before hop k, segment sizes min(deg, fanout_k) of ALL nodes sampled so
+// far (entries indexed by local id) -> segment offsets and the hop's edge count
+// ---------------------------------------------------------------------------------------------
+__global__ void __launch_bounds__(kScanBlock) k_cum_partial(CallArgs c) {
+    __shared__ uint32_t lds[kScanBlock / kWave][3];
+    const BatchArgs& b = c.b[blockIdx.y];
+    const int64_t U = b.meta->node_off[c.stage];
+    const int64_t t0 = (int64_t)blockIdx.x * kScanBlock * c.items_per_thread;
+    if (t0 >= U) return;
+    Tri sum = {0, 0, 0};
+    for (int it = 0; it < c.items_per_thread; ++it) {
+        const int64_t u = t0 + (int64_t)it * kScanBlock + threadIdx.x;
+        if (u < U && u < b.fr_cap) {
+            const uint32_t d = b.fr_deg[u];
+            sum.a += d < (uint32_t)c.fanout ? d : (uint32_t)c.fanout;
+        }
+    }
+    Tri total;
+    block_scan3(sum, total, lds);
+    if (threadIdx.x == 0) b.partial[blockIdx.x * 3] = total.a;
+}
+
+__global__ void __launch_bounds__(kScanBlock) k_cum_scan(CallArgs c) {
+    __shared__ uint32_t lds[kScanBlock / kWave][3];
+    const BatchArgs& b = c.b[blockIdx.y];
+    SampleMeta* m = b.meta;
+    const int64_t U = m->node_off[c.stage];
+    const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
+    const int64_t t0 = (int64_t)blockIdx.x * tile_size;
+    if (t0 >= U && !(U == 0 && blockIdx.x == 0)) return;
+    const int64_t edge_base = m->edge_off[c.stage - 1];
+    Tri pre = {0, 0, 0}, run;
+    for (int i = threadIdx.x; i < (int)blockIdx.x; i += kScanBlock) pre.a += b.partial[i * 3];
+    block_scan3(pre, run, lds);
+    uint64_t running = run.a;
+    for (int it = 0; it < c.items_per_thread; ++it) {
+        const int64_t u = t0 + (int64_t)it * kScanBlock + threadIdx.x;
+        Tri v = {0, 0, 0}, tot;
+        if (u < U && u < b.fr_cap) {
+            const uint32_t d = b.fr_deg[u];
+            v.a = d < (uint32_t)c.fanout ? d : (uint32_t)c.fanout;
+        }
+        const Tri ex = block_scan3(v, tot, lds);
+        if (u < U && u < b.fr_cap) b.fr_seg[u] = (uint32_t)(running + ex.a);
+        running += tot.a;
+    }
+    if (threadIdx.x == 0 && (U == 0 || t0 + tile_size >= U)) m->edge_off[c.stage] = edge_base + (int64_t)running;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -635,23 +697,25 @@ struct Bounds {
 };
 
 static qv_status compute_bounds(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, int n_hops,
-                                int64_t n_nodes, Bounds* b) {
+                                int64_t n_nodes, bool cumulative, Bounds* b) {
     if (n_hops < 1 || n_hops > QV_MAX_HOPS) return fail(ctx, QV_EINVAL, "n_hops %d outside [1, %d]", n_hops, QV_MAX_HOPS);
     if (!fanouts) return fail(ctx, QV_EINVAL, "fanouts is NULL");
     if (n_seeds < 0 || n_seeds >= ((int64_t)1 << 31)) return fail(ctx, QV_EINVAL, "n_seeds out of range");
+    // hop_front[k] = most nodes hop k+1 may expand: |F_k| (layer frontiers) or |n_id| after hop k
     b->hop_front[0] = n_seeds;
     b->hop_edges[0] = 0;
-    b->nodes = n_seeds; b->edges = 0; b->frontier = n_seeds;
+    b->nodes = n_seeds < n_nodes ? n_seeds : n_nodes; b->edges = 0; b->frontier = n_seeds;
     for (int k = 1; k <= n_hops; ++k) {
         int32_t l = fanouts[k - 1];
         if (l < 1 || l > QV_MAX_FANOUT) return fail(ctx, QV_EINVAL, "fanout %d outside [1, %d]", l, QV_MAX_FANOUT);
         int64_t e = b->hop_front[k - 1] * (int64_t)l;
         if (e >= ((int64_t)1 << 31)) return fail(ctx, QV_EINVAL, "hop %d may produce 2^31 or more edges", k);
         b->hop_edges[k] = e;
-        b->hop_front[k] = e < n_nodes ? e : n_nodes;
-        b->edges += e; b->frontier += b->hop_front[k]; b->nodes += e;
+        b->edges += e;
+        b->frontier += e < n_nodes ? e : n_nodes;
+        b->nodes = b->nodes + e < n_nodes ? b->nodes + e : n_nodes;
+        b->hop_front[k] = cumulative ? b->nodes : (e < n_nodes ? e : n_nodes);
     }
-    if (b->nodes > n_nodes) b->nodes = n_nodes;
     return QV_OK;
 }
 
@@ -778,7 +842,9 @@ static qv_status launch_sample(qv_ctx* ctx, const CallArgs& c, int64_t max_front
 
 static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, const int32_t* const* seeds,
                              const int64_t* n_seeds, const int32_t* fanouts, int n_hops, const uint64_t* rng_seeds,
-                             const qv_sample_out* outs, const char* who) {
+                             uint32_t flags, const qv_sample_out* outs, const char* who) {
+    if (flags & ~(uint32_t)QV_SAMPLE_CUMULATIVE) return fail(ctx, QV_EINVAL, "%s: unknown flag bits 0x%x", who, flags);
+    const bool cumulative = (flags & QV_SAMPLE_CUMULATIVE) != 0;
     if (!csr || !outs || !seeds || !n_seeds || !rng_seeds) return fail(ctx, QV_EINVAL, "%s: null argument", who);
     if (n_batches < 1 || n_batches > kMaxBatch) return fail(ctx, QV_EINVAL, "%s: n_batches %d outside [1, %d]", who, n_batches, kMaxBatch);
     int64_t max_seeds = 0;
@@ -791,10 +857,11 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
         if (n_seeds[i] > max_seeds) max_seeds = n_seeds[i];
     }
     Bounds bd;
-    qv_status rc = compute_bounds(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, &bd);
+    qv_status rc = compute_bounds(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, cumulative, &bd);
     if (rc != QV_OK) return rc;
     Layout L;
-    L.stage0 = max_seeds; L.edges = bd.edges; L.frontier = bd.frontier;
+    L.stage0 = max_seeds; L.edges = bd.edges;
+    L.frontier = cumulative ? (bd.nodes > 0 ? bd.nodes : 1) : bd.frontier;   // cumulative: one entry per node, at its local id
     rc = arena_begin(ctx, per_batch_bytes(L) * n_batches);
     if (rc != QV_OK) return rc;
     CallArgs c{};
@@ -804,7 +871,7 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     const size_t table_slots = c.direct ? (size_t)csr->n_nodes : (size_t)c.mask + 1;
     rc = table_prepare(ctx, n_batches, table_slots, !c.direct);
     if (rc != QV_OK) return rc;
-    c.epoch = ctx->epoch; c.n_hops = n_hops; c.status = ctx->d_status;
+    c.epoch = ctx->epoch; c.n_hops = n_hops; c.status = ctx->d_status; c.cumulative = cumulative ? 1 : 0;
     for (int i = 0; i < n_batches; ++i) {
         BatchArgs& b = c.b[i];
         if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "%s: scratch arena too small (internal sizing error)", who);
@@ -832,6 +899,15 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     if (rc != QV_OK) return rc;
     for (int k = 1; k <= n_hops; ++k) {
         c.stage = k; c.hop = k; c.fanout = fanouts[k - 1]; c.next_fanout = k < n_hops ? fanouts[k] : 0;
+        if (cumulative) {                       // segment offsets of every node sampled so far
+            int ipt, tiles;
+            tile_shape(bd.hop_front[k - 1], &ipt, &tiles);
+            c.items_per_thread = ipt;
+            dim3 grid((unsigned)tiles, (unsigned)n_batches);
+            hipLaunchKernelGGL(k_cum_partial, grid, dim3(kScanBlock), 0, ctx->stream, c);
+            hipLaunchKernelGGL(k_cum_scan, grid, dim3(kScanBlock), 0, ctx->stream, c);
+            QV_LAUNCH_CHECK(ctx, "k_cum_scan");
+        }
         rc = launch_sample(ctx, c, bd.hop_front[k - 1], n_batches);
         if (rc != QV_OK) return rc;
         rc = launch_dedup(ctx, c, csr->rowptr_bits, bd.hop_edges[k], n_batches);
@@ -850,13 +926,15 @@ using namespace qv;
 
 extern "C" {
 
-qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes) {
+qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes,
+                         uint32_t flags) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_reserve: ctx is NULL");
+    const bool cumulative = (flags & QV_SAMPLE_CUMULATIVE) != 0;
     Bounds bd;
-    qv_status rc = compute_bounds(ctx, n_seeds, fanouts, n_hops, n_nodes, &bd);
+    qv_status rc = compute_bounds(ctx, n_seeds, fanouts, n_hops, n_nodes, cumulative, &bd);
     if (rc != QV_OK) return rc;
     Layout L;
-    L.stage0 = n_seeds; L.edges = bd.edges; L.frontier = bd.frontier;
+    L.stage0 = n_seeds; L.edges = bd.edges; L.frontier = cumulative ? (bd.nodes > 0 ? bd.nodes : 1) : bd.frontier;
     const size_t want = per_batch_bytes(L) * kMaxBatch;
     if (want > ctx->arena_bytes) {
         rc = arena_begin(ctx, want);
@@ -915,17 +993,17 @@ qv_status qv_sample_hop(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier,
 }
 
 qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts,
-                    int32_t n_hops, uint64_t rng_seed, const qv_sample_out* out) {
+                    int32_t n_hops, uint64_t rng_seed, uint32_t flags, const qv_sample_out* out) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_sample: ctx is NULL");
     if (!out) return fail(ctx, QV_EINVAL, "qv_sample: null argument");
-    return sample_many(ctx, csr, 1, &seeds, &n_seeds, fanouts, n_hops, &rng_seed, out, "qv_sample");
+    return sample_many(ctx, csr, 1, &seeds, &n_seeds, fanouts, n_hops, &rng_seed, flags, out, "qv_sample");
 }
 
 qv_status qv_sample_many(qv_ctx* ctx, const qv_csr* csr, int32_t n_batches, const int32_t* const* seeds,
                          const int64_t* n_seeds, const int32_t* fanouts, int32_t n_hops, const uint64_t* rng_seeds,
-                         const qv_sample_out* outs) {
+                         uint32_t flags, const qv_sample_out* outs) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_sample_many: ctx is NULL");
-    return sample_many(ctx, csr, n_batches, seeds, n_seeds, fanouts, n_hops, rng_seeds, outs, "qv_sample_many");
+    return sample_many(ctx, csr, n_batches, seeds, n_seeds, fanouts, n_hops, rng_seeds, flags, outs, "qv_sample_many");
 }
 
 qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const int32_t* nbr, int64_t n_nbr,

@@ -100,6 +100,13 @@ def test_co_purchase_full_batch_sweep_and_tiered(qv, ctx):
     feat = qv.Features(ctx, qvgen.features_device(w.seed, w.n, w.dim, torch.float32))
     for i, n_seeds in enumerate(w.batch_sweep):
         check_batches(qv, ctx, w, rowptr, col, g, feat, [10 + i], n_seeds=n_seeds)
+    # nested-block variant (every hop expands all nodes sampled so far) at full size
+    seeds = w.seeds(77, 512)
+    out = qv.qv_sample(ctx, g, torch.from_numpy(seeds).cuda(), w.fanouts, 123, cumulative=True)
+    ctx.sync()
+    got, want = out.to_host(), oracle.sample(rowptr, col, seeds, w.fanouts, 123, cumulative=True)
+    for k in ("node_off", "edge_off", "frontier_off", "n_id", "row_local", "col_local", "nbr_global", "frontier"):
+        assert np.array_equal(got[k], want[k]), ("cumulative", k)
     Q, P, oQ = check_metrics(qv, ctx, w, rowptr, col, g)
     # PSGS summed over a batch predicts the sampled edge count (tree expansion, before dedup)
     seeds = w.seeds(3, 512)

@@ -195,6 +195,27 @@ def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
     c.close()
 
 
+@pytest.mark.parametrize("fanouts,n_seeds", [([10, 5], 64), ([15, 10, 5], 300), ([3, 3, 3, 3], 50), ([70, 4], 20), ([6], 100)])
+def test_cumulative_frontiers_match_oracle(qv, ctx, tiny, fanouts, n_seeds):
+    # every hop expands all nodes sampled so far (nested blocks)
+    w, rowptr, col, g = tiny
+    seeds = w.seeds(500 + n_seeds, n_seeds)
+    out = qv.qv_sample(ctx, g, dev(seeds), fanouts, 4242, cumulative=True)
+    ctx.sync()
+    want = oracle.sample(rowptr, col, seeds, fanouts, 4242, cumulative=True)
+    assert_sample_equal(out.to_host(), want)
+    assert qv.qv_sample_bounds(n_seeds, fanouts, w.n, cumulative=True) == oracle.sample_bounds(n_seeds, fanouts, w.n, True)
+    many = [w.seeds(600 + j, 40 + 30 * j) for j in range(3)]
+    outs = qv.qv_sample_many(ctx, g, [dev(s) for s in many], fanouts, [1, 2, 3], cumulative=True)
+    ctx.sync()
+    for j in range(3):
+        assert_sample_equal(outs[j].to_host(), oracle.sample(rowptr, col, many[j], fanouts, 1 + j, cumulative=True))
+    # and the layer-frontier mode still gives its own result on the same context
+    out = qv.qv_sample(ctx, g, dev(seeds), fanouts, 4242)
+    ctx.sync()
+    assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, fanouts, 4242))
+
+
 def test_graph_in_pinned_host_memory(qv, ctx, tiny):
     # topology read zero-copy over the host link: same results
     w, rowptr, col, _ = tiny

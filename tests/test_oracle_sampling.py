@@ -121,7 +121,7 @@ def test_uniform_also_across_nodes_hops_with_fixed_seed():
 
 
 # ------------------------------------------------------------------------------------------------
-def py_multi_hop(adj, seeds, fanouts, rng_seed):
+def py_multi_hop(adj, seeds, fanouts, rng_seed, cumulative=False):
     """Multi-hop sampling + relabel written differently from the oracle: per-hop lists, dedup by
     rescanning lists with `in` / index(), no hash map carried between the steps."""
     n_id = []
@@ -132,7 +132,7 @@ def py_multi_hop(adj, seeds, fanouts, rng_seed):
     edges = []          # (hop, target_global, nbr_global)
     for k, l in enumerate(fanouts, start=1):
         hop_nbrs = []
-        for v in frontiers[-1]:
+        for v in (list(n_id) if cumulative else frontiers[-1]):
             for p in py_positions(rng_seed, v, k, len(adj[v]), l):
                 hop_nbrs.append((v, adj[v][p]))
         nxt = []
@@ -167,6 +167,36 @@ def test_multi_hop_matches_independent_python(trial):
     assert [n_id[i] for i in o["col_local"]] == [g for _, _, g in edges]
     per_hop = [sum(1 for e in edges if e[0] == k) for k in range(1, K + 1)]
     assert o["edge_off"].tolist() == np.cumsum([0] + per_hop).tolist()
+
+
+@pytest.mark.parametrize("trial", range(8))
+def test_cumulative_mode_matches_independent_python(trial):
+    # every node sampled so far is expanded again in each hop (nested blocks)
+    rng = np.random.default_rng(700 + trial)
+    n = int(rng.integers(5, 40))
+    rowptr, col = random_graph(rng, n, max_deg=int(rng.integers(1, 9)))
+    adj = adjacency(rowptr, col)
+    fanouts = [int(rng.integers(1, 5)) for _ in range(int(rng.integers(1, 4)))]
+    seeds = rng.integers(0, n, size=int(rng.integers(1, 8))).astype(np.int32)
+    rs = int(rng.integers(0, 2 ** 62))
+    o = oracle.sample(rowptr, col, seeds, fanouts, rs, cumulative=True)
+    n_id, frontiers, edges = py_multi_hop(adj, seeds.tolist(), fanouts, rs, cumulative=True)
+    assert o["n_id"].tolist() == n_id
+    assert o["frontier"].tolist() == [g for f in frontiers for g in f]
+    assert o["nbr_global"].tolist() == [g for _, _, g in edges]
+    assert [n_id[i] for i in o["row_local"]] == [v for _, v, _ in edges]
+    assert [n_id[i] for i in o["col_local"]] == [g for _, _, g in edges]
+    # hop k expands exactly the first node_off[k] local ids, in order, each with its full segment
+    deg = np.diff(rowptr)
+    for k in range(1, len(fanouts) + 1):
+        expanded = o["n_id"][:o["node_off"][k]]
+        m = np.minimum(deg[expanded], fanouts[k - 1])
+        rows = o["row_local"][o["edge_off"][k - 1]:o["edge_off"][k]]
+        assert np.array_equal(rows, np.repeat(np.arange(len(expanded)), m))
+    # with one hop the two modes coincide
+    a = oracle.sample(rowptr, col, seeds, fanouts[:1], rs, cumulative=True)
+    b = oracle.sample(rowptr, col, seeds, fanouts[:1], rs)
+    assert all(np.array_equal(a[k], b[k]) for k in a)
 
 
 def check_sample_invariants(rowptr, col, seeds, fanouts, o):
