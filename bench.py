@@ -129,6 +129,9 @@ def main():
     ap.add_argument("--workload", default="citation")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--streams", type=int, default=1, help="batches in flight (one context per stream)")
+    ap.add_argument("--extra-streams", type=int, default=4,
+                    help="after the timed region, run the same batches again over this many streams and report "
+                         "that throughput beside the main figure (0 = skip; only when --streams is 1)")
     ap.add_argument("--batches-per-call", type=int, default=8,
                     help="independent batches per qv_sample_many / qv_gather_many call (1..8)")
     ap.add_argument("--table-budget-gib", type=float, default=-1.0,
@@ -318,6 +321,53 @@ def main():
     for c in ctxs:
         c.sync()                                           # raises on a deferred device error
 
+    # ---- the same batches over several streams (reported beside the main figure) -----------------
+    # With one stream every kernel's duration is its own, which is what the roofline entry needs;
+    # several contexts on their own streams let calls overlap (the paper's multiplexed pipelines),
+    # which raises whole-path throughput but stretches the individual kernels.
+    if S == 1 and args.extra_streams > 1 and not tiered:
+        S2 = args.extra_streams
+        ctxs2 = [ctx0] + [qv.Context(0, torch.cuda.Stream()) for _ in range(S2 - 1)]
+        plans2 = []
+        own = {}                                           # context index -> [(SampleBuffers, rows)] * B
+        for j, (first, cnt) in enumerate(calls):
+            k = j % S2
+            if k == 0:
+                plans2.append(plans[j])                    # context 0 keeps the buffers of the main region
+                continue
+            c = ctxs2[k]
+            if k not in own:
+                c.reserve(batch, w.fanouts, w.n)
+                own[k] = [(qv.SampleBuffers(c, batch, w.fanouts, w.n), feat.empty_rows(nb, "cuda")) for _ in range(B)]
+            views = []
+            for t in range(cnt):
+                v = copy.copy(own[k][t][0])
+                v.node_off, v.edge_off, v.frontier_off = offs[first + t]
+                views.append(v)
+            plans2.append(qv.ManyPlan(c, g, feat, views, [r for _, r in own[k][:cnt]], w.fanouts))
+
+        def call2(j):
+            first, cnt = calls[j]
+            p, c = plans2[j], ctxs2[j % S2]
+            for t in range(cnt):
+                p.seed_ptrs[t] = seeds_dev[first + t].data_ptr()
+                p.n_seeds[t] = batch
+                p.rng[t] = rng_seeds[first + t]
+            c.check(L.qv_sample_many(c.h, g.h, cnt, p.seed_ptrs, p.n_seeds, p.fan, p.k, p.rng, 0, p.outs))
+            c.check(L.qv_gather_many(c.h, feat.h, cnt, p.ids, p.n_ids, p.n_dev, p.out_ptrs, p.stride))
+
+        for j in range(n_warm_calls):
+            call2(j)
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for j in range(n_warm_calls, len(calls)):
+            call2(j)
+        torch.cuda.synchronize()
+        elapsed2 = time.perf_counter() - t2
+        for c in ctxs2:
+            c.sync()
+        extra["multi_stream"] = {"streams": S2, "ms_per_step": round(elapsed2 * 1e3 / K, 4)}
+
     # ---- latency pass (not part of the timed region): one batch per call, one at a time ---------
     n_lat = min(64, K)
     lat_plan = qv.ManyPlan(ctx0, g, feat, [bufs[0][0]], [rows[0][0]], w.fanouts)
@@ -401,6 +451,10 @@ def main():
         extra["cold_tier_GBps"] = round(cold_bytes / (sum(gather_ms) * 1e-3) / 1e9, 2)
         result["roofline"]["note"] = ("tiered: %.0f%% of the rows come over the host link, which bounds this "
                                       "kernel, not HBM" % (100 * extra["cold_row_fraction"]))
+    if "multi_stream" in extra:
+        ms2 = extra["multi_stream"]["ms_per_step"]
+        extra["multi_stream"]["value"] = round(tot_edges / K / (ms2 * 1e-3), 1)
+        extra["multi_stream"]["path_frac_hbm_peak"] = round(path_bytes / K / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
     result.update(extra)
 
     # ---- the oracle on this machine's host cores (a reported baseline, not the target) ------------

@@ -216,6 +216,37 @@ def test_cumulative_frontiers_match_oracle(qv, ctx, tiny, fanouts, n_seeds):
     assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, fanouts, 4242))
 
 
+def test_randomised_graphs_and_parameters(qv, ctx):
+    # seeded sweep over small random graphs (self-loops, multi-edges, sinks, hubs), hop counts,
+    # fanouts on both sides of the sub-wave group widths, seed counts, both frontier modes
+    rng = np.random.default_rng(20261127)
+    for case in range(40):
+        n = int(rng.integers(1, 400))
+        deg = np.minimum(rng.zipf(1.5, n), 300) * (rng.random(n) > 0.15)
+        rowptr = np.zeros(n + 1, np.int64)
+        rowptr[1:] = np.cumsum(deg)
+        col = rng.integers(0, n, rowptr[-1]).astype(np.int32)
+        if case % 2:
+            rowptr = rowptr.astype(np.int32)
+        g = make_graph(qv, ctx, rowptr, col)
+        K = int(rng.integers(1, 5))
+        fanouts = [int(rng.choice([1, 2, 5, 8, 9, 16, 17, 31, 33, 64, 65, 100])) for _ in range(K)]
+        while np.prod([f + 1 for f in fanouts]) * 50 > 3e6:
+            fanouts = fanouts[:-1]
+        cumulative = bool(rng.integers(0, 2))
+        sizes = [int(rng.integers(0, 50)) for _ in range(int(rng.integers(1, 5)))]
+        seeds = [rng.integers(0, n, s).astype(np.int32) for s in sizes]
+        rngs = [int(rng.integers(0, 2 ** 63)) for _ in sizes]
+        d_seeds = [dev(s) if len(s) else torch.zeros(0, dtype=torch.int32, device="cuda") for s in seeds]
+        outs = qv.qv_sample_many(ctx, g, d_seeds, fanouts, rngs, cumulative=cumulative)
+        ctx.sync()
+        for i in range(len(sizes)):
+            want = oracle.sample(rowptr, col, seeds[i], fanouts, rngs[i], cumulative=cumulative)
+            got = outs[i].to_host()
+            for k in ("node_off", "edge_off", "frontier_off", "n_id", "row_local", "col_local", "nbr_global", "frontier"):
+                assert np.array_equal(got[k], want[k]), (case, i, k, fanouts, cumulative)
+
+
 def test_graph_in_pinned_host_memory(qv, ctx, tiny):
     # topology read zero-copy over the host link: same results
     w, rowptr, col, _ = tiny
