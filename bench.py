@@ -121,6 +121,40 @@ def placement_ablation(qv, qvgen, w, ctx, g, table, P_pop, rowptr, col, tdtype):
     print(json.dumps({"metric": "placement_ablation", "workload": w.name, "hot_rows": int(n_hot), "rankings": res}), flush=True)
 
 
+def hardware_rates(qvgen):
+    import torch
+    out = {"metric": "hardware_rates", "unit": "1e9 operations/s", "rates": []}
+    names = {0: "atomicMin u64 (result unused)", 1: "atomicMin u32 (result unused)", 2: "store 8 B", 3: "load 8 B"}
+    for slots in (111_000_000, 1 << 20):
+        table = torch.full((slots,), -1, dtype=torch.int64, device="cuda")
+        for n_ops in (1_000_000, 8_000_000):
+            for mode in range(4):
+                best = 1e9
+                for rep in range(5):
+                    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                    e0.record()
+                    qvgen.random_ops_device(mode, table, n_ops, salt=rep * 7919 + mode)
+                    e1.record()
+                    torch.cuda.synchronize()
+                    best = min(best, e0.elapsed_time(e1))
+                out["rates"].append({"op": names[mode], "table_slots": slots, "ops": n_ops, "us": round(best * 1e3, 1),
+                                     "G_per_s": round(n_ops / best / 1e6, 1)})
+                log(str(out["rates"][-1]))
+        del table
+    a = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+    b = torch.empty_like(a)
+    best = 1e9
+    for _ in range(5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        qvgen.copy_device(a, b)
+        e1.record()
+        torch.cuda.synchronize()
+        best = min(best, e0.elapsed_time(e1))
+    out["plain_copy_1GiB"] = {"ms": round(best, 4), "TB_per_s_read_plus_write": round(2 * a.numel() * 4 / best / 1e9, 3)}
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -147,6 +181,9 @@ def main():
                          "ranked by FAP under the seed popularity, FAP under uniform seeds, in-degree, out-degree")
     ap.add_argument("--graph-in-host-memory", action="store_true",
                     help="keep rowptr / col in pinned host memory and sample through the host link (Section 4.3 (3))")
+    ap.add_argument("--hardware-rates", action="store_true",
+                    help="instead of the benchmark: rates of random device-scope atomics, stores and loads and of a "
+                         "plain copy on this GPU (the yardsticks DESIGN.md prices the kernels against)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB copy kernel (copy_bytes) so that hardware byte counters can be scaled")
     args = ap.parse_args()
@@ -163,6 +200,8 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     qv.lib()
     torch.cuda.set_device(0)
+    if args.hardware_rates:
+        return hardware_rates(qvgen)
     w = qvgen.workload(args.workload, args.scale)
     batch = args.batch or w.batch
     K, W, S = args.steps, args.warmup, max(1, args.streams)

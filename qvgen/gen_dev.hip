@@ -68,7 +68,42 @@ __global__ void copy_bytes(const uint4* __restrict__ src, uint4* __restrict__ ds
         dst[i] = src[i];
 }
 
+// Random single-word operations over a table: the yardstick for the dedup kernels, whose cost is
+// the number of random device-scope atomics / loads / stores rather than bytes.
+// mode 0: atomicMin u64 (result unused), 1: atomicMin u32, 2: store 8 B, 3: load 8 B.
+template <int MODE>
+__global__ void random_ops(uint64_t* t64, uint32_t* t32, uint64_t n_slots, int64_t n_ops, uint64_t salt, uint64_t* sink) {
+    uint64_t acc = 0;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_ops; i += (int64_t)gridDim.x * blockDim.x) {
+        const uint64_t s = mix64((uint64_t)i + salt) % n_slots;
+        if (MODE == 0) atomicMin((unsigned long long*)&t64[s], (unsigned long long)i);
+        if (MODE == 1) atomicMin(&t32[s], (uint32_t)i);
+        if (MODE == 2) t64[s] = (uint64_t)i;
+        if (MODE == 3) acc += t64[s];
+    }
+    if (acc == 0x123456789ull) *sink = acc;
+}
+
 }  // namespace
+
+extern "C" int qg_random_ops_device(int mode, void* table, int64_t n_slots, int64_t n_ops, uint64_t salt, void* stream) {
+    if (n_slots < 2 || n_ops <= 0) return 0;
+    int64_t blocks = (n_ops + 255) / 256;
+    if (blocks > 256 * 32) blocks = 256 * 32;
+    hipStream_t s = (hipStream_t)stream;
+    uint64_t* t64 = (uint64_t*)table;
+    uint32_t* t32 = (uint32_t*)table;
+    uint64_t* sink = t64 + (n_slots - 1);
+    dim3 g((unsigned)blocks), b(256);
+    switch (mode) {
+        case 0: hipLaunchKernelGGL(random_ops<0>, g, b, 0, s, t64, t32, (uint64_t)n_slots - 1, n_ops, salt, sink); break;
+        case 1: hipLaunchKernelGGL(random_ops<1>, g, b, 0, s, t64, t32, (uint64_t)n_slots - 1, n_ops, salt, sink); break;
+        case 2: hipLaunchKernelGGL(random_ops<2>, g, b, 0, s, t64, t32, (uint64_t)n_slots - 1, n_ops, salt, sink); break;
+        case 3: hipLaunchKernelGGL(random_ops<3>, g, b, 0, s, t64, t32, (uint64_t)n_slots - 1, n_ops, salt, sink); break;
+        default: return -1;
+    }
+    return (int)hipGetLastError();
+}
 
 extern "C" int qg_copy_device(const void* src, void* dst, int64_t n_bytes, void* stream) {
     int64_t n_vec = n_bytes / 16;
