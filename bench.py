@@ -259,7 +259,24 @@ def main():
                 Pdev = res
             else:
                 Qdev = res.clone()
-        log("psgs %.2f ms, access_prob %.2f ms over the whole graph" % (extra["psgs_ms"], extra["access_prob_ms"]))
+        # FAP again in its gather form over in-edges (a symmetrised graph is its own transpose)
+        t0 = time.perf_counter()
+        g_in = g if w.symmetrise else g.transpose()
+        if not w.symmetrise:
+            extra["csr_transpose_ms"] = round((time.perf_counter() - t0) * 1e3, 1)
+        qv.qv_access_prob(ctx0, g, w.fanouts, p0=p0, graph_in=g_in)
+        ctx0.sync()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(ctx0.stream)
+        P_in = qv.qv_access_prob(ctx0, g, w.fanouts, p0=p0, graph_in=g_in)
+        e1.record(ctx0.stream)
+        ctx0.sync()
+        extra["access_prob_in_edge_form_ms"] = round(e0.elapsed_time(e1), 3)
+        extra["access_prob_forms_max_rel_diff"] = float(((P_in - Pdev).abs() / Pdev.clamp_min(1e-30)).max().item())
+        del g_in, P_in
+        torch.cuda.empty_cache()
+        log("psgs %.2f ms, access_prob %.2f ms (scatter) / %.2f ms (gather over in-edges) over the whole graph"
+            % (extra["psgs_ms"], extra["access_prob_ms"], extra["access_prob_in_edge_form_ms"]))
 
     table_for_ablation = table if args.placement_ablation else None
     if tiered and not args.placement_ablation:

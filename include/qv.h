@@ -101,6 +101,18 @@ qv_status qv_csr_create(qv_ctx* ctx, int64_t n_nodes, int64_t n_edges, const voi
                         int32_t rowptr_bits, const int32_t* col, int32_t validate, qv_csr** out);
 void qv_csr_destroy(qv_csr* csr);
 
+/* The in-edge CSR of a graph (Section 5.1 sums, for each node, over the edges that end at it):
+ * row i of the result lists the sources j of the edges j -> i, in ascending order of j (parallel
+ * edges stay parallel).  Built on the device (edge sources, one stable radix sort of the edge
+ * list by destination, row boundaries from the sorted keys); the new arrays are device memory
+ * owned by the handle (rowptr of the same width as the input's; (n_nodes+1)*width + 4*n_edges
+ * bytes) and are freed by qv_csr_destroy.  About 8*n_edges bytes more are held during the call.
+ * Synchronises the context's stream.  A symmetric graph is its own in-edge CSR and needs none. */
+qv_status qv_csr_transpose(qv_ctx* ctx, const qv_csr* csr, qv_csr** out);
+/* Read-only views of a handle's arrays [dev] (for a transposed handle: the library's arrays). */
+const void* qv_csr_rowptr(const qv_csr* csr);
+const int32_t* qv_csr_col(const qv_csr* csr);
+
 /* ---------------------------------------------------------------------------------------------
  * Sampling  (paper Section 2.1, overview figure: seed -> layer-1 neighbours -> layer-2 ...;
  * Section 6: "k-hop neighbour sampling without replacement".  The paper prints no sampling
@@ -251,9 +263,14 @@ qv_status qv_psgs_batch_sum(qv_ctx* ctx, const float* psgs, int64_t n_nodes, con
 /* FAP, Section 5.1:  P[i] = sum_{k=0..K} p_k[i],  p_0 = seed distribution,
  *   p_k[i] = sum_{j -> i} p_{k-1}[j] * A_k[j][i]   (A as above).
  * p0 [dev] float[n_nodes] or NULL for the uniform 1/n_nodes.  prob_out [dev] float[n_nodes].
- * Sums are accumulated in fp64 and stored in fp32. */
-qv_status qv_access_prob(qv_ctx* ctx, const qv_csr* csr, const int32_t* fanouts /*[host]*/,
-                         int32_t n_hops, const float* p0, float* prob_out);
+ * Sums are accumulated in fp64 and stored in fp32.
+ * csr_in: the in-edge CSR of the same graph (row i lists the sources j of the edges j -> i), or
+ * NULL.  With it every sweep is a gather over in-edges (no atomics; several times faster);
+ * without it the sweeps scatter along out-edges with fp64 atomics.  For a symmetric
+ * (undirected) graph pass the graph itself. */
+qv_status qv_access_prob(qv_ctx* ctx, const qv_csr* csr, const qv_csr* csr_in,
+                         const int32_t* fanouts /*[host]*/, int32_t n_hops, const float* p0,
+                         float* prob_out);
 
 /* Placement order, Section 5.2 step (i): node ids sorted by prob descending, ties by smaller id.
  * prob [dev] float[n] (no NaNs), rank_out [dev] int32[n]. */

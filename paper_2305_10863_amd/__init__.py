@@ -19,7 +19,7 @@ QV_SAMPLE_CUMULATIVE, QV_FEAT_OWN_COPY = 1, 1
 
 EXPORTS = [
     "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget",
-    "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_sample_hop", "qv_sample", "qv_sample_many",
+    "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_csr_transpose", "qv_csr_rowptr", "qv_csr_col", "qv_sample_hop", "qv_sample", "qv_sample_many",
     "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc", "qv_feat_row_stride",
     "qv_gather", "qv_gather_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
 ]
@@ -61,6 +61,11 @@ def lib():
         L.qv_csr_create.argtypes = [vp, i64, i64, vp, i32, vp, i32, C.POINTER(vp)]
         L.qv_csr_destroy.argtypes = [vp]
         L.qv_csr_destroy.restype = None
+        L.qv_csr_transpose.argtypes = [vp, vp, C.POINTER(vp)]
+        L.qv_csr_rowptr.argtypes = [vp]
+        L.qv_csr_rowptr.restype = vp
+        L.qv_csr_col.argtypes = [vp]
+        L.qv_csr_col.restype = vp
         L.qv_sample_hop.argtypes = [vp, vp, vp, i64, i32, u64, i32, vp, i64, vp]
         L.qv_sample.argtypes = [vp, vp, vp, i64, C.POINTER(i32), i32, u64, C.c_uint32, C.POINTER(_SampleOut)]
         L.qv_sample_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i32), i32,
@@ -79,7 +84,7 @@ def lib():
         L.qv_gather.argtypes = [vp, vp, vp, i64, vp, vp, i64]
         L.qv_psgs.argtypes = [vp, vp, C.POINTER(i32), i32, vp]
         L.qv_psgs_batch_sum.argtypes = [vp, vp, i64, vp, i64, vp]
-        L.qv_access_prob.argtypes = [vp, vp, C.POINTER(i32), i32, vp, vp]
+        L.qv_access_prob.argtypes = [vp, vp, vp, C.POINTER(i32), i32, vp, vp]
         L.qv_place_rank.argtypes = [vp, vp, i64, vp]
         _lib = L
     return _lib
@@ -150,13 +155,38 @@ class Graph:
                 raise TypeError("%s must be a contiguous CUDA tensor or a pinned CPU tensor" % name)
         if rowptr.dtype not in (torch.int32, torch.int64) or col.dtype != torch.int32:
             raise TypeError("rowptr must be int32/int64 and col int32")
-        self.ctx, self.rowptr, self.col = ctx, rowptr, col
+        self.ctx, self.rowptr, self.col, self._rowptr_dtype = ctx, rowptr, col, rowptr.dtype
         self.n_nodes, self.n_edges = rowptr.numel() - 1, col.numel()
         h = C.c_void_p()
         ctx.check(lib().qv_csr_create(ctx.h, self.n_nodes, self.n_edges, _ptr(rowptr),
                                       32 if rowptr.dtype == torch.int32 else 64, _ptr(col),
                                       1 if validate else 0, C.byref(h)))
         self.h = h
+
+    def transpose(self):
+        """The in-edge CSR as a Graph whose arrays the library owns (qv_csr_transpose)."""
+        h = C.c_void_p()
+        self.ctx.check(lib().qv_csr_transpose(self.ctx.h, self.h, C.byref(h)))
+        t = Graph.__new__(Graph)
+        t.ctx, t.rowptr, t.col, t.h = self.ctx, None, None, h
+        t.n_nodes, t.n_edges, t._rowptr_dtype = self.n_nodes, self.n_edges, self._rowptr_dtype
+        return t
+
+    def arrays(self):
+        """(rowptr, col) as CUDA tensors; for a transposed graph, copies of the library's arrays."""
+        if self.rowptr is not None:
+            return self.rowptr, self.col
+        out = []
+        for ptr, n, dt, ts in ((lib().qv_csr_rowptr(self.h), self.n_nodes + 1, self._rowptr_dtype,
+                                "<i4" if self._rowptr_dtype == torch.int32 else "<i8"),
+                               (lib().qv_csr_col(self.h), self.n_edges, torch.int32, "<i4")):
+            if n == 0 or not ptr:
+                out.append(torch.empty(0, dtype=dt, device=self.ctx.device))
+                continue
+            view = type("_DevView", (), {"__cuda_array_interface__": {
+                "shape": (n,), "typestr": ts, "data": (ptr, False), "version": 2, "strides": None}})()
+            out.append(torch.as_tensor(view, device=self.ctx.device).clone())
+        return tuple(out)
 
     def __del__(self):
         if getattr(self, "h", None):
@@ -388,13 +418,15 @@ def qv_psgs_batch_sum(ctx, psgs, seeds):
     return out
 
 
-def qv_access_prob(ctx, graph, fanouts, p0=None, out=None):
+def qv_access_prob(ctx, graph, fanouts, p0=None, out=None, graph_in=None):
+    """graph_in: Graph of the in-edges (the transpose; the graph itself if it is symmetric) for the
+    atomic-free gather sweeps, or None for scatter sweeps."""
     if p0 is not None and (p0.dtype != torch.float32 or not p0.is_cuda or p0.numel() != graph.n_nodes):
         raise TypeError("p0 must be a float32 CUDA tensor with one entry per node")
     if out is None:
         out = torch.empty(max(graph.n_nodes, 1), dtype=torch.float32, device=ctx.device)
     arr, k = _fan(fanouts)
-    ctx.check(lib().qv_access_prob(ctx.h, graph.h, arr, k, _ptr(p0), _ptr(out)))
+    ctx.check(lib().qv_access_prob(ctx.h, graph.h, None if graph_in is None else graph_in.h, arr, k, _ptr(p0), _ptr(out)))
     return out[:graph.n_nodes]
 
 

@@ -6,12 +6,12 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libqv.so")
-SOURCES = ["ctx.hip", "sample.hip", "gather.hip", "metrics.hip"]
+SOURCES = ["ctx.hip", "sample.hip", "gather.hip", "metrics.hip", "transpose.hip"]
 FLAGS = ["-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 
 
-def build(force=True, jobs=4):
+def build(force=True, jobs=5):
     """Compile every source to an object (in parallel), then link."""
     objs, procs = [], []
     hdrs = [os.path.join(CSRC, "qv_internal.hpp"), os.path.join(HERE, "..", "include", "qv.h")]

@@ -205,6 +205,14 @@ qv_status qv_csr_create(qv_ctx* ctx, int64_t n_nodes, int64_t n_edges, const voi
     return QV_OK;
 }
 
-void qv_csr_destroy(qv_csr* csr) { delete csr; }
+const void* qv_csr_rowptr(const qv_csr* csr) { return csr ? csr->rowptr : nullptr; }
+const int32_t* qv_csr_col(const qv_csr* csr) { return csr ? csr->col : nullptr; }
+
+void qv_csr_destroy(qv_csr* csr) {
+    if (!csr) return;
+    if (csr->owned_rowptr) (void)hipFree(csr->owned_rowptr);
+    if (csr->owned_col) (void)hipFree(csr->owned_col);
+    delete csr;
+}
 
 }  // extern "C"

@@ -113,11 +113,108 @@ __global__ void k_fap_fold(int64_t n, const double* __restrict__ p_new, double* 
     }
 }
 
-__global__ void k_to_float(int64_t n, const double* __restrict__ src, float* __restrict__ dst) {
+// FAP with the in-edge CSR at hand: gather sweeps, no atomics.
+//   c_k[j]   = p_{k-1}[j] * min(deg_out j, l_k) / deg_out j      (what node j sends along each out-edge)
+//   p_k[i]   = sum over in-neighbours j of c_k[j]
+// One kernel per sweep computes p_k[i], adds it to the total and prepares c_{k+1}[i].  Rows longer
+// than kLongRow are left to k_fap_pull_long (a whole block per row) so that one hub does not hold
+// a 16-lane group for milliseconds.
+constexpr int64_t kLongRow = 8192;
+
+template <typename RPF>
+__device__ __forceinline__ double send_weight(const RPF* __restrict__ rowptr_f, int64_t i, int32_t fanout) {
+    const int64_t deg = (int64_t)rowptr_f[i + 1] - (int64_t)rowptr_f[i];
+    if (deg <= 0 || fanout <= 0) return 0.0;
+    return (double)(deg < fanout ? deg : (int64_t)fanout) / (double)deg;
+}
+
+template <typename RPF>
+__global__ void k_fap_pull_init(int64_t n, const float* __restrict__ p0, double uniform, const RPF* __restrict__ rowptr_f,
+                                int32_t fanout1, double* __restrict__ c_cur, double* __restrict__ p_tot, int32_t* n_long) {
     int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    for (int64_t i = tid; i < n; i += stride) dst[i] = (float)src[i];
+    if (tid == 0) *n_long = 0;
+    for (int64_t i = tid; i < n; i += stride) {
+        const double v = p0 ? (double)p0[i] : uniform;
+        p_tot[i] = v;
+        c_cur[i] = v * send_weight(rowptr_f, i, fanout1);
+    }
 }
+
+template <typename RPF>
+__device__ __forceinline__ void fap_finish_row(int64_t i, double p, const RPF* __restrict__ rowptr_f, int32_t next_fanout,
+                                               double* __restrict__ c_nxt, double* __restrict__ p_tot,
+                                               float* __restrict__ out) {
+    const double t = p_tot[i] + p;
+    p_tot[i] = t;
+    if (next_fanout > 0) c_nxt[i] = p * send_weight(rowptr_f, i, next_fanout);
+    if (out) out[i] = (float)t;
+}
+
+template <int G, typename RPT, typename RPF>
+__global__ void __launch_bounds__(256) k_fap_pull(const RPT* __restrict__ rowptr_t, const int32_t* __restrict__ col_t,
+                                                  const RPF* __restrict__ rowptr_f, int64_t n, int32_t next_fanout,
+                                                  const double* __restrict__ c_cur, double* __restrict__ c_nxt,
+                                                  double* __restrict__ p_tot, float* __restrict__ out,
+                                                  int32_t* __restrict__ long_rows, int32_t* n_long, int32_t long_cap) {
+    const int sub = threadIdx.x % G;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G;
+    const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / G;
+    for (int64_t i = group; i < n; i += n_groups) {
+        const int64_t rs = (int64_t)rowptr_t[i], re = (int64_t)rowptr_t[i + 1];
+        if (re - rs > kLongRow) {
+            if (sub == 0) {
+                const int32_t k = atomicAdd(n_long, 1);
+                if (k < long_cap) long_rows[k] = (int32_t)i;
+            }
+            continue;
+        }
+        double acc0 = 0.0, acc1 = 0.0;
+        int64_t e = rs + sub;
+        for (; e + G < re; e += 2 * G) {
+            const double x0 = c_cur[col_t[e]], x1 = c_cur[col_t[e + G]];
+            acc0 += x0; acc1 += x1;
+        }
+        if (e < re) acc0 += c_cur[col_t[e]];
+        const double p = group_sum<G>(acc0 + acc1);
+        if (sub == 0) fap_finish_row(i, p, rowptr_f, next_fanout, c_nxt, p_tot, out);
+    }
+}
+
+template <typename RPT, typename RPF>
+__global__ void __launch_bounds__(256) k_fap_pull_long(const RPT* __restrict__ rowptr_t, const int32_t* __restrict__ col_t,
+                                                       const RPF* __restrict__ rowptr_f, int32_t next_fanout,
+                                                       const double* __restrict__ c_cur, double* __restrict__ c_nxt,
+                                                       double* __restrict__ p_tot, float* __restrict__ out,
+                                                       const int32_t* __restrict__ long_rows, int32_t* n_long,
+                                                       int32_t long_cap) {
+    __shared__ double part[256 / kWave];
+    int32_t count = *n_long;
+    if (count > long_cap) count = long_cap;
+    for (int32_t k = blockIdx.x; k < count; k += gridDim.x) {
+        const int64_t i = long_rows[k];
+        const int64_t rs = (int64_t)rowptr_t[i], re = (int64_t)rowptr_t[i + 1];
+        double acc0 = 0.0, acc1 = 0.0;
+        int64_t e = rs + threadIdx.x;
+        for (; e + 256 < re; e += 512) {
+            const double x0 = c_cur[col_t[e]], x1 = c_cur[col_t[e + 256]];
+            acc0 += x0; acc1 += x1;
+        }
+        if (e < re) acc0 += c_cur[col_t[e]];
+        const double w = group_sum<kWave>(acc0 + acc1);
+        __syncthreads();
+        if (threadIdx.x % kWave == 0) part[threadIdx.x / kWave] = w;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double p = 0.0;
+            for (int q = 0; q < 256 / kWave; ++q) p += part[q];
+            fap_finish_row(i, p, rowptr_f, next_fanout, c_nxt, p_tot, out);
+        }
+    }
+}
+
+// the sweep is over: reset the long-row list for the next one (after k_fap_pull_long has read it)
+__global__ void k_fap_pull_reset(int32_t* n_long) { *n_long = 0; }
 
 // placement keys: ascending order of the key == descending prob, ties by ascending id
 __global__ void k_rank_keys(int64_t n, const float* __restrict__ prob, uint64_t* __restrict__ keys) {
@@ -180,6 +277,52 @@ static qv_status check_fanouts(qv_ctx* ctx, const char* who, const int32_t* fano
 
 using namespace qv;
 
+template <typename RPT, typename RPF>
+static qv_status fap_pull(qv_ctx* ctx, const qv_csr* g, const qv_csr* gin, const int32_t* fanouts, int n_hops,
+                          const float* p0, float* prob_out) {
+    const int64_t n = g->n_nodes;
+    const int64_t long_cap64 = gin->n_edges / kLongRow + 1;
+    const int32_t long_cap = (int32_t)long_cap64;
+    qv_status rc = arena_begin(ctx, 3 * align_up((size_t)n * 8) + align_up((size_t)long_cap * 4) + 4096);
+    if (rc != QV_OK) return rc;
+    double* c_cur = (double*)arena_take(ctx, (size_t)n * 8);
+    double* c_nxt = (double*)arena_take(ctx, (size_t)n * 8);
+    double* p_tot = (double*)arena_take(ctx, (size_t)n * 8);
+    int32_t* long_rows = (int32_t*)arena_take(ctx, (size_t)long_cap * 4);
+    int32_t* n_long = (int32_t*)arena_take(ctx, 4);
+    const RPT* rpt = (const RPT*)gin->rowptr;
+    const RPF* rpf = (const RPF*)g->rowptr;
+    const int ew = grid_for(n, 256 * 4, ctx->n_cu * 16);
+    hipLaunchKernelGGL((k_fap_pull_init<RPF>), dim3(ew), dim3(256), 0, ctx->stream, n, p0, 1.0 / (double)n, rpf, fanouts[0],
+                       c_cur, p_tot, n_long);
+    QV_LAUNCH_CHECK(ctx, "k_fap_pull_init");
+    const int G = group_width_for(n, gin->n_edges);
+    const int blocks = grid_for(n * G, 256, ctx->n_cu * 32);
+    for (int k = 1; k <= n_hops; ++k) {
+        const int32_t nf = k < n_hops ? fanouts[k] : 0;
+        float* out = k == n_hops ? prob_out : (float*)nullptr;
+#define QV_PULL(GW)                                                                                                    \
+    hipLaunchKernelGGL((k_fap_pull<GW, RPT, RPF>), dim3(blocks), dim3(256), 0, ctx->stream, rpt, gin->col, rpf, n, nf,     \
+                       (const double*)c_cur, c_nxt, p_tot, out, long_rows, n_long, long_cap)
+        switch (G) {
+            case 4: QV_PULL(4); break;
+            case 8: QV_PULL(8); break;
+            case 16: QV_PULL(16); break;
+            case 32: QV_PULL(32); break;
+            default: QV_PULL(64); break;
+        }
+#undef QV_PULL
+        QV_LAUNCH_CHECK(ctx, "k_fap_pull");
+        hipLaunchKernelGGL((k_fap_pull_long<RPT, RPF>), dim3(grid_for(long_cap, 1, ctx->n_cu * 4)), dim3(256), 0, ctx->stream,
+                           rpt, gin->col, rpf, nf, (const double*)c_cur, c_nxt, p_tot, out, (const int32_t*)long_rows, n_long,
+                           long_cap);
+        hipLaunchKernelGGL(k_fap_pull_reset, dim3(1), dim3(1), 0, ctx->stream, n_long);
+        QV_LAUNCH_CHECK(ctx, "k_fap_pull_long");
+        double* t = c_cur; c_cur = c_nxt; c_nxt = t;
+    }
+    return QV_OK;
+}
+
 extern "C" {
 
 qv_status qv_psgs(qv_ctx* ctx, const qv_csr* g, const int32_t* fanouts, int32_t n_hops, float* psgs_out) {
@@ -216,14 +359,22 @@ qv_status qv_psgs_batch_sum(qv_ctx* ctx, const float* psgs, int64_t n_nodes, con
     return QV_OK;
 }
 
-qv_status qv_access_prob(qv_ctx* ctx, const qv_csr* g, const int32_t* fanouts, int32_t n_hops, const float* p0,
-                         float* prob_out) {
+qv_status qv_access_prob(qv_ctx* ctx, const qv_csr* g, const qv_csr* g_in, const int32_t* fanouts, int32_t n_hops,
+                         const float* p0, float* prob_out) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_access_prob: ctx is NULL");
     if (!g || !prob_out) return fail(ctx, QV_EINVAL, "qv_access_prob: null argument");
     qv_status rc = check_fanouts(ctx, "qv_access_prob", fanouts, n_hops);
     if (rc != QV_OK) return rc;
     const int64_t n = g->n_nodes;
     if (n == 0) return QV_OK;
+    if (g_in) {
+        if (g_in->n_nodes != n || g_in->n_edges != g->n_edges)
+            return fail(ctx, QV_EINVAL, "qv_access_prob: the in-edge CSR must have the node and edge counts of the graph");
+        if (g_in->rowptr_bits == 32) return g->rowptr_bits == 32 ? fap_pull<int32_t, int32_t>(ctx, g, g_in, fanouts, n_hops, p0, prob_out)
+                                                                   : fap_pull<int32_t, int64_t>(ctx, g, g_in, fanouts, n_hops, p0, prob_out);
+        return g->rowptr_bits == 32 ? fap_pull<int64_t, int32_t>(ctx, g, g_in, fanouts, n_hops, p0, prob_out)
+                                     : fap_pull<int64_t, int64_t>(ctx, g, g_in, fanouts, n_hops, p0, prob_out);
+    }
     rc = arena_begin(ctx, 3 * align_up((size_t)n * 8) + 4096);
     if (rc != QV_OK) return rc;
     double* p_cur = (double*)arena_take(ctx, (size_t)n * 8);

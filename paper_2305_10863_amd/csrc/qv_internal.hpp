@@ -72,6 +72,8 @@ struct qv_csr {
     const void* rowptr;
     int rowptr_bits;
     const int32_t* col;
+    void* owned_rowptr = nullptr;      // set when the library allocated the arrays (qv_csr_transpose)
+    int32_t* owned_col = nullptr;
 };
 
 struct qv_feat {

@@ -69,8 +69,13 @@ def check_batches(qv, ctx, w, rowptr, col, g, feat, batches, n_seeds=None, table
 
 def check_metrics(qv, ctx, w, rowptr, col, g, p0=None):
     Q = qv.qv_psgs(ctx, g, w.fanouts)
-    P = qv.qv_access_prob(ctx, g, w.fanouts, p0=None if p0 is None else torch.from_numpy(p0.astype(np.float32)).cuda())
+    p0d = None if p0 is None else torch.from_numpy(p0.astype(np.float32)).cuda()
+    P = qv.qv_access_prob(ctx, g, w.fanouts, p0=p0d)
+    # the gather form over in-edges: a symmetrised graph is its own transpose, others get one built
+    g_in = g if w.symmetrise else g.transpose()
+    P_in = qv.qv_access_prob(ctx, g, w.fanouts, p0=p0d, graph_in=g_in)
     ctx.sync()
+    del g_in
     oQ = oracle.psgs(rowptr, col, w.fanouts)
     oP = oracle.access_prob(rowptr, col, w.fanouts, p0=None if p0 is None else p0.astype(np.float32).astype(np.float64))
     Qh, Ph = Q.cpu().numpy().astype(np.float64), P.cpu().numpy().astype(np.float64)
@@ -78,6 +83,9 @@ def check_metrics(qv, ctx, w, rowptr, col, g, p0=None):
     nz = oP != 0
     assert np.all(Ph[~nz] == 0)
     assert np.max(np.abs(Ph[nz] - oP[nz]) / oP[nz]) <= REL_TOL
+    Pi = P_in.cpu().numpy().astype(np.float64)
+    assert np.all(Pi[~nz] == 0)
+    assert np.max(np.abs(Pi[nz] - oP[nz]) / oP[nz]) <= REL_TOL
     return Q, P, oQ
 
 

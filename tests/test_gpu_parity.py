@@ -412,11 +412,97 @@ def test_psgs_and_access_prob_match_oracle(qv, ctx, name, w):
         assert rel_err(P2.cpu().numpy(), oracle.access_prob(rowptr, col, fanouts, p0=p0.astype(np.float64))) <= REL_TOL
         # accesses per request == expected sample size, on the GPU's own numbers
         assert abs(P.double().sum().item() - Q.double().mean().item()) <= 1e-4 * oQ.mean()
+        # the same through the in-edge CSR (gather sweeps, no atomics)
+        if fanouts is w.fanouts or len(fanouts) == 3:
+            g_in = transposed_graph(qv, ctx, rowptr, col)
+            P3 = qv.qv_access_prob(ctx, g, fanouts, graph_in=g_in)
+            P4 = qv.qv_access_prob(ctx, g, fanouts, p0=dev(p0), graph_in=g_in)
+            ctx.sync()
+            assert rel_err(P3.cpu().numpy(), oracle.access_prob(rowptr, col, fanouts)) <= REL_TOL
+            assert rel_err(P4.cpu().numpy(), oracle.access_prob(rowptr, col, fanouts, p0=p0.astype(np.float64))) <= REL_TOL
     seeds = w.seeds(0)
     Q = qv.qv_psgs(ctx, g, w.fanouts)
     s = qv.qv_psgs_batch_sum(ctx, Q, dev(seeds))
     ctx.sync()
     assert abs(s.item() - oracle.psgs(rowptr, col, w.fanouts)[seeds].sum()) <= 1e-4 * s.item()
+
+
+def transpose_csr(rowptr, col):
+    """In-edge CSR built with numpy only (a stable sort of the edges by destination)."""
+    n = len(rowptr) - 1
+    src = np.repeat(np.arange(n, dtype=np.int32), np.diff(rowptr))
+    order = np.argsort(col, kind="stable")
+    rowptr_t = np.zeros(n + 1, dtype=rowptr.dtype)
+    np.cumsum(np.bincount(col, minlength=n), out=rowptr_t[1:])
+    return rowptr_t, src[order]
+
+
+def transposed_graph(qv, ctx, rowptr, col):
+    rt, ct = transpose_csr(rowptr, col)
+    return make_graph(qv, ctx, rt, ct)
+
+
+@pytest.mark.parametrize("rp_dtype", [np.int32, np.int64])
+def test_access_prob_in_edge_form_directed_graph_with_hub_rows(qv, ctx, rp_dtype):
+    """A directed graph in which a few nodes receive tens of thousands of edges (in-rows beyond the
+    per-group limit, handled a block per row) and some nodes have no out- or no in-edges."""
+    rng = np.random.default_rng(20)
+    n = 60_000
+    deg = rng.integers(0, 12, n)
+    deg[rng.random(n) < 0.1] = 0
+    rowptr = np.zeros(n + 1, dtype=rp_dtype)
+    np.cumsum(deg, out=rowptr[1:])
+    col = rng.integers(100, n, int(rowptr[-1])).astype(np.int32)
+    hub = rng.random(len(col))
+    col[hub < 0.10] = 3                       # ~33k in-edges
+    col[(hub >= 0.10) & (hub < 0.14)] = 4     # ~13k in-edges
+    col[(hub >= 0.14) & (hub < 0.16)] = 5     # below the limit
+    g = make_graph(qv, ctx, rowptr, col)
+    rt, ct = transpose_csr(rowptr, col)
+    d_in = np.diff(rt)
+    assert d_in.max() > 20_000 and 8_192 < d_in[4] < 20_000 and d_in[5] < 8_192 and (d_in == 0).any()
+    g_in = make_graph(qv, ctx, rt.astype(np.int64 if rp_dtype is np.int32 else np.int32), ct)
+    # the library's own transpose: identical arrays (sources ascending within a row), same width
+    g_lib = g.transpose()
+    lrt, lct = g_lib.arrays()
+    assert lrt.cpu().numpy().dtype == rp_dtype
+    assert np.array_equal(lrt.cpu().numpy(), rt) and np.array_equal(lct.cpu().numpy(), ct)
+    P = qv.qv_access_prob(ctx, g, [5, 4, 3], graph_in=g_lib)
+    ctx.sync()
+    assert rel_err(P.cpu().numpy(), oracle.access_prob(rowptr, col, [5, 4, 3])) <= REL_TOL
+    # transposing twice gives the graph with every row sorted
+    brt, bct = g_lib.transpose().arrays()
+    assert np.array_equal(brt.cpu().numpy(), rowptr)
+    want_sorted = np.concatenate([np.sort(col[rowptr[v]:rowptr[v + 1]]) for v in range(0, n, 997)])
+    got_sorted = np.concatenate([bct.cpu().numpy()[rowptr[v]:rowptr[v + 1]] for v in range(0, n, 997)])
+    assert np.array_equal(got_sorted, want_sorted)
+    for fanouts in ([5, 4, 3], [20], [2, 2, 2, 2]):
+        P = qv.qv_access_prob(ctx, g, fanouts, graph_in=g_in)
+        Ppush = qv.qv_access_prob(ctx, g, fanouts)
+        ctx.sync()
+        want = oracle.access_prob(rowptr, col, fanouts)
+        assert rel_err(P.cpu().numpy(), want) <= REL_TOL
+        assert rel_err(Ppush.cpu().numpy(), want) <= REL_TOL
+    other_rowptr = np.ones(n, dtype=np.int64)          # n-1 nodes, one edge
+    other_rowptr[0] = 0
+    other = make_graph(qv, ctx, other_rowptr, np.zeros(1, dtype=np.int32))
+    with pytest.raises(qv.QvError):
+        qv.qv_access_prob(ctx, g, [3], graph_in=other)
+
+
+def test_csr_transpose_degenerate_graphs(qv, ctx):
+    # no edges at all, a single node with a self loop, and parallel edges
+    g0 = make_graph(qv, ctx, np.zeros(6, dtype=np.int64), np.zeros(0, dtype=np.int32))
+    rt, ct = g0.transpose().arrays()
+    assert np.array_equal(rt.cpu().numpy(), np.zeros(6, dtype=np.int64)) and ct.numel() == 0
+    g1 = make_graph(qv, ctx, np.array([0, 1], dtype=np.int32), np.array([0], dtype=np.int32))
+    rt, ct = g1.transpose().arrays()
+    assert rt.cpu().tolist() == [0, 1] and ct.cpu().tolist() == [0]
+    rowptr = np.array([0, 3, 3, 5], dtype=np.int32)
+    col = np.array([2, 2, 1, 0, 2], dtype=np.int32)
+    rt, ct = make_graph(qv, ctx, rowptr, col).transpose().arrays()
+    ert, ect = transpose_csr(rowptr, col)
+    assert rt.cpu().tolist() == ert.tolist() == [0, 1, 2, 5] and ct.cpu().tolist() == ect.tolist() == [2, 0, 0, 0, 2]
 
 
 def test_place_rank_large_with_ties(qv, ctx):
