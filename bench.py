@@ -24,7 +24,7 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 # Measured HBM bytes of k_gather over its algorithmic bytes (rocprofv3 FETCH_SIZE + WRITE_SIZE,
 # each scaled by a 1 GiB plain copy kernel; profiles/citation_k_gather_and_sampling_kernels.md).
 # Only quoted for the configuration that was profiled.
-GATHER_TRAFFIC_RATIO = {("citation", 1.0, 8): 0.992}
+GATHER_TRAFFIC_RATIO = {("citation", 1.0, 8): 0.972}
 
 
 def log(msg):
