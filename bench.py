@@ -259,7 +259,7 @@ def main():
                 Pdev = res
             else:
                 Qdev = res.clone()
-        # FAP again in its gather form over in-edges (a symmetrised graph is its own transpose)
+        # FAP again with the in-edge CSR at hand (a symmetrised graph is its own transpose)
         t0 = time.perf_counter()
         g_in = g if w.symmetrise else g.transpose()
         if not w.symmetrise:
@@ -275,7 +275,7 @@ def main():
         extra["access_prob_forms_max_rel_diff"] = float(((P_in - Pdev).abs() / Pdev.clamp_min(1e-30)).max().item())
         del g_in, P_in
         torch.cuda.empty_cache()
-        log("psgs %.2f ms, access_prob %.2f ms (scatter) / %.2f ms (gather over in-edges) over the whole graph"
+        log("psgs %.2f ms, access_prob %.2f ms (out-edges only) / %.2f ms (with the in-edge CSR) over the whole graph"
             % (extra["psgs_ms"], extra["access_prob_ms"], extra["access_prob_in_edge_form_ms"]))
 
     table_for_ablation = table if args.placement_ablation else None

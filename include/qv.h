@@ -74,6 +74,14 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts /*
  * batch is used.  Default 16 GiB; 0 selects the hash always.  Results are identical. */
 qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes);
 
+/* Testing / tuning aid for qv_access_prob when it is given the in-edge CSR: 0 (default) lets every
+ * sweep choose between gathering over in-edges and scattering along the out-edges of the nodes
+ * that carry mass; 1 always gathers; 2 always scatters.  Results agree to rounding. */
+#define QV_FAP_CHOOSE 0
+#define QV_FAP_GATHER 1
+#define QV_FAP_SCATTER 2
+qv_status qv_ctx_set_fap_direction(qv_ctx* ctx, int32_t direction);
+
 /* Testing aid.  The dedup tables are never cleared between calls: every call stamps its entries
  * with a fresh epoch number, and only when the counter is exhausted (about 10^6 calls) are the
  * tables cleared once.  This sets the counter so that a test can cross that point quickly. */
@@ -265,9 +273,11 @@ qv_status qv_psgs_batch_sum(qv_ctx* ctx, const float* psgs, int64_t n_nodes, con
  * p0 [dev] float[n_nodes] or NULL for the uniform 1/n_nodes.  prob_out [dev] float[n_nodes].
  * Sums are accumulated in fp64 and stored in fp32.
  * csr_in: the in-edge CSR of the same graph (row i lists the sources j of the edges j -> i), or
- * NULL.  With it every sweep is a gather over in-edges (no atomics; several times faster);
- * without it the sweeps scatter along out-edges with fp64 atomics.  For a symmetric
- * (undirected) graph pass the graph itself. */
+ * NULL.  Without it every sweep scatters along out-edges with fp64 atomics.  With it each sweep
+ * either gathers over in-edges (no atomics) or, when few nodes carry mass (a sparse p0, or a
+ * graph where most nodes have no in-edges), scatters from those nodes only; the choice is made
+ * on the device, the call stays asynchronous.  For a symmetric (undirected) graph pass the graph
+ * itself; for any other, qv_csr_transpose builds one. */
 qv_status qv_access_prob(qv_ctx* ctx, const qv_csr* csr, const qv_csr* csr_in,
                          const int32_t* fanouts /*[host]*/, int32_t n_hops, const float* p0,
                          float* prob_out);

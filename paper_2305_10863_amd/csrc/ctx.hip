@@ -133,6 +133,13 @@ qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes) {
     return QV_OK;
 }
 
+qv_status qv_ctx_set_fap_direction(qv_ctx* ctx, int32_t direction) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_set_fap_direction: ctx is NULL");
+    if (direction < 0 || direction > 2) return fail(ctx, QV_EINVAL, "qv_ctx_set_fap_direction: 0 (choose), 1 (gather) or 2 (scatter)");
+    ctx->fap_direction = direction;
+    return QV_OK;
+}
+
 qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes, uint32_t flags,
                            int64_t* max_nodes, int64_t* max_edges, int64_t* max_frontier) {
     if (n_seeds < 0 || n_hops < 1 || n_hops > QV_MAX_HOPS || !fanouts || n_nodes < 0)

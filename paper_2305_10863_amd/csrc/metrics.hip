@@ -113,42 +113,82 @@ __global__ void k_fap_fold(int64_t n, const double* __restrict__ p_new, double* 
     }
 }
 
-// FAP with the in-edge CSR at hand: gather sweeps, no atomics.
+// FAP with the in-edge CSR at hand.
 //   c_k[j]   = p_{k-1}[j] * min(deg_out j, l_k) / deg_out j      (what node j sends along each out-edge)
 //   p_k[i]   = sum over in-neighbours j of c_k[j]
-// One kernel per sweep computes p_k[i], adds it to the total and prepares c_{k+1}[i].  Rows longer
-// than kLongRow are left to k_fap_pull_long (a whole block per row) so that one hub does not hold
-// a 16-lane group for milliseconds.
+// Every sweep runs in one of two directions, chosen on the device from the number of out-edges that
+// leave nodes with mass (counted while the previous sweep finishes its rows):
+//   gather  (k_fap_pull, k_fap_pull_long): row i sums c_k over its in-row; no atomics; reads all edges.
+//   scatter (k_fap_scatter + k_fap_scatter_fold): nodes with mass add c_k[j] along their out-edges
+//           with fp64 atomics; reads only those edges.
+// A random atomic costs about 2.5 random loads on this GPU, so scatter is taken when fewer than
+// 1/2.5 of the edges are active (a sparse p_0; the later sweeps of a citation-like graph, where
+// two thirds of the nodes are never cited and so carry no mass after the first sweep).
+// Both kernels of both directions are launched every sweep; the ones not chosen return at once.
+// Rows longer than kLongRow are left to k_fap_pull_long (a whole block per row) so that one hub
+// does not hold a 16-lane group for milliseconds.
 constexpr int64_t kLongRow = 8192;
+constexpr double kAtomicPerLoadCost = 2.5;
+
+struct FapControl {
+    double active_edges;    // out-edges of nodes whose c of the coming sweep is non-zero (exact: integers below 2^53)
+    int32_t scatter;        // direction of the sweep being run
+    int32_t n_long;         // rows handed to k_fap_pull_long
+};
 
 template <typename RPF>
-__device__ __forceinline__ double send_weight(const RPF* __restrict__ rowptr_f, int64_t i, int32_t fanout) {
+__device__ __forceinline__ double send_weight(const RPF* __restrict__ rowptr_f, int64_t i, int32_t fanout, double* deg_out) {
     const int64_t deg = (int64_t)rowptr_f[i + 1] - (int64_t)rowptr_f[i];
+    *deg_out = (double)deg;
     if (deg <= 0 || fanout <= 0) return 0.0;
     return (double)(deg < fanout ? deg : (int64_t)fanout) / (double)deg;
 }
 
-template <typename RPF>
-__global__ void k_fap_pull_init(int64_t n, const float* __restrict__ p0, double uniform, const RPF* __restrict__ rowptr_f,
-                                int32_t fanout1, double* __restrict__ c_cur, double* __restrict__ p_tot, int32_t* n_long) {
-    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    int64_t stride = (int64_t)gridDim.x * blockDim.x;
-    if (tid == 0) *n_long = 0;
-    for (int64_t i = tid; i < n; i += stride) {
-        const double v = p0 ? (double)p0[i] : uniform;
-        p_tot[i] = v;
-        c_cur[i] = v * send_weight(rowptr_f, i, fanout1);
-    }
+// every lane of the wave calls this once, at the end of the kernel
+__device__ __forceinline__ void add_active(FapControl* ctl, double local) {
+    const double w = group_sum<kWave>(local);
+    if (threadIdx.x % kWave == 0 && w != 0.0) unsafeAtomicAdd(&ctl->active_edges, w);
 }
 
 template <typename RPF>
-__device__ __forceinline__ void fap_finish_row(int64_t i, double p, const RPF* __restrict__ rowptr_f, int32_t next_fanout,
-                                               double* __restrict__ c_nxt, double* __restrict__ p_tot,
-                                               float* __restrict__ out) {
+__global__ void k_fap_pull_init(int64_t n, const float* __restrict__ p0, double uniform, const RPF* __restrict__ rowptr_f,
+                                int32_t fanout1, double* __restrict__ c_cur, double* __restrict__ p_tot, FapControl* ctl) {
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    double active = 0.0;
+    for (int64_t i = tid; i < n; i += stride) {
+        const double v = p0 ? (double)p0[i] : uniform;
+        double deg;
+        const double c = v * send_weight(rowptr_f, i, fanout1, &deg);
+        p_tot[i] = v;
+        c_cur[i] = c;
+        if (c != 0.0) active += deg;
+    }
+    add_active(ctl, active);
+}
+
+__global__ void k_fap_control_clear(FapControl* ctl) { ctl->active_edges = 0.0; ctl->scatter = 0; ctl->n_long = 0; }
+
+// before each sweep: fix its direction, restart the counters the sweep fills for the next one
+__global__ void k_fap_decide(FapControl* ctl, double n_edges, int32_t allow_scatter) {
+    ctl->scatter = (allow_scatter && ctl->active_edges * kAtomicPerLoadCost < n_edges) ? 1 : 0;
+    ctl->active_edges = 0.0;
+    ctl->n_long = 0;
+}
+
+// p = p_k[i]: fold into the total, prepare c_{k+1}[i]; returns the out-edges i activates in the next sweep
+template <typename RPF>
+__device__ __forceinline__ double fap_finish_row(int64_t i, double p, const RPF* __restrict__ rowptr_f, int32_t next_fanout,
+                                                 double* __restrict__ c_nxt, double* __restrict__ p_tot,
+                                                 float* __restrict__ out) {
     const double t = p_tot[i] + p;
     p_tot[i] = t;
-    if (next_fanout > 0) c_nxt[i] = p * send_weight(rowptr_f, i, next_fanout);
     if (out) out[i] = (float)t;
+    if (next_fanout <= 0) return 0.0;
+    double deg;
+    const double c = p * send_weight(rowptr_f, i, next_fanout, &deg);
+    c_nxt[i] = c;
+    return c != 0.0 ? deg : 0.0;
 }
 
 template <int G, typename RPT, typename RPF>
@@ -156,15 +196,17 @@ __global__ void __launch_bounds__(256) k_fap_pull(const RPT* __restrict__ rowptr
                                                   const RPF* __restrict__ rowptr_f, int64_t n, int32_t next_fanout,
                                                   const double* __restrict__ c_cur, double* __restrict__ c_nxt,
                                                   double* __restrict__ p_tot, float* __restrict__ out,
-                                                  int32_t* __restrict__ long_rows, int32_t* n_long, int32_t long_cap) {
+                                                  int32_t* __restrict__ long_rows, FapControl* ctl, int32_t long_cap) {
+    if (ctl->scatter) return;
     const int sub = threadIdx.x % G;
     const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G;
     const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / G;
+    double active = 0.0;
     for (int64_t i = group; i < n; i += n_groups) {
         const int64_t rs = (int64_t)rowptr_t[i], re = (int64_t)rowptr_t[i + 1];
         if (re - rs > kLongRow) {
             if (sub == 0) {
-                const int32_t k = atomicAdd(n_long, 1);
+                const int32_t k = atomicAdd(&ctl->n_long, 1);
                 if (k < long_cap) long_rows[k] = (int32_t)i;
             }
             continue;
@@ -177,8 +219,9 @@ __global__ void __launch_bounds__(256) k_fap_pull(const RPT* __restrict__ rowptr
         }
         if (e < re) acc0 += c_cur[col_t[e]];
         const double p = group_sum<G>(acc0 + acc1);
-        if (sub == 0) fap_finish_row(i, p, rowptr_f, next_fanout, c_nxt, p_tot, out);
+        if (sub == 0) active += fap_finish_row(i, p, rowptr_f, next_fanout, c_nxt, p_tot, out);
     }
+    add_active(ctl, active);
 }
 
 template <typename RPT, typename RPF>
@@ -186,11 +229,13 @@ __global__ void __launch_bounds__(256) k_fap_pull_long(const RPT* __restrict__ r
                                                        const RPF* __restrict__ rowptr_f, int32_t next_fanout,
                                                        const double* __restrict__ c_cur, double* __restrict__ c_nxt,
                                                        double* __restrict__ p_tot, float* __restrict__ out,
-                                                       const int32_t* __restrict__ long_rows, int32_t* n_long,
+                                                       const int32_t* __restrict__ long_rows, FapControl* ctl,
                                                        int32_t long_cap) {
     __shared__ double part[256 / kWave];
-    int32_t count = *n_long;
+    if (ctl->scatter) return;
+    int32_t count = ctl->n_long;
     if (count > long_cap) count = long_cap;
+    double active = 0.0;
     for (int32_t k = blockIdx.x; k < count; k += gridDim.x) {
         const int64_t i = long_rows[k];
         const int64_t rs = (int64_t)rowptr_t[i], re = (int64_t)rowptr_t[i + 1];
@@ -208,13 +253,59 @@ __global__ void __launch_bounds__(256) k_fap_pull_long(const RPT* __restrict__ r
         if (threadIdx.x == 0) {
             double p = 0.0;
             for (int q = 0; q < 256 / kWave; ++q) p += part[q];
-            fap_finish_row(i, p, rowptr_f, next_fanout, c_nxt, p_tot, out);
+            active += fap_finish_row(i, p, rowptr_f, next_fanout, c_nxt, p_tot, out);
         }
+    }
+    add_active(ctl, active);
+}
+
+// scatter direction, step 1: the accumulator (the next sweep's c array) starts at zero
+__global__ void k_fap_scatter_clear(int64_t n, double* __restrict__ c_nxt, const FapControl* ctl) {
+    if (!ctl->scatter) return;
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = tid; i < n; i += stride) c_nxt[i] = 0.0;
+}
+
+// step 2: nodes with mass add what they send to each out-neighbour's accumulator
+template <int G, typename RPF>
+__global__ void __launch_bounds__(256) k_fap_scatter(const RPF* __restrict__ rowptr_f, const int32_t* __restrict__ col_f, int64_t n,
+                                                     const double* __restrict__ c_cur, double* __restrict__ acc,
+                                                     const FapControl* ctl) {
+    if (!ctl->scatter) return;
+    const int sub = threadIdx.x % G;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G;
+    const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / G;
+    for (int64_t j = group; j < n; j += n_groups) {
+        const double c = c_cur[j];
+        if (c == 0.0) continue;
+        const int64_t rs = (int64_t)rowptr_f[j], re = (int64_t)rowptr_f[j + 1];
+        for (int64_t e = rs + sub; e < re; e += G) unsafeAtomicAdd(&acc[col_f[e]], c);
     }
 }
 
-// the sweep is over: reset the long-row list for the next one (after k_fap_pull_long has read it)
-__global__ void k_fap_pull_reset(int32_t* n_long) { *n_long = 0; }
+// step 3: the accumulator holds p_k; finish every row in place (acc[i] becomes c_{k+1}[i])
+template <typename RPF>
+__global__ void k_fap_scatter_fold(int64_t n, const RPF* __restrict__ rowptr_f, int32_t next_fanout, double* acc,
+                                   double* __restrict__ p_tot, float* __restrict__ out, FapControl* ctl) {
+    if (!ctl->scatter) return;
+    int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    double active = 0.0;
+    for (int64_t i = tid; i < n; i += stride) {
+        const double p = acc[i];
+        const double t = p_tot[i] + p;
+        p_tot[i] = t;
+        if (out) out[i] = (float)t;
+        if (next_fanout > 0) {
+            double deg;
+            const double c = p * send_weight(rowptr_f, i, next_fanout, &deg);
+            acc[i] = c;
+            if (c != 0.0) active += deg;
+        }
+    }
+    add_active(ctl, active);
+}
 
 // placement keys: ascending order of the key == descending prob, ties by ascending id
 __global__ void k_rank_keys(int64_t n, const float* __restrict__ prob, uint64_t* __restrict__ keys) {
@@ -289,21 +380,27 @@ static qv_status fap_pull(qv_ctx* ctx, const qv_csr* g, const qv_csr* gin, const
     double* c_nxt = (double*)arena_take(ctx, (size_t)n * 8);
     double* p_tot = (double*)arena_take(ctx, (size_t)n * 8);
     int32_t* long_rows = (int32_t*)arena_take(ctx, (size_t)long_cap * 4);
-    int32_t* n_long = (int32_t*)arena_take(ctx, 4);
+    FapControl* ctl = (FapControl*)arena_take(ctx, sizeof(FapControl));
     const RPT* rpt = (const RPT*)gin->rowptr;
     const RPF* rpf = (const RPF*)g->rowptr;
     const int ew = grid_for(n, 256 * 4, ctx->n_cu * 16);
+    hipLaunchKernelGGL(k_fap_control_clear, dim3(1), dim3(1), 0, ctx->stream, ctl);
     hipLaunchKernelGGL((k_fap_pull_init<RPF>), dim3(ew), dim3(256), 0, ctx->stream, n, p0, 1.0 / (double)n, rpf, fanouts[0],
-                       c_cur, p_tot, n_long);
+                       c_cur, p_tot, ctl);
     QV_LAUNCH_CHECK(ctx, "k_fap_pull_init");
     const int G = group_width_for(n, gin->n_edges);
+    const int Gf = group_width_for(n, g->n_edges);
     const int blocks = grid_for(n * G, 256, ctx->n_cu * 32);
+    const int blocks_f = grid_for(n * Gf, 256, ctx->n_cu * 32);
+    const int32_t allow_scatter = ctx->fap_direction != 1;          // 1: gather only (testing aid)
+    const double edges_for_choice = ctx->fap_direction == 2 ? 1e300 : (double)gin->n_edges;   // 2: scatter whenever possible
     for (int k = 1; k <= n_hops; ++k) {
         const int32_t nf = k < n_hops ? fanouts[k] : 0;
         float* out = k == n_hops ? prob_out : (float*)nullptr;
+        hipLaunchKernelGGL(k_fap_decide, dim3(1), dim3(1), 0, ctx->stream, ctl, edges_for_choice, allow_scatter);
 #define QV_PULL(GW)                                                                                                    \
     hipLaunchKernelGGL((k_fap_pull<GW, RPT, RPF>), dim3(blocks), dim3(256), 0, ctx->stream, rpt, gin->col, rpf, n, nf,     \
-                       (const double*)c_cur, c_nxt, p_tot, out, long_rows, n_long, long_cap)
+                       (const double*)c_cur, c_nxt, p_tot, out, long_rows, ctl, long_cap)
         switch (G) {
             case 4: QV_PULL(4); break;
             case 8: QV_PULL(8); break;
@@ -314,10 +411,24 @@ static qv_status fap_pull(qv_ctx* ctx, const qv_csr* g, const qv_csr* gin, const
 #undef QV_PULL
         QV_LAUNCH_CHECK(ctx, "k_fap_pull");
         hipLaunchKernelGGL((k_fap_pull_long<RPT, RPF>), dim3(grid_for(long_cap, 1, ctx->n_cu * 4)), dim3(256), 0, ctx->stream,
-                           rpt, gin->col, rpf, nf, (const double*)c_cur, c_nxt, p_tot, out, (const int32_t*)long_rows, n_long,
+                           rpt, gin->col, rpf, nf, (const double*)c_cur, c_nxt, p_tot, out, (const int32_t*)long_rows, ctl,
                            long_cap);
-        hipLaunchKernelGGL(k_fap_pull_reset, dim3(1), dim3(1), 0, ctx->stream, n_long);
         QV_LAUNCH_CHECK(ctx, "k_fap_pull_long");
+        hipLaunchKernelGGL(k_fap_scatter_clear, dim3(ew), dim3(256), 0, ctx->stream, n, c_nxt, (const FapControl*)ctl);
+#define QV_SCAT(GW)                                                                                                    \
+    hipLaunchKernelGGL((k_fap_scatter<GW, RPF>), dim3(blocks_f), dim3(256), 0, ctx->stream, rpf, g->col, n,                \
+                       (const double*)c_cur, c_nxt, (const FapControl*)ctl)
+        switch (Gf) {
+            case 4: QV_SCAT(4); break;
+            case 8: QV_SCAT(8); break;
+            case 16: QV_SCAT(16); break;
+            case 32: QV_SCAT(32); break;
+            default: QV_SCAT(64); break;
+        }
+#undef QV_SCAT
+        QV_LAUNCH_CHECK(ctx, "k_fap_scatter");
+        hipLaunchKernelGGL((k_fap_scatter_fold<RPF>), dim3(ew), dim3(256), 0, ctx->stream, n, rpf, nf, c_nxt, p_tot, out, ctl);
+        QV_LAUNCH_CHECK(ctx, "k_fap_scatter_fold");
         double* t = c_cur; c_cur = c_nxt; c_nxt = t;
     }
     return QV_OK;

@@ -59,6 +59,7 @@ struct qv_ctx {
     size_t table_entries = 0;          // slots allocated (all batches of a call together)
     size_t table_keyw_entries = 0;     // entries allocated in keyw
     int64_t direct_budget_bytes = (int64_t)16 << 30;
+    int fap_direction = 0;             // qv_access_prob with an in-edge CSR: 0 choose per sweep, 1 gather only, 2 scatter only
     uint32_t epoch = 0;
     int32_t* d_status = nullptr;       // device status word
     int32_t* h_status = nullptr;       // pinned mirror

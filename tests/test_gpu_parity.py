@@ -476,13 +476,22 @@ def test_access_prob_in_edge_form_directed_graph_with_hub_rows(qv, ctx, rp_dtype
     want_sorted = np.concatenate([np.sort(col[rowptr[v]:rowptr[v + 1]]) for v in range(0, n, 997)])
     got_sorted = np.concatenate([bct.cpu().numpy()[rowptr[v]:rowptr[v + 1]] for v in range(0, n, 997)])
     assert np.array_equal(got_sorted, want_sorted)
+    sparse_p0 = np.zeros(n, dtype=np.float32)           # mass on a few nodes only: the first sweeps scatter
+    sparse_p0[[7, 1234, 40_000, 59_999]] = [0.4, 0.3, 0.2, 0.1]
     for fanouts in ([5, 4, 3], [20], [2, 2, 2, 2]):
-        P = qv.qv_access_prob(ctx, g, fanouts, graph_in=g_in)
+        want = oracle.access_prob(rowptr, col, fanouts)
+        want_sparse = oracle.access_prob(rowptr, col, fanouts, p0=sparse_p0.astype(np.float64))
         Ppush = qv.qv_access_prob(ctx, g, fanouts)
         ctx.sync()
-        want = oracle.access_prob(rowptr, col, fanouts)
-        assert rel_err(P.cpu().numpy(), want) <= REL_TOL
         assert rel_err(Ppush.cpu().numpy(), want) <= REL_TOL
+        for direction in (0, 1, 2):                     # choose per sweep, gather only, scatter only
+            ctx.set_fap_direction(direction)
+            P = qv.qv_access_prob(ctx, g, fanouts, graph_in=g_in)
+            Ps = qv.qv_access_prob(ctx, g, fanouts, p0=dev(sparse_p0), graph_in=g_in)
+            ctx.sync()
+            assert rel_err(P.cpu().numpy(), want) <= REL_TOL, direction
+            assert rel_err(Ps.cpu().numpy(), want_sparse) <= REL_TOL, direction
+        ctx.set_fap_direction(0)
     other_rowptr = np.ones(n, dtype=np.int64)          # n-1 nodes, one edge
     other_rowptr[0] = 0
     other = make_graph(qv, ctx, other_rowptr, np.zeros(1, dtype=np.int32))
