@@ -116,6 +116,16 @@ def placement_ablation(qv, qvgen, w, ctx, g, table, P_pop, rowptr, col, tdtype):
         rows = sum(ids.numel() for ids in batches[:8])
         res[name] = {"hbm_hit_rate": round(hit, 4), "gather_ms_8_batches": round(e0.elapsed_time(e1), 3),
                      "host_link_GBps": round((1 - hit) * rows * w.row_bytes / e0.elapsed_time(e1) / 1e6, 2)}
+        # the same rows requested in address order (Section 5.3 sorts reads of slow tiers by address):
+        # the cold tier holds its rows in ascending id order, so sorting the ids sorts the addresses
+        sorted_ids = [ids.sort().values.contiguous() for ids in batches[:8]]
+        qv.qv_gather_many(ctx, feat, sorted_ids, None, outs)
+        ctx.sync()
+        e0.record(ctx.stream)
+        qv.qv_gather_many(ctx, feat, sorted_ids, None, outs)
+        e1.record(ctx.stream)
+        ctx.sync()
+        res[name]["gather_ms_8_batches_address_sorted"] = round(e0.elapsed_time(e1), 3)
         log("%s: %s" % (name, res[name]))
         feat.close()
     print(json.dumps({"metric": "placement_ablation", "workload": w.name, "hot_rows": int(n_hot), "rankings": res}), flush=True)
@@ -178,7 +188,8 @@ def main():
                          "(Section 4.2.1), for batch sizes 1..4096, GPU path and CPU oracle side by side")
     ap.add_argument("--placement-ablation", action="store_true",
                     help="instead of the benchmark (tiered workload): HBM hit rate and gather time for hot sets "
-                         "ranked by FAP under the seed popularity, FAP under uniform seeds, in-degree, out-degree")
+                         "ranked by FAP under the seed popularity, FAP under uniform seeds, in-degree, out-degree; "
+                         "each also with the ids sorted by address")
     ap.add_argument("--graph-in-host-memory", action="store_true",
                     help="keep rowptr / col in pinned host memory and sample through the host link (Section 4.3 (3))")
     ap.add_argument("--hardware-rates", action="store_true",
