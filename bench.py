@@ -32,7 +32,9 @@ def log(msg):
 
 
 def algorithmic_bytes(n_frontier_entries, n_edges, n_unique, n_rows, row_bytes, rowptr_bytes, tiered):
-    """Bytes the method must move for one batch (per-unit figures: see the design doc, 'Measurement')."""
+    """Bytes the method must move for one batch.  Per unit: a frontier entry costs its id, two row
+    pointers and an 8-byte offset; a sampled edge 4 + 4 bytes in sampling and 4 + 8 + 8 in the
+    reindex; a new node 4; a gathered row its id (and lookup entry when tiered), read and written."""
     sample = n_frontier_entries * (4 + 2 * rowptr_bytes + 8) + n_edges * (4 + 4)
     reindex = n_edges * (4 + 8 + 8) + n_unique * 4 + n_frontier_entries * 4
     gather = n_rows * (4 + (4 if tiered else 0) + 2 * row_bytes)
@@ -194,7 +196,7 @@ def main():
                     help="keep rowptr / col in pinned host memory and sample through the host link (Section 4.3 (3))")
     ap.add_argument("--hardware-rates", action="store_true",
                     help="instead of the benchmark: rates of random device-scope atomics, stores and loads and of a "
-                         "plain copy on this GPU (the yardsticks DESIGN.md prices the kernels against)")
+                         "plain copy on this GPU (the yardsticks the dedup and gather kernels are priced against)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB copy kernel (copy_bytes) so that hardware byte counters can be scaled")
     args = ap.parse_args()
