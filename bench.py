@@ -136,11 +136,16 @@ def placement_ablation(qv, qvgen, w, ctx, g, table, P_pop, rowptr, col, tdtype):
 def hardware_rates(qvgen):
     import torch
     out = {"metric": "hardware_rates", "unit": "1e9 operations/s", "rates": []}
-    names = {0: "atomicMin u64 (result unused)", 1: "atomicMin u32 (result unused)", 2: "store 8 B", 3: "load 8 B"}
-    for slots in (111_000_000, 1 << 20):
+    names = {0: "atomicMin u64 (result unused)", 1: "atomicMin u32 (result unused)", 2: "store 8 B", 3: "load 8 B",
+             4: "atomicMin u64, workgroup scope", 5: "atomicMin u64, each XCD in its own eighth of the table",
+             6: "atomicMin u64, workgroup scope, each XCD in its own eighth", 7: "load 8 B, each XCD in its own eighth"}
+    xm = qvgen.xcd_map_device(4096).cpu()
+    out["workgroups_on_xcd_blockIdx_mod_8"] = int((xm == (torch.arange(4096, dtype=torch.int32) % 8)).sum().item())
+    out["workgroups_checked"] = 4096
+    for slots in (111_000_000, 1 << 23, 1 << 20):
         table = torch.full((slots,), -1, dtype=torch.int64, device="cuda")
         for n_ops in (1_000_000, 8_000_000):
-            for mode in range(4):
+            for mode in range(8):
                 best = 1e9
                 for rep in range(5):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
