@@ -20,7 +20,9 @@
  *     out of range, an output array too small) are recorded in a status word that qv_ctx_sync()
  *     returns; kernels never write outside the capacities they were given.
  *   - One context serves one stream; calls on one context must not overlap.  Use several
- *     contexts (one per stream) to keep several batches in flight.
+ *     contexts (one per stream) to keep several batches in flight.  The context's GPU must be
+ *     the calling thread's current device (qv_ctx_create makes it so; a caller that switches
+ *     devices switches back before calling).
  *   - ids are int32 (graphs of fewer than 2^31 nodes); rowptr is int32 or int64; offsets int64.
  */
 #ifndef QV_H
