@@ -217,6 +217,8 @@ const int32_t* qv_csr_col(const qv_csr* csr) { return csr ? csr->col : nullptr; 
 
 void qv_csr_destroy(qv_csr* csr) {
     if (!csr) return;
+    // owned arrays may still be read by work enqueued on the context's stream
+    if ((csr->owned_rowptr || csr->owned_col) && csr->ctx) (void)hipStreamSynchronize(csr->ctx->stream);
     if (csr->owned_rowptr) (void)hipFree(csr->owned_rowptr);
     if (csr->owned_col) (void)hipFree(csr->owned_col);
     delete csr;
