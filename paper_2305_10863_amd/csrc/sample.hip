@@ -1,6 +1,7 @@
 // Neighbour sampling (one sub-wave group per frontier node, Philox4x32-10 + Floyd's selection)
-// and dedup / relabel (open-addressing hash in HBM keyed by global id; first-occurrence order
-// recovered from the smallest position at which each id occurs).
+// and dedup / relabel (a table in HBM keyed by global id, addressed directly when the node count
+// allows and by open-addressing hash otherwise; first-occurrence order is recovered from the
+// smallest position at which each id occurs, found with one atomicMin per sampled edge).
 //
 // Launches of one qv_sample / qv_sample_many call (no host synchronisation anywhere; every
 // kernel takes up to QV_MAX_BATCHES independent batches along blockIdx.y):

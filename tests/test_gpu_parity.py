@@ -129,7 +129,9 @@ def test_sample_tiny_workload_all_batches(qv, ctx, tiny):
 
 
 @pytest.mark.parametrize("fanouts,n_seeds", [([10, 5], 1), ([15, 10, 5], 512), ([25, 10], 1000), ([3], 4096),
-                                             ([70, 2], 200), ([2, 2, 2, 2, 2, 2, 2, 2], 50), ([40, 33], 300)])
+                                             ([70, 2], 200), ([2, 2, 2, 2, 2, 2, 2, 2], 50), ([40, 33], 300),
+                                             # seed counts around tile boundaries of the dedup scan
+                                             ([4, 3], 4095), ([4, 3], 4097), ([5], 9000), ([6, 2], 255), ([6, 2], 257)])
 def test_sample_shapes(qv, ctx, tiny, fanouts, n_seeds):
     w, rowptr, col, g = tiny
     seeds = w.seeds(100 + n_seeds, n_seeds)
