@@ -111,3 +111,13 @@ def test_all_slots_at_once_rule_equals_sequential_floyd():
         assert got == want, (deg, fanout, seed)
         chains += sum(1 for s, p in enumerate(want) if p == deg - fanout + s)
     assert chains > 500            # the collision path was exercised, not just the easy one
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on one GPU only and says so instead of starting."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0
+    assert "ONE GPU" in (r.stderr + r.stdout)
