@@ -22,9 +22,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 # Measured HBM bytes of k_gather over its algorithmic bytes (rocprofv3 FETCH_SIZE + WRITE_SIZE,
-# each scaled by a 1 GiB plain copy kernel; profiles/citation_k_gather_and_sampling_kernels.md).
-# Only quoted for the configuration that was profiled.
-GATHER_TRAFFIC_RATIO = {("citation", 1.0, 8): 0.972}
+# each scaled by a 1 GiB plain copy kernel; profiles/citation_k_gather_and_sampling_kernels.md,
+# profiles/dense_social_and_co_purchase_kernel_durations.md).
+# Only quoted for the configurations that were profiled.
+GATHER_TRAFFIC_RATIO = {("citation", 1.0, 8): 0.972, ("dense_social", 1.0, 8): 1.024, ("co_purchase", 1.0, 8): 1.160}
 
 
 def log(msg):
