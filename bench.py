@@ -176,18 +176,18 @@ def hardware_rates(qvgen):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=256)
+    ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--workload", default="citation")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--streams", type=int, default=1, help="batches in flight (one context per stream)")
     ap.add_argument("--extra-streams", type=int, default=4,
                     help="after the timed region, run the same batches again over this many streams and report "
                          "that throughput beside the main figure (0 = skip; only when --streams is 1)")
-    ap.add_argument("--batches-per-call", type=int, default=8,
-                    help="independent batches per qv_sample_many / qv_gather_many call (1..8)")
+    ap.add_argument("--batches-per-call", type=int, default=32,
+                    help="independent batches per qv_sample_many / qv_gather_many call (1..32)")
     ap.add_argument("--table-budget-gib", type=float, default=-1.0,
-                    help="dedup table budget per context in GiB (0 = always hash; default: the library's)")
+                    help="dedup table budget per context in GiB (0 = always hash; default: 64 with one stream, else the library's 16)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-metrics", action="store_true", help="skip the PSGS / FAP whole-graph passes")
@@ -343,9 +343,12 @@ def main():
     nb, eb, fb = qv.qv_sample_bounds(batch, w.fanouts, w.n)
     bufs, rows = [], []
     for c in ctxs:
-        if args.table_budget_gib >= 0:
-            c.set_table_budget(int(args.table_budget_gib * 2 ** 30))
-        c.reserve(batch, w.fanouts, w.n)
+        # one context: let all its batches have directly addressed dedup tables (32 x 1.78 GB on the
+        # citation graph, a fifth of the 288 GB); several contexts keep the library's 16 GiB each
+        budget_gib = args.table_budget_gib if args.table_budget_gib >= 0 else (64.0 if S == 1 else -1.0)
+        if budget_gib >= 0:
+            c.set_table_budget(int(budget_gib * 2 ** 30))
+        c.reserve(batch, w.fanouts, w.n, n_batches=B)
         bufs.append([qv.SampleBuffers(c, batch, w.fanouts, w.n) for _ in range(B)])
         rows.append([feat.empty_rows(nb, "cuda") for _ in range(B)])
     Kh = len(w.fanouts)
@@ -402,18 +405,19 @@ def main():
     # which raises whole-path throughput but stretches the individual kernels.
     if S == 1 and args.extra_streams > 1 and not tiered:
         S2 = args.extra_streams
+        B2 = min(B, 8)                                     # per-batch arguments inline; 8 direct tables per context
         ctxs2 = [ctx0] + [qv.Context(0, torch.cuda.Stream()) for _ in range(S2 - 1)]
+        calls2 = ([(i, min(B2, W - i)) for i in range(0, W, B2)] +
+                  [(i, min(B2, W + K - i)) for i in range(W, W + K, B2)])
+        n_warm_calls2 = len(range(0, W, B2))
         plans2 = []
-        own = {}                                           # context index -> [(SampleBuffers, rows)] * B
-        for j, (first, cnt) in enumerate(calls):
+        own = {0: list(zip(bufs[0][:B2], rows[0][:B2]))}   # context index -> [(SampleBuffers, rows)] * B2
+        for j, (first, cnt) in enumerate(calls2):
             k = j % S2
-            if k == 0:
-                plans2.append(plans[j])                    # context 0 keeps the buffers of the main region
-                continue
             c = ctxs2[k]
             if k not in own:
-                c.reserve(batch, w.fanouts, w.n)
-                own[k] = [(qv.SampleBuffers(c, batch, w.fanouts, w.n), feat.empty_rows(nb, "cuda")) for _ in range(B)]
+                c.reserve(batch, w.fanouts, w.n, n_batches=B2)
+                own[k] = [(qv.SampleBuffers(c, batch, w.fanouts, w.n), feat.empty_rows(nb, "cuda")) for _ in range(B2)]
             views = []
             for t in range(cnt):
                 v = copy.copy(own[k][t][0])
@@ -422,7 +426,7 @@ def main():
             plans2.append(qv.ManyPlan(c, g, feat, views, [r for _, r in own[k][:cnt]], w.fanouts))
 
         def call2(j):
-            first, cnt = calls[j]
+            first, cnt = calls2[j]
             p, c = plans2[j], ctxs2[j % S2]
             for t in range(cnt):
                 p.seed_ptrs[t] = seeds_dev[first + t].data_ptr()
@@ -431,17 +435,17 @@ def main():
             c.check(L.qv_sample_many(c.h, g.h, cnt, p.seed_ptrs, p.n_seeds, p.fan, p.k, p.rng, 0, p.outs))
             c.check(L.qv_gather_many(c.h, feat.h, cnt, p.ids, p.n_ids, p.n_dev, p.out_ptrs, p.stride))
 
-        for j in range(n_warm_calls):
+        for j in range(n_warm_calls2):
             call2(j)
         torch.cuda.synchronize()
         t2 = time.perf_counter()
-        for j in range(n_warm_calls, len(calls)):
+        for j in range(n_warm_calls2, len(calls2)):
             call2(j)
         torch.cuda.synchronize()
         elapsed2 = time.perf_counter() - t2
         for c in ctxs2:
             c.sync()
-        extra["multi_stream"] = {"streams": S2, "ms_per_step": round(elapsed2 * 1e3 / K, 4)}
+        extra["multi_stream"] = {"streams": S2, "batches_per_call": B2, "ms_per_step": round(elapsed2 * 1e3 / K, 4)}
 
     # ---- latency pass (not part of the timed region): one batch per call, one at a time ---------
     n_lat = min(64, K)

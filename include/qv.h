@@ -49,7 +49,7 @@ typedef enum {
 
 #define QV_MAX_HOPS 8
 #define QV_MAX_FANOUT 1024
-#define QV_MAX_BATCHES 8     /* batches per qv_sample_many / qv_gather_many call */
+#define QV_MAX_BATCHES 32    /* batches per qv_sample_many / qv_gather_many call */
 
 /* ---------------------------------------------------------------------------------------------
  * Context
@@ -65,10 +65,12 @@ const char* qv_last_error(const qv_ctx* ctx);
  * QV_OK, QV_ERANGE or QV_ECAPACITY (or QV_EHIP if the stream reports a failure). */
 qv_status qv_ctx_sync(qv_ctx* ctx);
 
-/* Grow the scratch arena now so that later qv_sample / qv_reindex calls with at most `n_seeds`
- * seeds and these fanouts on a graph of `n_nodes` nodes allocate nothing.  Optional. */
+/* Grow the scratch arena and the dedup tables now so that later qv_sample / qv_sample_many /
+ * qv_reindex calls with at most `n_batches` batches of at most `n_seeds` seeds and these fanouts
+ * on a graph of `n_nodes` nodes allocate nothing.  Optional.  1 <= n_batches <= QV_MAX_BATCHES. */
 qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts /*[host]*/,
-                         int32_t n_hops, int64_t n_nodes, uint32_t flags /* as for qv_sample */);
+                         int32_t n_hops, int64_t n_nodes, uint32_t flags /* as for qv_sample */,
+                         int32_t n_batches);
 
 /* Dedup tables come in two forms.  When n_nodes x 16 bytes x (batches in the call) is at most
  * `bytes`, the table is addressed directly by node id (no probing, one atomic per sampled
@@ -182,7 +184,8 @@ qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_
  * sampled exactly as qv_sample(seeds[b], n_seeds[b], rng_seeds[b], &outs[b]) would sample it; the
  * batches share nothing but the launches.  seeds: [host] array of n_batches [dev] pointers;
  * n_seeds, rng_seeds: [host] arrays; outs: [host] array of output blocks ([dev] arrays inside).
- * 1 <= n_batches <= QV_MAX_BATCHES. */
+ * 1 <= n_batches <= QV_MAX_BATCHES.  Up to 8 batches travel in the kernel argument block; beyond
+ * that the per-batch arguments are copied to the device once per call (a few microseconds). */
 qv_status qv_sample_many(qv_ctx* ctx, const qv_csr* csr, int32_t n_batches,
                          const int32_t* const* seeds, const int64_t* n_seeds,
                          const int32_t* fanouts, int32_t n_hops, const uint64_t* rng_seeds,

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libqv.so")
 _lib = None
 
 QV_OK, QV_EINVAL, QV_ENOMEM, QV_EHIP, QV_ECAPACITY, QV_ERANGE = 0, -1, -2, -3, -4, -5
-QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 8
+QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 32
 QV_SAMPLE_CUMULATIVE, QV_FEAT_OWN_COPY = 1, 1
 
 EXPORTS = [
@@ -54,7 +54,7 @@ def lib():
         L.qv_last_error.argtypes = [vp]
         L.qv_last_error.restype = C.c_char_p
         L.qv_ctx_sync.argtypes = [vp]
-        L.qv_ctx_reserve.argtypes = [vp, i64, C.POINTER(i32), i32, i64, C.c_uint32]
+        L.qv_ctx_reserve.argtypes = [vp, i64, C.POINTER(i32), i32, i64, C.c_uint32, i32]
         L.qv_ctx_set_epoch.argtypes = [vp, C.c_uint32]
         L.qv_ctx_set_table_budget.argtypes = [vp, i64]
         L.qv_ctx_set_fap_direction.argtypes = [vp, i32]
@@ -134,9 +134,9 @@ class Context:
         """0 choose per sweep (default), 1 gather only, 2 scatter only; see qv_ctx_set_fap_direction."""
         self.check(lib().qv_ctx_set_fap_direction(self.h, direction))
 
-    def reserve(self, n_seeds, fanouts, n_nodes, cumulative=False):
+    def reserve(self, n_seeds, fanouts, n_nodes, cumulative=False, n_batches=8):
         arr, k = _fan(fanouts)
-        self.check(lib().qv_ctx_reserve(self.h, n_seeds, arr, k, n_nodes, 1 if cumulative else 0))
+        self.check(lib().qv_ctx_reserve(self.h, n_seeds, arr, k, n_nodes, 1 if cumulative else 0, n_batches))
 
     def close(self):
         if getattr(self, "h", None):

@@ -101,6 +101,9 @@ void qv_ctx_destroy(qv_ctx* ctx) {
     if (ctx->table_slots) (void)hipFree(ctx->table_slots);
     if (ctx->d_status) (void)hipFree(ctx->d_status);
     if (ctx->h_status) (void)hipHostFree(ctx->h_status);
+    if (ctx->args_ring) (void)hipHostFree(ctx->args_ring);
+    for (int i = 0; i < kArgsRing; ++i)
+        if (ctx->args_ev_live[i]) (void)hipEventDestroy(ctx->args_ev[i]);
     delete ctx;
 }
 

@@ -12,6 +12,7 @@ namespace qv {
 constexpr int kWave = 64;               // CDNA wavefront width
 constexpr int kScanBlock = 256;         // threads per block of the scan kernels
 constexpr int kMaxBatch = QV_MAX_BATCHES;
+constexpr int kArgsRing = 8;            // staging slots for per-batch arguments uploaded to the device
 
 // deferred device status bits (qv_ctx::d_status[0])
 constexpr int kStatRange = 1;
@@ -61,6 +62,12 @@ struct qv_ctx {
     int64_t direct_budget_bytes = (int64_t)16 << 30;
     int fap_direction = 0;             // qv_access_prob with an in-edge CSR: 0 choose per sweep, 1 gather only, 2 scatter only
     uint32_t epoch = 0;
+    // pinned staging ring for the per-batch arguments of calls with many batches
+    void* args_ring = nullptr;
+    hipEvent_t args_ev[qv::kArgsRing] = {};
+    bool args_ev_live[qv::kArgsRing] = {};
+    bool args_ev_used[qv::kArgsRing] = {};
+    int args_next = 0;
     int32_t* d_status = nullptr;       // device status word
     int32_t* h_status = nullptr;       // pinned mirror
     int n_cu = 256;

@@ -17,6 +17,7 @@
 // the ticket + publish + look-back chain was slower (12-17 us per stage) than two short kernels
 // (4-5 us each).
 #include "qv_internal.hpp"
+#include <cstring>
 #include <new>
 
 namespace qv {
@@ -161,7 +162,7 @@ struct BatchArgs {
     int64_t* n_id_len_out; int64_t* frontier_len_out;      // stand-alone reindex
 };
 
-struct CallArgs {
+struct CallHeader {
     // graph
     const void* rowptr; const int32_t* col; int64_t n_nodes;
     // table geometry (same for every batch of the call)
@@ -177,10 +178,25 @@ struct CallArgs {
     int32_t frontier_restart;       // stand-alone reindex: number this stage's frontier from 0
     int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
     int32_t* status;
-    BatchArgs b[kMaxBatch];
 };
 
-__device__ __forceinline__ TableView table_of(const CallArgs& c, const BatchArgs& b) {
+// The per-batch arguments travel in the kernel argument block while they fit (up to kInlineBatch
+// batches: no upload, lowest latency) and in device memory beyond that (one small copy per call).
+constexpr int kInlineBatch = 8;
+struct CallInline : CallHeader {
+    BatchArgs b[kInlineBatch];
+    __device__ __forceinline__ const BatchArgs& batch(int y) const { return b[y]; }
+};
+struct CallDevice : CallHeader {
+    const BatchArgs* b;
+    __device__ __forceinline__ const BatchArgs& batch(int y) const { return b[y]; }
+};
+struct CallArgs : CallHeader {      // host side: header + every batch of the call
+    BatchArgs b[kMaxBatch];
+    const BatchArgs* b_dev = nullptr;       // device copy (calls of more than kInlineBatch batches)
+};
+
+__device__ __forceinline__ TableView table_of(const CallHeader& c, const BatchArgs& b) {
     return TableView{b.keyw, b.slots, c.mask, c.shift, c.epoch, c.direct};
 }
 
@@ -188,8 +204,9 @@ __device__ __forceinline__ TableView table_of(const CallArgs& c, const BatchArgs
 // k_insert_ids: a flat id array -> table, recording the smallest position of every id.
 // The stage-0 launch is the first kernel of a call and also resets the scan state.
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_insert_ids(CallArgs c) {
-    const BatchArgs& b = c.b[blockIdx.y];
+template <typename A>
+__global__ void __launch_bounds__(256) k_insert_ids(A c) {
+    const BatchArgs& b = c.batch(blockIdx.y);
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int32_t* ids;
@@ -226,7 +243,7 @@ __global__ void __launch_bounds__(256) k_insert_ids(CallArgs c) {
 // ---------------------------------------------------------------------------------------------
 // k_sample: one group of G lanes per frontier node, fanout <= G
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void emit_edge(const CallArgs& c, const BatchArgs& b, const TableView& t, uint64_t tag,
+__device__ __forceinline__ void emit_edge(const CallHeader& c, const BatchArgs& b, const TableView& t, uint64_t tag,
                                           int64_t p, int32_t g, int32_t vl) {
     if (p < b.edge_cap) {
         b.nbr[p] = g;
@@ -246,9 +263,9 @@ __device__ __forceinline__ void emit_edge(const CallArgs& c, const BatchArgs& b,
     }
 }
 
-template <int G>
-__global__ void __launch_bounds__(256) k_sample(CallArgs c) {
-    const BatchArgs& b = c.b[blockIdx.y];
+template <int G, typename A>
+__global__ void __launch_bounds__(256) k_sample(A c) {
+    const BatchArgs& b = c.batch(blockIdx.y);
     const int sub = threadIdx.x % G;
     constexpr int groups_per_block = 256 / G;
     const SampleMeta* m = b.meta;
@@ -294,9 +311,10 @@ __global__ void __launch_bounds__(256) k_sample(CallArgs c) {
 
 // Fanouts above 64: one wave (= one block) per frontier node, slots processed 64 at a time,
 // earlier picks kept in LDS.
-__global__ void __launch_bounds__(64) k_sample_wide(CallArgs c) {
+template <typename A>
+__global__ void __launch_bounds__(64) k_sample_wide(A c) {
     __shared__ uint32_t picks[QV_MAX_FANOUT];
-    const BatchArgs& b = c.b[blockIdx.y];
+    const BatchArgs& b = c.batch(blockIdx.y);
     const int lane = threadIdx.x;
     const SampleMeta* m = b.meta;
     const int64_t fbeg = c.cumulative ? 0 : m->frontier_off[c.stage - 1];
@@ -378,7 +396,7 @@ struct StageView {
     uint16_t* flags;
 };
 
-__device__ __forceinline__ StageView stage_view(const CallArgs& c, const BatchArgs& b) {
+__device__ __forceinline__ StageView stage_view(const CallHeader& c, const BatchArgs& b) {
     StageView v;
     const SampleMeta* m = b.meta;
     if (c.stage == 0) {
@@ -394,15 +412,15 @@ __device__ __forceinline__ StageView stage_view(const CallArgs& c, const BatchAr
 }
 
 // slot of the id at position p (0xFFFFFFFF: the id was out of range or the table was full)
-__device__ __forceinline__ uint32_t slot_at(const CallArgs& c, const StageView& v, int64_t p, int32_t id) {
+__device__ __forceinline__ uint32_t slot_at(const CallHeader& c, const StageView& v, int64_t p, int32_t id) {
     if (!c.direct) return v.slot_of[p];
     return (id >= 0 && (c.n_nodes < 0 || (int64_t)id < c.n_nodes)) ? (uint32_t)id : 0xFFFFFFFFu;
 }
 
-template <typename RP>
-__global__ void __launch_bounds__(kScanBlock) k_flag(CallArgs c) {
+template <typename RP, typename A>
+__global__ void __launch_bounds__(kScanBlock) k_flag(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchArgs& b = c.b[blockIdx.y];
+    const BatchArgs& b = c.batch(blockIdx.y);
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     const StageView v = stage_view(c, b);
     const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
@@ -447,10 +465,10 @@ __global__ void __launch_bounds__(kScanBlock) k_flag(CallArgs c) {
     }
 }
 
-template <typename RP>
-__global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
+template <typename RP, typename A>
+__global__ void __launch_bounds__(kScanBlock) k_assign(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchArgs& b = c.b[blockIdx.y];
+    const BatchArgs& b = c.batch(blockIdx.y);
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     SampleMeta* m = b.meta;
     const StageView v = stage_view(c, b);
@@ -538,9 +556,10 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(CallArgs c) {
 // cumulative frontiers: before hop k, segment sizes min(deg, fanout_k) of ALL nodes sampled so
 // far (entries indexed by local id) -> segment offsets and the hop's edge count
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(kScanBlock) k_cum_partial(CallArgs c) {
+template <typename A>
+__global__ void __launch_bounds__(kScanBlock) k_cum_partial(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchArgs& b = c.b[blockIdx.y];
+    const BatchArgs& b = c.batch(blockIdx.y);
     const int64_t U = b.meta->node_off[c.stage];
     const int64_t t0 = (int64_t)blockIdx.x * kScanBlock * c.items_per_thread;
     if (t0 >= U) return;
@@ -557,9 +576,10 @@ __global__ void __launch_bounds__(kScanBlock) k_cum_partial(CallArgs c) {
     if (threadIdx.x == 0) b.partial[blockIdx.x * 3] = total.a;
 }
 
-__global__ void __launch_bounds__(kScanBlock) k_cum_scan(CallArgs c) {
+template <typename A>
+__global__ void __launch_bounds__(kScanBlock) k_cum_scan(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchArgs& b = c.b[blockIdx.y];
+    const BatchArgs& b = c.batch(blockIdx.y);
     SampleMeta* m = b.meta;
     const int64_t U = m->node_off[c.stage];
     const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
@@ -587,8 +607,9 @@ __global__ void __launch_bounds__(kScanBlock) k_cum_scan(CallArgs c) {
 // ---------------------------------------------------------------------------------------------
 // k_relabel: local id of every edge's neighbour; export of the sizes
 // ---------------------------------------------------------------------------------------------
-__global__ void __launch_bounds__(256) k_relabel(CallArgs c) {
-    const BatchArgs& b = c.b[blockIdx.y];
+template <typename A>
+__global__ void __launch_bounds__(256) k_relabel(A c) {
+    const BatchArgs& b = c.batch(blockIdx.y);
     const SampleMeta* m = b.meta;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -806,17 +827,63 @@ static bool carve(qv_ctx* ctx, const Layout& L, BatchArgs* b) {
            b->fr_rs && b->fr_deg && b->fr_seg && b->partial;
 }
 
+// Launch KERNEL<A> (QV_LAUNCH_A) or KERNEL<T1, A> (QV_LAUNCH_A1) with the argument form A that fits
+// the call: per-batch arguments inside the kernel argument block, or a pointer to their device copy.
+#define QV_LAUNCH_FORM(ctx, c, n_batches, grid, block, INLINE_KERNEL, DEVICE_KERNEL)                          \
+    do {                                                                                                    \
+        if ((n_batches) <= kInlineBatch) {                                                                  \
+            CallInline a_;                                                                                  \
+            static_cast<CallHeader&>(a_) = static_cast<const CallHeader&>(c);                               \
+            for (int i_ = 0; i_ < (n_batches); ++i_) a_.b[i_] = (c).b[i_];                                   \
+            hipLaunchKernelGGL(INLINE_KERNEL, grid, block, 0, (ctx)->stream, a_);                           \
+        } else {                                                                                            \
+            CallDevice a_;                                                                                  \
+            static_cast<CallHeader&>(a_) = static_cast<const CallHeader&>(c);                               \
+            a_.b = (c).b_dev;                                                                               \
+            hipLaunchKernelGGL(DEVICE_KERNEL, grid, block, 0, (ctx)->stream, a_);                           \
+        }                                                                                                   \
+    } while (0)
+#define QV_LAUNCH_A(ctx, c, n, grid, block, K) QV_LAUNCH_FORM(ctx, c, n, grid, block, (K<CallInline>), (K<CallDevice>))
+#define QV_LAUNCH_A1(ctx, c, n, grid, block, K, T1) \
+    QV_LAUNCH_FORM(ctx, c, n, grid, block, (K<T1, CallInline>), (K<T1, CallDevice>))
+
+// Calls of more than kInlineBatch batches: copy the per-batch arguments to the device once, through
+// a small ring of pinned staging slots (a slot is reused only after its copy has run).
+static qv_status upload_batches(qv_ctx* ctx, CallArgs* c, int n_batches) {
+    const size_t slot_bytes = sizeof(BatchArgs) * (size_t)kMaxBatch;
+    if (!ctx->args_ring) {
+        QV_HIP(ctx, hipHostMalloc((void**)&ctx->args_ring, slot_bytes * kArgsRing, hipHostMallocDefault));
+        for (int i = 0; i < kArgsRing; ++i) {
+            QV_HIP(ctx, hipEventCreateWithFlags(&ctx->args_ev[i], hipEventDisableTiming));
+            ctx->args_ev_live[i] = true;
+            ctx->args_ev_used[i] = false;
+        }
+    }
+    const int slot = ctx->args_next;
+    ctx->args_next = (slot + 1) % kArgsRing;
+    if (ctx->args_ev_used[slot]) QV_HIP(ctx, hipEventSynchronize(ctx->args_ev[slot]));
+    char* stage = (char*)ctx->args_ring + (size_t)slot * slot_bytes;
+    std::memcpy(stage, c->b, sizeof(BatchArgs) * (size_t)n_batches);
+    BatchArgs* dev = (BatchArgs*)arena_take(ctx, sizeof(BatchArgs) * (size_t)n_batches);
+    if (!dev) return fail(ctx, QV_ENOMEM, "scratch arena too small for the batch arguments (internal sizing error)");
+    QV_HIP(ctx, hipMemcpyAsync(dev, stage, sizeof(BatchArgs) * (size_t)n_batches, hipMemcpyHostToDevice, ctx->stream));
+    QV_HIP(ctx, hipEventRecord(ctx->args_ev[slot], ctx->stream));
+    ctx->args_ev_used[slot] = true;
+    c->b_dev = dev;
+    return QV_OK;
+}
+
 static qv_status launch_dedup(qv_ctx* ctx, CallArgs& c, int rowptr_bits, int64_t max_items, int n_batches) {
     int ipt, tiles;
     tile_shape(max_items, &ipt, &tiles);
     c.items_per_thread = ipt;
     dim3 grid((unsigned)tiles, (unsigned)n_batches);
     if (rowptr_bits == 32) {
-        hipLaunchKernelGGL(k_flag<int32_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
-        hipLaunchKernelGGL(k_assign<int32_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
+        QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kScanBlock), k_flag, int32_t);
+        QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kScanBlock), k_assign, int32_t);
     } else {
-        hipLaunchKernelGGL(k_flag<int64_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
-        hipLaunchKernelGGL(k_assign<int64_t>, grid, dim3(kScanBlock), 0, ctx->stream, c);
+        QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kScanBlock), k_flag, int64_t);
+        QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kScanBlock), k_assign, int64_t);
     }
     QV_LAUNCH_CHECK(ctx, "k_flag / k_assign");
     return QV_OK;
@@ -826,15 +893,15 @@ static qv_status launch_sample(qv_ctx* ctx, const CallArgs& c, int64_t max_front
     const int l = c.fanout;
     if (l > 64) {
         dim3 grid((unsigned)grid_for(max_frontier, 1, ctx->n_cu * 32), (unsigned)n_batches);
-        hipLaunchKernelGGL(k_sample_wide, grid, dim3(64), 0, ctx->stream, c);
+        QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(64), k_sample_wide);
     } else {
         const int G = l <= 8 ? 8 : l <= 16 ? 16 : l <= 32 ? 32 : 64;
         dim3 grid((unsigned)grid_for(max_frontier, 256 / G, ctx->n_cu * 8), (unsigned)n_batches);
         switch (G) {
-            case 8: hipLaunchKernelGGL(k_sample<8>, grid, dim3(256), 0, ctx->stream, c); break;
-            case 16: hipLaunchKernelGGL(k_sample<16>, grid, dim3(256), 0, ctx->stream, c); break;
-            case 32: hipLaunchKernelGGL(k_sample<32>, grid, dim3(256), 0, ctx->stream, c); break;
-            default: hipLaunchKernelGGL(k_sample<64>, grid, dim3(256), 0, ctx->stream, c); break;
+            case 8: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 8); break;
+            case 16: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 16); break;
+            case 32: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 32); break;
+            default: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 64); break;
         }
     }
     QV_LAUNCH_CHECK(ctx, "k_sample");
@@ -863,7 +930,7 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     Layout L;
     L.stage0 = max_seeds; L.edges = bd.edges;
     L.frontier = cumulative ? (bd.nodes > 0 ? bd.nodes : 1) : bd.frontier;   // cumulative: one entry per node, at its local id
-    rc = arena_begin(ctx, per_batch_bytes(L) * n_batches);
+    rc = arena_begin(ctx, per_batch_bytes(L) * n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch));
     if (rc != QV_OK) return rc;
     CallArgs c{};
     c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
@@ -888,11 +955,15 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
         b.node_off_out = o.node_off; b.edge_off_out = o.edge_off; b.frontier_off_out = o.frontier_off;
         b.n_id_len_out = nullptr; b.frontier_len_out = nullptr;
     }
+    if (n_batches > kInlineBatch) {
+        rc = upload_batches(ctx, &c, n_batches);
+        if (rc != QV_OK) return rc;
+    }
     // stage 0: the seeds
     c.stage = 0; c.next_fanout = fanouts[0];
     {
         dim3 grid((unsigned)grid_for(max_seeds, 256, ctx->n_cu * 4), (unsigned)n_batches);
-        hipLaunchKernelGGL(k_insert_ids, grid, dim3(256), 0, ctx->stream, c);
+        QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(256), k_insert_ids);
         QV_LAUNCH_CHECK(ctx, "k_insert_ids");
     }
     // edge_off[1] is preset by k_insert_ids for the stand-alone reindex; stage 0 overwrites it here
@@ -905,8 +976,8 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
             tile_shape(bd.hop_front[k - 1], &ipt, &tiles);
             c.items_per_thread = ipt;
             dim3 grid((unsigned)tiles, (unsigned)n_batches);
-            hipLaunchKernelGGL(k_cum_partial, grid, dim3(kScanBlock), 0, ctx->stream, c);
-            hipLaunchKernelGGL(k_cum_scan, grid, dim3(kScanBlock), 0, ctx->stream, c);
+            QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(kScanBlock), k_cum_partial);
+            QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(kScanBlock), k_cum_scan);
             QV_LAUNCH_CHECK(ctx, "k_cum_scan");
         }
         rc = launch_sample(ctx, c, bd.hop_front[k - 1], n_batches);
@@ -916,7 +987,7 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     }
     c.stage = n_hops;
     dim3 grid((unsigned)grid_for(bd.edges, 256 * 4, ctx->n_cu * 4), (unsigned)n_batches);
-    hipLaunchKernelGGL(k_relabel, grid, dim3(256), 0, ctx->stream, c);
+    QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(256), k_relabel);
     QV_LAUNCH_CHECK(ctx, "k_relabel");
     return QV_OK;
 }
@@ -928,23 +999,24 @@ using namespace qv;
 extern "C" {
 
 qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes,
-                         uint32_t flags) {
+                         uint32_t flags, int32_t n_batches) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_reserve: ctx is NULL");
+    if (n_batches < 1 || n_batches > kMaxBatch) return fail(ctx, QV_EINVAL, "qv_ctx_reserve: n_batches %d outside [1, %d]", n_batches, kMaxBatch);
     const bool cumulative = (flags & QV_SAMPLE_CUMULATIVE) != 0;
     Bounds bd;
     qv_status rc = compute_bounds(ctx, n_seeds, fanouts, n_hops, n_nodes, cumulative, &bd);
     if (rc != QV_OK) return rc;
     Layout L;
     L.stage0 = n_seeds; L.edges = bd.edges; L.frontier = cumulative ? (bd.nodes > 0 ? bd.nodes : 1) : bd.frontier;
-    const size_t want = per_batch_bytes(L) * kMaxBatch;
+    const size_t want = per_batch_bytes(L) * (size_t)n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch);
     if (want > ctx->arena_bytes) {
         rc = arena_begin(ctx, want);
         if (rc != QV_OK) return rc;
     }
     uint32_t mask; int shift;
     table_geometry(bd.nodes, &mask, &shift);
-    const bool direct = use_direct(ctx, n_nodes, kMaxBatch);
-    return table_prepare(ctx, kMaxBatch, direct ? (size_t)n_nodes : (size_t)mask + 1, !direct);
+    const bool direct = use_direct(ctx, n_nodes, n_batches);
+    return table_prepare(ctx, n_batches, direct ? (size_t)n_nodes : (size_t)mask + 1, !direct);
 }
 
 qv_status qv_sample_hop(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier, int64_t n_frontier,
@@ -1039,7 +1111,7 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
     // stage 0: the known ids
     c.stage = 0; c.next_fanout = 0; c.frontier_restart = 0; c.expect_all_first = 1;
     {
-        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(n_known, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);
+        QV_LAUNCH_A(ctx, c, 1, dim3(grid_for(n_known, 256, ctx->n_cu * 4)), dim3(256), k_insert_ids);
         QV_LAUNCH_CHECK(ctx, "k_insert_ids");
     }
     rc = launch_dedup(ctx, c, 32, n_known, 1);
@@ -1048,12 +1120,12 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
     c.stage = 1; c.frontier_restart = 1; c.expect_all_first = 0;
     b.fr_user = frontier_out; b.fr_user_cap = frontier_out ? n_nbr : 0;
     if (n_nbr > 0) {
-        hipLaunchKernelGGL(k_insert_ids, dim3(grid_for(n_nbr, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);
+        QV_LAUNCH_A(ctx, c, 1, dim3(grid_for(n_nbr, 256, ctx->n_cu * 4)), dim3(256), k_insert_ids);
         QV_LAUNCH_CHECK(ctx, "k_insert_ids");
     }
     rc = launch_dedup(ctx, c, 32, n_nbr, 1);
     if (rc != QV_OK) return rc;
-    hipLaunchKernelGGL(k_relabel, dim3(grid_for(n_nbr, 256 * 4, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, c);
+    QV_LAUNCH_A(ctx, c, 1, dim3(grid_for(n_nbr, 256 * 4, ctx->n_cu * 4)), dim3(256), k_relabel);
     QV_LAUNCH_CHECK(ctx, "k_relabel");
     return QV_OK;
 }

@@ -67,10 +67,10 @@ def check_batches(qv, ctx, w, rowptr, col, g, feat, batches, n_seeds=None, table
             assert got_rows.tobytes() == oracle.gather(compact, inv.astype(np.int32)).tobytes()
 
 
-def check_call_of_eight(qv, ctx, w, rowptr, col, g, feat, first_batch):
-    """The launch configuration the bench times: eight batches through one qv_sample_many and one
+def check_call_of_many(qv, ctx, w, rowptr, col, g, feat, first_batch, n_batches=32):
+    """The launch configuration the bench times: 32 batches through one qv_sample_many and one
     qv_gather_many call (device-side row counts), each batch compared with the oracle."""
-    idx = list(range(first_batch, first_batch + 8))
+    idx = list(range(first_batch, first_batch + n_batches))
     seeds = [w.seeds(b) for b in idx]
     rng = [w.rng_seed(b) for b in idx]
     outs = qv.qv_sample_many(ctx, g, [torch.from_numpy(s).cuda() for s in seeds], w.fanouts, rng)
@@ -79,10 +79,10 @@ def check_call_of_eight(qv, ctx, w, rowptr, col, g, feat, first_batch):
     for b, s, r, o, got_rows in zip(idx, seeds, rng, outs, rows):
         got, want = o.to_host(), oracle.sample(rowptr, col, s, w.fanouts, r)
         for k in ("node_off", "edge_off", "frontier_off", "n_id", "row_local", "col_local", "nbr_global", "frontier"):
-            assert np.array_equal(got[k], want[k]), (w.name, "call of eight", b, k)
+            assert np.array_equal(got[k], want[k]), (w.name, "call of many", b, k)
         U = len(want["n_id"])
         expect = qvgen.feature_rows_host(w.seed, want["n_id"], w.dim, w.feat_dtype)
-        assert got_rows[:U].cpu().numpy().tobytes() == expect.tobytes(), (w.name, "call of eight", b, "gather")
+        assert got_rows[:U].cpu().numpy().tobytes() == expect.tobytes(), (w.name, "call of many", b, "gather")
 
 
 def check_metrics(qv, ctx, w, rowptr, col, g, p0=None):
@@ -116,7 +116,10 @@ def test_dense_social_full(qv, ctx):
     feat = qv.Features(ctx, t_dev, own_copy=True)               # 2,408-byte rows at a 2,432-byte stride
     assert feat.row_stride == 2432
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(3), table=table)
-    check_call_of_eight(qv, ctx, w, rowptr, col, g, feat, 20)
+    ctx.set_table_budget(64 << 30)                              # as the bench: all 32 tables addressed directly
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)
+    ctx.set_table_budget(16 << 30)
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # default budget (hashed tables on the citation graph), arguments uploaded
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()
 
@@ -168,6 +171,9 @@ def test_citation_full(qv, ctx):
     assert rowptr.dtype == np.int64 and len(col) > 1_590_000_000
     feat = qv.Features(ctx, qvgen.features_device(w.seed, w.n, w.dim, torch.float16))
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(4))
-    check_call_of_eight(qv, ctx, w, rowptr, col, g, feat, 20)
+    ctx.set_table_budget(64 << 30)                              # as the bench: all 32 tables addressed directly
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)
+    ctx.set_table_budget(16 << 30)
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # default budget (hashed tables on the citation graph), arguments uploaded
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()

@@ -152,10 +152,10 @@ def test_sample_int64_rowptr_and_in_degree_skew(qv, ctx):
         assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, w.fanouts, w.rng_seed(b)))
 
 
-@pytest.mark.parametrize("n_batches", [1, 3, 8])
+@pytest.mark.parametrize("n_batches", [1, 3, 8, 9, 20, 32])      # up to 8: arguments inline; above: uploaded
 def test_sample_many_and_gather_many(qv, ctx, tiny, n_batches):
     w, rowptr, col, g = tiny
-    sizes = [64, 1, 500, 0, 2000, 64, 7, 300][:n_batches]
+    sizes = ([64, 1, 500, 0, 2000, 64, 7, 300] * 4)[:n_batches]
     fanouts = [15, 10, 5]
     seeds = [w.seeds(200 + i, n) if n else np.zeros(0, np.int32) for i, n in enumerate(sizes)]
     rngs = [w.rng_seed(200 + i) for i in range(n_batches)]
