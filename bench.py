@@ -25,7 +25,8 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 # each scaled by a 1 GiB plain copy kernel; profiles/citation_k_gather_and_sampling_kernels.md,
 # profiles/dense_social_and_co_purchase_kernel_durations.md).
 # Only quoted for the configurations that were profiled.
-GATHER_TRAFFIC_RATIO = {("citation", 1.0, 8): 0.972, ("dense_social", 1.0, 8): 1.024, ("co_purchase", 1.0, 8): 1.160}
+GATHER_TRAFFIC_RATIO = {("citation", 1.0, 32): 0.969, ("dense_social", 1.0, 32): 1.024, ("co_purchase", 1.0, 32): 1.160,
+                        ("citation", 1.0, 8): 0.972, ("dense_social", 1.0, 8): 1.024, ("co_purchase", 1.0, 8): 1.160}
 
 
 def log(msg):
