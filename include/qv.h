@@ -78,19 +78,6 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts /*
  * batch is used.  Default 16 GiB; 0 selects the hash always.  Results are identical. */
 qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes);
 
-/* Testing / tuning aid.  qv_sample / qv_sample_many find the first occurrence of every sampled
- * node in one of two ways with identical results: QV_DEDUP_ATOMIC, one atomicMin per sampled
- * edge into the dedup table (fewest kernels, lowest latency), or QV_DEDUP_PARTITIONED, the edges
- * of a hop are dealt into 16 hash buckets per batch and each bucket is resolved by one workgroup
- * in LDS (one more kernel per hop, several times fewer global atomics; needs
- * 16 x 8 bytes x (largest hop's edge bound) of scratch per batch).  QV_DEDUP_CHOOSE (default)
- * takes the partitioned form for calls whose a-priori edge bound, over all batches, is at
- * least 8 Mi edges. */
-#define QV_DEDUP_CHOOSE 0
-#define QV_DEDUP_ATOMIC 1
-#define QV_DEDUP_PARTITIONED 2
-qv_status qv_ctx_set_dedup_form(qv_ctx* ctx, int32_t form);
-
 /* Testing / tuning aid for qv_access_prob when it is given the in-edge CSR: 0 (default) lets every
  * sweep choose between gathering over in-edges and scattering along the out-edges of the nodes
  * that carry mass; 1 always gathers; 2 always scatters.  Results agree to rounding. */

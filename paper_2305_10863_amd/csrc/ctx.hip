@@ -136,13 +136,6 @@ qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes) {
     return QV_OK;
 }
 
-qv_status qv_ctx_set_dedup_form(qv_ctx* ctx, int32_t form) {
-    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_set_dedup_form: ctx is NULL");
-    if (form < 0 || form > 2) return fail(ctx, QV_EINVAL, "qv_ctx_set_dedup_form: 0 (choose), 1 (atomic) or 2 (partitioned)");
-    ctx->dedup_form = form;
-    return QV_OK;
-}
-
 qv_status qv_ctx_set_fap_direction(qv_ctx* ctx, int32_t direction) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_set_fap_direction: ctx is NULL");
     if (direction < 0 || direction > 2) return fail(ctx, QV_EINVAL, "qv_ctx_set_fap_direction: 0 (choose), 1 (gather) or 2 (scatter)");

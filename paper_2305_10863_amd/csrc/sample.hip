@@ -140,18 +140,6 @@ __global__ void k_table_clear(uint64_t* keyw, int64_t n_keyw, TableSlot* slots, 
 // ---------------------------------------------------------------------------------------------
 // per-batch state and per-launch arguments
 // ---------------------------------------------------------------------------------------------
-// Partitioned dedup of a hop (used for calls that are large enough to pay for one more kernel):
-// k_sample appends every edge as a (node, position) record to one of kParts buckets of its batch,
-// chosen by a hash of the node, and k_bucket_dedup (one workgroup per bucket) finds each node's
-// first position with LDS atomics.  No global atomic per edge: one per workgroup and bucket.
-constexpr int kParts = 16;
-constexpr int kPartShift = 28;               // bucket = top 4 bits of the multiplicative hash
-constexpr int kBucketSlots = 8192;           // entries of the bucket kernel's LDS table
-constexpr int kBucketProbes = 64;            // an insertion gives up after this many probes (next round)
-constexpr int kBucketThreads = 1024;
-constexpr uint32_t kDoneBit = 0x80000000u;   // record handled by an earlier round of the bucket kernel
-constexpr int64_t kPartitionedMinEdges = (int64_t)8 << 20;   // a-priori edge bound of the call from which the form is used
-
 struct BatchArgs {
     const int32_t* seeds;           // stage-0 ids
     int64_t n_seeds;
@@ -170,9 +158,6 @@ struct BatchArgs {
     uint16_t* seed_flags;           // stage-0 flags
     uint16_t* flags;                // per edge: first occurrence | new node << 1 | next-hop segment size << 2 | col_local written << 15
     uint32_t* partial;              // [kMaxTiles][3] per-tile counts of the stage being run
-    uint2* bucket;                  // partitioned dedup: kParts buckets of bucket_cap (node, position) records
-    uint32_t* fill;                 // [kParts] records in each bucket
-    int64_t bucket_cap;
     int64_t* node_off_out; int64_t* edge_off_out; int64_t* frontier_off_out;
     int64_t* n_id_len_out; int64_t* frontier_len_out;      // stand-alone reindex
 };
@@ -192,7 +177,6 @@ struct CallHeader {
     int32_t cumulative;             // hop k expands every node sampled so far, not only F_{k-1}
     int32_t frontier_restart;       // stand-alone reindex: number this stage's frontier from 0
     int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
-    int32_t partitioned;            // this hop's edges go through the buckets (k_bucket_dedup), not through atomicMin
     int32_t* status;
 };
 
@@ -238,7 +222,6 @@ __global__ void __launch_bounds__(256) k_insert_ids(A c) {
             m->stage_range[0] = 0;
             m->stage_range[1] = b.n_seeds;
         }
-        if (b.fill && tid < kParts) b.fill[tid] = 0;
     } else {                                    // stand-alone reindex, stage 1
         ids = b.nbr; slot_of = b.slot_of; n = b.edge_cap;
     }
@@ -280,55 +263,8 @@ __device__ __forceinline__ void emit_edge(const CallHeader& c, const BatchArgs& 
     }
 }
 
-// Partitioned form of emit_edge.  Every thread of the workgroup calls it once per round of the
-// sampling loop (`has_edge` false for lanes without an edge): the workgroup counts its records per
-// bucket in LDS, reserves space in each bucket with one global atomic, then writes the records.
-// The counters are double-buffered so that a round needs two barriers.
-struct ScatterLds {
-    uint32_t cnt[2][kParts];
-    uint32_t base[kParts];
-};
-
-__device__ __forceinline__ void emit_edge_partitioned(const CallHeader& c, const BatchArgs& b, ScatterLds& lds, int round,
-                                                      bool has_edge, int64_t p, int32_t g, int32_t vl) {
-    bool record = false;
-    if (has_edge) {
-        if (p < b.edge_cap) {
-            b.nbr[p] = g;
-            if (b.row_local) b.row_local[p] = vl;
-            if (g < 0 || (int64_t)g >= c.n_nodes) {
-                atomicOr(c.status, kStatRange);
-                b.flags[p] = 0x8000u;                   // closed, local id -1
-                b.col_local[p] = -1;
-            } else {
-                b.flags[p] = 0;
-                record = true;
-            }
-        } else {
-            atomicOr(c.status, kStatCapacity);
-        }
-    }
-    uint32_t* cnt = lds.cnt[round & 1];
-    if (threadIdx.x < kParts) lds.cnt[(round + 1) & 1][threadIdx.x] = 0;       // the next round's counters
-    const uint32_t part = ((uint32_t)g * 0x9E3779B1u) >> kPartShift;
-    uint32_t rank = 0;
-    if (record) rank = atomicAdd(&cnt[part], 1u);
-    __syncthreads();
-    if (threadIdx.x < kParts) {
-        const uint32_t n = cnt[threadIdx.x];
-        if (n) lds.base[threadIdx.x] = atomicAdd(&b.fill[threadIdx.x], n);
-    }
-    __syncthreads();
-    if (record) {
-        const int64_t at = (int64_t)lds.base[part] + rank;
-        if (at < b.bucket_cap) b.bucket[(int64_t)part * b.bucket_cap + at] = make_uint2((uint32_t)g, (uint32_t)p);
-        else atomicOr(c.status, kStatCapacity);
-    }
-}
-
 template <int G, typename A>
 __global__ void __launch_bounds__(256) k_sample(A c) {
-    __shared__ ScatterLds lds;
     const BatchArgs& b = c.batch(blockIdx.y);
     const int sub = threadIdx.x % G;
     constexpr int groups_per_block = 256 / G;
@@ -337,17 +273,14 @@ __global__ void __launch_bounds__(256) k_sample(A c) {
     const int64_t F = c.cumulative ? m->node_off[c.stage] : m->frontier_off[c.stage] - fbeg;
     const int64_t ebase = m->edge_off[c.stage - 1];
     const int64_t stride = (int64_t)gridDim.x * groups_per_block;
+    const int group_in_wave = (threadIdx.x % kWave) / G;
     const TableView t = table_of(c, b);
     const uint64_t tag = pos_tag(c.epoch, c.stage);
     const uint32_t l = (uint32_t)c.fanout;
-    if (c.partitioned) {
-        if (threadIdx.x < kParts) lds.cnt[0][threadIdx.x] = 0;
-        __syncthreads();
-    }
-    // the loop is uniform over the workgroup: every lane runs the same number of rounds
-    int round = 0;
-    for (int64_t fb = (int64_t)blockIdx.x * groups_per_block; fb < F; fb += stride, ++round) {
-        const int64_t f = fb + threadIdx.x / G;
+    // the loop is uniform over the wave: every lane runs the same number of iterations
+    int64_t f0 = (int64_t)blockIdx.x * groups_per_block + (threadIdx.x / kWave) * (kWave / G);
+    for (; f0 < F; f0 += stride) {
+        const int64_t f = f0 + group_in_wave;
         uint32_t d = 0, off = 0;
         int64_t rs = 0;
         int32_t v = 0, vl = -1;
@@ -369,11 +302,10 @@ __global__ void __launch_bounds__(256) k_sample(A c) {
             const uint32_t pick = floyd_resolve<G>(tdraw, active, false, base, sub, 0, (int)l);
             if (draw) pos = pick;
         }
-        const bool has_edge = (uint32_t)sub < mcount;
-        int32_t g = 0;
-        if (has_edge) g = c.col[rs + pos];
-        if (c.partitioned) emit_edge_partitioned(c, b, lds, round, has_edge, ebase + off + sub, g, vl);
-        else if (has_edge) emit_edge(c, b, t, tag, ebase + off + sub, g, vl);
+        if ((uint32_t)sub < mcount) {
+            const int32_t g = c.col[rs + pos];
+            emit_edge(c, b, t, tag, ebase + off + sub, g, vl);
+        }
     }
 }
 
@@ -382,7 +314,6 @@ __global__ void __launch_bounds__(256) k_sample(A c) {
 template <typename A>
 __global__ void __launch_bounds__(64) k_sample_wide(A c) {
     __shared__ uint32_t picks[QV_MAX_FANOUT];
-    __shared__ ScatterLds lds;
     const BatchArgs& b = c.batch(blockIdx.y);
     const int lane = threadIdx.x;
     const SampleMeta* m = b.meta;
@@ -392,11 +323,6 @@ __global__ void __launch_bounds__(64) k_sample_wide(A c) {
     const TableView t = table_of(c, b);
     const uint64_t tag = pos_tag(c.epoch, c.stage);
     const uint32_t l = (uint32_t)c.fanout;
-    if (c.partitioned) {
-        if (lane < kParts) lds.cnt[0][lane] = 0;
-        __syncthreads();
-    }
-    int round = 0;
     for (int64_t f = blockIdx.x; f < F; f += gridDim.x) {
         const int32_t v = b.fr_id[fbeg + f];
         const int64_t rs = b.fr_rs[fbeg + f];
@@ -421,10 +347,10 @@ __global__ void __launch_bounds__(64) k_sample_wide(A c) {
                 if (active) picks[s] = pos;
                 __syncthreads();
             }
-            int32_t g = 0;
-            if (s < mcount) g = c.col[rs + pos];
-            if (c.partitioned) emit_edge_partitioned(c, b, lds, round++, s < mcount, ebase + off + s, g, vl);
-            else if (s < mcount) emit_edge(c, b, t, tag, ebase + off + s, g, vl);
+            if (s < mcount) {
+                const int32_t g = c.col[rs + pos];
+                emit_edge(c, b, t, tag, ebase + off + s, g, vl);
+            }
         }
         __syncthreads();                                // picks are reused by the next node
     }
@@ -461,102 +387,6 @@ __device__ __forceinline__ Tri block_scan3(Tri v, Tri& total, uint32_t (*lds)[3]
 // Position p of the stage is a first occurrence iff the table's smallest tagged position for
 // its id is p itself; it is a new node iff that id has no local id yet.
 // ---------------------------------------------------------------------------------------------
-// ---------------------------------------------------------------------------------------------
-// k_bucket_dedup: one workgroup per (bucket, batch).  Finds the smallest position of every node in
-// the bucket with an LDS hash table, then does for the hop what k_flag does in the other form:
-// flags of the first occurrences (first / new / next-hop segment size / closed), local ids of the
-// positions whose node was numbered by an earlier stage.  Positions that repeat a node which is
-// new in this hop get a link to its first position (-(first + 2)) in col_local; k_assign numbers
-// the first position and k_relabel follows the link.
-// A bucket with more distinct nodes than the table holds is handled in rounds: a node that finds
-// no free entry within kBucketProbes probes waits for the next round (entries are never released
-// within a round, so all records of one node agree on whether it got in), records handled are
-// marked in the bucket.  Every record is finished after at most ceil(distinct / entries) + 1 rounds.
-// ---------------------------------------------------------------------------------------------
-template <typename RP, typename A>
-__global__ void __launch_bounds__(kBucketThreads) k_bucket_dedup(A c) {
-    __shared__ uint32_t keys[kBucketSlots];
-    __shared__ uint32_t minp[kBucketSlots];
-    __shared__ int32_t val[kBucketSlots];          // local id if the node is known, else the link code
-    __shared__ uint32_t pending;
-    const BatchArgs& b = c.batch(blockIdx.y);
-    const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
-    const int part = blockIdx.x;
-    int64_t n = b.fill[part];
-    if (n > b.bucket_cap) n = b.bucket_cap;
-    uint2* rec = b.bucket + (int64_t)part * b.bucket_cap;
-    const TableView t = table_of(c, b);
-    constexpr uint32_t kEmpty = 0xFFFFFFFFu;
-    for (int round = 0; round < (1 << 20); ++round) {           // ends when nothing is pending; the bound is a safety net
-        for (int i = threadIdx.x; i < kBucketSlots; i += kBucketThreads) { keys[i] = kEmpty; minp[i] = kEmpty; }
-        if (threadIdx.x == 0) pending = 0;
-        __syncthreads();
-        // pass 1: smallest position per node
-        for (int64_t i = threadIdx.x; i < n; i += kBucketThreads) {
-            const uint2 r = rec[i];
-            if (r.y & kDoneBit) continue;
-            uint32_t h = (r.x * 0x85EBCA6Bu) >> 19;             // 13 bits
-            bool in = false;
-            for (int probe = 0; probe < kBucketProbes; ++probe) {
-                const uint32_t old = atomicCAS(&keys[h], kEmpty, r.x);
-                if (old == kEmpty || old == r.x) { atomicMin(&minp[h], r.y); in = true; break; }
-                h = (h + 1) & (kBucketSlots - 1);
-            }
-            if (!in) pending = 1;
-        }
-        __syncthreads();
-        // per node: known or new, flags of its first position
-        for (int sidx = threadIdx.x; sidx < kBucketSlots; sidx += kBucketThreads) {
-            const uint32_t id = keys[sidx];
-            if (id == kEmpty) continue;
-            const uint32_t p = minp[sidx];
-            const uint32_t slot = t.direct ? id : table_insert(t, id);
-            uint32_t known = 0, seg = 0;
-            int32_t lid = -1;
-            if (slot == 0xFFFFFFFFu) {
-                atomicOr(c.status, kStatCapacity);
-                known = 1;                                       // closed with local id -1
-            } else {
-                const unsigned long long le = *reinterpret_cast<const unsigned long long*>(&b.slots[slot].lid);
-                if ((uint32_t)(le >> 32) == c.epoch) { known = 1; lid = (int32_t)(uint32_t)le; }
-            }
-            if (c.next_fanout > 0 && !c.cumulative) {
-                const uint32_t d = (uint32_t)((int64_t)rowptr[id + 1] - (int64_t)rowptr[id]);
-                seg = d < (uint32_t)c.next_fanout ? d : (uint32_t)c.next_fanout;
-            }
-            val[sidx] = known ? lid : -(int32_t)p - 2;
-            b.flags[p] = (uint16_t)(1u | ((known ^ 1u) << 1) | (seg << 2) | (known << 15));
-            if (known) b.col_local[p] = lid;
-            if (!c.direct) b.slot_of[p] = slot;
-        }
-        __syncthreads();
-        // pass 2: every other record of these nodes
-        for (int64_t i = threadIdx.x; i < n; i += kBucketThreads) {
-            const uint2 r = rec[i];
-            if (r.y & kDoneBit) continue;
-            uint32_t h = (r.x * 0x85EBCA6Bu) >> 19;
-            for (int probe = 0; probe < kBucketProbes; ++probe) {
-                const uint32_t k = keys[h];
-                if (k == r.x) {
-                    if (minp[h] != r.y) {
-                        const int32_t v = val[h];
-                        b.col_local[r.y] = v;
-                        if (v >= -1) b.flags[r.y] = 0x8000u;     // closed: numbered by an earlier stage
-                    }
-                    rec[i].y = r.y | kDoneBit;
-                    break;
-                }
-                if (k == kEmpty) break;                          // not in this round's table
-                h = (h + 1) & (kBucketSlots - 1);
-            }
-        }
-        __syncthreads();
-        if (!pending) break;
-        __syncthreads();                                         // everyone has read `pending` before it is reset
-    }
-    if (threadIdx.x == 0) b.fill[part] = 0;                      // empty for the next hop
-}
-
 constexpr int kMaxTiles = 1024;         // tiles per stage (k_assign sums the counts of earlier tiles itself)
 
 struct StageView {
@@ -600,10 +430,7 @@ __global__ void __launch_bounds__(kScanBlock) k_flag(A c) {
     Tri sum = {0, 0, 0};
     for (int it = 0; it < c.items_per_thread; ++it) {
         const int64_t p = t0 + (int64_t)it * kScanBlock + threadIdx.x;
-        if (p < v.end && c.partitioned) {                              // flags are final (k_bucket_dedup): count them
-            const uint32_t f = v.flags[p];
-            sum.a += f & 1u; sum.b += (f >> 1) & 1u; sum.c += (f >> 2) & 0x7FFu;
-        } else if (p < v.end) {
+        if (p < v.end) {
             const int32_t id = v.ids[p];
             const uint32_t slot = slot_at(c, v, p, id);
             uint32_t first = 0, isnew = 0, seg = 0, resolved = 0;
@@ -671,7 +498,7 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(A c) {
         if (x.a) {
             id = v.ids[p];
             slot = slot_at(c, v, p, id);
-            if (!x.b) lid = c.partitioned ? b.col_local[p] : b.slots[slot].lid;
+            if (!x.b) lid = b.slots[slot].lid;
             if (c.next_fanout > 0 && (!c.cumulative || x.b)) {
                 rs = (int64_t)rowptr[id]; deg = (uint32_t)((int64_t)rowptr[id + 1] - rs);
             }
@@ -793,11 +620,6 @@ __global__ void __launch_bounds__(256) k_relabel(A c) {
         // numbered by an earlier stage were written by k_flag, first occurrences by k_assign
         const uint32_t f = b.flags[p];
         if ((f & 0x8000u) || (f & 3u) == 3u) continue;
-        if (c.partitioned) {                            // link to the first position of a node new in its hop
-            const int32_t link = b.col_local[p];
-            if (link <= -2) b.col_local[p] = b.col_local[-(link + 2)];
-            continue;
-        }
         uint32_t slot;
         if (c.direct) {
             const int32_t g = b.nbr[p];
@@ -967,7 +789,6 @@ static bool use_direct(const qv_ctx* ctx, int64_t n_nodes, int n_tables) {
 
 struct Layout {                     // per-batch scratch sizes (elements)
     int64_t stage0, edges, frontier;
-    int64_t bucket_cap = 0;         // records per bucket (partitioned dedup), 0 = no buckets
 };
 
 static void tile_shape(int64_t max_items, int* ipt, int* tiles) {
@@ -985,7 +806,6 @@ static size_t per_batch_bytes(const Layout& L) {
     t += 2 * align_up((size_t)L.edges * 4) + align_up((size_t)L.edges * 2); // slot_of, nbr, flags
     t += 4 * align_up((size_t)L.frontier * 4) + align_up((size_t)L.frontier * 8);   // fr_id, fr_lid, fr_deg, fr_seg, fr_rs
     t += align_up((size_t)kMaxTiles * 3 * 4);                               // partial
-    if (L.bucket_cap > 0) t += align_up((size_t)kParts * (size_t)L.bucket_cap * 8) + align_up((size_t)kParts * 4);
     return t + 2048;
 }
 
@@ -1002,12 +822,6 @@ static bool carve(qv_ctx* ctx, const Layout& L, BatchArgs* b) {
     b->fr_deg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
     b->fr_seg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
     b->partial = (uint32_t*)arena_take(ctx, (size_t)kMaxTiles * 3 * 4);
-    b->bucket = nullptr; b->fill = nullptr; b->bucket_cap = L.bucket_cap;
-    if (L.bucket_cap > 0) {
-        b->bucket = (uint2*)arena_take(ctx, (size_t)kParts * (size_t)L.bucket_cap * 8);
-        b->fill = (uint32_t*)arena_take(ctx, (size_t)kParts * 4);
-        if (!b->bucket || !b->fill) return false;
-    }
     b->fr_cap = L.frontier;
     return b->meta && b->seed_slot && b->seed_flags && b->slot_of && b->nbr && b->flags && b->fr_id && b->fr_lid &&
            b->fr_rs && b->fr_deg && b->fr_seg && b->partial;
@@ -1056,29 +870,6 @@ static qv_status upload_batches(qv_ctx* ctx, CallArgs* c, int n_batches) {
     QV_HIP(ctx, hipEventRecord(ctx->args_ev[slot], ctx->stream));
     ctx->args_ev_used[slot] = true;
     c->b_dev = dev;
-    return QV_OK;
-}
-
-// Which dedup form a call uses.  The partitioned form adds a kernel per hop and pays off once the
-// call has enough edges to keep it busy; below that the per-edge atomicMin form has the lower latency.
-static bool use_partitioned(const qv_ctx* ctx, const Bounds& bd, int n_batches) {
-    if (bd.edges >= ((int64_t)1 << 31) - 2) return false;          // positions must fit 31 bits of a record
-    if (ctx->dedup_form == 1) return false;
-    if (ctx->dedup_form == 2) return true;
-    return bd.edges * (int64_t)n_batches >= kPartitionedMinEdges;
-}
-
-static int64_t bucket_cap_for(const Bounds& bd, int n_hops) {
-    int64_t cap = 1;
-    for (int k = 1; k <= n_hops; ++k) if (bd.hop_edges[k] > cap) cap = bd.hop_edges[k];
-    return cap;
-}
-
-static qv_status launch_bucket_dedup(qv_ctx* ctx, const CallArgs& c, int rowptr_bits, int n_batches) {
-    dim3 grid((unsigned)kParts, (unsigned)n_batches);
-    if (rowptr_bits == 32) QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kBucketThreads), k_bucket_dedup, int32_t);
-    else QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kBucketThreads), k_bucket_dedup, int64_t);
-    QV_LAUNCH_CHECK(ctx, "k_bucket_dedup");
     return QV_OK;
 }
 
@@ -1139,8 +930,6 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     Layout L;
     L.stage0 = max_seeds; L.edges = bd.edges;
     L.frontier = cumulative ? (bd.nodes > 0 ? bd.nodes : 1) : bd.frontier;   // cumulative: one entry per node, at its local id
-    const bool partitioned = use_partitioned(ctx, bd, n_batches);
-    if (partitioned) L.bucket_cap = bucket_cap_for(bd, n_hops);
     rc = arena_begin(ctx, per_batch_bytes(L) * n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch));
     if (rc != QV_OK) return rc;
     CallArgs c{};
@@ -1191,13 +980,8 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
             QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(kScanBlock), k_cum_scan);
             QV_LAUNCH_CHECK(ctx, "k_cum_scan");
         }
-        c.partitioned = partitioned ? 1 : 0;
         rc = launch_sample(ctx, c, bd.hop_front[k - 1], n_batches);
         if (rc != QV_OK) return rc;
-        if (partitioned) {
-            rc = launch_bucket_dedup(ctx, c, csr->rowptr_bits, n_batches);
-            if (rc != QV_OK) return rc;
-        }
         rc = launch_dedup(ctx, c, csr->rowptr_bits, bd.hop_edges[k], n_batches);
         if (rc != QV_OK) return rc;
     }
@@ -1224,7 +1008,6 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, i
     if (rc != QV_OK) return rc;
     Layout L;
     L.stage0 = n_seeds; L.edges = bd.edges; L.frontier = cumulative ? (bd.nodes > 0 ? bd.nodes : 1) : bd.frontier;
-    if (use_partitioned(ctx, bd, n_batches)) L.bucket_cap = bucket_cap_for(bd, n_hops);
     const size_t want = per_batch_bytes(L) * (size_t)n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch);
     if (want > ctx->arena_bytes) {
         rc = arena_begin(ctx, want);

@@ -130,10 +130,6 @@ def test_co_purchase_full_batch_sweep_and_tiered(qv, ctx):
     feat = qv.Features(ctx, qvgen.features_device(w.seed, w.n, w.dim, torch.float32))
     for i, n_seeds in enumerate(w.batch_sweep):
         check_batches(qv, ctx, w, rowptr, col, g, feat, [10 + i], n_seeds=n_seeds)
-    ctx.set_dedup_form(2)                                       # buckets resolved in LDS, whatever the call size
-    for i, n_seeds in enumerate(w.batch_sweep):
-        check_batches(qv, ctx, w, rowptr, col, g, feat, [30 + i], n_seeds=n_seeds)
-    ctx.set_dedup_form(0)
     # nested-block variant (every hop expands all nodes sampled so far) at full size
     seeds = w.seeds(77, 512)
     out = qv.qv_sample(ctx, g, torch.from_numpy(seeds).cuda(), w.fanouts, 123, cumulative=True)
@@ -175,12 +171,7 @@ def test_citation_full(qv, ctx):
     assert rowptr.dtype == np.int64 and len(col) > 1_590_000_000
     feat = qv.Features(ctx, qvgen.features_device(w.seed, w.n, w.dim, torch.float16))
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(4))
-    ctx.set_dedup_form(2)
-    check_batches(qv, ctx, w, rowptr, col, g, feat, range(4, 6))
-    ctx.set_dedup_form(1)                                       # the call of 32 below with per-edge atomics ...
-    ctx.set_table_budget(64 << 30)
-    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 100)
-    ctx.set_dedup_form(0)                                       # ... and as the library chooses for it (partitioned), as the bench
+    ctx.set_table_budget(64 << 30)                              # as the bench: all 32 tables addressed directly
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)
     ctx.set_table_budget(16 << 30)
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # default budget (hashed tables on the citation graph), arguments uploaded

@@ -25,16 +25,13 @@ def qv():
     return m
 
 
-@pytest.fixture(scope="module", params=["direct", "hashed", "direct-partitioned", "hashed-partitioned"])
+@pytest.fixture(scope="module", params=["direct", "hashed"])
 def ctx(qv, request):
-    """Every test runs with both forms of the dedup table (addressed by node id / open-addressing hash)
-    and both ways of finding first occurrences (per-edge atomicMin / buckets resolved in LDS)."""
+    """Every test runs with both forms of the dedup table (addressed by node id / open-addressing hash)."""
     c = qv.Context(0)
-    if request.param.startswith("hashed"):
+    if request.param == "hashed":
         c.set_table_budget(0)
         c._budget = 0
-    if request.param.endswith("partitioned"):
-        c.set_dedup_form(2)
     yield c
     c.close()
 
@@ -141,26 +138,6 @@ def test_sample_shapes(qv, ctx, tiny, fanouts, n_seeds):
     out = qv.qv_sample(ctx, g, dev(seeds), fanouts, 77)
     ctx.sync()
     assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, fanouts, 77))
-
-
-def test_sample_many_distinct_nodes_per_bucket(qv, ctx):
-    """A hop whose buckets hold more distinct nodes than the bucket kernel's LDS table (several
-    rounds per bucket in the partitioned form), and a hub that fills one bucket with repeats."""
-    rng = np.random.default_rng(5)
-    n = 300_000
-    deg = rng.integers(8, 25, n)
-    rowptr = np.zeros(n + 1, dtype=np.int64)
-    np.cumsum(deg, out=rowptr[1:])
-    col = rng.integers(0, n, int(rowptr[-1])).astype(np.int32)
-    col[rng.random(len(col)) < 0.15] = 12345                      # a hub: 15 % of all edges end there
-    g = make_graph(qv, ctx, rowptr, col)
-    seeds = rng.integers(0, n, 6000).astype(np.int32)
-    for cumulative in (False, True):
-        out = qv.qv_sample(ctx, g, dev(seeds), [12, 9], 31337, cumulative=cumulative)
-        ctx.sync()
-        want = oracle.sample(rowptr, col, seeds, [12, 9], 31337, cumulative=cumulative)
-        assert want["edge_off"][-1] > 500_000 and len(want["n_id"]) > 200_000
-        assert_sample_equal(out.to_host(), want)
 
 
 def test_sample_int64_rowptr_and_in_degree_skew(qv, ctx):
