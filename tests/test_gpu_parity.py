@@ -140,6 +140,26 @@ def test_sample_shapes(qv, ctx, tiny, fanouts, n_seeds):
     assert_sample_equal(out.to_host(), oracle.sample(rowptr, col, seeds, fanouts, 77))
 
 
+def test_sample_large_hop_with_a_hub(qv, ctx):
+    """A hop of more than half a million edges over 300 k nodes in which 15 % of all edges end at
+    one hub: long runs of repeats next to mostly distinct neighbours."""
+    rng = np.random.default_rng(5)
+    n = 300_000
+    deg = rng.integers(8, 25, n)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum(deg, out=rowptr[1:])
+    col = rng.integers(0, n, int(rowptr[-1])).astype(np.int32)
+    col[rng.random(len(col)) < 0.15] = 12345
+    g = make_graph(qv, ctx, rowptr, col)
+    seeds = rng.integers(0, n, 6000).astype(np.int32)
+    for cumulative in (False, True):
+        out = qv.qv_sample(ctx, g, dev(seeds), [12, 9], 31337, cumulative=cumulative)
+        ctx.sync()
+        want = oracle.sample(rowptr, col, seeds, [12, 9], 31337, cumulative=cumulative)
+        assert want["edge_off"][-1] > 500_000 and len(want["n_id"]) > 200_000
+        assert_sample_equal(out.to_host(), want)
+
+
 def test_sample_int64_rowptr_and_in_degree_skew(qv, ctx):
     w = qvgen.workload("citation", scale=0.003)
     rowptr, col = w.graph()
