@@ -33,8 +33,14 @@ def _p(a, t):
 def lib():
     global _lib
     if _lib is None:
-        build()
-        _lib = C.CDLL(_SO)
+        # QV_ORACLE_LIB: load this build of the oracle instead (tests/test_oracle_mutations.py points
+        # it at deliberately broken builds to check that the pins notice)
+        override = os.environ.get("QV_ORACLE_LIB")
+        if override:
+            _lib = C.CDLL(override)
+        else:
+            build()
+            _lib = C.CDLL(_SO)
         _lib.o_rand_below.restype = C.c_uint64
         _lib.o_rand_below.argtypes = [C.c_uint64, C.c_uint32, C.c_uint32, C.c_uint32, C.c_uint64]
         _lib.o_sample_positions.restype = C.c_int64
