@@ -148,6 +148,18 @@ qv_status qv_sample_hop(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier,
                         int64_t n_frontier, int32_t fanout, uint64_t rng_seed, int32_t hop,
                         int32_t* nbr_out, int64_t nbr_cap, int64_t* off_out);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): qv_sample_hop with the same arguments and results, but
+ * its scratch (row extents and segment offsets of the frontier, tile sums) lives in a fixed
+ * device array of the library, about 16 MiB per GPU, held until the process ends.  The call
+ * allocates and frees nothing.  n_frontier may be at most QV_NOALLOC_MAX_FRONTIER (QV_EINVAL
+ * beyond).  All calls on one GPU share that array, whatever their context: calls that overlap
+ * on one GPU race; serialise them (one stream, or events between streams). */
+#define QV_NOALLOC_MAX_FRONTIER 1048576
+qv_status qv_sample_hop_noalloc(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier,
+                                int64_t n_frontier, int32_t fanout, uint64_t rng_seed, int32_t hop,
+                                int32_t* nbr_out, int64_t nbr_cap, int64_t* off_out);
+
 /* Output block of qv_sample.  All arrays are caller-allocated [dev] memory. */
 typedef struct {
     int32_t* n_id;           /* distinct sampled nodes (global ids), the distinct seeds first,  */

@@ -15,11 +15,12 @@ _lib = None
 
 QV_OK, QV_EINVAL, QV_ENOMEM, QV_EHIP, QV_ECAPACITY, QV_ERANGE = 0, -1, -2, -3, -4, -5
 QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 32
+QV_NOALLOC_MAX_FRONTIER = 1 << 20
 QV_SAMPLE_CUMULATIVE, QV_FEAT_OWN_COPY = 1, 1
 
 EXPORTS = [
     "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget", "qv_ctx_set_fap_direction",
-    "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_csr_transpose", "qv_csr_rowptr", "qv_csr_col", "qv_sample_hop", "qv_sample", "qv_sample_many",
+    "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_csr_transpose", "qv_csr_rowptr", "qv_csr_col", "qv_sample_hop", "qv_sample_hop_noalloc", "qv_sample", "qv_sample_many",
     "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc", "qv_feat_row_stride",
     "qv_gather", "qv_gather_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
 ]
@@ -68,6 +69,7 @@ def lib():
         L.qv_csr_col.argtypes = [vp]
         L.qv_csr_col.restype = vp
         L.qv_sample_hop.argtypes = [vp, vp, vp, i64, i32, u64, i32, vp, i64, vp]
+        L.qv_sample_hop_noalloc.argtypes = [vp, vp, vp, i64, i32, u64, i32, vp, i64, vp]
         L.qv_sample.argtypes = [vp, vp, vp, i64, C.POINTER(i32), i32, u64, C.c_uint32, C.POINTER(_SampleOut)]
         L.qv_sample_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i32), i32,
                                      C.POINTER(u64), C.c_uint32, C.POINTER(_SampleOut)]
@@ -370,15 +372,20 @@ def qv_gather_many(ctx, feat, ids_list, n_ids_dev_list=None, outs=None):
     return outs
 
 
-def qv_sample_hop(ctx, graph, frontier, fanout, rng_seed, hop, nbr_cap=None):
-    """One hop.  Returns (nbr int32[cap], off int64[F+1]) device tensors; off[-1] = count."""
+def qv_sample_hop(ctx, graph, frontier, fanout, rng_seed, hop, nbr_cap=None, out=None, noalloc=False):
+    """One hop.  Returns (nbr int32[cap], off int64[F+1]) device tensors; off[-1] = count.
+    `out` = (nbr, off) tensors to write into; noalloc=True calls qv_sample_hop_noalloc (the
+    library's fixed scratch, no device allocation inside the call)."""
     _dev_i32(frontier, "frontier")
     F = frontier.numel()
     cap = F * fanout if nbr_cap is None else nbr_cap
-    nbr = torch.empty(max(cap, 1), dtype=torch.int32, device=ctx.device)
-    off = torch.zeros(F + 1, dtype=torch.int64, device=ctx.device)
-    ctx.check(lib().qv_sample_hop(ctx.h, graph.h, _ptr(frontier), F, fanout, C.c_uint64(rng_seed), hop,
-                                  _ptr(nbr), cap, _ptr(off)))
+    if out is None:
+        nbr = torch.empty(max(cap, 1), dtype=torch.int32, device=ctx.device)
+        off = torch.zeros(F + 1, dtype=torch.int64, device=ctx.device)
+    else:
+        nbr, off = out
+    fn = lib().qv_sample_hop_noalloc if noalloc else lib().qv_sample_hop
+    ctx.check(fn(ctx.h, graph.h, _ptr(frontier), F, fanout, C.c_uint64(rng_seed), hop, _ptr(nbr), cap, _ptr(off)))
     return nbr, off
 
 

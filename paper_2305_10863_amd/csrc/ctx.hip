@@ -89,6 +89,12 @@ qv_status qv_ctx_create(int device, void* hip_stream, qv_ctx** out) {
         return rc;
     }
     ctx->n_cu = prop.multiProcessorCount > 0 ? prop.multiProcessorCount : 256;
+    qv_status rc = static_scratch_bind(ctx);
+    if (rc != QV_OK) {
+        set_global_error(ctx->err.c_str());
+        qv_ctx_destroy(ctx);
+        return rc;
+    }
     *out = ctx;
     return QV_OK;
 }

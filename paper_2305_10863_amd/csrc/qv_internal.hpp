@@ -130,6 +130,10 @@ inline int grid_for(int64_t work_items, int per_block, int cap) {
     return (int)b;
 }
 
+// sample.hip: bind the fixed device scratch of qv_sample_hop_noalloc for the context's GPU (once
+// per device; the device must be current)
+qv_status static_scratch_bind(qv_ctx* ctx);
+
 // gather.hip: raw row gather used by qv_gather and by tier construction
 struct GatherJob {
     const int32_t* ids;

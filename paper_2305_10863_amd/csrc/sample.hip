@@ -18,6 +18,7 @@
 // (4-5 us each).
 #include "qv_internal.hpp"
 #include <cstring>
+#include <mutex>
 #include <new>
 
 namespace qv {
@@ -992,6 +993,102 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     return QV_OK;
 }
 
+// ---------------------------------------------------------------------------------------------
+// stand-alone hop, shared by qv_sample_hop (scratch from the context's arena) and
+// qv_sample_hop_noalloc (scratch in a fixed device array)
+// ---------------------------------------------------------------------------------------------
+struct HopScratch {
+    SampleMeta* meta;
+    uint32_t* partial;          // [kMaxDegTiles]
+    int64_t* fr_rs;             // [n_frontier] row start
+    uint32_t* fr_deg;           // [n_frontier] degree
+    uint32_t* fr_seg;           // [n_frontier] segment offset
+};
+
+static size_t hop_scratch_bytes(int64_t n_frontier) {
+    const size_t F = (size_t)n_frontier;
+    return align_up(sizeof(SampleMeta)) + align_up(kMaxDegTiles * 4) + align_up(F * 8) + 2 * align_up(F * 4) + 4096;
+}
+
+static qv_status check_hop_args(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier, int64_t n_frontier, int32_t fanout,
+                                int32_t hop, const int32_t* nbr_out, int64_t nbr_cap, const int64_t* off_out, const char* who) {
+    if (!csr || !off_out || (n_frontier > 0 && !frontier) || n_frontier < 0 || nbr_cap < 0 || (nbr_cap > 0 && !nbr_out))
+        return fail(ctx, QV_EINVAL, "%s: null or negative argument", who);
+    if (fanout < 1 || fanout > QV_MAX_FANOUT) return fail(ctx, QV_EINVAL, "%s: fanout %d outside [1, %d]", who, fanout, QV_MAX_FANOUT);
+    if (hop < 1) return fail(ctx, QV_EINVAL, "%s: hop is 1-based", who);
+    if (n_frontier * (int64_t)fanout >= ((int64_t)1 << 31)) return fail(ctx, QV_EINVAL, "%s: 2^31 or more edges possible", who);
+    return QV_OK;
+}
+
+static qv_status sample_hop_run(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier, int64_t n_frontier, int32_t fanout,
+                                uint64_t rng_seed, int32_t hop, int32_t* nbr_out, int64_t nbr_cap, int64_t* off_out,
+                                const HopScratch& s) {
+    if (!s.meta || !s.partial || !s.fr_rs || !s.fr_deg || !s.fr_seg)
+        return fail(ctx, QV_ENOMEM, "qv_sample_hop: scratch too small (internal sizing error)");
+    int64_t per = (n_frontier + (int64_t)kScanBlock * kMaxDegTiles - 1) / ((int64_t)kScanBlock * kMaxDegTiles);
+    if (per < 1) per = 1;
+    int64_t tiles = (n_frontier + kScanBlock * per - 1) / (kScanBlock * per);
+    if (tiles < 1) tiles = 1;
+    const int ipt = (int)per;
+    if (csr->rowptr_bits == 32) {
+        hipLaunchKernelGGL(k_deg_partial<int32_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int32_t*)csr->rowptr,
+                           csr->n_nodes, frontier, n_frontier, fanout, ipt, s.partial, ctx->d_status);
+        hipLaunchKernelGGL(k_deg_scan<int32_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int32_t*)csr->rowptr,
+                           csr->n_nodes, frontier, n_frontier, fanout, ipt, s.partial, off_out, s.fr_rs, s.fr_deg, s.fr_seg, s.meta);
+    } else {
+        hipLaunchKernelGGL(k_deg_partial<int64_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int64_t*)csr->rowptr,
+                           csr->n_nodes, frontier, n_frontier, fanout, ipt, s.partial, ctx->d_status);
+        hipLaunchKernelGGL(k_deg_scan<int64_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int64_t*)csr->rowptr,
+                           csr->n_nodes, frontier, n_frontier, fanout, ipt, s.partial, off_out, s.fr_rs, s.fr_deg, s.fr_seg, s.meta);
+    }
+    QV_LAUNCH_CHECK(ctx, "k_deg_scan");
+    if (n_frontier == 0) return QV_OK;
+    CallArgs c{};
+    c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
+    c.stage = 1; c.hop = hop; c.fanout = fanout; c.status = ctx->d_status;
+    BatchArgs& b = c.b[0];
+    b.rng_seed = rng_seed; b.meta = s.meta;
+    b.fr_id = const_cast<int32_t*>(frontier); b.fr_lid = const_cast<int32_t*>(frontier);   // local ids unused (row_local == NULL)
+    b.fr_rs = s.fr_rs; b.fr_deg = s.fr_deg; b.fr_seg = s.fr_seg;
+    b.nbr = nbr_out; b.row_local = nullptr; b.slot_of = nullptr; b.edge_cap = nbr_cap;
+    return launch_sample(ctx, c, n_frontier, 1);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Fixed scratch of qv_sample_hop_noalloc: one array per GPU, held until the process ends.  In
+// host code the array's name is only a stand-in; its device address is asked for once per device
+// (static_scratch_bind, called from qv_ctx_create with that device current) and kept here.
+// ---------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes =
+    ((sizeof(SampleMeta) + 255) / 256 * 256) + (((size_t)kMaxDegTiles * 4 + 255) / 256 * 256) +
+    (size_t)QV_NOALLOC_MAX_FRONTIER * 16 + 3 * 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static char* g_scratch_ptr[kMaxDevices] = {};
+
+qv_status static_scratch_bind(qv_ctx* ctx) {
+    if (ctx->device < 0 || ctx->device >= kMaxDevices) return QV_OK;      // such a device simply has no no-alloc entry point
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (g_scratch_ptr[ctx->device]) return QV_OK;
+    void* p = nullptr;
+    QV_HIP(ctx, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[ctx->device] = (char*)p;
+    return QV_OK;
+}
+
+static qv_status static_scratch_of(qv_ctx* ctx, char** out) {
+    char* p = nullptr;
+    if (ctx->device >= 0 && ctx->device < kMaxDevices) {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        p = g_scratch_ptr[ctx->device];
+    }
+    if (!p) return fail(ctx, QV_EHIP, "qv_sample_hop_noalloc: the fixed scratch of GPU %d was not bound at context creation", ctx->device);
+    *out = p;
+    return QV_OK;
+}
+
 }  // namespace qv
 
 using namespace qv;
@@ -1023,46 +1120,43 @@ qv_status qv_sample_hop(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier,
                         int32_t fanout, uint64_t rng_seed, int32_t hop, int32_t* nbr_out, int64_t nbr_cap,
                         int64_t* off_out) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_sample_hop: ctx is NULL");
-    if (!csr || !off_out || (n_frontier > 0 && !frontier) || n_frontier < 0 || nbr_cap < 0 || (nbr_cap > 0 && !nbr_out))
-        return fail(ctx, QV_EINVAL, "qv_sample_hop: null or negative argument");
-    if (fanout < 1 || fanout > QV_MAX_FANOUT) return fail(ctx, QV_EINVAL, "qv_sample_hop: fanout %d outside [1, %d]", fanout, QV_MAX_FANOUT);
-    if (hop < 1) return fail(ctx, QV_EINVAL, "qv_sample_hop: hop is 1-based");
-    if (n_frontier * (int64_t)fanout >= ((int64_t)1 << 31)) return fail(ctx, QV_EINVAL, "qv_sample_hop: 2^31 or more edges possible");
-    const size_t F = (size_t)n_frontier;
-    qv_status rc = arena_begin(ctx, align_up(sizeof(SampleMeta)) + align_up(kMaxDegTiles * 4) + align_up(F * 8) + 2 * align_up(F * 4) + 4096);
+    qv_status rc = check_hop_args(ctx, csr, frontier, n_frontier, fanout, hop, nbr_out, nbr_cap, off_out, "qv_sample_hop");
     if (rc != QV_OK) return rc;
-    SampleMeta* meta = (SampleMeta*)arena_take(ctx, sizeof(SampleMeta));
-    uint32_t* partial = (uint32_t*)arena_take(ctx, kMaxDegTiles * 4);
-    int64_t* fr_rs = (int64_t*)arena_take(ctx, F * 8);
-    uint32_t* fr_deg = (uint32_t*)arena_take(ctx, F * 4);
-    uint32_t* fr_seg = (uint32_t*)arena_take(ctx, F * 4);
-    int64_t per = (n_frontier + (int64_t)kScanBlock * kMaxDegTiles - 1) / ((int64_t)kScanBlock * kMaxDegTiles);
-    if (per < 1) per = 1;
-    int64_t tiles = (n_frontier + kScanBlock * per - 1) / (kScanBlock * per);
-    if (tiles < 1) tiles = 1;
-    const int ipt = (int)per;
-    if (csr->rowptr_bits == 32) {
-        hipLaunchKernelGGL(k_deg_partial<int32_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int32_t*)csr->rowptr,
-                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, ctx->d_status);
-        hipLaunchKernelGGL(k_deg_scan<int32_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int32_t*)csr->rowptr,
-                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, off_out, fr_rs, fr_deg, fr_seg, meta);
-    } else {
-        hipLaunchKernelGGL(k_deg_partial<int64_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int64_t*)csr->rowptr,
-                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, ctx->d_status);
-        hipLaunchKernelGGL(k_deg_scan<int64_t>, dim3((unsigned)tiles), dim3(kScanBlock), 0, ctx->stream, (const int64_t*)csr->rowptr,
-                           csr->n_nodes, frontier, n_frontier, fanout, ipt, partial, off_out, fr_rs, fr_deg, fr_seg, meta);
-    }
-    QV_LAUNCH_CHECK(ctx, "k_deg_scan");
-    if (n_frontier == 0) return QV_OK;
-    CallArgs c{};
-    c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
-    c.stage = 1; c.hop = hop; c.fanout = fanout; c.status = ctx->d_status;
-    BatchArgs& b = c.b[0];
-    b.rng_seed = rng_seed; b.meta = meta;
-    b.fr_id = const_cast<int32_t*>(frontier); b.fr_lid = const_cast<int32_t*>(frontier);   // local ids unused (row_local == NULL)
-    b.fr_rs = fr_rs; b.fr_deg = fr_deg; b.fr_seg = fr_seg;
-    b.nbr = nbr_out; b.row_local = nullptr; b.slot_of = nullptr; b.edge_cap = nbr_cap;
-    return launch_sample(ctx, c, n_frontier, 1);
+    rc = arena_begin(ctx, hop_scratch_bytes(n_frontier));
+    if (rc != QV_OK) return rc;
+    HopScratch s;
+    const size_t F = (size_t)n_frontier;
+    s.meta = (SampleMeta*)arena_take(ctx, sizeof(SampleMeta));
+    s.partial = (uint32_t*)arena_take(ctx, kMaxDegTiles * 4);
+    s.fr_rs = (int64_t*)arena_take(ctx, F * 8);
+    s.fr_deg = (uint32_t*)arena_take(ctx, F * 4);
+    s.fr_seg = (uint32_t*)arena_take(ctx, F * 4);
+    return sample_hop_run(ctx, csr, frontier, n_frontier, fanout, rng_seed, hop, nbr_out, nbr_cap, off_out, s);
+}
+
+qv_status qv_sample_hop_noalloc(qv_ctx* ctx, const qv_csr* csr, const int32_t* frontier, int64_t n_frontier,
+                                int32_t fanout, uint64_t rng_seed, int32_t hop, int32_t* nbr_out, int64_t nbr_cap,
+                                int64_t* off_out) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_sample_hop_noalloc: ctx is NULL");
+    qv_status rc = check_hop_args(ctx, csr, frontier, n_frontier, fanout, hop, nbr_out, nbr_cap, off_out, "qv_sample_hop_noalloc");
+    if (rc != QV_OK) return rc;
+    if (n_frontier > QV_NOALLOC_MAX_FRONTIER)
+        return fail(ctx, QV_EINVAL, "qv_sample_hop_noalloc: n_frontier %lld exceeds the fixed scratch (%d entries); use qv_sample_hop",
+                    (long long)n_frontier, QV_NOALLOC_MAX_FRONTIER);
+    char* base = nullptr;
+    rc = static_scratch_of(ctx, &base);
+    if (rc != QV_OK) return rc;
+    // carve the device's fixed array: the same five pieces qv_sample_hop takes from the arena, each at
+    // its place for the largest frontier, so nothing depends on the sizes of earlier calls
+    constexpr size_t Fmax = (size_t)QV_NOALLOC_MAX_FRONTIER;
+    HopScratch s;
+    size_t at = 0;
+    s.meta = (SampleMeta*)(base + at);     at += align_up(sizeof(SampleMeta));
+    s.partial = (uint32_t*)(base + at);    at += align_up(kMaxDegTiles * 4);
+    s.fr_rs = (int64_t*)(base + at);       at += align_up(Fmax * 8);
+    s.fr_deg = (uint32_t*)(base + at);     at += align_up(Fmax * 4);
+    s.fr_seg = (uint32_t*)(base + at);
+    return sample_hop_run(ctx, csr, frontier, n_frontier, fanout, rng_seed, hop, nbr_out, nbr_cap, off_out, s);
 }
 
 qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_t n_seeds, const int32_t* fanouts,
