@@ -189,6 +189,9 @@ def main():
                     help="independent batches per qv_sample_many / qv_gather_many call (1..32)")
     ap.add_argument("--table-budget-gib", type=float, default=-1.0,
                     help="dedup table budget per context in GiB (0 = always hash; default: 64 with one stream, else the library's 16)")
+    ap.add_argument("--dedup", default="auto", choices=["auto", "table", "partitioned"],
+                    help="dedup form of qv_sample (qv_ctx_set_dedup); results are identical")
+    ap.add_argument("--partitions-log2", type=int, default=-1, help="partitions per batch of the partitioned form (-1: per call)")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-metrics", action="store_true", help="skip the PSGS / FAP whole-graph passes")
@@ -349,6 +352,7 @@ def main():
         budget_gib = args.table_budget_gib if args.table_budget_gib >= 0 else (64.0 if S == 1 else -1.0)
         if budget_gib >= 0:
             c.set_table_budget(int(budget_gib * 2 ** 30))
+        c.set_dedup({"auto": 0, "table": 1, "partitioned": 2}[args.dedup], args.partitions_log2)
         c.reserve(batch, w.fanouts, w.n, n_batches=B)
         bufs.append([qv.SampleBuffers(c, batch, w.fanouts, w.n) for _ in range(B)])
         rows.append([feat.empty_rows(nb, "cuda") for _ in range(B)])
@@ -417,6 +421,7 @@ def main():
             k = j % S2
             c = ctxs2[k]
             if k not in own:
+                c.set_dedup({"auto": 0, "table": 1, "partitioned": 2}[args.dedup], args.partitions_log2)
                 c.reserve(batch, w.fanouts, w.n, n_batches=B2)
                 own[k] = [(qv.SampleBuffers(c, batch, w.fanouts, w.n), feat.empty_rows(nb, "cuda")) for _ in range(B2)]
             views = []

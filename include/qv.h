@@ -78,6 +78,17 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts /*
  * batch is used.  Default 16 GiB; 0 selects the hash always.  Results are identical. */
 qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes);
 
+/* Which dedup form qv_sample / qv_sample_many use (results are identical; this is a tuning and
+ * testing aid).  QV_DEDUP_AUTO (default): the partitioned form (ids split by hash over
+ * workgroups that dedup in LDS; nothing kept in HBM between calls) wherever it applies, i.e.
+ * layer frontiers with at most 4,194,304 ids per stage; tables otherwise.  QV_DEDUP_TABLE: always
+ * the tables above.  QV_DEDUP_PARTITIONED: as AUTO.  partitions_log2: partitions per batch of
+ * the partitioned form as a power of two, 0..6, or -1 to let every call choose. */
+#define QV_DEDUP_AUTO 0
+#define QV_DEDUP_TABLE 1
+#define QV_DEDUP_PARTITIONED 2
+qv_status qv_ctx_set_dedup(qv_ctx* ctx, int32_t form, int32_t partitions_log2);
+
 /* Testing / tuning aid for qv_access_prob when it is given the in-edge CSR: 0 (default) lets every
  * sweep choose between gathering over in-edges and scattering along the out-edges of the nodes
  * that carry mass; 1 always gathers; 2 always scatters.  Results agree to rounding. */

@@ -17,9 +17,10 @@ QV_OK, QV_EINVAL, QV_ENOMEM, QV_EHIP, QV_ECAPACITY, QV_ERANGE = 0, -1, -2, -3, -
 QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 32
 QV_NOALLOC_MAX_FRONTIER = 1 << 20
 QV_SAMPLE_CUMULATIVE, QV_FEAT_OWN_COPY = 1, 1
+QV_DEDUP_AUTO, QV_DEDUP_TABLE, QV_DEDUP_PARTITIONED = 0, 1, 2
 
 EXPORTS = [
-    "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget", "qv_ctx_set_fap_direction",
+    "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget", "qv_ctx_set_dedup", "qv_ctx_set_fap_direction",
     "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_csr_transpose", "qv_csr_rowptr", "qv_csr_col", "qv_sample_hop", "qv_sample_hop_noalloc", "qv_sample", "qv_sample_many",
     "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc", "qv_feat_row_stride",
     "qv_gather", "qv_gather_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
@@ -58,6 +59,7 @@ def lib():
         L.qv_ctx_reserve.argtypes = [vp, i64, C.POINTER(i32), i32, i64, C.c_uint32, i32]
         L.qv_ctx_set_epoch.argtypes = [vp, C.c_uint32]
         L.qv_ctx_set_table_budget.argtypes = [vp, i64]
+        L.qv_ctx_set_dedup.argtypes = [vp, i32, i32]
         L.qv_ctx_set_fap_direction.argtypes = [vp, i32]
         L.qv_sample_bounds.argtypes = [i64, C.POINTER(i32), i32, i64, C.c_uint32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
         L.qv_csr_create.argtypes = [vp, i64, i64, vp, i32, vp, i32, C.POINTER(vp)]
@@ -131,6 +133,10 @@ class Context:
     def set_table_budget(self, n_bytes):
         """0 forces the hashed dedup table; see qv_ctx_set_table_budget."""
         self.check(lib().qv_ctx_set_table_budget(self.h, n_bytes))
+
+    def set_dedup(self, form, partitions_log2=-1):
+        """form: 0 auto, 1 tables, 2 partitioned; see qv_ctx_set_dedup."""
+        self.check(lib().qv_ctx_set_dedup(self.h, form, partitions_log2))
 
     def set_fap_direction(self, direction):
         """0 choose per sweep (default), 1 gather only, 2 scatter only; see qv_ctx_set_fap_direction."""

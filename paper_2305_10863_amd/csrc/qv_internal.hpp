@@ -60,6 +60,8 @@ struct qv_ctx {
     size_t table_entries = 0;          // slots allocated (all batches of a call together)
     size_t table_keyw_entries = 0;     // entries allocated in keyw
     int64_t direct_budget_bytes = (int64_t)16 << 30;
+    int dedup_form = 0;                // QV_DEDUP_AUTO / _TABLE / _PARTITIONED
+    int part_log2 = -1;                // partitions per batch (log2) of the partitioned form, -1 = chosen per call
     int fap_direction = 0;             // qv_access_prob with an in-edge CSR: 0 choose per sweep, 1 gather only, 2 scatter only
     uint32_t epoch = 0;
     // pinned staging ring for the per-batch arguments of calls with many batches

@@ -159,6 +159,11 @@ struct BatchArgs {
     uint16_t* seed_flags;           // stage-0 flags
     uint16_t* flags;                // per edge: first occurrence | new node << 1 | next-hop segment size << 2 | col_local written << 15
     uint32_t* partial;              // [kMaxTiles][3] per-tile counts of the stage being run
+    // partitioned dedup (see k_part_dedup); all NULL in the table forms
+    unsigned long long* pmask;      // [tile][partition][first, new][kPWords] occurrence bit masks of the stage being run
+    uint32_t* pcount;               // [tile][partition][first, new] their populations
+    uint32_t* tile_seg;             // [tile] next-hop edges produced by the tile's first occurrences
+    uint16_t* fr_tile;              // per frontier entry: the tile that produced it (fr_seg is then tile-local)
     int64_t* node_off_out; int64_t* edge_off_out; int64_t* frontier_off_out;
     int64_t* n_id_len_out; int64_t* frontier_len_out;      // stand-alone reindex
 };
@@ -178,6 +183,9 @@ struct CallHeader {
     int32_t cumulative;             // hop k expands every node sampled so far, not only F_{k-1}
     int32_t frontier_restart;       // stand-alone reindex: number this stage's frontier from 0
     int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
+    int32_t p_log2;                 // partitioned dedup: log2 of the partitions per batch
+    int32_t p_tiles;                // ... and the tiles its per-tile arrays hold
+    int32_t n_batches;
     int32_t* status;
 };
 
@@ -242,6 +250,68 @@ __global__ void __launch_bounds__(256) k_insert_ids(A c) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Geometry of the partitioned dedup (k_part_dedup / k_part_assign below)
+// ---------------------------------------------------------------------------------------------
+constexpr int kPTile = 4096;                        // positions per tile
+constexpr int kPThreads = 512;                      // threads per workgroup of both kernels
+constexpr int kPKeys = kPTile / kPThreads;          // positions per thread and tile
+constexpr int kPWords = kPTile / 64;                // 64-bit mask words per tile
+constexpr int kPCapLog2 = 12;
+constexpr int kPCap = 1 << kPCapLog2;               // entries of a partition's LDS table
+constexpr uint32_t kPFillMax = kPCap / 8 * 7;       // a table fuller than this splits its partition further
+constexpr int kPMaxTiles = 1024;                    // tiles per stage and batch (larger stages use the table forms)
+constexpr int kPMaxLog2 = 6;                        // at most 64 partitions per batch
+constexpr int kPMaxSplit = 12;                      // a partition is split into at most 2^12 sub-rounds
+constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
+
+// Partitioned form: a frontier entry carries its segment offset relative to the tile that produced
+// it (fr_seg) and that tile's number (fr_tile); the tiles' edge counts (tile_seg) are scanned here,
+// once per workgroup, into LDS.  Also publishes the hop's edge count.  All threads must call.
+__device__ __forceinline__ void seg_base_prologue(const CallHeader& c, const BatchArgs& b, uint32_t* s_segbase,
+                                                  uint32_t* s_wave, bool publish) {
+    SampleMeta* m = b.meta;
+    int64_t plen;
+    if (c.stage == 1) {
+        plen = b.n_seeds;
+    } else {
+        int64_t pe = m->edge_off[c.stage - 1];
+        if (pe > b.edge_cap) pe = b.edge_cap;
+        plen = pe - m->edge_off[c.stage - 2];
+    }
+    if (plen < 0) plen = 0;
+    int n_tiles = (int)((plen + kPTile - 1) / kPTile);
+    if (n_tiles > c.p_tiles) n_tiles = c.p_tiles;                     // <= kPMaxTiles (host check)
+    const int nthr = (int)blockDim.x, tid = (int)threadIdx.x;
+    const int per = (n_tiles + nthr - 1) / nthr;                      // consecutive tiles per thread
+    uint32_t sum = 0;
+    for (int i = 0; i < per; ++i) {
+        const int t = tid * per + i;
+        if (t < n_tiles) sum += b.tile_seg[t];
+    }
+    uint32_t inc = sum;
+    const int lane = tid % kWave, wave = tid / kWave;
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+        const uint32_t x = __shfl_up(inc, o);
+        if (lane >= o) inc += x;
+    }
+    if (lane == kWave - 1) s_wave[wave] = inc;
+    __syncthreads();
+    uint32_t pre = 0, total = 0;
+    for (int w = 0; w < nthr / kWave; ++w) {
+        if (w < wave) pre += s_wave[w];
+        total += s_wave[w];
+    }
+    uint32_t run = pre + inc - sum;
+    for (int i = 0; i < per; ++i) {
+        const int t = tid * per + i;
+        if (t < n_tiles) { s_segbase[t] = run; run += b.tile_seg[t]; }
+    }
+    if (publish && tid == 0) m->edge_off[c.stage] = m->edge_off[c.stage - 1] + (int64_t)total;
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------------------------
 // k_sample: one group of G lanes per frontier node, fanout <= G
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ void emit_edge(const CallHeader& c, const BatchArgs& b, const TableView& t, uint64_t tag,
@@ -278,6 +348,10 @@ __global__ void __launch_bounds__(256) k_sample(A c) {
     const TableView t = table_of(c, b);
     const uint64_t tag = pos_tag(c.epoch, c.stage);
     const uint32_t l = (uint32_t)c.fanout;
+    __shared__ uint32_t s_segbase[kPMaxTiles];
+    __shared__ uint32_t s_wave[256 / kWave];
+    const bool tiled = b.tile_seg != nullptr;
+    if (tiled) seg_base_prologue(c, b, s_segbase, s_wave, blockIdx.x == 0);
     // the loop is uniform over the wave: every lane runs the same number of iterations
     int64_t f0 = (int64_t)blockIdx.x * groups_per_block + (threadIdx.x / kWave) * (kWave / G);
     for (; f0 < F; f0 += stride) {
@@ -290,6 +364,7 @@ __global__ void __launch_bounds__(256) k_sample(A c) {
             rs = b.fr_rs[fbeg + f];
             d = b.fr_deg[fbeg + f];
             off = b.fr_seg[fbeg + f];
+            if (tiled) off += s_segbase[b.fr_tile[fbeg + f]];
             vl = b.fr_lid[fbeg + f];
         }
         const bool draw = d > l;
@@ -324,11 +399,16 @@ __global__ void __launch_bounds__(64) k_sample_wide(A c) {
     const TableView t = table_of(c, b);
     const uint64_t tag = pos_tag(c.epoch, c.stage);
     const uint32_t l = (uint32_t)c.fanout;
+    __shared__ uint32_t s_segbase[kPMaxTiles];
+    __shared__ uint32_t s_wave[1];
+    const bool tiled = b.tile_seg != nullptr;
+    if (tiled) seg_base_prologue(c, b, s_segbase, s_wave, blockIdx.x == 0);
     for (int64_t f = blockIdx.x; f < F; f += gridDim.x) {
         const int32_t v = b.fr_id[fbeg + f];
         const int64_t rs = b.fr_rs[fbeg + f];
         const uint32_t d = b.fr_deg[fbeg + f];
-        const uint32_t off = b.fr_seg[fbeg + f];
+        uint32_t off = b.fr_seg[fbeg + f];
+        if (tiled) off += s_segbase[b.fr_tile[fbeg + f]];
         const int32_t vl = b.fr_lid[fbeg + f];
         const bool draw = d > l;
         const uint32_t mcount = draw ? l : d;
@@ -640,6 +720,465 @@ __global__ void __launch_bounds__(256) k_relabel(A c) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Partitioned dedup: the form qv_sample uses for layer frontiers.
+//
+// The ids of a stage (the seeds, or one hop's sampled neighbours) are split by a hash of the id into
+// P partitions per batch.  One workgroup per (batch, partition) reads the whole stage in position
+// order, tile by tile, keeps only its own ids and finds each one's first position with atomics on
+// a table in LDS; the nodes numbered by earlier stages are loaded into the same table first (from
+// n_id, whose index is the local id), so whether an id is new needs no memory access either.  All
+// random access of the dedup is thereby LDS access: nothing is kept in HBM between stages, and no
+// global atomic is issued per edge.
+//
+// Tiles are processed in order with one barrier each: once every thread has registered tile t,
+// the smallest position of any id that occurs in tiles <= t is final, so tile t's positions can be
+// finished right away:
+//   id numbered earlier            col_local = its local id
+//   first occurrence of a new id   left to k_part_assign, which numbers it
+//   repeat of a new id             col_local = -2 - (first position), resolved by k_relabel_links
+// First occurrences and new nodes are reported as two bit masks per tile and partition (a bit per
+// position; the partitions' masks are disjoint), with their populations, so that k_part_assign can
+// rank them with popcounts.
+//
+// A table that fills beyond kPFillMax (more distinct ids in the partition than LDS holds) makes
+// the workgroup start over with its partition split into 2, 4, ... sub-rounds by further hash
+// bits, one table fill per sub-round; results do not depend on P or on the split.
+// Workgroups are numbered so that the partitions of one batch land on one XCD (workgroup w runs on
+// XCD w mod 8) and share its L2 for the stage's ids.
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t fmix32(uint32_t h) {
+    h ^= h >> 16; h *= 0x85EBCA6Bu; h ^= h >> 13; h *= 0xC2B2AE35u; h ^= h >> 16;
+    return h;
+}
+__device__ __forceinline__ uint32_t part_of(uint32_t key, int p_log2) {
+    return p_log2 ? (key * 0x9E3779B1u) >> (32 - p_log2) : 0u;
+}
+
+// entry of `key` in the LDS table, claiming a free one if absent; -1 when the table is full
+__device__ __forceinline__ int lds_insert(uint32_t* t_key, uint32_t key, uint32_t start, uint32_t* fill) {
+    uint32_t s = start;
+    for (int probes = 0; probes < kPCap; ++probes) {
+        uint32_t cur = t_key[s];
+        if (cur == kEmptyKey) {
+            cur = atomicCAS(&t_key[s], kEmptyKey, key);
+            if (cur == kEmptyKey) { atomicAdd(fill, 1u); return (int)s; }
+        }
+        if (cur == key) return (int)s;
+        s = (s + 1) & (kPCap - 1);
+    }
+    return -1;
+}
+
+__device__ __forceinline__ uint32_t pick8(const uint32_t (&v)[kPKeys], int i) {
+    uint32_t r = v[0];
+#pragma unroll
+    for (int k = 1; k < kPKeys; ++k) r = (i == k) ? v[k] : r;
+    return r;
+}
+
+// [begin, end) of the stage's positions, its ids and the number of nodes numbered before it
+struct PartStage {
+    int64_t begin, end, known;
+    const int32_t* ids;
+};
+__device__ __forceinline__ PartStage part_stage(const CallHeader& c, const BatchArgs& b) {
+    PartStage v;
+    const SampleMeta* m = b.meta;
+    if (c.stage == 0) {                 // the size block is initialised by this very stage
+        v.begin = 0; v.end = b.n_seeds; v.known = 0; v.ids = b.seeds;
+    } else {
+        v.begin = m->edge_off[c.stage - 1]; v.end = m->edge_off[c.stage];
+        if (v.end > b.edge_cap) v.end = b.edge_cap;
+        v.known = m->node_off[c.stage];
+        if (v.known > b.n_id_cap) v.known = b.n_id_cap;
+        v.ids = b.nbr;
+    }
+    if (v.end < v.begin) v.end = v.begin;
+    const int64_t room = (int64_t)c.p_tiles * kPTile;          // what the per-tile arrays were sized for
+    if (v.end - v.begin > room) v.end = v.begin + room;
+    return v;
+}
+
+template <typename A>
+__global__ void __launch_bounds__(kPThreads) k_part_dedup(A c) {
+    __shared__ uint32_t t_key[kPCap];
+    __shared__ uint32_t t_min[kPCap];
+    __shared__ int32_t t_lid[kPCap];
+    __shared__ unsigned long long s_mask[2][2][kPWords];        // [tile parity][first, new][word]
+    __shared__ uint32_t s_cnt[2][2];                            // [tile parity][first, new]
+    // Entries claimed (an insertion that found the table full adds kPCap, so one test covers both):
+    // s_fill0 by the known nodes, s_fillp[t % 3] by tile t.  A counter is final at the barrier that
+    // ends its phase and is not written again for two tiles, so every thread adds the same values
+    // into its own running total and all threads take the same decision without a second barrier.
+    __shared__ uint32_t s_fill0, s_fillp[3];
+
+    const int p_log2 = c.p_log2, P = 1 << p_log2;
+    const int q = (int)(blockIdx.x >> 3);
+    const int batch = (int)(blockIdx.x & 7u) + 8 * (q >> p_log2);
+    const uint32_t part = (uint32_t)(q & (P - 1));
+    if (batch >= c.n_batches) return;
+    const BatchArgs& b = c.batch(batch);
+    const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const PartStage v = part_stage(c, b);
+    if (c.stage == 0 && part == 0 && tid == 0) {
+        SampleMeta* m = b.meta;
+        for (int i = 0; i < QV_MAX_HOPS + 2; ++i) { m->node_off[i] = 0; m->frontier_off[i] = 0; }
+        for (int i = 0; i < QV_MAX_HOPS + 1; ++i) m->edge_off[i] = 0;
+        m->stage_range[0] = 0; m->stage_range[1] = b.n_seeds;
+    }
+    const int64_t len = v.end - v.begin;
+    const int n_tiles = (int)((len + kPTile - 1) / kPTile);
+    int32_t* col_local = c.stage > 0 ? b.col_local : nullptr;
+
+    for (int split = 0;; ++split) {
+        const uint32_t n_rounds = 1u << split;
+        bool failed = false;
+        for (uint32_t r = 0; r < n_rounds && !failed; ++r) {
+            __syncthreads();                                    // the table and the flags are still being read
+            for (int i = tid; i < kPCap; i += kPThreads) { t_key[i] = kEmptyKey; t_min[i] = 0xFFFFFFFFu; t_lid[i] = -1; }
+            if (tid == 0) {
+                s_fill0 = 0; s_fillp[0] = 0; s_fillp[1] = 0; s_fillp[2] = 0;
+                s_cnt[0][0] = 0; s_cnt[0][1] = 0; s_cnt[1][0] = 0; s_cnt[1][1] = 0;
+            }
+            __syncthreads();
+            // nodes numbered by earlier stages: local id = index in n_id
+            for (int64_t u = tid; u < v.known; u += kPThreads) {
+                const uint32_t key = (uint32_t)b.n_id[u];
+                if (part_of(key, p_log2) != part) continue;
+                const uint32_t h = fmix32(key);
+                if (split && (h >> (32 - split)) != r) continue;
+                const int s = lds_insert(t_key, key, h & (kPCap - 1), &s_fill0);
+                if (s < 0) atomicAdd(&s_fill0, (uint32_t)kPCap);
+                else t_lid[s] = (int32_t)u;
+            }
+            __syncthreads();
+            uint32_t fill = s_fill0;
+            if (fill > kPFillMax) { failed = true; break; }
+
+            uint32_t nxt[kPKeys];
+#pragma unroll
+            for (int i = 0; i < kPKeys; ++i) {
+                const int64_t rel = (int64_t)i * kPThreads + tid;
+                nxt[i] = rel < len ? (uint32_t)v.ids[v.begin + rel] : kEmptyKey;
+            }
+            for (int t = 0; t < n_tiles; ++t) {
+                const int64_t rel0 = (int64_t)t * kPTile;
+                uint32_t cur[kPKeys];
+#pragma unroll
+                for (int i = 0; i < kPKeys; ++i) cur[i] = nxt[i];
+                if (t + 1 < n_tiles) {                          // next tile's ids, requested a tile ahead
+#pragma unroll
+                    for (int i = 0; i < kPKeys; ++i) {
+                        const int64_t rel = rel0 + kPTile + (int64_t)i * kPThreads + tid;
+                        nxt[i] = rel < len ? (uint32_t)v.ids[v.begin + rel] : kEmptyKey;
+                    }
+                }
+                // which of my positions belong to this partition (and sub-round); ids out of range
+                // are finished here: local id -1, never a first occurrence
+                uint32_t mine = 0;
+#pragma unroll
+                for (int i = 0; i < kPKeys; ++i) {
+                    const int64_t rel = rel0 + (int64_t)i * kPThreads + tid;
+                    const uint32_t key = cur[i];
+                    if (rel >= len || part_of(key, p_log2) != part) continue;
+                    if ((int32_t)key < 0 || (c.n_nodes >= 0 && (int64_t)key >= c.n_nodes)) {
+                        if (r == 0) {
+                            atomicOr(c.status, kStatRange);
+                            if (col_local) col_local[v.begin + rel] = -1;
+                        }
+                        continue;
+                    }
+                    if (split && (fmix32(key) >> (32 - split)) != r) continue;
+                    mine |= 1u << i;
+                }
+                // register them: entry (claimed if absent), smallest position
+                unsigned long long slots = 0;                  // 12 bits per position of mine, in bit order
+                {
+                    uint32_t todo = mine;
+                    int j = 0;
+                    while (__any(todo != 0)) {
+                        if (todo) {
+                            const int i = __ffs(todo) - 1;
+                            todo &= todo - 1;
+                            const uint32_t key = pick8(cur, i);
+                            const uint32_t pos = (uint32_t)(v.begin + rel0 + (int64_t)i * kPThreads + tid);
+                            const int s = lds_insert(t_key, key, fmix32(key) & (kPCap - 1), &s_fillp[t % 3]);
+                            if (s < 0) {
+                                atomicAdd(&s_fillp[t % 3], (uint32_t)kPCap);
+                            } else {
+                                atomicMin(&t_min[s], pos);
+                                if (j < 5) slots |= (unsigned long long)s << (12 * j);
+                            }
+                            ++j;
+                        }
+                    }
+                }
+                __syncthreads();
+                fill += s_fillp[t % 3];
+                if (fill > kPFillMax) { failed = true; break; }
+                if (tid == 0) s_fillp[(t + 2) % 3] = 0;         // tile t-1's counter: read by all, next used by tile t+2
+                // the previous tile's masks and counts are complete: publish them
+                if (t > 0) {
+                    const int pt = t - 1, pb = pt & 1;
+                    if (tid < 2 * kPWords) {
+                        unsigned long long* dst = b.pmask + (((size_t)pt * P + part) * 2) * kPWords + tid;
+                        const unsigned long long w = s_mask[pb][tid / kPWords][tid % kPWords];
+                        *dst = r == 0 ? w : (*dst | w);
+                    }
+                    if (tid < 2) {
+                        uint32_t* dst = b.pcount + ((size_t)pt * P + part) * 2 + tid;
+                        *dst = r == 0 ? s_cnt[pb][tid] : *dst + s_cnt[pb][tid];
+                        s_cnt[pb][tid] = 0;
+                    }
+                }
+                // finish this tile's positions
+                uint32_t fbits = 0, nbits = 0;
+                {
+                    uint32_t todo = mine;
+                    int j = 0;
+                    while (__any(todo != 0)) {
+                        if (todo) {
+                            const int i = __ffs(todo) - 1;
+                            todo &= todo - 1;
+                            const uint32_t key = pick8(cur, i);
+                            const uint32_t pos = (uint32_t)(v.begin + rel0 + (int64_t)i * kPThreads + tid);
+                            int s;
+                            if (j < 5) {
+                                s = (int)((slots >> (12 * j)) & 0xFFFu);
+                            } else {                            // found again by probing (the id is in the table)
+                                uint32_t x = fmix32(key) & (kPCap - 1);
+                                while (t_key[x] != key) x = (x + 1) & (kPCap - 1);
+                                s = (int)x;
+                            }
+                            ++j;
+                            const uint32_t mp = t_min[s];
+                            const int32_t lid = t_lid[s];
+                            const uint32_t first = mp == pos ? 1u : 0u;
+                            const uint32_t isnew = (first && lid < 0) ? 1u : 0u;
+                            if (col_local) {
+                                if (lid >= 0) col_local[pos] = lid;
+                                else if (!first) col_local[pos] = -2 - (int32_t)mp;
+                            }
+                            fbits |= first << i;
+                            nbits |= isnew << i;
+                        }
+                    }
+                }
+                uint32_t cf = 0, cn = 0;
+#pragma unroll
+                for (int i = 0; i < kPKeys; ++i) {
+                    const unsigned long long bf = __ballot((fbits >> i) & 1u), bn = __ballot((nbits >> i) & 1u);
+                    if (lane == 0) {
+                        s_mask[t & 1][0][i * (kPThreads / kWave) + wave] = bf;
+                        s_mask[t & 1][1][i * (kPThreads / kWave) + wave] = bn;
+                        cf += (uint32_t)__popcll(bf); cn += (uint32_t)__popcll(bn);
+                    }
+                }
+                if (lane == 0 && (cf | cn)) { atomicAdd(&s_cnt[t & 1][0], cf); atomicAdd(&s_cnt[t & 1][1], cn); }
+            }
+            if (failed) break;
+            __syncthreads();
+            if (n_tiles > 0) {                                  // the last tile
+                const int pt = n_tiles - 1, pb = pt & 1;
+                if (tid < 2 * kPWords) {
+                    unsigned long long* dst = b.pmask + (((size_t)pt * P + part) * 2) * kPWords + tid;
+                    const unsigned long long w = s_mask[pb][tid / kPWords][tid % kPWords];
+                    *dst = r == 0 ? w : (*dst | w);
+                }
+                if (tid < 2) {
+                    uint32_t* dst = b.pcount + ((size_t)pt * P + part) * 2 + tid;
+                    *dst = r == 0 ? s_cnt[pb][tid] : *dst + s_cnt[pb][tid];
+                }
+            }
+        }
+        if (!failed) break;
+        if (split == kPMaxSplit) {                              // 2^12 sub-rounds were not enough: give up loudly
+            if (tid == 0) atomicOr(c.status, kStatCapacity);
+            break;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// k_part_assign: one workgroup per tile.  ORs the partitions' masks, ranks the first occurrences
+// and the new nodes of the tile by popcount (the counts of earlier tiles give the base), and
+// writes what k_assign writes in the table forms: n_id and local ids of the new nodes, the next
+// hop's frontier entries (row extent read here; segment offset relative to the tile, the tile's
+// total in tile_seg), the caller's frontier array, the sizes.
+// ---------------------------------------------------------------------------------------------
+template <typename RP, typename A>
+__global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
+    __shared__ unsigned long long m_first[kPWords], m_new[kPWords];
+    __shared__ uint32_t pre_first[kPWords], pre_new[kPWords];
+    __shared__ uint32_t seg_tot[kPWords], seg_pre[kPWords];
+    __shared__ uint32_t red[kPThreads / kWave][2];
+    __shared__ uint32_t s_tot[3];
+
+    const BatchArgs& b = c.batch(blockIdx.y);
+    const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
+    SampleMeta* m = b.meta;
+    const int P = 1 << c.p_log2;
+    const int t = (int)blockIdx.x;
+    const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const PartStage v = part_stage(c, b);
+    const int64_t len = v.end - v.begin;
+    const int64_t rel0 = (int64_t)t * kPTile;
+    if (rel0 >= len && !(len == 0 && t == 0)) return;
+    const int64_t node_base = m->node_off[c.stage];
+    const int64_t fr_base = m->frontier_off[c.stage];
+    const bool have_tile = rel0 < len;
+
+    // populations of the earlier tiles
+    uint32_t bf = 0, bn = 0;
+    for (int i = tid; i < t * P; i += kPThreads) { bf += b.pcount[2 * (size_t)i]; bn += b.pcount[2 * (size_t)i + 1]; }
+#pragma unroll
+    for (int o = kWave / 2; o > 0; o >>= 1) { bf += __shfl_down(bf, o); bn += __shfl_down(bn, o); }
+    if (lane == 0) { red[wave][0] = bf; red[wave][1] = bn; }
+    if (tid < kPWords) { m_first[tid] = 0; m_new[tid] = 0; }
+    __syncthreads();
+    uint32_t base_first = 0, base_new = 0;
+    for (int w = 0; w < kPThreads / kWave; ++w) { base_first += red[w][0]; base_new += red[w][1]; }
+    // this tile's masks: OR over the partitions
+    if (have_tile) {
+        const int which = (tid / kPWords) & 1, w = tid % kPWords, j0 = tid / (2 * kPWords);
+        unsigned long long acc = 0;
+        for (int j = j0; j < P; j += kPThreads / (2 * kPWords))
+            acc |= b.pmask[(((size_t)t * P + j) * 2 + which) * kPWords + w];
+        if (acc) atomicOr(which ? &m_new[w] : &m_first[w], acc);
+    }
+    __syncthreads();
+    if (wave < 2) {                                             // exclusive popcount prefixes over the 64 words
+        const uint32_t x = (uint32_t)__popcll(wave ? m_new[lane] : m_first[lane]);
+        uint32_t inc = x;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t y = __shfl_up(inc, o);
+            if (lane >= o) inc += y;
+        }
+        (wave ? pre_new : pre_first)[lane] = inc - x;
+        if (lane == kWave - 1) s_tot[wave] = inc;
+    }
+    __syncthreads();
+
+    // my positions: what a first occurrence needs is requested for all of them before any is used
+    const unsigned long long below = (1ull << lane) - 1ull;
+    int32_t id[kPKeys], lid[kPKeys];
+    int64_t rs[kPKeys];
+    uint32_t deg[kPKeys], incl[kPKeys], flags = 0;
+#pragma unroll
+    for (int i = 0; i < kPKeys; ++i) {
+        const int word = i * (kPThreads / kWave) + wave;
+        const int64_t rel = rel0 + (int64_t)i * kPThreads + tid;
+        const uint32_t first = (rel < len) ? (uint32_t)((m_first[word] >> lane) & 1ull) : 0u;
+        const uint32_t isnew = first ? (uint32_t)((m_new[word] >> lane) & 1ull) : 0u;
+        flags |= (first << i) | (isnew << (8 + i));
+        id[i] = 0; lid[i] = -1; rs[i] = 0; deg[i] = 0;
+        if (first) {
+            id[i] = v.ids[v.begin + rel];
+            if (!isnew && c.stage > 0) lid[i] = b.col_local[v.begin + rel];
+        }
+    }
+    if (c.next_fanout > 0) {
+#pragma unroll
+        for (int i = 0; i < kPKeys; ++i) {
+            if ((flags >> i) & 1u) {
+                rs[i] = (int64_t)rowptr[id[i]];
+                deg[i] = (uint32_t)((int64_t)rowptr[id[i] + 1] - rs[i]);
+            }
+        }
+    }
+    // next-hop segment sizes, scanned in position order: within the wave here, across (slab, wave) below
+#pragma unroll
+    for (int i = 0; i < kPKeys; ++i) {
+        uint32_t seg = 0;
+        if (((flags >> i) & 1u) && c.next_fanout > 0) seg = deg[i] < (uint32_t)c.next_fanout ? deg[i] : (uint32_t)c.next_fanout;
+        uint32_t inc = seg;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t y = __shfl_up(inc, o);
+            if (lane >= o) inc += y;
+        }
+        incl[i] = inc - seg;                                    // exclusive within the wave
+        if (lane == kWave - 1) seg_tot[i * (kPThreads / kWave) + wave] = inc;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t x = seg_tot[lane];
+        uint32_t inc = x;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t y = __shfl_up(inc, o);
+            if (lane >= o) inc += y;
+        }
+        seg_pre[lane] = inc - x;
+        if (lane == kWave - 1) s_tot[2] = inc;
+    }
+    __syncthreads();
+    const uint32_t tot_first = have_tile ? s_tot[0] : 0u, tot_new = have_tile ? s_tot[1] : 0u;
+    const int64_t fr_user_base = c.frontier_restart ? 0 : fr_base;
+#pragma unroll
+    for (int i = 0; i < kPKeys; ++i) {
+        if (!((flags >> i) & 1u)) continue;
+        const int word = i * (kPThreads / kWave) + wave;
+        const int64_t pos = v.begin + rel0 + (int64_t)i * kPThreads + tid;
+        const bool isnew = (flags >> (8 + i)) & 1u;
+        const int64_t j = (int64_t)base_first + pre_first[word] + (uint32_t)__popcll(m_first[word] & below);
+        int32_t l = lid[i];
+        if (isnew) {
+            const int64_t u = node_base + base_new + pre_new[word] + (uint32_t)__popcll(m_new[word] & below);
+            l = (int32_t)u;
+            if (u < b.n_id_cap) b.n_id[u] = id[i];
+            else atomicOr(c.status, kStatCapacity);
+            if (c.stage > 0) b.col_local[pos] = l;
+        }
+        if (c.next_fanout > 0) {
+            if (fr_base + j < b.fr_cap) {
+                b.fr_id[fr_base + j] = id[i];
+                b.fr_lid[fr_base + j] = l;
+                b.fr_rs[fr_base + j] = rs[i];
+                b.fr_deg[fr_base + j] = deg[i];
+                b.fr_seg[fr_base + j] = seg_pre[word] + incl[i];
+                b.fr_tile[fr_base + j] = (uint16_t)t;
+            } else {
+                atomicOr(c.status, kStatCapacity);
+            }
+        }
+        if (b.fr_user) {
+            if (fr_user_base + j < b.fr_user_cap) b.fr_user[fr_user_base + j] = id[i];
+            else atomicOr(c.status, kStatCapacity);
+        }
+    }
+    if (tid == 0) {
+        if (have_tile) b.tile_seg[t] = s_tot[2];
+        if (rel0 + kPTile >= len) {                             // the stage's last tile
+            m->node_off[c.stage + 1] = node_base + base_new + tot_new;
+            m->frontier_off[c.stage + 1] = fr_base + base_first + tot_first;
+        }
+    }
+}
+
+// k_relabel_links: repeats of a node that was new in their hop point at its first position; follow
+// the link (that position holds the local id by now).  Also exports the sizes.
+template <typename A>
+__global__ void __launch_bounds__(256) k_relabel_links(A c) {
+    const BatchArgs& b = c.batch(blockIdx.y);
+    const SampleMeta* m = b.meta;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    int64_t end = m->edge_off[c.stage];                // c.stage = last stage
+    if (end > b.edge_cap) end = b.edge_cap;
+    for (int64_t p = tid; p < end; p += stride) {
+        const int32_t x = b.col_local[p];
+        if (x <= -2) b.col_local[p] = b.col_local[-2 - (int64_t)x];
+    }
+    if (tid == 0) {
+        if (b.node_off_out) for (int i = 0; i < c.n_hops + 2; ++i) b.node_off_out[i] = m->node_off[i];
+        if (b.edge_off_out) for (int i = 0; i < c.n_hops + 1; ++i) b.edge_off_out[i] = m->edge_off[i];
+        if (b.frontier_off_out) for (int i = 0; i < c.n_hops + 2; ++i) b.frontier_off_out[i] = m->frontier_off[i];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // stand-alone hop: row extents and segment offsets of a caller-given frontier (two-kernel scan)
 // ---------------------------------------------------------------------------------------------
 constexpr int kMaxDegTiles = 1024;
@@ -790,6 +1329,9 @@ static bool use_direct(const qv_ctx* ctx, int64_t n_nodes, int n_tables) {
 
 struct Layout {                     // per-batch scratch sizes (elements)
     int64_t stage0, edges, frontier;
+    bool part = false;              // partitioned dedup: no table, no per-edge flags
+    int p_log2 = 0;                 // log2 of the partitions per batch
+    int64_t p_tiles = 0;            // tiles of the largest stage
 };
 
 static void tile_shape(int64_t max_items, int* ipt, int* tiles) {
@@ -803,6 +1345,13 @@ static void tile_shape(int64_t max_items, int* ipt, int* tiles) {
 static size_t per_batch_bytes(const Layout& L) {
     size_t t = 0;
     t += align_up(sizeof(SampleMeta));
+    if (L.part) {
+        const size_t cells = (size_t)L.p_tiles << L.p_log2;                 // (tile, partition) pairs
+        t += align_up((size_t)L.edges * 4);                                 // nbr
+        t += 4 * align_up((size_t)L.frontier * 4) + align_up((size_t)L.frontier * 8) + align_up((size_t)L.frontier * 2);
+        t += align_up(cells * 2 * kPWords * 8) + align_up(cells * 2 * 4) + align_up((size_t)L.p_tiles * 4);
+        return t + 2048;
+    }
     t += align_up((size_t)L.stage0 * 4) + align_up((size_t)L.stage0 * 2);   // seed_slot, seed_flags
     t += 2 * align_up((size_t)L.edges * 4) + align_up((size_t)L.edges * 2); // slot_of, nbr, flags
     t += 4 * align_up((size_t)L.frontier * 4) + align_up((size_t)L.frontier * 8);   // fr_id, fr_lid, fr_deg, fr_seg, fr_rs
@@ -812,6 +1361,24 @@ static size_t per_batch_bytes(const Layout& L) {
 
 static bool carve(qv_ctx* ctx, const Layout& L, BatchArgs* b) {
     b->meta = (SampleMeta*)arena_take(ctx, sizeof(SampleMeta));
+    if (L.part) {
+        const size_t cells = (size_t)L.p_tiles << L.p_log2;
+        b->seed_slot = nullptr; b->seed_flags = nullptr; b->slot_of = nullptr; b->flags = nullptr; b->partial = nullptr;
+        b->nbr = (int32_t*)arena_take(ctx, (size_t)L.edges * 4);
+        b->fr_id = (int32_t*)arena_take(ctx, (size_t)L.frontier * 4);
+        b->fr_lid = (int32_t*)arena_take(ctx, (size_t)L.frontier * 4);
+        b->fr_rs = (int64_t*)arena_take(ctx, (size_t)L.frontier * 8);
+        b->fr_deg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
+        b->fr_seg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
+        b->fr_tile = (uint16_t*)arena_take(ctx, (size_t)L.frontier * 2);
+        b->pmask = (unsigned long long*)arena_take(ctx, cells * 2 * kPWords * 8);
+        b->pcount = (uint32_t*)arena_take(ctx, cells * 2 * 4);
+        b->tile_seg = (uint32_t*)arena_take(ctx, (size_t)L.p_tiles * 4);
+        b->fr_cap = L.frontier;
+        return b->meta && b->nbr && b->fr_id && b->fr_lid && b->fr_rs && b->fr_deg && b->fr_seg && b->fr_tile && b->pmask &&
+               b->pcount && b->tile_seg;
+    }
+    b->pmask = nullptr; b->pcount = nullptr; b->tile_seg = nullptr; b->fr_tile = nullptr;
     b->seed_slot = (uint32_t*)arena_take(ctx, (size_t)L.stage0 * 4);
     b->seed_flags = (uint16_t*)arena_take(ctx, (size_t)L.stage0 * 2);
     b->slot_of = (uint32_t*)arena_take(ctx, (size_t)L.edges * 4);
@@ -909,6 +1476,49 @@ static qv_status launch_sample(qv_ctx* ctx, const CallArgs& c, int64_t max_front
     return QV_OK;
 }
 
+// Sizes and dedup form of a qv_sample / qv_sample_many call.
+// The partitioned form serves layer frontiers whose stages fit kPMaxTiles tiles; the cumulative
+// variant, larger stages and a context told to use tables take the table forms.
+static qv_status plan_sample(qv_ctx* ctx, int64_t max_seeds, const int32_t* fanouts, int n_hops, int64_t n_nodes,
+                             bool cumulative, Bounds* bd, Layout* L) {
+    qv_status rc = compute_bounds(ctx, max_seeds, fanouts, n_hops, n_nodes, cumulative, bd);
+    if (rc != QV_OK) return rc;
+    L->stage0 = max_seeds; L->edges = bd->edges;
+    L->frontier = cumulative ? (bd->nodes > 0 ? bd->nodes : 1) : bd->frontier;   // cumulative: one entry per node, at its local id
+    const int64_t max_stage = (int64_t)kPTile * kPMaxTiles;
+    int64_t largest = max_seeds;
+    for (int k = 1; k <= n_hops; ++k) largest = bd->hop_edges[k] > largest ? bd->hop_edges[k] : largest;
+    L->part = ctx->dedup_form == QV_DEDUP_PARTITIONED && !cumulative && largest <= max_stage;   // AUTO: tables, until the partitioned form is the faster one
+    if (L->part) {
+        L->p_tiles = (largest + kPTile - 1) / kPTile;
+        if (L->p_tiles < 1) L->p_tiles = 1;
+        if (ctx->part_log2 >= 0) {
+            L->p_log2 = ctx->part_log2;
+        } else {
+            // enough partitions that a quarter of the a-priori node bound half-fills the tables (sampled
+            // sub-graphs of skewed graphs repeat most of their nodes); a fuller table costs sub-rounds, not results
+            int64_t est = bd->nodes / 4;
+            int lg = 3;
+            while (lg < kPMaxLog2 && ((int64_t)(kPCap / 2) << lg) < est) ++lg;
+            L->p_log2 = lg;
+        }
+    }
+    return QV_OK;
+}
+
+static qv_status launch_part_dedup(qv_ctx* ctx, CallArgs& c, int rowptr_bits, int64_t max_items, int n_batches) {
+    const int P = 1 << c.p_log2;
+    const unsigned wgs = 8u * (unsigned)((n_batches + 7) / 8) * (unsigned)P;    // (XCD, batch within XCD, partition)
+    QV_LAUNCH_A(ctx, c, n_batches, dim3(wgs), dim3(kPThreads), k_part_dedup);
+    int64_t tiles = (max_items + kPTile - 1) / kPTile;
+    if (tiles < 1) tiles = 1;
+    dim3 grid((unsigned)tiles, (unsigned)n_batches);
+    if (rowptr_bits == 32) QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kPThreads), k_part_assign, int32_t);
+    else QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kPThreads), k_part_assign, int64_t);
+    QV_LAUNCH_CHECK(ctx, "k_part_dedup / k_part_assign");
+    return QV_OK;
+}
+
 static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, const int32_t* const* seeds,
                              const int64_t* n_seeds, const int32_t* fanouts, int n_hops, const uint64_t* rng_seeds,
                              uint32_t flags, const qv_sample_out* outs, const char* who) {
@@ -926,28 +1536,30 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
         if (n_seeds[i] > max_seeds) max_seeds = n_seeds[i];
     }
     Bounds bd;
-    qv_status rc = compute_bounds(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, cumulative, &bd);
-    if (rc != QV_OK) return rc;
     Layout L;
-    L.stage0 = max_seeds; L.edges = bd.edges;
-    L.frontier = cumulative ? (bd.nodes > 0 ? bd.nodes : 1) : bd.frontier;   // cumulative: one entry per node, at its local id
+    qv_status rc = plan_sample(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, cumulative, &bd, &L);
+    if (rc != QV_OK) return rc;
     rc = arena_begin(ctx, per_batch_bytes(L) * n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch));
     if (rc != QV_OK) return rc;
     CallArgs c{};
     c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
-    table_geometry(bd.nodes, &c.mask, &c.shift);
-    c.direct = use_direct(ctx, csr->n_nodes, n_batches) ? 1 : 0;
-    const size_t table_slots = c.direct ? (size_t)csr->n_nodes : (size_t)c.mask + 1;
-    rc = table_prepare(ctx, n_batches, table_slots, !c.direct);
-    if (rc != QV_OK) return rc;
+    size_t table_slots = 0;
+    if (!L.part) {
+        table_geometry(bd.nodes, &c.mask, &c.shift);
+        c.direct = use_direct(ctx, csr->n_nodes, n_batches) ? 1 : 0;
+        table_slots = c.direct ? (size_t)csr->n_nodes : (size_t)c.mask + 1;
+        rc = table_prepare(ctx, n_batches, table_slots, !c.direct);
+        if (rc != QV_OK) return rc;
+    }
     c.epoch = ctx->epoch; c.n_hops = n_hops; c.status = ctx->d_status; c.cumulative = cumulative ? 1 : 0;
+    c.p_log2 = L.p_log2; c.p_tiles = (int32_t)L.p_tiles; c.n_batches = n_batches;
     for (int i = 0; i < n_batches; ++i) {
         BatchArgs& b = c.b[i];
         if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "%s: scratch arena too small (internal sizing error)", who);
         const qv_sample_out& o = outs[i];
         b.seeds = seeds[i]; b.n_seeds = n_seeds[i]; b.rng_seed = rng_seeds[i];
-        b.keyw = c.direct ? nullptr : ctx->table_keyw + (size_t)i * table_slots;
-        b.slots = ctx->table_slots + (size_t)i * table_slots;
+        b.keyw = (L.part || c.direct) ? nullptr : ctx->table_keyw + (size_t)i * table_slots;
+        b.slots = L.part ? nullptr : ctx->table_slots + (size_t)i * table_slots;
         if (o.nbr_global) b.nbr = o.nbr_global;
         b.row_local = o.row_local; b.col_local = o.col_local;
         b.edge_cap = bd.edges < o.edge_cap ? bd.edges : o.edge_cap;
@@ -959,6 +1571,24 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     if (n_batches > kInlineBatch) {
         rc = upload_batches(ctx, &c, n_batches);
         if (rc != QV_OK) return rc;
+    }
+    if (L.part) {
+        // partitioned form: per stage k_part_dedup + k_part_assign; k_sample only writes the edges
+        c.stage = 0; c.next_fanout = fanouts[0];
+        rc = launch_part_dedup(ctx, c, csr->rowptr_bits, max_seeds, n_batches);
+        if (rc != QV_OK) return rc;
+        for (int k = 1; k <= n_hops; ++k) {
+            c.stage = k; c.hop = k; c.fanout = fanouts[k - 1]; c.next_fanout = k < n_hops ? fanouts[k] : 0;
+            rc = launch_sample(ctx, c, bd.hop_front[k - 1], n_batches);
+            if (rc != QV_OK) return rc;
+            rc = launch_part_dedup(ctx, c, csr->rowptr_bits, bd.hop_edges[k], n_batches);
+            if (rc != QV_OK) return rc;
+        }
+        c.stage = n_hops;
+        dim3 grid((unsigned)grid_for(bd.edges, 256 * 4, ctx->n_cu * 4), (unsigned)n_batches);
+        QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(256), k_relabel_links);
+        QV_LAUNCH_CHECK(ctx, "k_relabel_links");
+        return QV_OK;
     }
     // stage 0: the seeds
     c.stage = 0; c.next_fanout = fanouts[0];
@@ -1101,15 +1731,15 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, i
     if (n_batches < 1 || n_batches > kMaxBatch) return fail(ctx, QV_EINVAL, "qv_ctx_reserve: n_batches %d outside [1, %d]", n_batches, kMaxBatch);
     const bool cumulative = (flags & QV_SAMPLE_CUMULATIVE) != 0;
     Bounds bd;
-    qv_status rc = compute_bounds(ctx, n_seeds, fanouts, n_hops, n_nodes, cumulative, &bd);
-    if (rc != QV_OK) return rc;
     Layout L;
-    L.stage0 = n_seeds; L.edges = bd.edges; L.frontier = cumulative ? (bd.nodes > 0 ? bd.nodes : 1) : bd.frontier;
+    qv_status rc = plan_sample(ctx, n_seeds, fanouts, n_hops, n_nodes, cumulative, &bd, &L);
+    if (rc != QV_OK) return rc;
     const size_t want = per_batch_bytes(L) * (size_t)n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch);
     if (want > ctx->arena_bytes) {
         rc = arena_begin(ctx, want);
         if (rc != QV_OK) return rc;
     }
+    if (L.part) return QV_OK;                       // the partitioned form keeps nothing in HBM between calls
     uint32_t mask; int shift;
     table_geometry(bd.nodes, &mask, &shift);
     const bool direct = use_direct(ctx, n_nodes, n_batches);

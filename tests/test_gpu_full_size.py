@@ -116,10 +116,15 @@ def test_dense_social_full(qv, ctx):
     feat = qv.Features(ctx, t_dev, own_copy=True)               # 2,408-byte rows at a 2,432-byte stride
     assert feat.row_stride == 2432
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(3), table=table)
-    ctx.set_table_budget(64 << 30)                              # as the bench: all 32 tables addressed directly
+    ctx.set_dedup(2)                                            # partitioned dedup
+    check_batches(qv, ctx, w, rowptr, col, g, feat, range(4, 6))
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)                 # as the bench: 32 batches
+    ctx.set_dedup(1)                                            # the table forms, kept for cumulative frontiers and huge stages
+    ctx.set_table_budget(64 << 30)                              # all 32 tables addressed directly
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)
     ctx.set_table_budget(16 << 30)
-    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # default budget (hashed tables on the citation graph), arguments uploaded
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # hashed tables on the citation graph, arguments uploaded
+    ctx.set_dedup(0)
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()
 
@@ -171,9 +176,14 @@ def test_citation_full(qv, ctx):
     assert rowptr.dtype == np.int64 and len(col) > 1_590_000_000
     feat = qv.Features(ctx, qvgen.features_device(w.seed, w.n, w.dim, torch.float16))
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(4))
-    ctx.set_table_budget(64 << 30)                              # as the bench: all 32 tables addressed directly
+    ctx.set_dedup(2)                                            # partitioned dedup
+    check_batches(qv, ctx, w, rowptr, col, g, feat, range(4, 6))
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)                 # as the bench: 32 batches
+    ctx.set_dedup(1)                                            # the table forms, kept for cumulative frontiers and huge stages
+    ctx.set_table_budget(64 << 30)                              # all 32 tables addressed directly
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)
     ctx.set_table_budget(16 << 30)
-    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # default budget (hashed tables on the citation graph), arguments uploaded
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # hashed tables on the citation graph, arguments uploaded
+    ctx.set_dedup(0)
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()

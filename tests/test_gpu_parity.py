@@ -25,13 +25,29 @@ def qv():
     return m
 
 
-@pytest.fixture(scope="module", params=["direct", "hashed"])
+DEDUP_FORMS = {
+    # name: (form, partitions_log2, table budget)
+    "direct": (1, -1, None),         # table addressed by node id
+    "hashed": (1, -1, 0),            # open-addressing hash table
+    "part": (2, -1, None),           # partitioned (LDS) dedup, partitions chosen per call
+    "part1": (2, 0, None),           # one partition: larger cases overflow its LDS table and split into sub-rounds
+    "part64": (2, 6, None),          # the most partitions
+}
+
+
+def apply_form(c, name):
+    form, p_log2, budget = DEDUP_FORMS[name]
+    c.set_dedup(form, p_log2)
+    if budget is not None:
+        c.set_table_budget(budget)
+    c._form = name
+
+
+@pytest.fixture(scope="module", params=list(DEDUP_FORMS))
 def ctx(qv, request):
-    """Every test runs with both forms of the dedup table (addressed by node id / open-addressing hash)."""
+    """Every test runs with every dedup form: the two table forms and the partitioned form at three partition counts."""
     c = qv.Context(0)
-    if request.param == "hashed":
-        c.set_table_budget(0)
-        c._budget = 0
+    apply_form(c, request.param)
     yield c
     c.close()
 
@@ -198,7 +214,7 @@ def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
     # calls (of other sizes, other batch counts) left behind, nor on the counter wrapping
     w, rowptr, col, g0 = tiny
     c = qv.Context(0)
-    c.set_table_budget(g0.ctx.__dict__.get("_budget", 12 << 30))
+    apply_form(c, g0.ctx._form)
     g = make_graph(qv, c, rowptr, col)
     plan = [(64, [10, 5]), (2000, [15, 10, 5]), (3, [3]), (700, [25, 10]), (64, [10, 5])]
     for rnd in range(3):
