@@ -62,6 +62,11 @@ struct qv_ctx {
     int64_t direct_budget_bytes = (int64_t)16 << 30;
     int dedup_form = 0;                // QV_DEDUP_AUTO / _TABLE / _PARTITIONED
     int part_log2 = -1;                // partitions per batch (log2) of the partitioned form, -1 = chosen per call
+    int part_auto_log2 = -1;           // ... the count in use when it is chosen per call, and the call shape it was found for
+    int64_t part_auto_bound = -1;
+    bool part_stats_reset = true;      // the device's report words must be cleared before the next call
+    int part_stable = 0;               // reports in a row that left the count alone
+    unsigned part_calls = 0;
     int fap_direction = 0;             // qv_access_prob with an in-edge CSR: 0 choose per sweep, 1 gather only, 2 scatter only
     uint32_t epoch = 0;
     // pinned staging ring for the per-batch arguments of calls with many batches

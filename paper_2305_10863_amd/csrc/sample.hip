@@ -21,7 +21,29 @@
 #include <mutex>
 #include <new>
 
+// Pointers that a kernel reads out of an argument record carry no address space, and the compiler
+// then emits FLAT accesses for them.  A FLAT access counts against the LDS counter as well as the
+// memory counter, so every wait for an LDS result also waits for all global loads and stores in
+// flight.  Kernels therefore work on a copy of the record whose pointers are typed as global
+// memory (BatchG below); on the host the qualifier is empty.
+#if defined(__HIP_DEVICE_COMPILE__)
+#define QV_G __attribute__((address_space(1)))
+#else
+#define QV_G
+#endif
+
 namespace qv {
+
+template <typename T>
+__device__ __forceinline__ T QV_G* gptr(T* p) { return (T QV_G*)p; }
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global
+// load and store the wave has in flight (prefetches, fire-and-forget result stores), which costs a
+// full memory round trip per barrier; the kernels that use this one exchange data between their
+// threads through LDS alone.
+__device__ __forceinline__ void lds_barrier() {
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
 
 // ---------------------------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): counter (node, hop, slot, 0), key = the 64-bit seed.
@@ -86,8 +108,8 @@ __device__ __forceinline__ uint32_t floyd_resolve(uint32_t t, bool active, bool 
 // hash table
 // ---------------------------------------------------------------------------------------------
 struct TableView {
-    uint64_t* keyw;                 // hashed form only
-    TableSlot* slots;
+    uint64_t QV_G* keyw;            // hashed form only
+    TableSlot QV_G* slots;
     uint32_t mask;
     int32_t shift;
     uint32_t epoch;
@@ -168,6 +190,81 @@ struct BatchArgs {
     int64_t* n_id_len_out; int64_t* frontier_len_out;      // stand-alone reindex
 };
 
+// BatchArgs as the kernels see it: the same fields, pointers typed as global memory.
+struct BatchG {
+    const int32_t QV_G* seeds;
+    int64_t n_seeds;
+    uint64_t rng_seed;
+    uint64_t QV_G* keyw;
+    TableSlot QV_G* slots;
+    SampleMeta QV_G* meta;
+    uint32_t QV_G* seed_slot;
+    uint32_t QV_G* slot_of;
+    int32_t QV_G* nbr;
+    int32_t QV_G* row_local;
+    int32_t QV_G* col_local;
+    int64_t edge_cap;
+    int32_t QV_G* n_id;
+    int64_t n_id_cap;
+    int32_t QV_G* fr_id;
+    int32_t QV_G* fr_lid;
+    int64_t QV_G* fr_rs;
+    uint32_t QV_G* fr_deg;
+    uint32_t QV_G* fr_seg;
+    int64_t fr_cap;
+    int32_t QV_G* fr_user;
+    int64_t fr_user_cap;
+    uint16_t QV_G* seed_flags;
+    uint16_t QV_G* flags;
+    uint32_t QV_G* partial;
+    unsigned long long QV_G* pmask;
+    uint32_t QV_G* pcount;
+    uint32_t QV_G* tile_seg;
+    uint16_t QV_G* fr_tile;
+    int64_t QV_G* node_off_out;
+    int64_t QV_G* edge_off_out;
+    int64_t QV_G* frontier_off_out;
+    int64_t QV_G* n_id_len_out;
+    int64_t QV_G* frontier_len_out;
+    template <typename Rec>             // BatchArgs in the kernel argument block, or in global memory
+    __device__ __forceinline__ explicit BatchG(const Rec& a)
+        : seeds(gptr(a.seeds)),
+          n_seeds(a.n_seeds),
+          rng_seed(a.rng_seed),
+          keyw(gptr(a.keyw)),
+          slots(gptr(a.slots)),
+          meta(gptr(a.meta)),
+          seed_slot(gptr(a.seed_slot)),
+          slot_of(gptr(a.slot_of)),
+          nbr(gptr(a.nbr)),
+          row_local(gptr(a.row_local)),
+          col_local(gptr(a.col_local)),
+          edge_cap(a.edge_cap),
+          n_id(gptr(a.n_id)),
+          n_id_cap(a.n_id_cap),
+          fr_id(gptr(a.fr_id)),
+          fr_lid(gptr(a.fr_lid)),
+          fr_rs(gptr(a.fr_rs)),
+          fr_deg(gptr(a.fr_deg)),
+          fr_seg(gptr(a.fr_seg)),
+          fr_cap(a.fr_cap),
+          fr_user(gptr(a.fr_user)),
+          fr_user_cap(a.fr_user_cap),
+          seed_flags(gptr(a.seed_flags)),
+          flags(gptr(a.flags)),
+          partial(gptr(a.partial)),
+          pmask(gptr(a.pmask)),
+          pcount(gptr(a.pcount)),
+          tile_seg(gptr(a.tile_seg)),
+          fr_tile(gptr(a.fr_tile)),
+          node_off_out(gptr(a.node_off_out)),
+          edge_off_out(gptr(a.edge_off_out)),
+          frontier_off_out(gptr(a.frontier_off_out)),
+          n_id_len_out(gptr(a.n_id_len_out)),
+          frontier_len_out(gptr(a.frontier_len_out)) {}
+};
+
+
 struct CallHeader {
     // graph
     const void* rowptr; const int32_t* col; int64_t n_nodes;
@@ -198,14 +295,14 @@ struct CallInline : CallHeader {
 };
 struct CallDevice : CallHeader {
     const BatchArgs* b;
-    __device__ __forceinline__ const BatchArgs& batch(int y) const { return b[y]; }
+    __device__ __forceinline__ const BatchArgs QV_G& batch(int y) const { return *gptr(b + y); }
 };
 struct CallArgs : CallHeader {      // host side: header + every batch of the call
     BatchArgs b[kMaxBatch];
     const BatchArgs* b_dev = nullptr;       // device copy (calls of more than kInlineBatch batches)
 };
 
-__device__ __forceinline__ TableView table_of(const CallHeader& c, const BatchArgs& b) {
+__device__ __forceinline__ TableView table_of(const CallHeader& c, const BatchG& b) {
     return TableView{b.keyw, b.slots, c.mask, c.shift, c.epoch, c.direct};
 }
 
@@ -215,7 +312,7 @@ __device__ __forceinline__ TableView table_of(const CallHeader& c, const BatchAr
 // ---------------------------------------------------------------------------------------------
 template <typename A>
 __global__ void __launch_bounds__(256) k_insert_ids(A c) {
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int32_t* ids;
@@ -267,7 +364,7 @@ constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
 // Partitioned form: a frontier entry carries its segment offset relative to the tile that produced
 // it (fr_seg) and that tile's number (fr_tile); the tiles' edge counts (tile_seg) are scanned here,
 // once per workgroup, into LDS.  Also publishes the hop's edge count.  All threads must call.
-__device__ __forceinline__ void seg_base_prologue(const CallHeader& c, const BatchArgs& b, uint32_t* s_segbase,
+__device__ __forceinline__ void seg_base_prologue(const CallHeader& c, const BatchG& b, uint32_t* s_segbase,
                                                   uint32_t* s_wave, bool publish) {
     SampleMeta* m = b.meta;
     int64_t plen;
@@ -314,7 +411,7 @@ __device__ __forceinline__ void seg_base_prologue(const CallHeader& c, const Bat
 // ---------------------------------------------------------------------------------------------
 // k_sample: one group of G lanes per frontier node, fanout <= G
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ void emit_edge(const CallHeader& c, const BatchArgs& b, const TableView& t, uint64_t tag,
+__device__ __forceinline__ void emit_edge(const CallHeader& c, const BatchG& b, const TableView& t, uint64_t tag,
                                           int64_t p, int32_t g, int32_t vl) {
     if (p < b.edge_cap) {
         b.nbr[p] = g;
@@ -334,53 +431,80 @@ __device__ __forceinline__ void emit_edge(const CallHeader& c, const BatchArgs& 
     }
 }
 
+// Per round a group of G lanes takes S consecutive frontier entries (S = 1, 2, 4 or 8): its first S
+// lanes load one entry each, then the group works through them, one per sub-round, the entry's
+// fields broadcast inside the group.  The neighbour ids of all S sub-rounds are requested before
+// any is stored, so a wave keeps S random col reads per group in flight: with many entries the
+// kernel's time is the latency of those reads.  S is the smallest power of two with which the
+// grid covers the frontier in one round, so a small frontier still spreads over many waves.
 template <int G, typename A>
 __global__ void __launch_bounds__(256) k_sample(A c) {
-    const BatchArgs& b = c.batch(blockIdx.y);
-    const int sub = threadIdx.x % G;
-    constexpr int groups_per_block = 256 / G;
-    const SampleMeta* m = b.meta;
+    const BatchG b(c.batch(blockIdx.y));
+    const int lane = threadIdx.x % kWave, sub = lane % G;
+    const SampleMeta QV_G* m = b.meta;
     const int64_t fbeg = c.cumulative ? 0 : m->frontier_off[c.stage - 1];
     const int64_t F = c.cumulative ? m->node_off[c.stage] : m->frontier_off[c.stage] - fbeg;
     const int64_t ebase = m->edge_off[c.stage - 1];
-    const int64_t stride = (int64_t)gridDim.x * groups_per_block;
-    const int group_in_wave = (threadIdx.x % kWave) / G;
     const TableView t = table_of(c, b);
     const uint64_t tag = pos_tag(c.epoch, c.stage);
     const uint32_t l = (uint32_t)c.fanout;
+    const int32_t QV_G* col = gptr(c.col);
     __shared__ uint32_t s_segbase[kPMaxTiles];
     __shared__ uint32_t s_wave[256 / kWave];
     const bool tiled = b.tile_seg != nullptr;
     if (tiled) seg_base_prologue(c, b, s_segbase, s_wave, blockIdx.x == 0);
-    // the loop is uniform over the wave: every lane runs the same number of iterations
-    int64_t f0 = (int64_t)blockIdx.x * groups_per_block + (threadIdx.x / kWave) * (kWave / G);
-    for (; f0 < F; f0 += stride) {
-        const int64_t f = f0 + group_in_wave;
-        uint32_t d = 0, off = 0;
-        int64_t rs = 0;
-        int32_t v = 0, vl = -1;
-        if (f < F) {
-            v = b.fr_id[fbeg + f];
-            rs = b.fr_rs[fbeg + f];
-            d = b.fr_deg[fbeg + f];
-            off = b.fr_seg[fbeg + f];
-            if (tiled) off += s_segbase[b.fr_tile[fbeg + f]];
-            vl = b.fr_lid[fbeg + f];
+    constexpr int kAhead = 8;                                   // most sub-rounds per round
+    constexpr int groups_per_wave = kWave / G;
+    const int64_t n_groups = (int64_t)gridDim.x * (256 / G);
+    int S = 1;
+    while (S < kAhead && n_groups * S < F) S <<= 1;
+    const int64_t wave_global = (int64_t)blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
+    const int64_t per_wave = (int64_t)groups_per_wave * S;      // entries per wave and round
+    const int64_t round_stride = (int64_t)gridDim.x * (256 / kWave) * per_wave;
+    // the loops are uniform over the wave: every lane runs the same number of iterations
+    for (int64_t w0 = wave_global * per_wave; w0 < F; w0 += round_stride) {
+        const int64_t f = w0 + (int64_t)(lane / G) * S + sub;   // a group's S entries are consecutive
+        uint32_t d_own = 0, off_own = 0, rs_lo = 0, rs_hi = 0;
+        int32_t v_own = 0, vl_own = -1;
+        if (sub < S && f < F) {
+            v_own = b.fr_id[fbeg + f];
+            const int64_t rs = b.fr_rs[fbeg + f];
+            rs_lo = (uint32_t)rs; rs_hi = (uint32_t)((uint64_t)rs >> 32);
+            d_own = b.fr_deg[fbeg + f];
+            off_own = b.fr_seg[fbeg + f];
+            if (tiled) off_own += s_segbase[b.fr_tile[fbeg + f]];
+            vl_own = b.fr_lid[fbeg + f];
         }
-        const bool draw = d > l;
-        const uint32_t mcount = draw ? l : d;
-        uint32_t pos = (uint32_t)sub;
-        if (__any(draw)) {
-            const bool active = draw && (uint32_t)sub < l;
-            const uint32_t base = d - l;                      // meaningful only where draw
-            uint32_t tdraw = 0xFFFFFFFFu;
-            if (active) tdraw = rand_below(b.rng_seed, (uint32_t)v, (uint32_t)c.hop, (uint32_t)sub, base + (uint32_t)sub + 1u);
-            const uint32_t pick = floyd_resolve<G>(tdraw, active, false, base, sub, 0, (int)l);
-            if (draw) pos = pick;
+        int32_t g[kAhead];
+#pragma unroll
+        for (int j = 0; j < kAhead; ++j) {                      // j: the group's lane whose entry is expanded
+            if (j >= S) break;
+            const uint32_t d = __shfl(d_own, j, G);
+            const bool draw = d > l;
+            const uint32_t mcount = draw ? l : d;
+            uint32_t pos = (uint32_t)sub;
+            if (__any(draw)) {
+                const int32_t v = __shfl(v_own, j, G);
+                const bool active = draw && (uint32_t)sub < l;
+                const uint32_t base = d - l;                    // meaningful only where draw
+                uint32_t tdraw = 0xFFFFFFFFu;
+                if (active) tdraw = rand_below(b.rng_seed, (uint32_t)v, (uint32_t)c.hop, (uint32_t)sub, base + (uint32_t)sub + 1u);
+                const uint32_t pick = floyd_resolve<G>(tdraw, active, false, base, sub, 0, (int)l);
+                if (draw) pos = pick;
+            }
+            // (shuffles stay outside the branch: a lane that is switched off cannot be read from)
+            const int64_t rs = (int64_t)(((uint64_t)__shfl(rs_hi, j, G) << 32) | __shfl(rs_lo, j, G));
+            g[j] = 0;
+            if ((uint32_t)sub < mcount) g[j] = col[rs + pos];
         }
-        if ((uint32_t)sub < mcount) {
-            const int32_t g = c.col[rs + pos];
-            emit_edge(c, b, t, tag, ebase + off + sub, g, vl);
+#pragma unroll
+        for (int j = 0; j < kAhead; ++j) {
+            if (j >= S) break;
+            const uint32_t d = __shfl(d_own, j, G);
+            const uint32_t off = __shfl(off_own, j, G);
+            const int32_t vl = __shfl(vl_own, j, G);
+            const uint32_t mcount = d > l ? l : d;
+            if ((uint32_t)sub < mcount) emit_edge(c, b, t, tag, ebase + off + sub, g[j], vl);
         }
     }
 }
@@ -390,7 +514,7 @@ __global__ void __launch_bounds__(256) k_sample(A c) {
 template <typename A>
 __global__ void __launch_bounds__(64) k_sample_wide(A c) {
     __shared__ uint32_t picks[QV_MAX_FANOUT];
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     const int lane = threadIdx.x;
     const SampleMeta* m = b.meta;
     const int64_t fbeg = c.cumulative ? 0 : m->frontier_off[c.stage - 1];
@@ -472,12 +596,12 @@ constexpr int kMaxTiles = 1024;         // tiles per stage (k_assign sums the co
 
 struct StageView {
     int64_t begin, end;
-    const int32_t* ids;
-    const uint32_t* slot_of;
-    uint16_t* flags;
+    const int32_t QV_G* ids;
+    const uint32_t QV_G* slot_of;
+    uint16_t QV_G* flags;
 };
 
-__device__ __forceinline__ StageView stage_view(const CallHeader& c, const BatchArgs& b) {
+__device__ __forceinline__ StageView stage_view(const CallHeader& c, const BatchG& b) {
     StageView v;
     const SampleMeta* m = b.meta;
     if (c.stage == 0) {
@@ -501,7 +625,7 @@ __device__ __forceinline__ uint32_t slot_at(const CallHeader& c, const StageView
 template <typename RP, typename A>
 __global__ void __launch_bounds__(kScanBlock) k_flag(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     const StageView v = stage_view(c, b);
     const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
@@ -549,7 +673,7 @@ __global__ void __launch_bounds__(kScanBlock) k_flag(A c) {
 template <typename RP, typename A>
 __global__ void __launch_bounds__(kScanBlock) k_assign(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     SampleMeta* m = b.meta;
     const StageView v = stage_view(c, b);
@@ -640,7 +764,7 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(A c) {
 template <typename A>
 __global__ void __launch_bounds__(kScanBlock) k_cum_partial(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     const int64_t U = b.meta->node_off[c.stage];
     const int64_t t0 = (int64_t)blockIdx.x * kScanBlock * c.items_per_thread;
     if (t0 >= U) return;
@@ -660,7 +784,7 @@ __global__ void __launch_bounds__(kScanBlock) k_cum_partial(A c) {
 template <typename A>
 __global__ void __launch_bounds__(kScanBlock) k_cum_scan(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     SampleMeta* m = b.meta;
     const int64_t U = m->node_off[c.stage];
     const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
@@ -690,7 +814,7 @@ __global__ void __launch_bounds__(kScanBlock) k_cum_scan(A c) {
 // ---------------------------------------------------------------------------------------------
 template <typename A>
 __global__ void __launch_bounds__(256) k_relabel(A c) {
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     const SampleMeta* m = b.meta;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -779,9 +903,9 @@ __device__ __forceinline__ uint32_t pick8(const uint32_t (&v)[kPKeys], int i) {
 // [begin, end) of the stage's positions, its ids and the number of nodes numbered before it
 struct PartStage {
     int64_t begin, end, known;
-    const int32_t* ids;
+    const int32_t QV_G* ids;
 };
-__device__ __forceinline__ PartStage part_stage(const CallHeader& c, const BatchArgs& b) {
+__device__ __forceinline__ PartStage part_stage(const CallHeader& c, const BatchG& b) {
     PartStage v;
     const SampleMeta* m = b.meta;
     if (c.stage == 0) {                 // the size block is initialised by this very stage
@@ -817,7 +941,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_dedup(A c) {
     const int batch = (int)(blockIdx.x & 7u) + 8 * (q >> p_log2);
     const uint32_t part = (uint32_t)(q & (P - 1));
     if (batch >= c.n_batches) return;
-    const BatchArgs& b = c.batch(batch);
+    const BatchG b(c.batch(batch));
     const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const PartStage v = part_stage(c, b);
     if (c.stage == 0 && part == 0 && tid == 0) {
@@ -1014,7 +1138,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
     __shared__ uint32_t red[kPThreads / kWave][2];
     __shared__ uint32_t s_tot[3];
 
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     SampleMeta* m = b.meta;
     const int P = 1 << c.p_log2;
@@ -1161,7 +1285,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
 // the link (that position holds the local id by now).  Also exports the sizes.
 template <typename A>
 __global__ void __launch_bounds__(256) k_relabel_links(A c) {
-    const BatchArgs& b = c.batch(blockIdx.y);
+    const BatchG b(c.batch(blockIdx.y));
     const SampleMeta* m = b.meta;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -1464,7 +1588,10 @@ static qv_status launch_sample(qv_ctx* ctx, const CallArgs& c, int64_t max_front
         QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(64), k_sample_wide);
     } else {
         const int G = l <= 8 ? 8 : l <= 16 ? 16 : l <= 32 ? 32 : 64;
-        dim3 grid((unsigned)grid_for(max_frontier, 256 / G, ctx->n_cu * 8), (unsigned)n_batches);
+        // enough workgroups for one group per entry while the frontier is small; beyond the cap the
+        // kernel gives every group up to 8 entries per round (its S)
+        const int cap = n_batches >= 8 ? ctx->n_cu * 32 / n_batches : ctx->n_cu * 8;
+        dim3 grid((unsigned)grid_for(max_frontier, 256 / G, cap), (unsigned)n_batches);
         switch (G) {
             case 8: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 8); break;
             case 16: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 16); break;
