@@ -17,6 +17,7 @@
 // the ticket + publish + look-back chain was slower (12-17 us per stage) than two short kernels
 // (4-5 us each).
 #include "qv_internal.hpp"
+#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -282,6 +283,7 @@ struct CallHeader {
     int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
     int32_t p_log2;                 // partitioned dedup: log2 of the partitions per batch
     int32_t p_tiles;                // ... and the tiles its per-tile arrays hold
+    uint32_t* part_stats;           // [0] fullest LDS table of the call, [1] deepest split, [2] partitions_log2 + 1 (device, may be NULL)
     int32_t n_batches;
     int32_t* status;
 };
@@ -393,7 +395,7 @@ __device__ __forceinline__ void seg_base_prologue(const CallHeader& c, const Bat
         if (lane >= o) inc += x;
     }
     if (lane == kWave - 1) s_wave[wave] = inc;
-    __syncthreads();
+    lds_barrier();
     uint32_t pre = 0, total = 0;
     for (int w = 0; w < nthr / kWave; ++w) {
         if (w < wave) pre += s_wave[w];
@@ -405,7 +407,7 @@ __device__ __forceinline__ void seg_base_prologue(const CallHeader& c, const Bat
         if (t < n_tiles) { s_segbase[t] = run; run += b.tile_seg[t]; }
     }
     if (publish && tid == 0) m->edge_off[c.stage] = m->edge_off[c.stage - 1] + (int64_t)total;
-    __syncthreads();
+    lds_barrier();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -878,26 +880,20 @@ __device__ __forceinline__ uint32_t part_of(uint32_t key, int p_log2) {
     return p_log2 ? (key * 0x9E3779B1u) >> (32 - p_log2) : 0u;
 }
 
-// entry of `key` in the LDS table, claiming a free one if absent; -1 when the table is full
-__device__ __forceinline__ int lds_insert(uint32_t* t_key, uint32_t key, uint32_t start, uint32_t* fill) {
+// entry of `key` in the LDS table, claiming a free one if absent (then *claimed, the caller's own
+// counter, goes up by one); -1 when the table is full
+__device__ __forceinline__ int lds_insert(uint32_t* t_key, uint32_t key, uint32_t start, uint32_t* claimed) {
     uint32_t s = start;
     for (int probes = 0; probes < kPCap; ++probes) {
         uint32_t cur = t_key[s];
         if (cur == kEmptyKey) {
             cur = atomicCAS(&t_key[s], kEmptyKey, key);
-            if (cur == kEmptyKey) { atomicAdd(fill, 1u); return (int)s; }
+            if (cur == kEmptyKey) { ++*claimed; return (int)s; }
         }
         if (cur == key) return (int)s;
         s = (s + 1) & (kPCap - 1);
     }
     return -1;
-}
-
-__device__ __forceinline__ uint32_t pick8(const uint32_t (&v)[kPKeys], int i) {
-    uint32_t r = v[0];
-#pragma unroll
-    for (int k = 1; k < kPKeys; ++k) r = (i == k) ? v[k] : r;
-    return r;
 }
 
 // [begin, end) of the stage's positions, its ids and the number of nodes numbered before it
@@ -923,19 +919,43 @@ __device__ __forceinline__ PartStage part_stage(const CallHeader& c, const Batch
     return v;
 }
 
-template <typename A>
-__global__ void __launch_bounds__(kPThreads) k_part_dedup(A c) {
-    __shared__ uint32_t t_key[kPCap];
-    __shared__ uint32_t t_min[kPCap];
-    __shared__ int32_t t_lid[kPCap];
-    __shared__ unsigned long long s_mask[2][2][kPWords];        // [tile parity][first, new][word]
-    __shared__ uint32_t s_cnt[2][2];                            // [tile parity][first, new]
+// shared state of one k_part_dedup workgroup
+struct PartLds {
+    uint32_t t_key[kPCap];                              // the partition's table: id,
+    uint32_t t_min[kPCap];                              //   its smallest position in this stage,
+    int32_t t_lid[kPCap];                               //   its local id if an earlier stage numbered it, else -1
+    unsigned long long s_mask[2][2][kPWords];           // [tile parity][first, new][word]
+    uint32_t s_cnt[2][2];                               // [tile parity][first, new]
     // Entries claimed (an insertion that found the table full adds kPCap, so one test covers both):
     // s_fill0 by the known nodes, s_fillp[t % 3] by tile t.  A counter is final at the barrier that
     // ends its phase and is not written again for two tiles, so every thread adds the same values
     // into its own running total and all threads take the same decision without a second barrier.
-    __shared__ uint32_t s_fill0, s_fillp[3];
+    uint32_t s_fill0, s_fillp[3];
+    // per wave: the ids of the current tile that this partition owns (later: their table entries) and
+    // where they stand (slot << 6 | lane); sized for a tile in which every id is the partition's
+    uint32_t q_key[kPThreads / kWave][kPKeys * kWave];
+    uint16_t q_tag[kPThreads / kWave][kPKeys * kWave];
+};
 
+// masks and populations of tile `pt` of this partition: stored by sub-round 0, merged by later ones
+__device__ __forceinline__ void part_publish(const BatchG& b, PartLds& S, int pt, int P, uint32_t part, uint32_t r, int tid) {
+    const int pb = pt & 1;
+    if (tid < 2 * kPWords) {
+        unsigned long long QV_G* dst = b.pmask + (((size_t)pt * P + part) * 2) * kPWords + tid;
+        const unsigned long long w = S.s_mask[pb][tid / kPWords][tid % kPWords];
+        *dst = r == 0 ? w : (*dst | w);
+        S.s_mask[pb][tid / kPWords][tid % kPWords] = 0;        // bits are OR-ed in by the tile after next
+    }
+    if (tid < 2) {
+        uint32_t QV_G* dst = b.pcount + ((size_t)pt * P + part) * 2 + tid;
+        *dst = r == 0 ? S.s_cnt[pb][tid] : *dst + S.s_cnt[pb][tid];
+        S.s_cnt[pb][tid] = 0;
+    }
+}
+
+template <typename A>
+__global__ void __launch_bounds__(kPThreads) k_part_dedup(A c) {
+    __shared__ PartLds S;
     const int p_log2 = c.p_log2, P = 1 << p_log2;
     const int q = (int)(blockIdx.x >> 3);
     const int batch = (int)(blockIdx.x & 7u) + 8 * (q >> p_log2);
@@ -945,181 +965,182 @@ __global__ void __launch_bounds__(kPThreads) k_part_dedup(A c) {
     const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const PartStage v = part_stage(c, b);
     if (c.stage == 0 && part == 0 && tid == 0) {
-        SampleMeta* m = b.meta;
+        SampleMeta QV_G* m = b.meta;
         for (int i = 0; i < QV_MAX_HOPS + 2; ++i) { m->node_off[i] = 0; m->frontier_off[i] = 0; }
         for (int i = 0; i < QV_MAX_HOPS + 1; ++i) m->edge_off[i] = 0;
         m->stage_range[0] = 0; m->stage_range[1] = b.n_seeds;
     }
     const int64_t len = v.end - v.begin;
     const int n_tiles = (int)((len + kPTile - 1) / kPTile);
-    int32_t* col_local = c.stage > 0 ? b.col_local : nullptr;
+    int32_t QV_G* col_local = c.stage > 0 ? b.col_local : nullptr;
+    const int32_t QV_G* ids = v.ids + v.begin;
+    int32_t QV_G* status = gptr(c.status);
+    uint32_t* q_key = S.q_key[wave];
+    uint16_t* q_tag = S.q_tag[wave];
+    uint32_t fill = 0;
+    int split = 0;
 
-    for (int split = 0;; ++split) {
+    auto load_tile = [&](int t, uint32_t (&dst)[kPKeys]) {
+#pragma unroll
+        for (int i = 0; i < kPKeys; ++i) {
+            const int64_t rel = (int64_t)t * kPTile + (int64_t)i * kPThreads + tid;
+            dst[i] = rel < len ? (uint32_t)ids[rel] : kEmptyKey;
+        }
+    };
+
+    for (;; ++split) {
         const uint32_t n_rounds = 1u << split;
         bool failed = false;
         for (uint32_t r = 0; r < n_rounds && !failed; ++r) {
-            __syncthreads();                                    // the table and the flags are still being read
-            for (int i = tid; i < kPCap; i += kPThreads) { t_key[i] = kEmptyKey; t_min[i] = 0xFFFFFFFFu; t_lid[i] = -1; }
+            lds_barrier();                                      // the table and the counters are still being read
+            // the first tiles' ids: requested before the table is even cleared
+            uint32_t bufA[kPKeys], bufB[kPKeys];
+            load_tile(0, bufA);
+            load_tile(1, bufB);
+            for (int i = tid; i < kPCap; i += kPThreads) { S.t_key[i] = kEmptyKey; S.t_min[i] = 0xFFFFFFFFu; S.t_lid[i] = -1; }
+            if (tid < 4 * kPWords) (&S.s_mask[0][0][0])[tid] = 0;
             if (tid == 0) {
-                s_fill0 = 0; s_fillp[0] = 0; s_fillp[1] = 0; s_fillp[2] = 0;
-                s_cnt[0][0] = 0; s_cnt[0][1] = 0; s_cnt[1][0] = 0; s_cnt[1][1] = 0;
+                S.s_fill0 = 0; S.s_fillp[0] = 0; S.s_fillp[1] = 0; S.s_fillp[2] = 0;
+                S.s_cnt[0][0] = 0; S.s_cnt[0][1] = 0; S.s_cnt[1][0] = 0; S.s_cnt[1][1] = 0;
             }
-            __syncthreads();
-            // nodes numbered by earlier stages: local id = index in n_id
-            for (int64_t u = tid; u < v.known; u += kPThreads) {
-                const uint32_t key = (uint32_t)b.n_id[u];
-                if (part_of(key, p_log2) != part) continue;
-                const uint32_t h = fmix32(key);
-                if (split && (h >> (32 - split)) != r) continue;
-                const int s = lds_insert(t_key, key, h & (kPCap - 1), &s_fill0);
-                if (s < 0) atomicAdd(&s_fill0, (uint32_t)kPCap);
-                else t_lid[s] = (int32_t)u;
+            lds_barrier();
+            // nodes numbered by earlier stages: local id = index in n_id (eight reads in flight per thread)
+            uint32_t claimed0 = 0;
+            for (int64_t u0 = 0; u0 < v.known; u0 += (int64_t)kPThreads * kPKeys) {
+                uint32_t k[kPKeys];
+#pragma unroll
+                for (int i = 0; i < kPKeys; ++i) {
+                    const int64_t u = u0 + (int64_t)i * kPThreads + tid;
+                    k[i] = u < v.known ? (uint32_t)b.n_id[u] : kEmptyKey;
+                }
+#pragma unroll
+                for (int i = 0; i < kPKeys; ++i) {
+                    const int64_t u = u0 + (int64_t)i * kPThreads + tid;
+                    if (u >= v.known || part_of(k[i], p_log2) != part) continue;
+                    const uint32_t h = fmix32(k[i]);
+                    if (split && (h >> (32 - split)) != r) continue;
+                    const int s2 = lds_insert(S.t_key, k[i], h & (kPCap - 1), &claimed0);
+                    if (s2 < 0) claimed0 += (uint32_t)kPCap;
+                    else S.t_lid[s2] = (int32_t)u;
+                }
             }
-            __syncthreads();
-            uint32_t fill = s_fill0;
+            if (claimed0) atomicAdd(&S.s_fill0, claimed0);
+            lds_barrier();
+            fill = S.s_fill0;
             if (fill > kPFillMax) { failed = true; break; }
 
-            uint32_t nxt[kPKeys];
-#pragma unroll
-            for (int i = 0; i < kPKeys; ++i) {
-                const int64_t rel = (int64_t)i * kPThreads + tid;
-                nxt[i] = rel < len ? (uint32_t)v.ids[v.begin + rel] : kEmptyKey;
-            }
-            for (int t = 0; t < n_tiles; ++t) {
+            // One tile: returns false when the table overflowed (decided identically by every thread).
+            // A wave first moves the ids it owns (about 1/P of its 512) into its own queue in LDS, then
+            // works through the queue with all lanes busy: handling them where they stand, a few
+            // active lanes per instruction, made the kernel instruction-bound.
+            auto do_tile = [&](int t, const uint32_t (&cur)[kPKeys]) -> bool {
                 const int64_t rel0 = (int64_t)t * kPTile;
-                uint32_t cur[kPKeys];
-#pragma unroll
-                for (int i = 0; i < kPKeys; ++i) cur[i] = nxt[i];
-                if (t + 1 < n_tiles) {                          // next tile's ids, requested a tile ahead
-#pragma unroll
-                    for (int i = 0; i < kPKeys; ++i) {
-                        const int64_t rel = rel0 + kPTile + (int64_t)i * kPThreads + tid;
-                        nxt[i] = rel < len ? (uint32_t)v.ids[v.begin + rel] : kEmptyKey;
-                    }
-                }
-                // which of my positions belong to this partition (and sub-round); ids out of range
-                // are finished here: local id -1, never a first occurrence
-                uint32_t mine = 0;
+                uint32_t n_own = 0;                             // wave-uniform
 #pragma unroll
                 for (int i = 0; i < kPKeys; ++i) {
                     const int64_t rel = rel0 + (int64_t)i * kPThreads + tid;
                     const uint32_t key = cur[i];
-                    if (rel >= len || part_of(key, p_log2) != part) continue;
-                    if ((int32_t)key < 0 || (c.n_nodes >= 0 && (int64_t)key >= c.n_nodes)) {
+                    bool own = rel < len && part_of(key, p_log2) == part;
+                    if (own && ((int32_t)key < 0 || (c.n_nodes >= 0 && (int64_t)key >= c.n_nodes))) {
+                        // an id out of range is finished here: local id -1, never a first occurrence
                         if (r == 0) {
-                            atomicOr(c.status, kStatRange);
+                            atomicOr((int*)status, kStatRange);
                             if (col_local) col_local[v.begin + rel] = -1;
                         }
-                        continue;
+                        own = false;
                     }
-                    if (split && (fmix32(key) >> (32 - split)) != r) continue;
-                    mine |= 1u << i;
+                    if (own && split && (fmix32(key) >> (32 - split)) != r) own = false;
+                    const unsigned long long m = __ballot(own);
+                    if (own) {
+                        const uint32_t e = n_own + __mbcnt_hi((uint32_t)(m >> 32), __mbcnt_lo((uint32_t)m, 0u));
+                        q_key[e] = key;
+                        q_tag[e] = (uint16_t)((i << 6) | lane);
+                    }
+                    n_own += (uint32_t)__popcll(m);
                 }
-                // register them: entry (claimed if absent), smallest position
-                unsigned long long slots = 0;                  // 12 bits per position of mine, in bit order
-                {
-                    uint32_t todo = mine;
-                    int j = 0;
-                    while (__any(todo != 0)) {
-                        if (todo) {
-                            const int i = __ffs(todo) - 1;
-                            todo &= todo - 1;
-                            const uint32_t key = pick8(cur, i);
-                            const uint32_t pos = (uint32_t)(v.begin + rel0 + (int64_t)i * kPThreads + tid);
-                            const int s = lds_insert(t_key, key, fmix32(key) & (kPCap - 1), &s_fillp[t % 3]);
-                            if (s < 0) {
-                                atomicAdd(&s_fillp[t % 3], (uint32_t)kPCap);
-                            } else {
-                                atomicMin(&t_min[s], pos);
-                                if (j < 5) slots |= (unsigned long long)s << (12 * j);
-                            }
-                            ++j;
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the queue is read by other lanes of the wave
+                // register them: entry (claimed if absent), smallest position; the entry replaces the id in the queue
+                uint32_t claimed = 0;
+                for (uint32_t e0 = 0; e0 < n_own; e0 += kWave) {
+                    const uint32_t e = e0 + (uint32_t)lane;
+                    if (e < n_own) {
+                        const uint32_t key = q_key[e], tag = q_tag[e];
+                        const uint32_t pos = (uint32_t)(v.begin + rel0) + (tag >> 6) * kPThreads + (uint32_t)(wave * kWave) + (tag & 63u);
+                        const int s2 = lds_insert(S.t_key, key, fmix32(key) & (kPCap - 1), &claimed);
+                        if (s2 < 0) {
+                            claimed += (uint32_t)kPCap;
+                        } else {
+                            atomicMin(&S.t_min[s2], pos);
+                            q_key[e] = (uint32_t)s2;
                         }
                     }
                 }
-                __syncthreads();
-                fill += s_fillp[t % 3];
-                if (fill > kPFillMax) { failed = true; break; }
-                if (tid == 0) s_fillp[(t + 2) % 3] = 0;         // tile t-1's counter: read by all, next used by tile t+2
+                if (claimed) atomicAdd(&S.s_fillp[t % 3], claimed);
+                lds_barrier();
+                fill += S.s_fillp[t % 3];
+                if (fill > kPFillMax) return false;
+                if (tid == 0) S.s_fillp[(t + 2) % 3] = 0;       // tile t-1's counter: read by all, next used by tile t+2
                 // the previous tile's masks and counts are complete: publish them
-                if (t > 0) {
-                    const int pt = t - 1, pb = pt & 1;
-                    if (tid < 2 * kPWords) {
-                        unsigned long long* dst = b.pmask + (((size_t)pt * P + part) * 2) * kPWords + tid;
-                        const unsigned long long w = s_mask[pb][tid / kPWords][tid % kPWords];
-                        *dst = r == 0 ? w : (*dst | w);
-                    }
-                    if (tid < 2) {
-                        uint32_t* dst = b.pcount + ((size_t)pt * P + part) * 2 + tid;
-                        *dst = r == 0 ? s_cnt[pb][tid] : *dst + s_cnt[pb][tid];
-                        s_cnt[pb][tid] = 0;
-                    }
-                }
+                if (t > 0) part_publish(b, S, t - 1, P, part, r, tid);
                 // finish this tile's positions
-                uint32_t fbits = 0, nbits = 0;
-                {
-                    uint32_t todo = mine;
-                    int j = 0;
-                    while (__any(todo != 0)) {
-                        if (todo) {
-                            const int i = __ffs(todo) - 1;
-                            todo &= todo - 1;
-                            const uint32_t key = pick8(cur, i);
-                            const uint32_t pos = (uint32_t)(v.begin + rel0 + (int64_t)i * kPThreads + tid);
-                            int s;
-                            if (j < 5) {
-                                s = (int)((slots >> (12 * j)) & 0xFFFu);
-                            } else {                            // found again by probing (the id is in the table)
-                                uint32_t x = fmix32(key) & (kPCap - 1);
-                                while (t_key[x] != key) x = (x + 1) & (kPCap - 1);
-                                s = (int)x;
-                            }
-                            ++j;
-                            const uint32_t mp = t_min[s];
-                            const int32_t lid = t_lid[s];
-                            const uint32_t first = mp == pos ? 1u : 0u;
-                            const uint32_t isnew = (first && lid < 0) ? 1u : 0u;
-                            if (col_local) {
-                                if (lid >= 0) col_local[pos] = lid;
-                                else if (!first) col_local[pos] = -2 - (int32_t)mp;
-                            }
-                            fbits |= first << i;
-                            nbits |= isnew << i;
+                uint32_t cf = 0, cn = 0;
+                for (uint32_t e0 = 0; e0 < n_own; e0 += kWave) {
+                    const uint32_t e = e0 + (uint32_t)lane;
+                    uint32_t first = 0, isnew = 0;
+                    if (e < n_own) {
+                        const uint32_t s2 = q_key[e], tag = q_tag[e];
+                        const uint32_t pos = (uint32_t)(v.begin + rel0) + (tag >> 6) * kPThreads + (uint32_t)(wave * kWave) + (tag & 63u);
+                        const uint32_t mp = S.t_min[s2];
+                        const int32_t lid = S.t_lid[s2];
+                        first = mp == pos ? 1u : 0u;
+                        isnew = (first && lid < 0) ? 1u : 0u;
+                        if (col_local) {
+                            if (lid >= 0) col_local[pos] = lid;
+                            else if (!first) col_local[pos] = -2 - (int32_t)mp;
+                        }
+                        if (first) {
+                            const int word = (int)(tag >> 6) * (kPThreads / kWave) + wave;
+                            const unsigned long long bit = 1ull << (tag & 63u);
+                            atomicOr(&S.s_mask[t & 1][0][word], bit);
+                            if (isnew) atomicOr(&S.s_mask[t & 1][1][word], bit);
                         }
                     }
+                    cf += (uint32_t)__popcll(__ballot(first));
+                    cn += (uint32_t)__popcll(__ballot(isnew));
                 }
-                uint32_t cf = 0, cn = 0;
+                if (lane == 0 && (cf | cn)) { atomicAdd(&S.s_cnt[t & 1][0], cf); atomicAdd(&S.s_cnt[t & 1][1], cn); }
+                return true;
+            };
+
+            // tiles in order, two buffers: a tile's ids are requested two tiles before they are used
+            for (int t = 0; t < n_tiles; t += 2) {
+                uint32_t cur[kPKeys];
 #pragma unroll
-                for (int i = 0; i < kPKeys; ++i) {
-                    const unsigned long long bf = __ballot((fbits >> i) & 1u), bn = __ballot((nbits >> i) & 1u);
-                    if (lane == 0) {
-                        s_mask[t & 1][0][i * (kPThreads / kWave) + wave] = bf;
-                        s_mask[t & 1][1][i * (kPThreads / kWave) + wave] = bn;
-                        cf += (uint32_t)__popcll(bf); cn += (uint32_t)__popcll(bn);
-                    }
-                }
-                if (lane == 0 && (cf | cn)) { atomicAdd(&s_cnt[t & 1][0], cf); atomicAdd(&s_cnt[t & 1][1], cn); }
+                for (int i = 0; i < kPKeys; ++i) cur[i] = bufA[i];
+                load_tile(t + 2, bufA);
+                if (!do_tile(t, cur)) { failed = true; break; }
+                if (t + 1 >= n_tiles) break;
+#pragma unroll
+                for (int i = 0; i < kPKeys; ++i) cur[i] = bufB[i];
+                load_tile(t + 3, bufB);
+                if (!do_tile(t + 1, cur)) { failed = true; break; }
             }
             if (failed) break;
-            __syncthreads();
-            if (n_tiles > 0) {                                  // the last tile
-                const int pt = n_tiles - 1, pb = pt & 1;
-                if (tid < 2 * kPWords) {
-                    unsigned long long* dst = b.pmask + (((size_t)pt * P + part) * 2) * kPWords + tid;
-                    const unsigned long long w = s_mask[pb][tid / kPWords][tid % kPWords];
-                    *dst = r == 0 ? w : (*dst | w);
-                }
-                if (tid < 2) {
-                    uint32_t* dst = b.pcount + ((size_t)pt * P + part) * 2 + tid;
-                    *dst = r == 0 ? s_cnt[pb][tid] : *dst + s_cnt[pb][tid];
-                }
-            }
+            lds_barrier();
+            if (n_tiles > 0) part_publish(b, S, n_tiles - 1, P, part, r, tid);
         }
         if (!failed) break;
         if (split == kPMaxSplit) {                              // 2^12 sub-rounds were not enough: give up loudly
-            if (tid == 0) atomicOr(c.status, kStatCapacity);
+            if (tid == 0) atomicOr((int*)status, kStatCapacity);
             break;
         }
+    }
+    // what the host's choice of the partition count goes by: fullest table, deepest split
+    if (tid == 0 && c.part_stats) {
+        uint32_t QV_G* st = gptr(c.part_stats);
+        if (split == 0) atomicMax((uint32_t*)&st[0], fill);
+        else atomicMax((uint32_t*)&st[1], (uint32_t)split);
+        st[2] = (uint32_t)p_log2 + 1u;
     }
 }
 
@@ -1142,14 +1163,15 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     SampleMeta* m = b.meta;
     const int P = 1 << c.p_log2;
-    const int t = (int)blockIdx.x;
     const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const PartStage v = part_stage(c, b);
     const int64_t len = v.end - v.begin;
-    const int64_t rel0 = (int64_t)t * kPTile;
-    if (rel0 >= len && !(len == 0 && t == 0)) return;
     const int64_t node_base = m->node_off[c.stage];
     const int64_t fr_base = m->frontier_off[c.stage];
+    // the grid holds fewer workgroups than the a-priori bound has tiles: each takes every gridDim.x-th tile
+    for (int t = (int)blockIdx.x;; t += (int)gridDim.x) {
+    const int64_t rel0 = (int64_t)t * kPTile;
+    if (rel0 >= len && !(len == 0 && t == 0)) return;
     const bool have_tile = rel0 < len;
 
     // populations of the earlier tiles
@@ -1159,7 +1181,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
     for (int o = kWave / 2; o > 0; o >>= 1) { bf += __shfl_down(bf, o); bn += __shfl_down(bn, o); }
     if (lane == 0) { red[wave][0] = bf; red[wave][1] = bn; }
     if (tid < kPWords) { m_first[tid] = 0; m_new[tid] = 0; }
-    __syncthreads();
+    lds_barrier();
     uint32_t base_first = 0, base_new = 0;
     for (int w = 0; w < kPThreads / kWave; ++w) { base_first += red[w][0]; base_new += red[w][1]; }
     // this tile's masks: OR over the partitions
@@ -1170,7 +1192,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
             acc |= b.pmask[(((size_t)t * P + j) * 2 + which) * kPWords + w];
         if (acc) atomicOr(which ? &m_new[w] : &m_first[w], acc);
     }
-    __syncthreads();
+    lds_barrier();
     if (wave < 2) {                                             // exclusive popcount prefixes over the 64 words
         const uint32_t x = (uint32_t)__popcll(wave ? m_new[lane] : m_first[lane]);
         uint32_t inc = x;
@@ -1182,7 +1204,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
         (wave ? pre_new : pre_first)[lane] = inc - x;
         if (lane == kWave - 1) s_tot[wave] = inc;
     }
-    __syncthreads();
+    lds_barrier();
 
     // my positions: what a first occurrence needs is requested for all of them before any is used
     const unsigned long long below = (1ull << lane) - 1ull;
@@ -1225,7 +1247,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
         incl[i] = inc - seg;                                    // exclusive within the wave
         if (lane == kWave - 1) seg_tot[i * (kPThreads / kWave) + wave] = inc;
     }
-    __syncthreads();
+    lds_barrier();
     if (wave == 0) {
         const uint32_t x = seg_tot[lane];
         uint32_t inc = x;
@@ -1237,7 +1259,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
         seg_pre[lane] = inc - x;
         if (lane == kWave - 1) s_tot[2] = inc;
     }
-    __syncthreads();
+    lds_barrier();
     const uint32_t tot_first = have_tile ? s_tot[0] : 0u, tot_new = have_tile ? s_tot[1] : 0u;
     const int64_t fr_user_base = c.frontier_restart ? 0 : fr_base;
 #pragma unroll
@@ -1278,6 +1300,8 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
             m->node_off[c.stage + 1] = node_base + base_new + tot_new;
             m->frontier_off[c.stage + 1] = fr_base + base_first + tot_first;
         }
+    }
+    lds_barrier();                                              // the shared arrays are reused by the next tile
     }
 }
 
@@ -1603,6 +1627,39 @@ static qv_status launch_sample(qv_ctx* ctx, const CallArgs& c, int64_t max_front
     return QV_OK;
 }
 
+// How many partitions per batch, when the caller leaves it open.  A partition's LDS table should
+// end a call about half full: fuller tables probe longer and, past kPFillMax, split into sub-rounds
+// that read the stage again; emptier ones mean more workgroups each reading the whole stage.  The
+// a-priori node bound says little (sampled sub-graphs of skewed graphs repeat most of their nodes),
+// so the kernels report the fullest table and the deepest split of a call (part_stats), the host
+// copies the words back without waiting for them, and a later call moves the count one step.
+// Results never depend on it.
+constexpr int kStatsWord = 16;                      // part_stats = d_status + kStatsWord: fill, split, partitions_log2 + 1
+static void part_adapt(qv_ctx* ctx, int64_t nodes_bound) {
+    if (ctx->part_auto_log2 < 0 || ctx->part_auto_bound != nodes_bound) {   // first call, or another call shape
+        int lg = 3;
+        while (lg < kPMaxLog2 && ((int64_t)(kPCap / 2) << lg) < nodes_bound / 8) ++lg;
+        ctx->part_auto_log2 = lg;
+        ctx->part_auto_bound = nodes_bound;
+        ctx->part_stats_reset = true;
+        ctx->part_stable = 0;
+        return;
+    }
+    volatile int32_t* h = ctx->h_status + kStatsWord;
+    const uint32_t fill = (uint32_t)h[0], split = (uint32_t)h[1];
+    if (h[2] != ctx->part_auto_log2 + 1 || (fill == 0 && split == 0)) return;  // nothing (new) has arrived
+    int lg = ctx->part_auto_log2;
+    if ((split > 0 || fill > kPCap * 5 / 8) && lg < kPMaxLog2) ++lg;
+    else if (split == 0 && fill < kPCap * 9 / 32 && lg > 3) --lg;
+    if (lg != ctx->part_auto_log2) {
+        ctx->part_auto_log2 = lg;
+        ctx->part_stats_reset = true;
+        ctx->part_stable = 0;
+    } else if (ctx->part_stable < 1000) {
+        ++ctx->part_stable;
+    }
+}
+
 // Sizes and dedup form of a qv_sample / qv_sample_many call.
 // The partitioned form serves layer frontiers whose stages fit kPMaxTiles tiles; the cumulative
 // variant, larger stages and a context told to use tables take the table forms.
@@ -1622,12 +1679,8 @@ static qv_status plan_sample(qv_ctx* ctx, int64_t max_seeds, const int32_t* fano
         if (ctx->part_log2 >= 0) {
             L->p_log2 = ctx->part_log2;
         } else {
-            // enough partitions that a quarter of the a-priori node bound half-fills the tables (sampled
-            // sub-graphs of skewed graphs repeat most of their nodes); a fuller table costs sub-rounds, not results
-            int64_t est = bd->nodes / 4;
-            int lg = 3;
-            while (lg < kPMaxLog2 && ((int64_t)(kPCap / 2) << lg) < est) ++lg;
-            L->p_log2 = lg;
+            part_adapt(ctx, bd->nodes);
+            L->p_log2 = ctx->part_auto_log2;
         }
     }
     return QV_OK;
@@ -1639,6 +1692,8 @@ static qv_status launch_part_dedup(qv_ctx* ctx, CallArgs& c, int rowptr_bits, in
     QV_LAUNCH_A(ctx, c, n_batches, dim3(wgs), dim3(kPThreads), k_part_dedup);
     int64_t tiles = (max_items + kPTile - 1) / kPTile;
     if (tiles < 1) tiles = 1;
+    const int64_t cap = n_batches >= 4 ? ctx->n_cu * 8 / n_batches : ctx->n_cu * 2;   // a-priori bounds are loose: most tiles do not exist
+    if (tiles > cap) tiles = cap;
     dim3 grid((unsigned)tiles, (unsigned)n_batches);
     if (rowptr_bits == 32) QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kPThreads), k_part_assign, int32_t);
     else QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kPThreads), k_part_assign, int64_t);
@@ -1680,6 +1735,15 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     }
     c.epoch = ctx->epoch; c.n_hops = n_hops; c.status = ctx->d_status; c.cumulative = cumulative ? 1 : 0;
     c.p_log2 = L.p_log2; c.p_tiles = (int32_t)L.p_tiles; c.n_batches = n_batches;
+    const bool adaptive = L.part && ctx->part_log2 < 0;
+    if (adaptive) {
+        c.part_stats = reinterpret_cast<uint32_t*>(ctx->d_status + kStatsWord);
+        if (ctx->part_stats_reset) {                // the count changed: earlier reports no longer apply
+            QV_HIP(ctx, hipMemsetAsync(ctx->d_status + kStatsWord, 0, 3 * sizeof(int32_t), ctx->stream));
+            ctx->h_status[kStatsWord] = 0; ctx->h_status[kStatsWord + 1] = 0; ctx->h_status[kStatsWord + 2] = 0;
+            ctx->part_stats_reset = false;
+        }
+    }
     for (int i = 0; i < n_batches; ++i) {
         BatchArgs& b = c.b[i];
         if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "%s: scratch arena too small (internal sizing error)", who);
@@ -1715,6 +1779,10 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
         dim3 grid((unsigned)grid_for(bd.edges, 256 * 4, ctx->n_cu * 4), (unsigned)n_batches);
         QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(256), k_relabel_links);
         QV_LAUNCH_CHECK(ctx, "k_relabel_links");
+        // report back: every call while the count is still moving, every 32nd once it has settled
+        if (adaptive && (ctx->part_stable < 8 || (++ctx->part_calls & 31) == 0))
+            QV_HIP(ctx, hipMemcpyAsync(ctx->h_status + kStatsWord, ctx->d_status + kStatsWord, 3 * sizeof(int32_t),
+                                       hipMemcpyDeviceToHost, ctx->stream));
         return QV_OK;
     }
     // stage 0: the seeds
