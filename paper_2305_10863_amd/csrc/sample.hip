@@ -17,7 +17,6 @@
 // the ticket + publish + look-back chain was slower (12-17 us per stage) than two short kernels
 // (4-5 us each).
 #include "qv_internal.hpp"
-#include <cstdlib>
 #include <cstring>
 #include <mutex>
 #include <new>
@@ -183,8 +182,10 @@ struct BatchArgs {
     uint16_t* flags;                // per edge: first occurrence | new node << 1 | next-hop segment size << 2 | col_local written << 15
     uint32_t* partial;              // [kMaxTiles][3] per-tile counts of the stage being run
     // partitioned dedup (see k_part_dedup); all NULL in the table forms
-    unsigned long long* pmask;      // [tile][partition][first, new][kPWords] occurrence bit masks of the stage being run
-    uint32_t* pcount;               // [tile][partition][first, new] their populations
+    uint2* dealt;                   // the stage's (id, position) records, tile by tile, each tile sorted by partition
+    int32_t* result;                // per record: what k_part_dedup found out about it (see there)
+    uint16_t* run_off;              // [tile][P + 1] where each partition's records start inside the tile's 4096
+    uint32_t* pcount;               // [tile][partition][first, new] populations
     uint32_t* tile_seg;             // [tile] next-hop edges produced by the tile's first occurrences
     uint16_t* fr_tile;              // per frontier entry: the tile that produced it (fr_seg is then tile-local)
     int64_t* node_off_out; int64_t* edge_off_out; int64_t* frontier_off_out;
@@ -218,7 +219,9 @@ struct BatchG {
     uint16_t QV_G* seed_flags;
     uint16_t QV_G* flags;
     uint32_t QV_G* partial;
-    unsigned long long QV_G* pmask;
+    uint2 QV_G* dealt;
+    int32_t QV_G* result;
+    uint16_t QV_G* run_off;
     uint32_t QV_G* pcount;
     uint32_t QV_G* tile_seg;
     uint16_t QV_G* fr_tile;
@@ -254,7 +257,9 @@ struct BatchG {
           seed_flags(gptr(a.seed_flags)),
           flags(gptr(a.flags)),
           partial(gptr(a.partial)),
-          pmask(gptr(a.pmask)),
+          dealt(gptr(a.dealt)),
+          result(gptr(a.result)),
+          run_off(gptr(a.run_off)),
           pcount(gptr(a.pcount)),
           tile_seg(gptr(a.tile_seg)),
           fr_tile(gptr(a.fr_tile)),
@@ -352,7 +357,9 @@ __global__ void __launch_bounds__(256) k_insert_ids(A c) {
 // Geometry of the partitioned dedup (k_part_dedup / k_part_assign below)
 // ---------------------------------------------------------------------------------------------
 constexpr int kPTile = 4096;                        // positions per tile
-constexpr int kPThreads = 512;                      // threads per workgroup of both kernels
+constexpr int kPThreads = 512;                      // threads per workgroup of k_part_deal and k_part_assign
+constexpr int kDThreads = 1024;                     // ... and of k_part_dedup (more waves to hide its LDS chains behind)
+constexpr int kDKeys = 4;                           // ids / records a k_part_dedup thread has in flight
 constexpr int kPKeys = kPTile / kPThreads;          // positions per thread and tile
 constexpr int kPWords = kPTile / 64;                // 64-bit mask words per tile
 constexpr int kPCapLog2 = 12;
@@ -849,35 +856,40 @@ __global__ void __launch_bounds__(256) k_relabel(A c) {
 // Partitioned dedup: the form qv_sample uses for layer frontiers.
 //
 // The ids of a stage (the seeds, or one hop's sampled neighbours) are split by a hash of the id into
-// P partitions per batch.  One workgroup per (batch, partition) reads the whole stage in position
-// order, tile by tile, keeps only its own ids and finds each one's first position with atomics on
-// a table in LDS; the nodes numbered by earlier stages are loaded into the same table first (from
-// n_id, whose index is the local id), so whether an id is new needs no memory access either.  All
-// random access of the dedup is thereby LDS access: nothing is kept in HBM between stages, and no
-// global atomic is issued per edge.
-//
-// Tiles are processed in order with one barrier each: once every thread has registered tile t,
-// the smallest position of any id that occurs in tiles <= t is final, so tile t's positions can be
-// finished right away:
-//   id numbered earlier            col_local = its local id
-//   first occurrence of a new id   left to k_part_assign, which numbers it
-//   repeat of a new id             col_local = -2 - (first position), resolved by k_relabel_links
-// First occurrences and new nodes are reported as two bit masks per tile and partition (a bit per
-// position; the partitions' masks are disjoint), with their populations, so that k_part_assign can
-// rank them with popcounts.
-//
+// P partitions per batch, and each partition is deduplicated by one workgroup in a table in LDS.
+// All random access of the dedup is thereby LDS access: nothing is kept in HBM between stages, no
+// global atomic is issued per edge, and every global access is a coalesced stream.  Three kernels
+// per stage:
+//   k_part_deal    one workgroup per tile of 4,096 positions: a counting sort of the tile's
+//                  (id, position) records by partition, through LDS, into the tile's own region
+//                  of `dealt`; run_off says where each partition's run starts inside the tile.
+//   k_part_dedup   one workgroup per (batch, partition): loads the nodes numbered by earlier stages
+//                  into its table (from n_id, whose index is the local id; every workgroup reads all
+//                  of n_id and keeps its share), then walks its runs, a wave per tile: pass 1
+//                  registers every record (entry claimed if absent, smallest position by atomicMin),
+//                  pass 2 writes one result word per record, beside it in `result`:
+//                      >= 0   local id of a node numbered earlier | first occurrence in this stage << 30
+//                      -1     first occurrence of a new node (k_part_assign numbers it)
+//                      <= -2  repeat of a new node: -2 - (its first position); k_relabel_links follows it
+//                  and counts the first occurrences and new nodes of every tile (pcount).
+//   k_part_assign  one workgroup per tile: brings the results back into position order through LDS,
+//                  ranks first occurrences and new nodes, writes local ids, n_id, the next frontier.
 // A table that fills beyond kPFillMax (more distinct ids in the partition than LDS holds) makes
-// the workgroup start over with its partition split into 2, 4, ... sub-rounds by further hash
-// bits, one table fill per sub-round; results do not depend on P or on the split.
-// Workgroups are numbered so that the partitions of one batch land on one XCD (workgroup w runs on
-// XCD w mod 8) and share its L2 for the stage's ids.
+// k_part_dedup start over with its partition split into 2, 4, ... sub-rounds by further hash bits,
+// one table fill per sub-round; results do not depend on P or on the split.  Its workgroups are
+// numbered so that the partitions of one batch land on one XCD (workgroup w runs on XCD w mod 8).
 // ---------------------------------------------------------------------------------------------
 __device__ __forceinline__ uint32_t fmix32(uint32_t h) {
     h ^= h >> 16; h *= 0x85EBCA6Bu; h ^= h >> 13; h *= 0xC2B2AE35u; h ^= h >> 16;
     return h;
 }
+// Partition of an id: full-rate shifts and xors only (a 32-bit multiply costs four of them, and
+// k_part_dedup evaluates this for every known node in every workgroup).  Any spread will do:
+// the table index inside a partition comes from fmix32.
 __device__ __forceinline__ uint32_t part_of(uint32_t key, int p_log2) {
-    return p_log2 ? (key * 0x9E3779B1u) >> (32 - p_log2) : 0u;
+    uint32_t h = key ^ (key >> 15);
+    h ^= h >> 7;
+    return h & ((1u << p_log2) - 1u);
 }
 
 // entry of `key` in the LDS table, claiming a free one if absent (then *claimed, the caller's own
@@ -919,42 +931,96 @@ __device__ __forceinline__ PartStage part_stage(const CallHeader& c, const Batch
     return v;
 }
 
+constexpr int32_t kResNone = INT32_MIN;            // k_part_assign: a position that was not dealt (id out of range)
+
+template <typename A>
+__global__ void __launch_bounds__(kPThreads) k_part_deal(A c) {
+    __shared__ uint32_t hist[(1 << kPMaxLog2) + 1], offs[(1 << kPMaxLog2) + 1];
+    __shared__ uint2 sorted[kPTile];
+    const BatchG b(c.batch(blockIdx.y));
+    const int p_log2 = c.p_log2, P = 1 << p_log2;
+    const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const PartStage v = part_stage(c, b);
+    if (c.stage == 0 && blockIdx.x == 0 && tid == 0) {      // first kernel of a call: the size block starts at zero
+        SampleMeta QV_G* m = b.meta;
+        for (int i = 0; i < QV_MAX_HOPS + 2; ++i) { m->node_off[i] = 0; m->frontier_off[i] = 0; }
+        for (int i = 0; i < QV_MAX_HOPS + 1; ++i) m->edge_off[i] = 0;
+        m->stage_range[0] = 0; m->stage_range[1] = b.n_seeds;
+    }
+    const int64_t len = v.end - v.begin;
+    const int n_tiles = (int)((len + kPTile - 1) / kPTile);
+    const int32_t QV_G* ids = v.ids + v.begin;
+    const uint32_t n_valid = c.n_nodes >= 0 ? (uint32_t)c.n_nodes : 0x80000000u;   // ids are valid below this (as unsigned)
+    for (int t = (int)blockIdx.x; t < n_tiles; t += (int)gridDim.x) {
+        const int64_t rel0 = (int64_t)t * kPTile;
+        if (tid <= P) hist[tid] = 0;
+        lds_barrier();
+        uint32_t key[kPKeys], where[kPKeys];                // where = partition << 16 | rank inside the partition's run
+        bool bad = false;
+#pragma unroll
+        for (int i = 0; i < kPKeys; ++i) {
+            const int64_t rel = rel0 + (int64_t)i * kPThreads + tid;
+            key[i] = rel < len ? (uint32_t)ids[rel] : 0xFFFFFFFFu;
+        }
+#pragma unroll
+        for (int i = 0; i < kPKeys; ++i) {
+            const int64_t rel = rel0 + (int64_t)i * kPThreads + tid;
+            where[i] = 0xFFFFFFFFu;
+            if (key[i] < n_valid) {
+                const uint32_t part = part_of(key[i], p_log2);
+                where[i] = (part << 16) | atomicAdd(&hist[part], 1u);
+            } else if (rel < len) {
+                bad = true;
+            }
+        }
+        if (bad) atomicOr((int*)gptr(c.status), kStatRange);
+        lds_barrier();
+        if (wave == 0) {                                    // exclusive scan of the run lengths
+            const uint32_t x = lane < P ? hist[lane] : 0u;
+            uint32_t inc = x;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const uint32_t y = __shfl_up(inc, o);
+                if (lane >= o) inc += y;
+            }
+            if (lane < P) {
+                offs[lane] = inc - x;
+                b.run_off[(size_t)t * (P + 1) + lane] = (uint16_t)(inc - x);
+            }
+            if (lane == P - 1) {
+                offs[P] = inc;
+                b.run_off[(size_t)t * (P + 1) + P] = (uint16_t)inc;
+            }
+        }
+        lds_barrier();
+#pragma unroll
+        for (int i = 0; i < kPKeys; ++i) {
+            if (where[i] == 0xFFFFFFFFu) continue;
+            const uint32_t pos = (uint32_t)(v.begin + rel0 + (int64_t)i * kPThreads + tid);
+            sorted[offs[where[i] >> 16] + (where[i] & 0xFFFFu)] = make_uint2(key[i], pos);
+        }
+        lds_barrier();
+        const uint32_t total = offs[P];
+        for (uint32_t k = (uint32_t)tid; k < total; k += kPThreads) b.dealt[(size_t)t * kPTile + k] = sorted[k];
+        lds_barrier();                                      // hist, offs and sorted are reused by the next tile
+    }
+}
+
 // shared state of one k_part_dedup workgroup
 struct PartLds {
     uint32_t t_key[kPCap];                              // the partition's table: id,
     uint32_t t_min[kPCap];                              //   its smallest position in this stage,
     int32_t t_lid[kPCap];                               //   its local id if an earlier stage numbered it, else -1
-    unsigned long long s_mask[2][2][kPWords];           // [tile parity][first, new][word]
-    uint32_t s_cnt[2][2];                               // [tile parity][first, new]
-    // Entries claimed (an insertion that found the table full adds kPCap, so one test covers both):
-    // s_fill0 by the known nodes, s_fillp[t % 3] by tile t.  A counter is final at the barrier that
-    // ends its phase and is not written again for two tiles, so every thread adds the same values
-    // into its own running total and all threads take the same decision without a second barrier.
-    uint32_t s_fill0, s_fillp[3];
-    // per wave: the ids of the current tile that this partition owns (later: their table entries) and
-    // where they stand (slot << 6 | lane); sized for a tile in which every id is the partition's
-    uint32_t q_key[kPThreads / kWave][kPKeys * kWave];
-    uint16_t q_tag[kPThreads / kWave][kPKeys * kWave];
+    uint32_t run_at[kPMaxTiles + 1];                    // records of this partition before tile t (its runs laid end to end)
+    uint16_t run_beg[kPMaxTiles];                       // where its run starts inside tile t
+    uint32_t cnt_first[kPMaxTiles], cnt_new[kPMaxTiles];// per tile: first occurrences, new nodes
+    uint32_t s_wave[kDThreads / kWave];
+    uint2 queue[kDThreads / kWave][2 * kWave];          // per wave: (id, local id) of known nodes waiting to be inserted
+    uint32_t s_fill;                                    // entries claimed (+ kPCap for every insertion that found the table full)
 };
 
-// masks and populations of tile `pt` of this partition: stored by sub-round 0, merged by later ones
-__device__ __forceinline__ void part_publish(const BatchG& b, PartLds& S, int pt, int P, uint32_t part, uint32_t r, int tid) {
-    const int pb = pt & 1;
-    if (tid < 2 * kPWords) {
-        unsigned long long QV_G* dst = b.pmask + (((size_t)pt * P + part) * 2) * kPWords + tid;
-        const unsigned long long w = S.s_mask[pb][tid / kPWords][tid % kPWords];
-        *dst = r == 0 ? w : (*dst | w);
-        S.s_mask[pb][tid / kPWords][tid % kPWords] = 0;        // bits are OR-ed in by the tile after next
-    }
-    if (tid < 2) {
-        uint32_t QV_G* dst = b.pcount + ((size_t)pt * P + part) * 2 + tid;
-        *dst = r == 0 ? S.s_cnt[pb][tid] : *dst + S.s_cnt[pb][tid];
-        S.s_cnt[pb][tid] = 0;
-    }
-}
-
 template <typename A>
-__global__ void __launch_bounds__(kPThreads) k_part_dedup(A c) {
+__global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 waves per SIMD: two workgroups per CU
     __shared__ PartLds S;
     const int p_log2 = c.p_log2, P = 1 << p_log2;
     const int q = (int)(blockIdx.x >> 3);
@@ -964,183 +1030,178 @@ __global__ void __launch_bounds__(kPThreads) k_part_dedup(A c) {
     const BatchG b(c.batch(batch));
     const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const PartStage v = part_stage(c, b);
-    if (c.stage == 0 && part == 0 && tid == 0) {
-        SampleMeta QV_G* m = b.meta;
-        for (int i = 0; i < QV_MAX_HOPS + 2; ++i) { m->node_off[i] = 0; m->frontier_off[i] = 0; }
-        for (int i = 0; i < QV_MAX_HOPS + 1; ++i) m->edge_off[i] = 0;
-        m->stage_range[0] = 0; m->stage_range[1] = b.n_seeds;
-    }
     const int64_t len = v.end - v.begin;
     const int n_tiles = (int)((len + kPTile - 1) / kPTile);
-    int32_t QV_G* col_local = c.stage > 0 ? b.col_local : nullptr;
-    const int32_t QV_G* ids = v.ids + v.begin;
-    int32_t QV_G* status = gptr(c.status);
-    uint32_t* q_key = S.q_key[wave];
-    uint16_t* q_tag = S.q_tag[wave];
+    // Where this partition's records are: its runs, one per tile, are numbered end to end, so that
+    // the workgroup's threads can share them evenly whatever the runs' lengths (run_at = exclusive
+    // scan of the run lengths).
+    static_assert(kPMaxTiles <= kDThreads, "one tile per thread in the scan below");
+    {
+        uint32_t sum = 0;
+        if (tid < n_tiles) {
+            const uint32_t beg = b.run_off[(size_t)tid * (P + 1) + part];
+            sum = b.run_off[(size_t)tid * (P + 1) + part + 1] - beg;
+            S.run_beg[tid] = (uint16_t)beg;
+        }
+        uint32_t inc = sum;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t y = __shfl_up(inc, o);
+            if (lane >= o) inc += y;
+        }
+        if (lane == kWave - 1) S.s_wave[wave] = inc;
+        lds_barrier();
+        uint32_t pre = 0;
+        for (int w = 0; w < wave; ++w) pre += S.s_wave[w];
+        if (tid < n_tiles) S.run_at[tid] = pre + inc - sum;
+        if (tid == n_tiles - 1) S.run_at[n_tiles] = pre + inc;
+        if (n_tiles == 0 && tid == 0) S.run_at[0] = 0;
+    }
+    lds_barrier();
+    const uint32_t n_rec = S.run_at[n_tiles];
+    // address of record e (0 <= e < n_rec) in `dealt` / `result`, and its tile
+    auto locate = [&](uint32_t e, int* tile) -> size_t {
+        int lo = 0, hi = n_tiles;                               // run_at[lo] <= e < run_at[hi]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (S.run_at[mid] <= e) lo = mid; else hi = mid;
+        }
+        *tile = lo;
+        return (size_t)lo * kPTile + S.run_beg[lo] + (e - S.run_at[lo]);
+    };
     uint32_t fill = 0;
     int split = 0;
-
-    auto load_tile = [&](int t, uint32_t (&dst)[kPKeys]) {
-#pragma unroll
-        for (int i = 0; i < kPKeys; ++i) {
-            const int64_t rel = (int64_t)t * kPTile + (int64_t)i * kPThreads + tid;
-            dst[i] = rel < len ? (uint32_t)ids[rel] : kEmptyKey;
-        }
-    };
-
     for (;; ++split) {
         const uint32_t n_rounds = 1u << split;
         bool failed = false;
         for (uint32_t r = 0; r < n_rounds && !failed; ++r) {
-            lds_barrier();                                      // the table and the counters are still being read
-            // the first tiles' ids: requested before the table is even cleared
-            uint32_t bufA[kPKeys], bufB[kPKeys];
-            load_tile(0, bufA);
-            load_tile(1, bufB);
-            for (int i = tid; i < kPCap; i += kPThreads) { S.t_key[i] = kEmptyKey; S.t_min[i] = 0xFFFFFFFFu; S.t_lid[i] = -1; }
-            if (tid < 4 * kPWords) (&S.s_mask[0][0][0])[tid] = 0;
-            if (tid == 0) {
-                S.s_fill0 = 0; S.s_fillp[0] = 0; S.s_fillp[1] = 0; S.s_fillp[2] = 0;
-                S.s_cnt[0][0] = 0; S.s_cnt[0][1] = 0; S.s_cnt[1][0] = 0; S.s_cnt[1][1] = 0;
-            }
+            lds_barrier();                                      // the table is still being read
+            for (int i = tid; i < kPCap; i += kDThreads) { S.t_key[i] = kEmptyKey; S.t_min[i] = 0xFFFFFFFFu; S.t_lid[i] = -1; }
+            if (r == 0) for (int t = tid; t < n_tiles; t += kDThreads) { S.cnt_first[t] = 0; S.cnt_new[t] = 0; }
+            if (tid == 0) S.s_fill = 0;
             lds_barrier();
-            // nodes numbered by earlier stages: local id = index in n_id (eight reads in flight per thread)
-            uint32_t claimed0 = 0;
-            for (int64_t u0 = 0; u0 < v.known; u0 += (int64_t)kPThreads * kPKeys) {
-                uint32_t k[kPKeys];
+            // Nodes numbered by earlier stages: local id = index in n_id.  Every workgroup reads all of
+            // n_id and keeps its share, about one id in P: a wave collects its share in a small queue
+            // in LDS and inserts 64 at a time with all lanes busy (inserting them where they stand,
+            // a lane or two per instruction, cost more than everything else in this kernel).
+            uint32_t claimed = 0;
+            {
+                uint2* queue = S.queue[wave];
+                uint32_t qn = 0;                                // wave-uniform
+                auto insert_front = [&](uint32_t n) {           // the first n (<= 64) queue entries
+                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // written by other lanes of the wave
+                    if ((uint32_t)lane < n) {
+                        const uint2 e = queue[lane];
+                        const int s2 = lds_insert(S.t_key, e.x, fmix32(e.x) & (kPCap - 1), &claimed);
+                        if (s2 < 0) claimed += (uint32_t)kPCap;
+                        else S.t_lid[s2] = (int32_t)e.y;
+                    }
+                };
+                uint32_t nxt[kDKeys];
 #pragma unroll
-                for (int i = 0; i < kPKeys; ++i) {
-                    const int64_t u = u0 + (int64_t)i * kPThreads + tid;
-                    k[i] = u < v.known ? (uint32_t)b.n_id[u] : kEmptyKey;
+                for (int i = 0; i < kDKeys; ++i) {
+                    const int64_t u = (int64_t)i * kDThreads + tid;
+                    nxt[i] = u < v.known ? (uint32_t)b.n_id[u] : kEmptyKey;
+                }
+                for (int64_t u0 = 0; u0 < v.known; u0 += (int64_t)kDThreads * kDKeys) {
+                    uint32_t k[kDKeys];
+#pragma unroll
+                    for (int i = 0; i < kDKeys; ++i) {          // this round's ids; the next round's are requested now
+                        k[i] = nxt[i];
+                        const int64_t u = u0 + (int64_t)kDThreads * kDKeys + (int64_t)i * kDThreads + tid;
+                        nxt[i] = u < v.known ? (uint32_t)b.n_id[u] : kEmptyKey;
+                    }
+#pragma unroll
+                    for (int i = 0; i < kDKeys; ++i) {
+                        const int64_t u = u0 + (int64_t)i * kDThreads + tid;
+                        bool own = u < v.known && part_of(k[i], p_log2) == part;
+                        if (own && split && (fmix32(k[i]) >> (32 - split)) != r) own = false;
+                        const unsigned long long m = __ballot(own);
+                        if (own) queue[qn + __mbcnt_hi((uint32_t)(m >> 32), __mbcnt_lo((uint32_t)m, 0u))] = make_uint2(k[i], (uint32_t)u);
+                        qn += (uint32_t)__popcll(m);
+                        if (qn >= kWave) {
+                            insert_front(kWave);
+                            const uint2 rest = queue[kWave + lane];         // what did not fit the batch moves to the front
+                            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                            qn -= kWave;
+                            if ((uint32_t)lane < qn) queue[lane] = rest;
+                        }
+                    }
+                }
+                insert_front(qn);
+            }
+            // pass 1: register every record (eight per thread requested together)
+            for (uint32_t e0 = 0; e0 < n_rec; e0 += kDThreads * kDKeys) {
+                uint2 rec[kDKeys];
+#pragma unroll
+                for (int i = 0; i < kDKeys; ++i) {
+                    const uint32_t e = e0 + (uint32_t)(i * kDThreads + tid);
+                    int tile;
+                    rec[i] = make_uint2(kEmptyKey, 0u);
+                    if (e < n_rec) rec[i] = b.dealt[locate(e, &tile)];
                 }
 #pragma unroll
-                for (int i = 0; i < kPKeys; ++i) {
-                    const int64_t u = u0 + (int64_t)i * kPThreads + tid;
-                    if (u >= v.known || part_of(k[i], p_log2) != part) continue;
-                    const uint32_t h = fmix32(k[i]);
+                for (int i = 0; i < kDKeys; ++i) {
+                    if (rec[i].x == kEmptyKey) continue;
+                    const uint32_t h = fmix32(rec[i].x);
                     if (split && (h >> (32 - split)) != r) continue;
-                    const int s2 = lds_insert(S.t_key, k[i], h & (kPCap - 1), &claimed0);
-                    if (s2 < 0) claimed0 += (uint32_t)kPCap;
-                    else S.t_lid[s2] = (int32_t)u;
+                    const int s2 = lds_insert(S.t_key, rec[i].x, h & (kPCap - 1), &claimed);
+                    if (s2 < 0) claimed += (uint32_t)kPCap;
+                    else atomicMin(&S.t_min[s2], rec[i].y);
                 }
             }
-            if (claimed0) atomicAdd(&S.s_fill0, claimed0);
+            if (claimed) atomicAdd(&S.s_fill, claimed);
             lds_barrier();
-            fill = S.s_fill0;
+            fill = S.s_fill;
             if (fill > kPFillMax) { failed = true; break; }
-
-            // One tile: returns false when the table overflowed (decided identically by every thread).
-            // A wave first moves the ids it owns (about 1/P of its 512) into its own queue in LDS, then
-            // works through the queue with all lanes busy: handling them where they stand, a few
-            // active lanes per instruction, made the kernel instruction-bound.
-            auto do_tile = [&](int t, const uint32_t (&cur)[kPKeys]) -> bool {
-                const int64_t rel0 = (int64_t)t * kPTile;
-                uint32_t n_own = 0;                             // wave-uniform
+            // pass 2: every id's smallest position is final
+            for (uint32_t e0 = 0; e0 < n_rec; e0 += kDThreads * kDKeys) {
+                uint2 rec[kDKeys];
+                size_t at[kDKeys];
+                int tile[kDKeys];
 #pragma unroll
-                for (int i = 0; i < kPKeys; ++i) {
-                    const int64_t rel = rel0 + (int64_t)i * kPThreads + tid;
-                    const uint32_t key = cur[i];
-                    bool own = rel < len && part_of(key, p_log2) == part;
-                    if (own && ((int32_t)key < 0 || (c.n_nodes >= 0 && (int64_t)key >= c.n_nodes))) {
-                        // an id out of range is finished here: local id -1, never a first occurrence
-                        if (r == 0) {
-                            atomicOr((int*)status, kStatRange);
-                            if (col_local) col_local[v.begin + rel] = -1;
-                        }
-                        own = false;
-                    }
-                    if (own && split && (fmix32(key) >> (32 - split)) != r) own = false;
-                    const unsigned long long m = __ballot(own);
-                    if (own) {
-                        const uint32_t e = n_own + __mbcnt_hi((uint32_t)(m >> 32), __mbcnt_lo((uint32_t)m, 0u));
-                        q_key[e] = key;
-                        q_tag[e] = (uint16_t)((i << 6) | lane);
-                    }
-                    n_own += (uint32_t)__popcll(m);
+                for (int i = 0; i < kDKeys; ++i) {
+                    const uint32_t e = e0 + (uint32_t)(i * kDThreads + tid);
+                    rec[i] = make_uint2(kEmptyKey, 0u); at[i] = 0; tile[i] = 0;
+                    if (e < n_rec) { at[i] = locate(e, &tile[i]); rec[i] = b.dealt[at[i]]; }
                 }
-                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // the queue is read by other lanes of the wave
-                // register them: entry (claimed if absent), smallest position; the entry replaces the id in the queue
-                uint32_t claimed = 0;
-                for (uint32_t e0 = 0; e0 < n_own; e0 += kWave) {
-                    const uint32_t e = e0 + (uint32_t)lane;
-                    if (e < n_own) {
-                        const uint32_t key = q_key[e], tag = q_tag[e];
-                        const uint32_t pos = (uint32_t)(v.begin + rel0) + (tag >> 6) * kPThreads + (uint32_t)(wave * kWave) + (tag & 63u);
-                        const int s2 = lds_insert(S.t_key, key, fmix32(key) & (kPCap - 1), &claimed);
-                        if (s2 < 0) {
-                            claimed += (uint32_t)kPCap;
-                        } else {
-                            atomicMin(&S.t_min[s2], pos);
-                            q_key[e] = (uint32_t)s2;
-                        }
+#pragma unroll
+                for (int i = 0; i < kDKeys; ++i) {
+                    if (rec[i].x == kEmptyKey) continue;
+                    uint32_t x = fmix32(rec[i].x);
+                    if (split && (x >> (32 - split)) != r) continue;
+                    x &= kPCap - 1;
+                    while (S.t_key[x] != rec[i].x) x = (x + 1) & (kPCap - 1);         // pass 1 put it there
+                    const uint32_t mp = S.t_min[x];
+                    const int32_t lid = S.t_lid[x];
+                    const bool first = mp == rec[i].y;
+                    b.result[at[i]] = lid >= 0 ? (lid | (first ? 1 << 30 : 0)) : first ? -1 : -2 - (int32_t)mp;
+                    if (first) {
+                        atomicAdd(&S.cnt_first[tile[i]], 1u);
+                        if (lid < 0) atomicAdd(&S.cnt_new[tile[i]], 1u);
                     }
                 }
-                if (claimed) atomicAdd(&S.s_fillp[t % 3], claimed);
-                lds_barrier();
-                fill += S.s_fillp[t % 3];
-                if (fill > kPFillMax) return false;
-                if (tid == 0) S.s_fillp[(t + 2) % 3] = 0;       // tile t-1's counter: read by all, next used by tile t+2
-                // the previous tile's masks and counts are complete: publish them
-                if (t > 0) part_publish(b, S, t - 1, P, part, r, tid);
-                // finish this tile's positions
-                uint32_t cf = 0, cn = 0;
-                for (uint32_t e0 = 0; e0 < n_own; e0 += kWave) {
-                    const uint32_t e = e0 + (uint32_t)lane;
-                    uint32_t first = 0, isnew = 0;
-                    if (e < n_own) {
-                        const uint32_t s2 = q_key[e], tag = q_tag[e];
-                        const uint32_t pos = (uint32_t)(v.begin + rel0) + (tag >> 6) * kPThreads + (uint32_t)(wave * kWave) + (tag & 63u);
-                        const uint32_t mp = S.t_min[s2];
-                        const int32_t lid = S.t_lid[s2];
-                        first = mp == pos ? 1u : 0u;
-                        isnew = (first && lid < 0) ? 1u : 0u;
-                        if (col_local) {
-                            if (lid >= 0) col_local[pos] = lid;
-                            else if (!first) col_local[pos] = -2 - (int32_t)mp;
-                        }
-                        if (first) {
-                            const int word = (int)(tag >> 6) * (kPThreads / kWave) + wave;
-                            const unsigned long long bit = 1ull << (tag & 63u);
-                            atomicOr(&S.s_mask[t & 1][0][word], bit);
-                            if (isnew) atomicOr(&S.s_mask[t & 1][1][word], bit);
-                        }
-                    }
-                    cf += (uint32_t)__popcll(__ballot(first));
-                    cn += (uint32_t)__popcll(__ballot(isnew));
-                }
-                if (lane == 0 && (cf | cn)) { atomicAdd(&S.s_cnt[t & 1][0], cf); atomicAdd(&S.s_cnt[t & 1][1], cn); }
-                return true;
-            };
-
-            // tiles in order, two buffers: a tile's ids are requested two tiles before they are used
-            for (int t = 0; t < n_tiles; t += 2) {
-                uint32_t cur[kPKeys];
-#pragma unroll
-                for (int i = 0; i < kPKeys; ++i) cur[i] = bufA[i];
-                load_tile(t + 2, bufA);
-                if (!do_tile(t, cur)) { failed = true; break; }
-                if (t + 1 >= n_tiles) break;
-#pragma unroll
-                for (int i = 0; i < kPKeys; ++i) cur[i] = bufB[i];
-                load_tile(t + 3, bufB);
-                if (!do_tile(t + 1, cur)) { failed = true; break; }
             }
-            if (failed) break;
-            lds_barrier();
-            if (n_tiles > 0) part_publish(b, S, n_tiles - 1, P, part, r, tid);
         }
         if (!failed) break;
         if (split == kPMaxSplit) {                              // 2^12 sub-rounds were not enough: give up loudly
-            if (tid == 0) atomicOr((int*)status, kStatCapacity);
+            if (tid == 0) atomicOr((int*)gptr(c.status), kStatCapacity);
             break;
         }
     }
+    lds_barrier();
+    for (int t = tid; t < n_tiles; t += kDThreads) {
+        b.pcount[((size_t)t * P + part) * 2] = S.cnt_first[t];
+        b.pcount[((size_t)t * P + part) * 2 + 1] = S.cnt_new[t];
+    }
     // what the host's choice of the partition count goes by: fullest table, deepest split
     if (tid == 0 && c.part_stats) {
+        // (looked at first: a thousand workgroups' atomics on one word would queue up behind each other,
+        // and once a few calls have run hardly any workgroup has anything new to report)
         uint32_t QV_G* st = gptr(c.part_stats);
-        if (split == 0) atomicMax((uint32_t*)&st[0], fill);
-        else atomicMax((uint32_t*)&st[1], (uint32_t)split);
-        st[2] = (uint32_t)p_log2 + 1u;
+        if (split == 0) { if (fill > st[0]) atomicMax((uint32_t*)&st[0], fill); }
+        else if ((uint32_t)split > st[1]) atomicMax((uint32_t*)&st[1], (uint32_t)split);
+        if (st[2] != (uint32_t)p_log2 + 1u) st[2] = (uint32_t)p_log2 + 1u;
     }
 }
 
@@ -1151,9 +1212,10 @@ __global__ void __launch_bounds__(kPThreads) k_part_dedup(A c) {
 // hop's frontier entries (row extent read here; segment offset relative to the tile, the tile's
 // total in tile_seg), the caller's frontier array, the sizes.
 // ---------------------------------------------------------------------------------------------
-template <typename RP, typename A>
-__global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
-    __shared__ unsigned long long m_first[kPWords], m_new[kPWords];
+template <typename RP, bool kNext, typename A>     // kNext: a next hop exists (frontier entries with row extents are built)
+__global__ void __launch_bounds__(kPThreads, 4) k_part_assign(A c) {    // 4 waves per SIMD: two workgroups per CU
+    __shared__ int32_t res[kPTile];                             // k_part_dedup's result word of every position of the tile
+    __shared__ unsigned long long m_first[kPWords], m_new[kPWords];   // bit per position: first occurrence, new node
     __shared__ uint32_t pre_first[kPWords], pre_new[kPWords];
     __shared__ uint32_t seg_tot[kPWords], seg_pre[kPWords];
     __shared__ uint32_t red[kPThreads / kWave][2];
@@ -1180,17 +1242,27 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
 #pragma unroll
     for (int o = kWave / 2; o > 0; o >>= 1) { bf += __shfl_down(bf, o); bn += __shfl_down(bn, o); }
     if (lane == 0) { red[wave][0] = bf; red[wave][1] = bn; }
-    if (tid < kPWords) { m_first[tid] = 0; m_new[tid] = 0; }
+    for (int k = tid; k < kPTile; k += kPThreads) res[k] = kResNone;
     lds_barrier();
     uint32_t base_first = 0, base_new = 0;
     for (int w = 0; w < kPThreads / kWave; ++w) { base_first += red[w][0]; base_new += red[w][1]; }
-    // this tile's masks: OR over the partitions
+    // the tile's records are sorted by partition: bring their results back into position order
     if (have_tile) {
-        const int which = (tid / kPWords) & 1, w = tid % kPWords, j0 = tid / (2 * kPWords);
-        unsigned long long acc = 0;
-        for (int j = j0; j < P; j += kPThreads / (2 * kPWords))
-            acc |= b.pmask[(((size_t)t * P + j) * 2 + which) * kPWords + w];
-        if (acc) atomicOr(which ? &m_new[w] : &m_first[w], acc);
+        const uint32_t total = b.run_off[(size_t)t * (P + 1) + P];
+        const uint32_t pos0 = (uint32_t)(v.begin + rel0);
+        for (uint32_t k = (uint32_t)tid; k < total; k += kPThreads) {
+            const uint2 rec = b.dealt[(size_t)t * kPTile + k];
+            res[(rec.y - pos0) & (kPTile - 1)] = b.result[(size_t)t * kPTile + k];
+        }
+    }
+    lds_barrier();
+    int32_t rr[kPKeys];
+#pragma unroll
+    for (int i = 0; i < kPKeys; ++i) {
+        rr[i] = res[i * kPThreads + tid];
+        const bool first = rr[i] == -1 || (rr[i] >= 0 && ((rr[i] >> 30) & 1));
+        const unsigned long long mf = __ballot(first), mn = __ballot(rr[i] == -1);
+        if (lane == 0) { m_first[i * (kPThreads / kWave) + wave] = mf; m_new[i * (kPThreads / kWave) + wave] = mn; }
     }
     lds_barrier();
     if (wave < 2) {                                             // exclusive popcount prefixes over the 64 words
@@ -1221,10 +1293,14 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
         id[i] = 0; lid[i] = -1; rs[i] = 0; deg[i] = 0;
         if (first) {
             id[i] = v.ids[v.begin + rel];
-            if (!isnew && c.stage > 0) lid[i] = b.col_local[v.begin + rel];
+            if (!isnew) lid[i] = rr[i] & 0x3FFFFFFF;
         }
+        // local id of every position that has one by now; a repeat of a new node keeps its link, a
+        // position that was not dealt (id out of range) gets -1; new nodes are numbered below
+        if (c.stage > 0 && rel < len && rr[i] != -1)
+            b.col_local[v.begin + rel] = rr[i] >= 0 ? (rr[i] & 0x3FFFFFFF) : rr[i] == kResNone ? -1 : rr[i];
     }
-    if (c.next_fanout > 0) {
+    if (kNext) {
 #pragma unroll
         for (int i = 0; i < kPKeys; ++i) {
             if ((flags >> i) & 1u) {
@@ -1234,10 +1310,11 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
         }
     }
     // next-hop segment sizes, scanned in position order: within the wave here, across (slab, wave) below
+    if (kNext) {
 #pragma unroll
     for (int i = 0; i < kPKeys; ++i) {
         uint32_t seg = 0;
-        if (((flags >> i) & 1u) && c.next_fanout > 0) seg = deg[i] < (uint32_t)c.next_fanout ? deg[i] : (uint32_t)c.next_fanout;
+        if ((flags >> i) & 1u) seg = deg[i] < (uint32_t)c.next_fanout ? deg[i] : (uint32_t)c.next_fanout;
         uint32_t inc = seg;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) {
@@ -1260,6 +1337,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
         if (lane == kWave - 1) s_tot[2] = inc;
     }
     lds_barrier();
+    }
     const uint32_t tot_first = have_tile ? s_tot[0] : 0u, tot_new = have_tile ? s_tot[1] : 0u;
     const int64_t fr_user_base = c.frontier_restart ? 0 : fr_base;
 #pragma unroll
@@ -1277,7 +1355,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
             else atomicOr(c.status, kStatCapacity);
             if (c.stage > 0) b.col_local[pos] = l;
         }
-        if (c.next_fanout > 0) {
+        if (kNext) {
             if (fr_base + j < b.fr_cap) {
                 b.fr_id[fr_base + j] = id[i];
                 b.fr_lid[fr_base + j] = l;
@@ -1295,7 +1373,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_assign(A c) {
         }
     }
     if (tid == 0) {
-        if (have_tile) b.tile_seg[t] = s_tot[2];
+        if (kNext && have_tile) b.tile_seg[t] = s_tot[2];
         if (rel0 + kPTile >= len) {                             // the stage's last tile
             m->node_off[c.stage + 1] = node_base + base_new + tot_new;
             m->frontier_off[c.stage + 1] = fr_base + base_first + tot_first;
@@ -1497,7 +1575,10 @@ static size_t per_batch_bytes(const Layout& L) {
         const size_t cells = (size_t)L.p_tiles << L.p_log2;                 // (tile, partition) pairs
         t += align_up((size_t)L.edges * 4);                                 // nbr
         t += 4 * align_up((size_t)L.frontier * 4) + align_up((size_t)L.frontier * 8) + align_up((size_t)L.frontier * 2);
-        t += align_up(cells * 2 * kPWords * 8) + align_up(cells * 2 * 4) + align_up((size_t)L.p_tiles * 4);
+        const size_t slots = (size_t)L.p_tiles * kPTile;                    // records of the largest stage
+        t += align_up(slots * 8) + align_up(slots * 4);                     // dealt, result
+        t += align_up(((size_t)L.p_tiles << L.p_log2) * 2 + (size_t)L.p_tiles * 2);     // run_off
+        t += align_up(cells * 2 * 4) + align_up((size_t)L.p_tiles * 4);     // pcount, tile_seg
         return t + 2048;
     }
     t += align_up((size_t)L.stage0 * 4) + align_up((size_t)L.stage0 * 2);   // seed_slot, seed_flags
@@ -1519,14 +1600,17 @@ static bool carve(qv_ctx* ctx, const Layout& L, BatchArgs* b) {
         b->fr_deg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
         b->fr_seg = (uint32_t*)arena_take(ctx, (size_t)L.frontier * 4);
         b->fr_tile = (uint16_t*)arena_take(ctx, (size_t)L.frontier * 2);
-        b->pmask = (unsigned long long*)arena_take(ctx, cells * 2 * kPWords * 8);
+        const size_t slots = (size_t)L.p_tiles * kPTile;
+        b->dealt = (uint2*)arena_take(ctx, slots * 8);
+        b->result = (int32_t*)arena_take(ctx, slots * 4);
+        b->run_off = (uint16_t*)arena_take(ctx, ((size_t)L.p_tiles << L.p_log2) * 2 + (size_t)L.p_tiles * 2);
         b->pcount = (uint32_t*)arena_take(ctx, cells * 2 * 4);
         b->tile_seg = (uint32_t*)arena_take(ctx, (size_t)L.p_tiles * 4);
         b->fr_cap = L.frontier;
-        return b->meta && b->nbr && b->fr_id && b->fr_lid && b->fr_rs && b->fr_deg && b->fr_seg && b->fr_tile && b->pmask &&
+        return b->meta && b->nbr && b->fr_id && b->fr_lid && b->fr_rs && b->fr_deg && b->fr_seg && b->fr_tile && b->dealt && b->result && b->run_off &&
                b->pcount && b->tile_seg;
     }
-    b->pmask = nullptr; b->pcount = nullptr; b->tile_seg = nullptr; b->fr_tile = nullptr;
+    b->dealt = nullptr; b->result = nullptr; b->run_off = nullptr; b->pcount = nullptr; b->tile_seg = nullptr; b->fr_tile = nullptr;
     b->seed_slot = (uint32_t*)arena_take(ctx, (size_t)L.stage0 * 4);
     b->seed_flags = (uint16_t*)arena_take(ctx, (size_t)L.stage0 * 2);
     b->slot_of = (uint32_t*)arena_take(ctx, (size_t)L.edges * 4);
@@ -1688,16 +1772,25 @@ static qv_status plan_sample(qv_ctx* ctx, int64_t max_seeds, const int32_t* fano
 
 static qv_status launch_part_dedup(qv_ctx* ctx, CallArgs& c, int rowptr_bits, int64_t max_items, int n_batches) {
     const int P = 1 << c.p_log2;
-    const unsigned wgs = 8u * (unsigned)((n_batches + 7) / 8) * (unsigned)P;    // (XCD, batch within XCD, partition)
-    QV_LAUNCH_A(ctx, c, n_batches, dim3(wgs), dim3(kPThreads), k_part_dedup);
     int64_t tiles = (max_items + kPTile - 1) / kPTile;
     if (tiles < 1) tiles = 1;
-    const int64_t cap = n_batches >= 4 ? ctx->n_cu * 8 / n_batches : ctx->n_cu * 2;   // a-priori bounds are loose: most tiles do not exist
-    if (tiles > cap) tiles = cap;
     dim3 grid((unsigned)tiles, (unsigned)n_batches);
-    if (rowptr_bits == 32) QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kPThreads), k_part_assign, int32_t);
-    else QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(kPThreads), k_part_assign, int64_t);
-    QV_LAUNCH_CHECK(ctx, "k_part_dedup / k_part_assign");
+    {   // the a-priori bounds are loose (most tiles do not exist): k_part_deal strides over the tiles
+        const int64_t cap = n_batches >= 4 ? ctx->n_cu * 8 / n_batches : ctx->n_cu * 2;
+        dim3 deal_grid((unsigned)(tiles < cap ? tiles : cap), (unsigned)n_batches);
+        QV_LAUNCH_A(ctx, c, n_batches, deal_grid, dim3(kPThreads), k_part_deal);
+    }
+    const unsigned wgs = 8u * (unsigned)((n_batches + 7) / 8) * (unsigned)P;    // (XCD, batch within XCD, partition)
+    QV_LAUNCH_A(ctx, c, n_batches, dim3(wgs), dim3(kDThreads), k_part_dedup);
+    const bool next = c.next_fanout > 0;
+    if (rowptr_bits == 32) {
+        if (next) QV_LAUNCH_FORM(ctx, c, n_batches, grid, dim3(kPThreads), (k_part_assign<int32_t, true, CallInline>), (k_part_assign<int32_t, true, CallDevice>));
+        else QV_LAUNCH_FORM(ctx, c, n_batches, grid, dim3(kPThreads), (k_part_assign<int32_t, false, CallInline>), (k_part_assign<int32_t, false, CallDevice>));
+    } else {
+        if (next) QV_LAUNCH_FORM(ctx, c, n_batches, grid, dim3(kPThreads), (k_part_assign<int64_t, true, CallInline>), (k_part_assign<int64_t, true, CallDevice>));
+        else QV_LAUNCH_FORM(ctx, c, n_batches, grid, dim3(kPThreads), (k_part_assign<int64_t, false, CallInline>), (k_part_assign<int64_t, false, CallDevice>));
+    }
+    QV_LAUNCH_CHECK(ctx, "k_part_deal / k_part_dedup / k_part_assign");
     return QV_OK;
 }
 
