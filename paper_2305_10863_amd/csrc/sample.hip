@@ -367,6 +367,7 @@ constexpr int kPCap = 1 << kPCapLog2;               // entries of a partition's 
 constexpr uint32_t kPFillMax = kPCap / 8 * 7;       // a table fuller than this splits its partition further
 constexpr int kPMaxTiles = 1024;                    // tiles per stage and batch (larger stages use the table forms)
 constexpr int kPMaxLog2 = 6;                        // at most 64 partitions per batch
+constexpr int kPMaxProbes = 128;                    // longer probe sequences count as overflow (unheard of below kPFillMax)
 constexpr int kPMaxSplit = 12;                      // a partition is split into at most 2^12 sub-rounds
 constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
 
@@ -893,10 +894,11 @@ __device__ __forceinline__ uint32_t part_of(uint32_t key, int p_log2) {
 }
 
 // entry of `key` in the LDS table, claiming a free one if absent (then *claimed, the caller's own
-// counter, goes up by one); -1 when the table is full
+// counter, goes up by one); -1 when none is found within kPMaxProbes entries, which callers treat
+// like a full table (a table filling up would otherwise be walked end to end by every insertion)
 __device__ __forceinline__ int lds_insert(uint32_t* t_key, uint32_t key, uint32_t start, uint32_t* claimed) {
     uint32_t s = start;
-    for (int probes = 0; probes < kPCap; ++probes) {
+    for (int probes = 0; probes < kPMaxProbes; ++probes) {
         uint32_t cur = t_key[s];
         if (cur == kEmptyKey) {
             cur = atomicCAS(&t_key[s], kEmptyKey, key);
@@ -1097,22 +1099,16 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                         else S.t_lid[s2] = (int32_t)e.y;
                     }
                 };
-                uint32_t nxt[kDKeys];
+                constexpr int kPre = 12;                        // ids a thread requests together (their latency is the loop's time)
+                for (int64_t u0 = 0; u0 < v.known; u0 += (int64_t)kDThreads * kPre) {
+                    uint32_t k[kPre];
 #pragma unroll
-                for (int i = 0; i < kDKeys; ++i) {
-                    const int64_t u = (int64_t)i * kDThreads + tid;
-                    nxt[i] = u < v.known ? (uint32_t)b.n_id[u] : kEmptyKey;
-                }
-                for (int64_t u0 = 0; u0 < v.known; u0 += (int64_t)kDThreads * kDKeys) {
-                    uint32_t k[kDKeys];
-#pragma unroll
-                    for (int i = 0; i < kDKeys; ++i) {          // this round's ids; the next round's are requested now
-                        k[i] = nxt[i];
-                        const int64_t u = u0 + (int64_t)kDThreads * kDKeys + (int64_t)i * kDThreads + tid;
-                        nxt[i] = u < v.known ? (uint32_t)b.n_id[u] : kEmptyKey;
+                    for (int i = 0; i < kPre; ++i) {
+                        const int64_t u = u0 + (int64_t)i * kDThreads + tid;
+                        k[i] = u < v.known ? (uint32_t)b.n_id[u] : kEmptyKey;
                     }
 #pragma unroll
-                    for (int i = 0; i < kDKeys; ++i) {
+                    for (int i = 0; i < kPre; ++i) {
                         const int64_t u = u0 + (int64_t)i * kDThreads + tid;
                         bool own = u < v.known && part_of(k[i], p_log2) == part;
                         if (own && split && (fmix32(k[i]) >> (32 - split)) != r) own = false;
@@ -1756,7 +1752,7 @@ static qv_status plan_sample(qv_ctx* ctx, int64_t max_seeds, const int32_t* fano
     const int64_t max_stage = (int64_t)kPTile * kPMaxTiles;
     int64_t largest = max_seeds;
     for (int k = 1; k <= n_hops; ++k) largest = bd->hop_edges[k] > largest ? bd->hop_edges[k] : largest;
-    L->part = ctx->dedup_form == QV_DEDUP_PARTITIONED && !cumulative && largest <= max_stage;   // AUTO: tables, until the partitioned form is the faster one
+    L->part = ctx->dedup_form != QV_DEDUP_TABLE && !cumulative && largest <= max_stage;
     if (L->part) {
         L->p_tiles = (largest + kPTile - 1) / kPTile;
         if (L->p_tiles < 1) L->p_tiles = 1;
