@@ -27,6 +27,7 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 # Only quoted for the configurations that were profiled.
 GATHER_TRAFFIC_RATIO = {("citation", 1.0, 32): 0.969, ("dense_social", 1.0, 32): 1.024, ("co_purchase", 1.0, 32): 1.160,
                         ("citation", 1.0, 8): 0.972, ("dense_social", 1.0, 8): 1.024, ("co_purchase", 1.0, 8): 1.160}
+GATHER_TRAFFIC_PROFILE = "profiles/ (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 of k_gather over its algorithmic bytes, same workload and batches per call)"
 
 
 def log(msg):
@@ -182,13 +183,14 @@ def main():
     ap.add_argument("--workload", default="citation")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the workload (debugging only)")
     ap.add_argument("--streams", type=int, default=1, help="batches in flight (one context per stream)")
-    ap.add_argument("--extra-streams", type=int, default=4,
-                    help="after the timed region, run the same batches again over this many streams and report "
-                         "that throughput beside the main figure (0 = skip; only when --streams is 1)")
-    ap.add_argument("--batches-per-call", type=int, default=32,
-                    help="independent batches per qv_sample_many / qv_gather_many call (1..32)")
+    ap.add_argument("--extra-streams", type=int, default=16,
+                    help="after the timed region, time the same region over 1, 2, 4, 8, 16 streams up to this many and "
+                         "report ms per step for each (0 = skip; only when --streams is 1)")
+    ap.add_argument("--batches-per-call", type=int, default=64,
+                    help="independent batches per qv_sample_many / qv_gather_many call (1..64)")
+    ap.add_argument("--latency-samples", type=int, default=200, help="single-batch calls timed for p50 / p99 (at least 200)")
     ap.add_argument("--table-budget-gib", type=float, default=-1.0,
-                    help="dedup table budget per context in GiB (0 = always hash; default: 64 with one stream, else the library's 16)")
+                    help="dedup table budget per context in GiB for the table forms (0 = always hash; default: the library's 16)")
     ap.add_argument("--dedup", default="auto", choices=["auto", "table", "partitioned"],
                     help="dedup form of qv_sample (qv_ctx_set_dedup); results are identical")
     ap.add_argument("--partitions-log2", type=int, default=-1, help="partitions per batch of the partitioned form (-1: per call)")
@@ -337,143 +339,163 @@ def main():
         return placement_ablation(qv, qvgen, w, ctx0, g, table_for_ablation, Pdev, rowptr, col, tdtype)
 
     # ---- batches, contexts, buffers -------------------------------------------------------------
+    # The timed region is a whole number of full calls (never a short call: --steps is rounded up to
+    # calls of B batches), repeated until at least 50 ms have been timed; the median region gives
+    # the figures.  Warm-up runs every timed batch once, so that nothing is touched for the first time
+    # inside the region.
     import copy
+    import math
     B = max(1, min(args.batches_per_call, qv.QV_MAX_BATCHES))
-    n_batches = K + W
+    calls_per_region = max(1, math.ceil(K / B))
+    calls_per_region = math.ceil(calls_per_region / S) * S          # every stream gets the same number of calls
+    n_batches = calls_per_region * B
     seeds_host = [w.seeds(b, batch) for b in range(n_batches)]
     seeds_dev = [torch.from_numpy(s).cuda() for s in seeds_host]
     rng_seeds = [w.rng_seed(b) for b in range(n_batches)]
-    ctxs = [ctx0] + [qv.Context(0, torch.cuda.Stream()) for _ in range(S - 1)]
+    dedup_form = {"auto": 0, "table": 1, "partitioned": 2}[args.dedup]
     nb, eb, fb = qv.qv_sample_bounds(batch, w.fanouts, w.n)
-    bufs, rows = [], []
-    for c in ctxs:
-        # one context: let all its batches have directly addressed dedup tables (32 x 1.78 GB on the
-        # citation graph, a fifth of the 288 GB); several contexts keep the library's 16 GiB each
-        budget_gib = args.table_budget_gib if args.table_budget_gib >= 0 else (64.0 if S == 1 else -1.0)
-        if budget_gib >= 0:
-            c.set_table_budget(int(budget_gib * 2 ** 30))
-        c.set_dedup({"auto": 0, "table": 1, "partitioned": 2}[args.dedup], args.partitions_log2)
-        c.reserve(batch, w.fanouts, w.n, n_batches=B)
-        bufs.append([qv.SampleBuffers(c, batch, w.fanouts, w.n) for _ in range(B)])
-        rows.append([feat.empty_rows(nb, "cuda") for _ in range(B)])
     Kh = len(w.fanouts)
-    # per-step size blocks so that counts can be read after the timed region
+    L = qv.lib()
+
+    made_contexts = []
+
+    def new_context(stream):
+        c = qv.Context(0, stream)
+        made_contexts.append(c)
+        if args.table_budget_gib >= 0:
+            c.set_table_budget(int(args.table_budget_gib * 2 ** 30))
+        c.set_dedup(dedup_form, args.partitions_log2)
+        c.reserve(batch, w.fanouts, w.n, n_batches=B)
+        return c
+
+    # output rows are sized from what the batches really produce (the a-priori node bound is 15 x
+    # larger on the citation workload); the sizes of every timed batch are checked against it below
+    ctx0.set_dedup(dedup_form, args.partitions_log2)
+    probe = [qv.qv_sample(ctx0, g, seeds_dev[i], w.fanouts, rng_seeds[i]) for i in range(min(4, n_batches))]
+    ctx0.sync()
+    row_cap = min(nb, 2 * max(int(o.node_off[-1].item()) for o in probe) + 1024)
+    del probe
+
+    class Lane:
+        """One context (stream) with the buffers of one call."""
+        def __init__(self, ctx):
+            self.ctx = ctx
+            self.bufs = [qv.SampleBuffers(ctx, batch, w.fanouts, w.n, want_frontier=False, want_nbr_global=False)
+                         for _ in range(B)]
+            self.rows = [feat.empty_rows(row_cap, "cuda") for _ in range(B)]
+            self.plan = qv.ManyPlan(ctx, g, feat, self.bufs, self.rows, w.fanouts)
+            for t in range(B):
+                self.plan.n_ids[t] = row_cap
+
+    lanes = [Lane(ctx0 if i == 0 else new_context(torch.cuda.Stream())) for i in range(S)]
+    if S >= 1:
+        if args.table_budget_gib >= 0:
+            ctx0.set_table_budget(int(args.table_budget_gib * 2 ** 30))
+        ctx0.reserve(batch, w.fanouts, w.n, n_batches=B)
+    # per-batch size blocks so that counts can be read after the timed region
     offs = [(torch.zeros(Kh + 2, dtype=torch.int64, device="cuda"), torch.zeros(Kh + 1, dtype=torch.int64, device="cuda"),
              torch.zeros(Kh + 2, dtype=torch.int64, device="cuda")) for _ in range(n_batches)]
 
-    # calls: (first batch, count); warm-up and timed batches are never mixed in one call
-    def split(lo, hi):
-        return [(i, min(B, hi - i)) for i in range(lo, hi, B)]
-    calls = split(0, W) + split(W, W + K)
-    n_warm_calls = len(split(0, W))
-    plans, ev = [], []
-    for j, (first, cnt) in enumerate(calls):
-        c = ctxs[j % S]
-        views = []
-        for t in range(cnt):
-            v = copy.copy(bufs[j % S][t])
-            v.node_off, v.edge_off, v.frontier_off = offs[first + t]
-            views.append(v)
-        plans.append(qv.ManyPlan(c, g, feat, views, rows[j % S][:cnt], w.fanouts))
-        ev.append([torch.cuda.Event(enable_timing=True) for _ in range(3)])
-    L = qv.lib()
+    plan_cache = {}
 
-    def call(j):
-        first, cnt = calls[j]
-        p, c = plans[j], ctxs[j % S]
-        for t in range(cnt):
-            p.seed_ptrs[t] = seeds_dev[first + t].data_ptr()
-            p.n_seeds[t] = batch
-            p.rng[t] = rng_seeds[first + t]
-        ev[j][0].record(c.stream)
-        c.check(L.qv_sample_many(c.h, g.h, cnt, p.seed_ptrs, p.n_seeds, p.fan, p.k, p.rng, 0, p.outs))
-        ev[j][1].record(c.stream)
-        c.check(L.qv_gather_many(c.h, feat.h, cnt, p.ids, p.n_ids, p.n_dev, p.out_ptrs, p.stride))
-        ev[j][2].record(c.stream)
-
-    for j in range(n_warm_calls):
-        call(j)
-    torch.cuda.synchronize()
-    for c in ctxs:
-        c.sync()
-    t_start = time.perf_counter()
-    for j in range(n_warm_calls, len(calls)):
-        call(j)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t_start
-    for c in ctxs:
-        c.sync()                                           # raises on a deferred device error
-
-    # ---- the same batches over several streams (reported beside the main figure) -----------------
-    # With one stream every kernel's duration is its own, which is what the roofline entry needs;
-    # several contexts on their own streams let calls overlap (the paper's multiplexed pipelines),
-    # which raises whole-path throughput but stretches the individual kernels.
-    if S == 1 and args.extra_streams > 1 and not tiered:
-        S2 = args.extra_streams
-        B2 = min(B, 8)                                     # per-batch arguments inline; 8 direct tables per context
-        ctxs2 = [ctx0] + [qv.Context(0, torch.cuda.Stream()) for _ in range(S2 - 1)]
-        calls2 = ([(i, min(B2, W - i)) for i in range(0, W, B2)] +
-                  [(i, min(B2, W + K - i)) for i in range(W, W + K, B2)])
-        n_warm_calls2 = len(range(0, W, B2))
-        plans2 = []
-        own = {0: list(zip(bufs[0][:B2], rows[0][:B2]))}   # context index -> [(SampleBuffers, rows)] * B2
-        for j, (first, cnt) in enumerate(calls2):
-            k = j % S2
-            c = ctxs2[k]
-            if k not in own:
-                c.set_dedup({"auto": 0, "table": 1, "partitioned": 2}[args.dedup], args.partitions_log2)
-                c.reserve(batch, w.fanouts, w.n, n_batches=B2)
-                own[k] = [(qv.SampleBuffers(c, batch, w.fanouts, w.n), feat.empty_rows(nb, "cuda")) for _ in range(B2)]
+    def plan_for(lane, j):
+        """Argument arrays of call j (batches j*B .. j*B+B-1) on this lane, marshalled once."""
+        key = (id(lane), j)
+        p = plan_cache.get(key)
+        if p is None:
             views = []
-            for t in range(cnt):
-                v = copy.copy(own[k][t][0])
-                v.node_off, v.edge_off, v.frontier_off = offs[first + t]
+            for t in range(B):
+                v = copy.copy(lane.bufs[t])
+                v.node_off, v.edge_off, v.frontier_off = offs[j * B + t]
                 views.append(v)
-            plans2.append(qv.ManyPlan(c, g, feat, views, [r for _, r in own[k][:cnt]], w.fanouts))
-
-        def call2(j):
-            first, cnt = calls2[j]
-            p, c = plans2[j], ctxs2[j % S2]
-            for t in range(cnt):
-                p.seed_ptrs[t] = seeds_dev[first + t].data_ptr()
+            p = qv.ManyPlan(lane.ctx, g, feat, views, lane.rows, w.fanouts)
+            for t in range(B):
+                p.n_ids[t] = row_cap
+                p.seed_ptrs[t] = seeds_dev[j * B + t].data_ptr()
                 p.n_seeds[t] = batch
-                p.rng[t] = rng_seeds[first + t]
-            c.check(L.qv_sample_many(c.h, g.h, cnt, p.seed_ptrs, p.n_seeds, p.fan, p.k, p.rng, 0, p.outs))
-            c.check(L.qv_gather_many(c.h, feat.h, cnt, p.ids, p.n_ids, p.n_dev, p.out_ptrs, p.stride))
+                p.rng[t] = rng_seeds[j * B + t]
+            plan_cache[key] = p
+        return p
 
-        for j in range(n_warm_calls2):
-            call2(j)
+    def issue(lane, j, events=None):
+        """One full call: the B batches of call j through sampling and gather."""
+        p, c = plan_for(lane, j), lane.ctx
+        if events:
+            events[0].record(c.stream)
+        c.check(L.qv_sample_many(c.h, g.h, B, p.seed_ptrs, p.n_seeds, p.fan, p.k, p.rng, 0, p.outs))
+        if events:
+            events[1].record(c.stream)
+        c.check(L.qv_gather_many(c.h, feat.h, B, p.ids, p.n_ids, p.n_dev, p.out_ptrs, p.stride))
+        if events:
+            events[2].record(c.stream)
+
+    def region(lns, timed_events=None, n_calls=None):
+        n_calls = n_calls or calls_per_region
         torch.cuda.synchronize()
-        t2 = time.perf_counter()
-        for j in range(n_warm_calls2, len(calls2)):
-            call2(j)
+        t0 = time.perf_counter()
+        for j in range(n_calls):
+            issue(lns[j % len(lns)], j % calls_per_region, timed_events[j] if timed_events else None)
         torch.cuda.synchronize()
-        elapsed2 = time.perf_counter() - t2
-        for c in ctxs2:
-            c.sync()
-        extra["multi_stream"] = {"streams": S2, "batches_per_call": B2, "ms_per_step": round(elapsed2 * 1e3 / K, 4)}
+        return time.perf_counter() - t0
+
+    def measure(lns, min_seconds, min_regions, with_events, n_calls=None):
+        times, evs = [], []
+        for _ in range(max(2, math.ceil(W / max(1, n_batches)))):      # warm-up: whole regions
+            region(lns, None, n_calls)
+        while (sum(times) < min_seconds or len(times) < min_regions) and len(times) < 400:
+            e = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(calls_per_region)] if with_events else None
+            times.append(region(lns, e, n_calls))
+            if e:
+                evs.append(e)
+        for ln in lns:
+            ln.ctx.sync()                                      # raises on a deferred device error
+        return times, evs
+
+    region_s, region_ev = measure(lanes, 0.05, 5, True)
+    elapsed = float(np.median(region_s))                       # seconds per region of n_batches steps
+
+    # ---- the same region over other stream counts (reported beside the main figure) --------------
+    # With one stream every kernel's duration is its own, which is what the roofline entry needs;
+    # several contexts on their own streams let calls overlap (the paper's multiplexed pipelines).
+    sweep = {}
+    if args.extra_streams > 0 and not tiered and S == 1:
+        sweep_lanes = list(lanes)
+        for S2 in (1, 2, 4, 8, 16):
+            if S2 > args.extra_streams:
+                continue
+            while len(sweep_lanes) < S2:
+                sweep_lanes.append(Lane(new_context(torch.cuda.Stream())))
+            n_calls = max(calls_per_region, 2 * S2)            # at least two calls per stream in flight
+            ts, _ = measure(sweep_lanes[:S2], 0.03, 3, False, n_calls)
+            sweep[str(S2)] = round(float(np.median(ts)) * 1e3 / (n_calls * B), 5)
+        del sweep_lanes
+        plan_cache = {k: v for k, v in plan_cache.items() if k[0] in {id(ln) for ln in lanes}}
+        torch.cuda.empty_cache()
 
     # ---- latency pass (not part of the timed region): one batch per call, one at a time ---------
-    n_lat = min(64, K)
-    lat_plan = qv.ManyPlan(ctx0, g, feat, [bufs[0][0]], [rows[0][0]], w.fanouts)
+    n_lat = max(220, args.latency_samples + 20)
+    lat_plan = qv.ManyPlan(ctx0, g, feat, [lanes[0].bufs[0]], [lanes[0].rows[0]], w.fanouts)
+    lat_plan.n_ids[0] = row_cap
     lat_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_lat)]
     for i in range(n_lat):
         lat_ev[i][0].record(ctx0.stream)
-        lat_plan.run([seeds_dev[W + i]], [rng_seeds[W + i]])
+        lat_plan.run([seeds_dev[i % n_batches]], [rng_seeds[i % n_batches]])
         lat_ev[i][1].record(ctx0.stream)
         ctx0.sync()
-    lat_ms = [a.elapsed_time(b) for a, b in lat_ev[4:]] or [a.elapsed_time(b) for a, b in lat_ev]
+    lat_ms = [a.elapsed_time(b) for a, b in lat_ev[20:]]
 
-    # ---- accounting -------------------------------------------------------------------------
+    # ---- accounting (one region) ---------------------------------------------------------------
     tot_edges = tot_unique = tot_front = 0
     samp_b = reidx_b = gath_b = 0
     if Qdev is not None:        # PSGS summed over a batch's seeds: the predicted size of its sampled tree
-        sums = [qv.qv_psgs_batch_sum(ctx0, Qdev, seeds_dev[i]) for i in range(W, W + min(K, 32))]
+        sums = [qv.qv_psgs_batch_sum(ctx0, Qdev, seeds_dev[i]) for i in range(min(n_batches, 32))]
         ctx0.sync()
         extra["psgs_sum_per_batch"] = round(float(np.mean([x.item() for x in sums])), 1)
-    for i in range(W, W + K):
+    max_unique = 0
+    for i in range(n_batches):
         no, eo, fo = (t.cpu().numpy() for t in offs[i])
         U, E, F = int(no[-1]), int(eo[-1]), int(fo[Kh])        # frontier entries expanded = F_0..F_{K-1}
+        max_unique = max(max_unique, U)
         tot_edges += E
         tot_unique += U
         tot_front += F
@@ -481,25 +503,25 @@ def main():
         samp_b += sb
         reidx_b += rb
         gath_b += gb
+    assert max_unique <= row_cap, "a batch produced more distinct nodes (%d) than the output rows hold (%d)" % (max_unique, row_cap)
     if tiered:                  # rows of the last call's batches that came over the host link
-        first, cnt = calls[-1]
         cold = tot = 0
-        for t in range(cnt):
-            U = int(offs[first + t][0][-1].item())
-            ids = plans[-1].bufs[t].n_id[:U].long()
+        last = lanes[(calls_per_region - 1) % S]
+        for t in range(B):
+            U = int(offs[(calls_per_region - 1) * B + t][0][-1].item())
+            ids = last.bufs[t].n_id[:U].long()
             cold += int((~hot_mask[ids]).sum().item())
             tot += U
         extra["cold_row_fraction"] = round(cold / max(tot, 1), 4)
-    timed = range(n_warm_calls, len(calls))
-    sample_ms = [ev[j][0].elapsed_time(ev[j][1]) for j in timed]
-    gather_ms = [ev[j][1].elapsed_time(ev[j][2]) for j in timed]
-    batch_ms = [ev[j][0].elapsed_time(ev[j][2]) for j in timed]
-    n_launch = len(timed)
-    ms_per_step = elapsed * 1e3 / K
+    sample_ms = [e[0].elapsed_time(e[1]) for reg in region_ev for e in reg]
+    gather_ms = [e[1].elapsed_time(e[2]) for reg in region_ev for e in reg]
+    batch_ms = [e[0].elapsed_time(e[2]) for reg in region_ev for e in reg]
+    ms_per_step = elapsed * 1e3 / n_batches
     gather_avg_ms = float(np.mean(gather_ms))
-    gather_bytes_per_launch = gath_b / n_launch
+    gather_bytes_per_launch = gath_b / calls_per_region
     achieved = gather_bytes_per_launch / (gather_avg_ms * 1e-3) / 1e9
     path_bytes = samp_b + reidx_b + gath_b
+    ratio = GATHER_TRAFFIC_RATIO.get((w.name, args.scale, B))
 
     result = {
         "metric": "sampled_edges_per_s",
@@ -513,56 +535,98 @@ def main():
         "config": {"workload": "%s: %d nodes, %d edges, %s x %d features, fanouts %s, batch %d%s" %
                    (w.name, w.n, n_edges_graph, "fp16" if tdtype == torch.float16 else "fp32", w.dim, w.fanouts,
                     batch, ", %d rows in HBM / rest host-pinned" % feat.n_hot if tiered else ", features all in HBM"),
-                   "streams": S, "batches_per_call": B, "scale": args.scale},
-        "sampled_edges_per_batch": round(tot_edges / K, 1),
-        "unique_nodes_per_batch": round(tot_unique / K, 1),
-        "gathered_feature_GBps": round(tot_unique * w.row_bytes / (sum(gather_ms) * 1e-3) / 1e9, 2),
+                   "streams": S, "batches_per_call": B, "scale": args.scale, "dedup": args.dedup},
+        "timed": {"steps_per_region": n_batches, "calls_per_region": calls_per_region, "regions": len(region_s),
+                  "region_ms_median": round(elapsed * 1e3, 4), "region_ms_min": round(min(region_s) * 1e3, 4),
+                  "region_ms_max": round(max(region_s) * 1e3, 4), "timed_seconds": round(sum(region_s), 4),
+                  "note": "--steps is rounded up to whole calls of batches_per_call; the region is repeated until 50 ms "
+                          "have been timed and the median region is reported"},
+        "sampled_edges_per_batch": round(tot_edges / n_batches, 1),
+        "unique_nodes_per_batch": round(tot_unique / n_batches, 1),
+        "gathered_feature_GBps": round(tot_unique * w.row_bytes / calls_per_region / (gather_avg_ms * 1e-3) / 1e9, 2),
         "gather_frac_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
         "path_algorithmic_GBps": round(path_bytes / elapsed / 1e9, 2),
         "path_frac_hbm_peak": round(path_bytes / elapsed / 1e9 / HBM_PEAK_GBPS, 4),
         "p50_batch_latency_ms": round(float(np.percentile(lat_ms, 50)), 4),
         "p99_batch_latency_ms": round(float(np.percentile(lat_ms, 99)), 4),
+        "latency_samples": len(lat_ms),
         "p50_call_latency_ms": round(float(np.percentile(batch_ms, 50)), 4),
         "sample_ms_avg": round(float(np.mean(sample_ms)), 4),
         "gather_ms_avg": round(gather_avg_ms, 4),
         "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": (round(GATHER_TRAFFIC_RATIO[(w.name, args.scale, B)] * gather_bytes_per_launch)
-                                 if (w.name, args.scale, B) in GATHER_TRAFFIC_RATIO else None),
-                     "bytes_per_launch": round(gather_bytes_per_launch), "avg_launch_ms": round(gather_avg_ms, 5)},
+                     "traffic": round(ratio * gather_bytes_per_launch) if ratio else None,
+                     "traffic_source": (GATHER_TRAFFIC_PROFILE if ratio else
+                                        "no rocprofv3 counter run is committed for this workload and batches per call"),
+                     "bytes_per_launch": round(gather_bytes_per_launch), "avg_launch_ms": round(gather_avg_ms, 5),
+                     "launches_timed": len(gather_ms)},
     }
     if tiered:
         cold_bytes = extra["cold_row_fraction"] * tot_unique * w.row_bytes
-        extra["cold_tier_GBps"] = round(cold_bytes / (sum(gather_ms) * 1e-3) / 1e9, 2)
+        extra["cold_tier_GBps"] = round(cold_bytes / calls_per_region / (gather_avg_ms * 1e-3) / 1e9, 2)
         result["roofline"]["note"] = ("tiered: %.0f%% of the rows come over the host link, which bounds this "
                                       "kernel, not HBM" % (100 * extra["cold_row_fraction"]))
-    if "multi_stream" in extra:
-        ms2 = extra["multi_stream"]["ms_per_step"]
-        extra["multi_stream"]["value"] = round(tot_edges / K / (ms2 * 1e-3), 1)
-        extra["multi_stream"]["path_frac_hbm_peak"] = round(path_bytes / K / (ms2 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4)
+    if sweep:
+        extra["stream_sweep"] = {"batches_per_call": B, "ms_per_step_by_streams": sweep,
+                                 "best_path_frac_hbm_peak": round(path_bytes / n_batches / (min(sweep.values()) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                                 "best_value": round(tot_edges / n_batches / (min(sweep.values()) * 1e-3), 1)}
     result.update(extra)
 
     # ---- the oracle on this machine's host cores (a reported baseline, not the target) ------------
     if not args.no_cpu_baseline:
         import oracle
+        from concurrent.futures import ThreadPoolExecutor
         sub_rows = min(w.n, 4_000_000)
         host_table = qvgen.features_host(w.seed, sub_rows, w.dim, w.feat_dtype)
-        t_budget, t_used, e_cpu, nb_cpu = 15.0, 0.0, 0, 0
-        for i in range(W, W + K):
+
+        def one(i):
             t1 = time.perf_counter()
-            o = oracle.sample(rowptr, col, seeds_host[i], w.fanouts, rng_seeds[i])
+            o = oracle.sample(rowptr, col, seeds_host[i % n_batches], w.fanouts, rng_seeds[i % n_batches])
             oracle.gather(host_table, o["n_id"] % sub_rows)
-            t_used += time.perf_counter() - t1
-            e_cpu += int(o["edge_off"][-1])
-            nb_cpu += 1
-            if t_used > t_budget:
-                break
+            return time.perf_counter() - t1, int(o["edge_off"][-1])
+
+        t_budget, t_used, e_cpu, nb_cpu = 10.0, 0.0, 0, 0
+        while t_used < t_budget and nb_cpu < 4 * n_batches:
+            dt, e = one(nb_cpu)
+            t_used += dt; e_cpu += e; nb_cpu += 1
         result["cpu_baseline"] = {
             "value": round(e_cpu / t_used, 1), "unit": "edges/s", "cores": 1, "kind": "oracle",
-            "sample": "%d of the timed batches, single-threaded oracle sample+reindex+gather; gather rows taken "
+            "sample": "%d batches of the timed workload, single-threaded oracle sample+reindex+gather; gather rows taken "
                       "modulo a %d-row host table" % (nb_cpu, sub_rows),
             "ms_per_batch": round(t_used * 1e3 / nb_cpu, 3)}
-    print(json.dumps(result), flush=True)
+        # the same oracle, one independent batch per thread on T threads (the oracle releases the interpreter lock)
+        T = max(1, min(os.cpu_count() or 1, int(os.environ.get("OMP_NUM_THREADS", "16")), 16))
+        per_thread = max(1, int(10.0 / (t_used / nb_cpu) / 1.0))
+        per_thread = min(per_thread, 64)
+        t1 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=T) as pool:
+            res = list(pool.map(lambda th: sum(one(th * per_thread + j)[1] for j in range(per_thread)), range(T)))
+        t_mt = time.perf_counter() - t1
+        result["cpu_baseline_threads"] = {
+            "value": round(sum(res) / t_mt, 1), "unit": "edges/s", "cores": T, "kind": "oracle",
+            "sample": "%d threads x %d batches each, the unmodified single-threaded oracle on independent batches" % (T, per_thread),
+            "seconds": round(t_mt, 2)}
+    import subprocess
+    try:
+        result["git"] = subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], stderr=subprocess.DEVNULL).decode().strip()
+    except Exception:
+        result["git"] = None
+    line = json.dumps(result)
+    try:
+        os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)
+        with open(os.path.join(ROOT, "gpurun_out", "bench_%s.json" % w.name), "w") as f:
+            f.write(line + "\n")
+    except OSError:
+        pass
+    print(line, flush=True)
+    # handles go before the interpreter starts tearing the GPU runtime down
+    torch.cuda.synchronize()
+    plan_cache.clear()
+    feat.close()
+    for c in made_contexts:
+        c.close()
+    g.__del__()
+    ctx0.close()
 
 
 if __name__ == "__main__":

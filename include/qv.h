@@ -19,6 +19,9 @@
  *     caller copies them back after synchronising.  Conditions only the device can detect (an id
  *     out of range, an output array too small) are recorded in a status word that qv_ctx_sync()
  *     returns; kernels never write outside the capacities they were given.
+ *   - Graph and feature handles may be used by any context of the same GPU and may outlive the
+ *     context that created them; destroying a handle whose memory the library owns waits for the
+ *     whole device first.
  *   - One context serves one stream; calls on one context must not overlap.  Use several
  *     contexts (one per stream) to keep several batches in flight.  The context's GPU must be
  *     the calling thread's current device (qv_ctx_create makes it so; a caller that switches
@@ -49,7 +52,7 @@ typedef enum {
 
 #define QV_MAX_HOPS 8
 #define QV_MAX_FANOUT 1024
-#define QV_MAX_BATCHES 32    /* batches per qv_sample_many / qv_gather_many call */
+#define QV_MAX_BATCHES 64    /* batches per qv_sample_many / qv_gather_many call */
 
 /* ---------------------------------------------------------------------------------------------
  * Context
@@ -80,10 +83,12 @@ qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes);
 
 /* Which dedup form qv_sample / qv_sample_many use (results are identical; this is a tuning and
  * testing aid).  QV_DEDUP_AUTO (default): the partitioned form (ids split by hash over
- * workgroups that dedup in LDS; nothing kept in HBM between calls) wherever it applies, i.e.
- * layer frontiers with at most 4,194,304 ids per stage; tables otherwise.  QV_DEDUP_TABLE: always
- * the tables above.  QV_DEDUP_PARTITIONED: as AUTO.  partitions_log2: partitions per batch of
- * the partitioned form as a power of two, 0..6, or -1 to let every call choose. */
+ * workgroups that dedup in LDS; nothing kept in HBM between calls) for calls that carry enough
+ * edges to pay for its extra kernels (a-priori edge bound x batches >= 8 Mi), the tables above
+ * otherwise.  QV_DEDUP_TABLE: always tables.  QV_DEDUP_PARTITIONED: the partitioned form
+ * wherever it applies, i.e. layer frontiers with at most 4,194,304 ids per stage.
+ * partitions_log2: partitions per batch of the partitioned form as a power of two, 0..6, or -1
+ * to let the library settle on a count from what earlier calls report. */
 #define QV_DEDUP_AUTO 0
 #define QV_DEDUP_TABLE 1
 #define QV_DEDUP_PARTITIONED 2
@@ -237,6 +242,8 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
 /* Build a feature table of n_rows x dim elements of elem_bytes (2 or 4) bytes.
  *   table          [dev|host] (table_on_device says which) row-major, contiguous.
  *   hbm_budget_bytes  bytes of HBM the table may occupy; < 0 or >= the table size = all in HBM.
+ *                  The HBM tier holds floor(budget / row bytes) rows and never exceeds the budget
+ *                  (its rows are padded to a line-aligned stride only where that still fits).
  *   rank           [dev] int32[n_rows] placement order (most popular first, e.g. from
  *                  qv_place_rank); required when the budget is smaller than the table.
  *   flags          0, or QV_FEAT_OWN_COPY.

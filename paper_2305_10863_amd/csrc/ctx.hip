@@ -224,7 +224,7 @@ qv_status qv_csr_create(qv_ctx* ctx, int64_t n_nodes, int64_t n_edges, const voi
                                         "of 2^31 or more entries, or a column id outside [0, n_nodes))");
         if (rc != QV_OK) return rc;
     }
-    qv_csr* g = new (std::nothrow) qv_csr{ctx, n_nodes, n_edges, rowptr, rowptr_bits, col};
+    qv_csr* g = new (std::nothrow) qv_csr{ctx, ctx->device, n_nodes, n_edges, rowptr, rowptr_bits, col};
     if (!g) return fail(ctx, QV_ENOMEM, "qv_csr_create: out of host memory");
     *out = g;
     return QV_OK;
@@ -236,7 +236,12 @@ const int32_t* qv_csr_col(const qv_csr* csr) { return csr ? csr->col : nullptr; 
 void qv_csr_destroy(qv_csr* csr) {
     if (!csr) return;
     // owned arrays may still be read by work enqueued on the context's stream
-    if ((csr->owned_rowptr || csr->owned_col) && csr->ctx) (void)hipStreamSynchronize(csr->ctx->stream);
+    if (csr->owned_rowptr || csr->owned_col) {
+        int prev = -1;
+        if (hipGetDevice(&prev) == hipSuccess && prev != csr->device) (void)hipSetDevice(csr->device);
+        (void)hipDeviceSynchronize();
+        if (prev >= 0 && prev != csr->device) (void)hipSetDevice(prev);
+    }
     if (csr->owned_rowptr) (void)hipFree(csr->owned_rowptr);
     if (csr->owned_col) (void)hipFree(csr->owned_col);
     delete csr;

@@ -140,7 +140,12 @@ extern "C" {
 
 void qv_feat_destroy(qv_feat* f) {
     if (!f) return;
-    if (f->ctx) (void)hipStreamSynchronize(f->ctx->stream);
+    // any context's stream may still be gathering from this table, and the creating context may be
+    // gone already: wait for the device the memory lives on
+    int prev = -1;
+    if (hipGetDevice(&prev) == hipSuccess && prev != f->device) (void)hipSetDevice(f->device);
+    (void)hipDeviceSynchronize();
+    if (prev >= 0 && prev != f->device) (void)hipSetDevice(prev);
     if (f->hot_owned) (void)hipFree(f->hot_owned);
     if (f->cold_host) (void)hipHostFree(f->cold_host);
     if (f->loc) (void)hipFree(f->loc);
@@ -165,7 +170,7 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
     if (!all_hot && !rank) return fail(ctx, QV_EINVAL, "qv_feat_create: a budget below the table size needs `rank`");
     qv_feat* f = new (std::nothrow) qv_feat();
     if (!f) return fail(ctx, QV_ENOMEM, "qv_feat_create: out of host memory");
-    f->ctx = ctx; f->n_rows = n_rows; f->dim = dim; f->elem_bytes = elem_bytes; f->row_bytes = row_bytes;
+    f->ctx = ctx; f->device = ctx->device; f->n_rows = n_rows; f->dim = dim; f->elem_bytes = elem_bytes; f->row_bytes = row_bytes;
     f->hot = nullptr; f->hot_owned = nullptr; f->cold_host = nullptr; f->cold_dev = nullptr; f->loc = nullptr;
     f->hot_stride = row_bytes; f->cold_stride = row_bytes;
     f->n_hot = all_hot ? n_rows : hbm_budget_bytes / row_bytes;
@@ -188,8 +193,11 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
             FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(n_rows * pad_stride + 256)));
             FEAT_TRY(hipMalloc((void**)&iota, (size_t)n_rows * 4 + 256));
             if (rc == QV_OK) {
-                std::vector<int32_t> h((size_t)n_rows);
-                for (int64_t i = 0; i < n_rows; ++i) h[(size_t)i] = (int32_t)i;
+                std::vector<int32_t> h;
+                try {
+                    h.resize((size_t)n_rows);
+                } catch (...) { rc = fail(ctx, QV_ENOMEM, "qv_feat_create: out of host memory"); }
+                for (int64_t i = 0; i < n_rows && rc == QV_OK; ++i) h[(size_t)i] = (int32_t)i;
                 FEAT_TRY(hipMemcpyAsync(iota, h.data(), (size_t)n_rows * 4, hipMemcpyHostToDevice, ctx->stream));
                 FEAT_TRY(hipStreamSynchronize(ctx->stream));
             }
@@ -210,7 +218,10 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
         }
     } else {
         const int64_t n_hot = f->n_hot, n_cold = n_rows - n_hot;
-        f->hot_stride = pad_stride; f->cold_stride = pad_stride;
+        // the HBM tier holds floor(budget / row bytes) rows and never more bytes than the budget: rows are
+        // padded to line-aligned strides only where the padded tier still fits
+        const int64_t hot_stride = n_hot * pad_stride <= hbm_budget_bytes ? pad_stride : row_bytes;
+        f->hot_stride = hot_stride; f->cold_stride = pad_stride;
         std::vector<int32_t> h_rank, h_loc, cold_ids;
         try {
             h_rank.resize((size_t)n_rows); h_loc.assign((size_t)n_rows, -1); cold_ids.reserve((size_t)n_cold);
@@ -219,7 +230,10 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
         FEAT_TRY(hipStreamSynchronize(ctx->stream));
         if (rc == QV_OK) {
             // rank must be a permutation of the row ids
-            std::vector<char> seen((size_t)n_rows, 0);
+            std::vector<char> seen;
+            try {
+                seen.assign((size_t)n_rows, 0);
+            } catch (...) { rc = fail(ctx, QV_ENOMEM, "qv_feat_create: out of host memory"); }
             for (int64_t i = 0; i < n_rows && rc == QV_OK; ++i) {
                 int32_t id = h_rank[i];
                 if (id < 0 || id >= n_rows || seen[id]) rc = fail(ctx, QV_EINVAL, "qv_feat_create: rank is not a permutation");
@@ -234,7 +248,7 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
         }
         FEAT_TRY(hipMalloc((void**)&f->loc, (size_t)n_rows * 4 + 256));
         FEAT_TRY(hipMemcpyAsync(f->loc, h_loc.data(), (size_t)n_rows * 4, hipMemcpyHostToDevice, ctx->stream));
-        FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(n_hot * pad_stride + 256)));
+        FEAT_TRY(hipMalloc((void**)&f->hot_owned, (size_t)(n_hot * hot_stride + 256)));
         FEAT_TRY(hipHostMalloc((void**)&f->cold_host, (size_t)(n_cold * pad_stride + 256), hipHostMallocMapped));
         FEAT_TRY(hipHostGetDevicePointer((void**)&f->cold_dev, f->cold_host, 0));
         f->hot = f->hot_owned;
@@ -245,7 +259,7 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
             FEAT_TRY(hipMemcpyAsync(d_cold_ids, cold_ids.data(), (size_t)n_cold * 4, hipMemcpyHostToDevice, ctx->stream));
             if (rc == QV_OK) {
                 GatherJob job{rank, n_hot, nullptr, f->hot_owned};
-                rc = launch_gather(ctx, whole, &job, 1, pad_stride);
+                rc = launch_gather(ctx, whole, &job, 1, hot_stride);
             }
             if (rc == QV_OK) {
                 GatherJob job{d_cold_ids, n_cold, nullptr, (char*)f->cold_dev};
@@ -258,14 +272,14 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
             for (int64_t c = 0; c < n_cold; ++c)
                 std::memcpy(f->cold_host + c * pad_stride, src + (int64_t)cold_ids[c] * row_bytes, (size_t)row_bytes);
             // hot rows: stage through pinned memory in chunks
-            const int64_t chunk_rows = std::max<int64_t>(1, (64ll << 20) / pad_stride);
+            const int64_t chunk_rows = std::max<int64_t>(1, (64ll << 20) / hot_stride);
             char* stage = nullptr;
-            FEAT_TRY(hipHostMalloc((void**)&stage, (size_t)(chunk_rows * pad_stride), hipHostMallocDefault));
+            FEAT_TRY(hipHostMalloc((void**)&stage, (size_t)(chunk_rows * hot_stride), hipHostMallocDefault));
             for (int64_t i0 = 0; i0 < n_hot && rc == QV_OK; i0 += chunk_rows) {
                 int64_t cnt = std::min(chunk_rows, n_hot - i0);
                 for (int64_t i = 0; i < cnt; ++i)
-                    std::memcpy(stage + i * pad_stride, src + (int64_t)h_rank[i0 + i] * row_bytes, (size_t)row_bytes);
-                FEAT_TRY(hipMemcpyAsync(f->hot_owned + i0 * pad_stride, stage, (size_t)(cnt * pad_stride),
+                    std::memcpy(stage + i * hot_stride, src + (int64_t)h_rank[i0 + i] * row_bytes, (size_t)row_bytes);
+                FEAT_TRY(hipMemcpyAsync(f->hot_owned + i0 * hot_stride, stage, (size_t)(cnt * hot_stride),
                                         hipMemcpyHostToDevice, ctx->stream));
                 FEAT_TRY(hipStreamSynchronize(ctx->stream));
             }

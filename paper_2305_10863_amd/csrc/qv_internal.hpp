@@ -82,7 +82,8 @@ struct qv_ctx {
 };
 
 struct qv_csr {
-    qv_ctx* ctx;
+    qv_ctx* ctx;                       // the creating context (not dereferenced after creation: it may be destroyed first)
+    int device = 0;
     int64_t n_nodes, n_edges;
     const void* rowptr;
     int rowptr_bits;
@@ -92,7 +93,8 @@ struct qv_csr {
 };
 
 struct qv_feat {
-    qv_ctx* ctx;
+    qv_ctx* ctx;                       // the creating context (not dereferenced after creation: it may be destroyed first)
+    int device;
     int64_t n_rows, n_hot;
     int32_t dim, elem_bytes;
     int64_t row_bytes;

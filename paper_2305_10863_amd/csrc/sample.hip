@@ -1744,7 +1744,7 @@ static void part_adapt(qv_ctx* ctx, int64_t nodes_bound) {
 // The partitioned form serves layer frontiers whose stages fit kPMaxTiles tiles; the cumulative
 // variant, larger stages and a context told to use tables take the table forms.
 static qv_status plan_sample(qv_ctx* ctx, int64_t max_seeds, const int32_t* fanouts, int n_hops, int64_t n_nodes,
-                             bool cumulative, Bounds* bd, Layout* L) {
+                             bool cumulative, int n_batches, Bounds* bd, Layout* L) {
     qv_status rc = compute_bounds(ctx, max_seeds, fanouts, n_hops, n_nodes, cumulative, bd);
     if (rc != QV_OK) return rc;
     L->stage0 = max_seeds; L->edges = bd->edges;
@@ -1752,7 +1752,12 @@ static qv_status plan_sample(qv_ctx* ctx, int64_t max_seeds, const int32_t* fano
     const int64_t max_stage = (int64_t)kPTile * kPMaxTiles;
     int64_t largest = max_seeds;
     for (int k = 1; k <= n_hops; ++k) largest = bd->hop_edges[k] > largest ? bd->hop_edges[k] : largest;
-    L->part = ctx->dedup_form != QV_DEDUP_TABLE && !cumulative && largest <= max_stage;
+    // The partitioned form runs more kernels per stage (a fixed cost per call of some 0.1 ms) and does
+    // less work per edge: it pays once a call carries enough edges (measured crossover on a 111 M
+    // node graph: 12 batches of 1,024 seeds, whose a-priori bound is 0.94 M edges each).
+    const bool big_call = bd->edges * (int64_t)n_batches >= (int64_t)8 << 20;
+    L->part = (ctx->dedup_form == QV_DEDUP_PARTITIONED || (ctx->dedup_form == QV_DEDUP_AUTO && big_call)) && !cumulative &&
+              largest <= max_stage;
     if (L->part) {
         L->p_tiles = (largest + kPTile - 1) / kPTile;
         if (L->p_tiles < 1) L->p_tiles = 1;
@@ -1808,7 +1813,7 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     }
     Bounds bd;
     Layout L;
-    qv_status rc = plan_sample(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, cumulative, &bd, &L);
+    qv_status rc = plan_sample(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, cumulative, n_batches, &bd, &L);
     if (rc != QV_OK) return rc;
     rc = arena_begin(ctx, per_batch_bytes(L) * n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch));
     if (rc != QV_OK) return rc;
@@ -2016,7 +2021,7 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, i
     const bool cumulative = (flags & QV_SAMPLE_CUMULATIVE) != 0;
     Bounds bd;
     Layout L;
-    qv_status rc = plan_sample(ctx, n_seeds, fanouts, n_hops, n_nodes, cumulative, &bd, &L);
+    qv_status rc = plan_sample(ctx, n_seeds, fanouts, n_hops, n_nodes, cumulative, n_batches, &bd, &L);
     if (rc != QV_OK) return rc;
     const size_t want = per_batch_bytes(L) * (size_t)n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch);
     if (want > ctx->arena_bytes) {

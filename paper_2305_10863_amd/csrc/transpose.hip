@@ -110,7 +110,7 @@ qv_status qv_csr_transpose(qv_ctx* ctx, const qv_csr* csr, qv_csr** out) {
     if (rc == QV_OK) rc = sync_rc;
     release(rc != QV_OK);
     if (rc != QV_OK) return rc;
-    qv_csr* t = new (std::nothrow) qv_csr{ctx, n, E, rowptr_t, csr->rowptr_bits, col_t, rowptr_t, col_t};
+    qv_csr* t = new (std::nothrow) qv_csr{ctx, ctx->device, n, E, rowptr_t, csr->rowptr_bits, col_t, rowptr_t, col_t};
     if (!t) {
         (void)hipFree(rowptr_t);
         if (col_t) (void)hipFree(col_t);
