@@ -227,6 +227,16 @@ class Features:
         # a borrowed device table must stay alive as long as the handle
         self._keep = table if (table.is_cuda and self.n_hot == self.n_rows) else None
 
+    def loc(self):
+        """Copy of the lookup table (int32[n_rows]: >= 0 HBM row, < 0 ~host row), or None when every
+        row is in HBM in id order."""
+        ptr = lib().qv_feat_loc(self.h)
+        if not ptr:
+            return None
+        view = type("_DevView", (), {"__cuda_array_interface__": {
+            "shape": (self.n_rows,), "typestr": "<i4", "data": (ptr, False), "version": 2, "strides": None}})()
+        return torch.as_tensor(view, device=self.ctx.device).clone()
+
     def empty_rows(self, n, device):
         """An (n, dim) output tensor whose rows start at the tier's (line-aligned) stride."""
         esz = self.row_bytes // self.dim

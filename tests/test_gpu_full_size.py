@@ -166,6 +166,7 @@ def test_co_purchase_full_batch_sweep_and_tiered(qv, ctx):
     del big
     torch.cuda.empty_cache()
     assert feat_t.n_hot == n_hot
+    assert np.array_equal(feat_t.loc().cpu().numpy(), o_loc)       # the lookup table at full size
     check_batches(qv, ctx, wt, rowptr, col, g, feat_t, range(2))
     feat_t.close()
 

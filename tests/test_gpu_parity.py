@@ -209,6 +209,19 @@ def test_sample_many_and_gather_many(qv, ctx, tiny, n_batches):
     feat.close()
 
 
+def test_call_of_64_batches(qv, ctx, tiny):
+    # the largest call: QV_MAX_BATCHES batches of unequal sizes through one set of launches
+    w, rowptr, col, g = tiny
+    n = qv.QV_MAX_BATCHES
+    assert n == 64
+    seeds = [w.seeds(700 + j, 1 + (37 * j) % 300) for j in range(n)]
+    rng = [900 + j for j in range(n)]
+    outs = qv.qv_sample_many(ctx, g, [dev(s) for s in seeds], [7, 4, 3], rng)
+    ctx.sync()
+    for j in range(n):
+        assert_sample_equal(outs[j].to_host(), oracle.sample(rowptr, col, seeds[j], [7, 4, 3], rng[j]))
+
+
 def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
     # the dedup tables are not cleared between calls; results must not depend on what earlier
     # calls (of other sizes, other batch counts) left behind, nor on the counter wrapping
@@ -412,8 +425,8 @@ def test_tiered_gather_and_placement(qv, ctx, on_device):
     src = qvgen.features_device(9, n, dim, torch.float32) if on_device else torch.from_numpy(table)
     feat = qv.Features(ctx, src, hbm_budget_bytes=budget, rank=rank)
     assert feat.n_hot == 3000
-    loc_ptr = qv.lib().qv_feat_loc(feat.h)
-    assert loc_ptr
+    # the lookup table itself: hot index = position in the ranking, cold index = order of the remaining ids
+    assert np.array_equal(feat.loc().cpu().numpy(), o_loc)
     ids = rng.integers(0, n, 50000).astype(np.int32)
     out = qv.qv_gather(ctx, feat, dev(ids))
     ctx.sync()
