@@ -185,6 +185,8 @@ struct BatchArgs {
     uint2* dealt;                   // the stage's (id, position) records, tile by tile, each tile sorted by partition
     int32_t* result;                // per record: what k_part_dedup found out about it (see there)
     uint16_t* run_off;              // [tile][P + 1] where each partition's records start inside the tile's 4096
+    uint2* kdealt;                  // n_id dealt the same way, in tiles of 4,096 local ids: (id, local id) records
+    uint16_t* krun_off;             // [tile of n_id][P + 1]
     uint32_t* pcount;               // [tile][partition][first, new] populations
     uint32_t* tile_seg;             // [tile] next-hop edges produced by the tile's first occurrences
     uint16_t* fr_tile;              // per frontier entry: the tile that produced it (fr_seg is then tile-local)
@@ -222,6 +224,8 @@ struct BatchG {
     uint2 QV_G* dealt;
     int32_t QV_G* result;
     uint16_t QV_G* run_off;
+    uint2 QV_G* kdealt;
+    uint16_t QV_G* krun_off;
     uint32_t QV_G* pcount;
     uint32_t QV_G* tile_seg;
     uint16_t QV_G* fr_tile;
@@ -260,6 +264,8 @@ struct BatchG {
           dealt(gptr(a.dealt)),
           result(gptr(a.result)),
           run_off(gptr(a.run_off)),
+          kdealt(gptr(a.kdealt)),
+          krun_off(gptr(a.krun_off)),
           pcount(gptr(a.pcount)),
           tile_seg(gptr(a.tile_seg)),
           fr_tile(gptr(a.fr_tile)),
@@ -288,6 +294,7 @@ struct CallHeader {
     int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
     int32_t p_log2;                 // partitioned dedup: log2 of the partitions per batch
     int32_t p_tiles;                // ... and the tiles its per-tile arrays hold
+    int32_t deal_blocks;            // k_part_deal: workgroups (per batch) that deal the stage's ids; the rest deal n_id
     uint32_t* part_stats;           // [0] fullest LDS table of the call, [1] deepest split, [2] partitions_log2 + 1 (device, may be NULL)
     int32_t n_batches;
     int32_t* status;
@@ -951,27 +958,25 @@ __global__ void __launch_bounds__(kPThreads) k_part_deal(A c) {
     }
     const int64_t len = v.end - v.begin;
     const int n_tiles = (int)((len + kPTile - 1) / kPTile);
-    const int32_t QV_G* ids = v.ids + v.begin;
     const uint32_t n_valid = c.n_nodes >= 0 ? (uint32_t)c.n_nodes : 0x80000000u;   // ids are valid below this (as unsigned)
-    for (int t = (int)blockIdx.x; t < n_tiles; t += (int)gridDim.x) {
-        const int64_t rel0 = (int64_t)t * kPTile;
+    // counting sort of the ids src[0 .. n) (n <= 4,096) by partition; the record of src[k] is (id, tag0 + k)
+    auto deal_tile = [&](const int32_t QV_G* src, int64_t n, uint32_t tag0, uint2 QV_G* out, uint16_t QV_G* out_off) {
         if (tid <= P) hist[tid] = 0;
         lds_barrier();
         uint32_t key[kPKeys], where[kPKeys];                // where = partition << 16 | rank inside the partition's run
         bool bad = false;
 #pragma unroll
         for (int i = 0; i < kPKeys; ++i) {
-            const int64_t rel = rel0 + (int64_t)i * kPThreads + tid;
-            key[i] = rel < len ? (uint32_t)ids[rel] : 0xFFFFFFFFu;
+            const int rel = i * kPThreads + tid;
+            key[i] = rel < n ? (uint32_t)src[rel] : 0xFFFFFFFFu;
         }
 #pragma unroll
         for (int i = 0; i < kPKeys; ++i) {
-            const int64_t rel = rel0 + (int64_t)i * kPThreads + tid;
             where[i] = 0xFFFFFFFFu;
             if (key[i] < n_valid) {
                 const uint32_t part = part_of(key[i], p_log2);
                 where[i] = (part << 16) | atomicAdd(&hist[part], 1u);
-            } else if (rel < len) {
+            } else if (i * kPThreads + tid < n) {
                 bad = true;
             }
         }
@@ -987,24 +992,44 @@ __global__ void __launch_bounds__(kPThreads) k_part_deal(A c) {
             }
             if (lane < P) {
                 offs[lane] = inc - x;
-                b.run_off[(size_t)t * (P + 1) + lane] = (uint16_t)(inc - x);
+                out_off[lane] = (uint16_t)(inc - x);
             }
             if (lane == P - 1) {
                 offs[P] = inc;
-                b.run_off[(size_t)t * (P + 1) + P] = (uint16_t)inc;
+                out_off[P] = (uint16_t)inc;
             }
         }
         lds_barrier();
 #pragma unroll
         for (int i = 0; i < kPKeys; ++i) {
             if (where[i] == 0xFFFFFFFFu) continue;
-            const uint32_t pos = (uint32_t)(v.begin + rel0 + (int64_t)i * kPThreads + tid);
-            sorted[offs[where[i] >> 16] + (where[i] & 0xFFFFu)] = make_uint2(key[i], pos);
+            sorted[offs[where[i] >> 16] + (where[i] & 0xFFFFu)] = make_uint2(key[i], tag0 + (uint32_t)(i * kPThreads + tid));
         }
         lds_barrier();
         const uint32_t total = offs[P];
-        for (uint32_t k = (uint32_t)tid; k < total; k += kPThreads) b.dealt[(size_t)t * kPTile + k] = sorted[k];
+        for (uint32_t k = (uint32_t)tid; k < total; k += kPThreads) out[k] = sorted[k];
         lds_barrier();                                      // hist, offs and sorted are reused by the next tile
+    };
+    // the stage's ids: records (id, position)
+    const int stage_blocks = c.deal_blocks, node_blocks = (int)gridDim.x - stage_blocks;
+    for (int t = (int)blockIdx.x; (int)blockIdx.x < stage_blocks && t < n_tiles; t += stage_blocks) {
+        const int64_t rel0 = (int64_t)t * kPTile;
+        deal_tile(v.ids + v.begin + rel0, len - rel0 < kPTile ? len - rel0 : kPTile, (uint32_t)(v.begin + rel0),
+                  b.dealt + (size_t)t * kPTile, b.run_off + (size_t)t * (P + 1));
+    }
+    // the nodes the previous stage numbered: records (id, local id), in tiles of 4,096 local ids (the
+    // tile the previous stage left unfinished is dealt again in full)
+    if (c.stage > 0 && (int)blockIdx.x >= stage_blocks) {
+        const SampleMeta QV_G* m = b.meta;
+        int64_t known = m->node_off[c.stage], before = m->node_off[c.stage - 1];
+        if (known > b.n_id_cap) known = b.n_id_cap;
+        if (before > known) before = known;
+        const int first = (int)(before / kPTile), end = (int)((known + kPTile - 1) / kPTile);
+        for (int j = first + (int)blockIdx.x - stage_blocks; j < end; j += node_blocks) {
+            const int64_t u0 = (int64_t)j * kPTile;
+            deal_tile(b.n_id + u0, known - u0 < kPTile ? known - u0 : kPTile, (uint32_t)u0,
+                      b.kdealt + (size_t)j * kPTile, b.krun_off + (size_t)j * (P + 1));
+        }
     }
 }
 
@@ -1017,7 +1042,6 @@ struct PartLds {
     uint16_t run_beg[kPMaxTiles];                       // where its run starts inside tile t
     uint32_t cnt_first[kPMaxTiles], cnt_new[kPMaxTiles];// per tile: first occurrences, new nodes
     uint32_t s_wave[kDThreads / kWave];
-    uint2 queue[kDThreads / kWave][2 * kWave];          // per wave: (id, local id) of known nodes waiting to be inserted
     uint32_t s_fill;                                    // entries claimed (+ kPCap for every insertion that found the table full)
 };
 
@@ -1082,49 +1106,21 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
             if (r == 0) for (int t = tid; t < n_tiles; t += kDThreads) { S.cnt_first[t] = 0; S.cnt_new[t] = 0; }
             if (tid == 0) S.s_fill = 0;
             lds_barrier();
-            // Nodes numbered by earlier stages: local id = index in n_id.  Every workgroup reads all of
-            // n_id and keeps its share, about one id in P: a wave collects its share in a small queue
-            // in LDS and inserts 64 at a time with all lanes busy (inserting them where they stand,
-            // a lane or two per instruction, cost more than everything else in this kernel).
+            // nodes numbered by earlier stages, from their dealt records: a wave per tile of n_id, a lane per record of the run
             uint32_t claimed = 0;
             {
-                uint2* queue = S.queue[wave];
-                uint32_t qn = 0;                                // wave-uniform
-                auto insert_front = [&](uint32_t n) {           // the first n (<= 64) queue entries
-                    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");     // written by other lanes of the wave
-                    if ((uint32_t)lane < n) {
-                        const uint2 e = queue[lane];
-                        const int s2 = lds_insert(S.t_key, e.x, fmix32(e.x) & (kPCap - 1), &claimed);
+                const int n_ktiles = (int)((v.known + kPTile - 1) / kPTile);
+                for (int j = wave; j < n_ktiles; j += kDThreads / kWave) {
+                    const uint32_t beg = b.krun_off[(size_t)j * (P + 1) + part], end = b.krun_off[(size_t)j * (P + 1) + part + 1];
+                    for (uint32_t k = beg + (uint32_t)lane; k < end; k += kWave) {
+                        const uint2 rec = b.kdealt[(size_t)j * kPTile + k];
+                        const uint32_t h = fmix32(rec.x);
+                        if (split && (h >> (32 - split)) != r) continue;
+                        const int s2 = lds_insert(S.t_key, rec.x, h & (kPCap - 1), &claimed);
                         if (s2 < 0) claimed += (uint32_t)kPCap;
-                        else S.t_lid[s2] = (int32_t)e.y;
-                    }
-                };
-                constexpr int kPre = 12;                        // ids a thread requests together (their latency is the loop's time)
-                for (int64_t u0 = 0; u0 < v.known; u0 += (int64_t)kDThreads * kPre) {
-                    uint32_t k[kPre];
-#pragma unroll
-                    for (int i = 0; i < kPre; ++i) {
-                        const int64_t u = u0 + (int64_t)i * kDThreads + tid;
-                        k[i] = u < v.known ? (uint32_t)b.n_id[u] : kEmptyKey;
-                    }
-#pragma unroll
-                    for (int i = 0; i < kPre; ++i) {
-                        const int64_t u = u0 + (int64_t)i * kDThreads + tid;
-                        bool own = u < v.known && part_of(k[i], p_log2) == part;
-                        if (own && split && (fmix32(k[i]) >> (32 - split)) != r) own = false;
-                        const unsigned long long m = __ballot(own);
-                        if (own) queue[qn + __mbcnt_hi((uint32_t)(m >> 32), __mbcnt_lo((uint32_t)m, 0u))] = make_uint2(k[i], (uint32_t)u);
-                        qn += (uint32_t)__popcll(m);
-                        if (qn >= kWave) {
-                            insert_front(kWave);
-                            const uint2 rest = queue[kWave + lane];         // what did not fit the batch moves to the front
-                            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-                            qn -= kWave;
-                            if ((uint32_t)lane < qn) queue[lane] = rest;
-                        }
+                        else S.t_lid[s2] = (int32_t)rec.y;
                     }
                 }
-                insert_front(qn);
             }
             // pass 1: register every record (eight per thread requested together)
             for (uint32_t e0 = 0; e0 < n_rec; e0 += kDThreads * kDKeys) {
@@ -1554,6 +1550,7 @@ struct Layout {                     // per-batch scratch sizes (elements)
     bool part = false;              // partitioned dedup: no table, no per-edge flags
     int p_log2 = 0;                 // log2 of the partitions per batch
     int64_t p_tiles = 0;            // tiles of the largest stage
+    int64_t k_tiles = 0;            // tiles of n_id
 };
 
 static void tile_shape(int64_t max_items, int* ipt, int* tiles) {
@@ -1574,6 +1571,8 @@ static size_t per_batch_bytes(const Layout& L) {
         const size_t slots = (size_t)L.p_tiles * kPTile;                    // records of the largest stage
         t += align_up(slots * 8) + align_up(slots * 4);                     // dealt, result
         t += align_up(((size_t)L.p_tiles << L.p_log2) * 2 + (size_t)L.p_tiles * 2);     // run_off
+        t += align_up((size_t)L.k_tiles * kPTile * 8);                      // kdealt
+        t += align_up(((size_t)L.k_tiles << L.p_log2) * 2 + (size_t)L.k_tiles * 2);     // krun_off
         t += align_up(cells * 2 * 4) + align_up((size_t)L.p_tiles * 4);     // pcount, tile_seg
         return t + 2048;
     }
@@ -1600,13 +1599,15 @@ static bool carve(qv_ctx* ctx, const Layout& L, BatchArgs* b) {
         b->dealt = (uint2*)arena_take(ctx, slots * 8);
         b->result = (int32_t*)arena_take(ctx, slots * 4);
         b->run_off = (uint16_t*)arena_take(ctx, ((size_t)L.p_tiles << L.p_log2) * 2 + (size_t)L.p_tiles * 2);
+        b->kdealt = (uint2*)arena_take(ctx, (size_t)L.k_tiles * kPTile * 8);
+        b->krun_off = (uint16_t*)arena_take(ctx, ((size_t)L.k_tiles << L.p_log2) * 2 + (size_t)L.k_tiles * 2);
         b->pcount = (uint32_t*)arena_take(ctx, cells * 2 * 4);
         b->tile_seg = (uint32_t*)arena_take(ctx, (size_t)L.p_tiles * 4);
         b->fr_cap = L.frontier;
-        return b->meta && b->nbr && b->fr_id && b->fr_lid && b->fr_rs && b->fr_deg && b->fr_seg && b->fr_tile && b->dealt && b->result && b->run_off &&
+        return b->meta && b->nbr && b->fr_id && b->fr_lid && b->fr_rs && b->fr_deg && b->fr_seg && b->fr_tile && b->dealt && b->result && b->run_off && b->kdealt && b->krun_off &&
                b->pcount && b->tile_seg;
     }
-    b->dealt = nullptr; b->result = nullptr; b->run_off = nullptr; b->pcount = nullptr; b->tile_seg = nullptr; b->fr_tile = nullptr;
+    b->dealt = nullptr; b->result = nullptr; b->run_off = nullptr; b->kdealt = nullptr; b->krun_off = nullptr; b->pcount = nullptr; b->tile_seg = nullptr; b->fr_tile = nullptr;
     b->seed_slot = (uint32_t*)arena_take(ctx, (size_t)L.stage0 * 4);
     b->seed_flags = (uint16_t*)arena_take(ctx, (size_t)L.stage0 * 2);
     b->slot_of = (uint32_t*)arena_take(ctx, (size_t)L.edges * 4);
@@ -1761,6 +1762,7 @@ static qv_status plan_sample(qv_ctx* ctx, int64_t max_seeds, const int32_t* fano
     if (L->part) {
         L->p_tiles = (largest + kPTile - 1) / kPTile;
         if (L->p_tiles < 1) L->p_tiles = 1;
+        L->k_tiles = (bd->nodes + kPTile - 1) / kPTile + 1;
         if (ctx->part_log2 >= 0) {
             L->p_log2 = ctx->part_log2;
         } else {
@@ -1778,7 +1780,9 @@ static qv_status launch_part_dedup(qv_ctx* ctx, CallArgs& c, int rowptr_bits, in
     dim3 grid((unsigned)tiles, (unsigned)n_batches);
     {   // the a-priori bounds are loose (most tiles do not exist): k_part_deal strides over the tiles
         const int64_t cap = n_batches >= 4 ? ctx->n_cu * 8 / n_batches : ctx->n_cu * 2;
-        dim3 deal_grid((unsigned)(tiles < cap ? tiles : cap), (unsigned)n_batches);
+        c.deal_blocks = (int32_t)(tiles < cap ? tiles : cap);
+        const int node_blocks = c.stage == 0 ? 0 : n_batches >= 4 ? 8 : 32;      // workgroups of their own for the tiles of n_id
+        dim3 deal_grid((unsigned)(c.deal_blocks + node_blocks), (unsigned)n_batches);
         QV_LAUNCH_A(ctx, c, n_batches, deal_grid, dim3(kPThreads), k_part_deal);
     }
     const unsigned wgs = 8u * (unsigned)((n_batches + 7) / 8) * (unsigned)P;    // (XCD, batch within XCD, partition)
