@@ -294,6 +294,7 @@ struct CallHeader {
     int32_t expect_all_first;       // stand-alone reindex stage 0: ids must be distinct
     int32_t p_log2;                 // partitioned dedup: log2 of the partitions per batch
     int32_t p_tiles;                // ... and the tiles its per-tile arrays hold
+    int32_t deal_all_nodes;         // k_part_deal: the partition count changed: deal all of n_id again, not only its new part
     int32_t deal_blocks;            // k_part_deal: workgroups (per batch) that deal the stage's ids; the rest deal n_id
     uint32_t* part_stats;           // [0] fullest LDS table of the call, [1] deepest split, [2] partitions_log2 + 1 (device, may be NULL)
     int32_t n_batches;
@@ -1024,7 +1025,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_deal(A c) {
         int64_t known = m->node_off[c.stage], before = m->node_off[c.stage - 1];
         if (known > b.n_id_cap) known = b.n_id_cap;
         if (before > known) before = known;
-        const int first = (int)(before / kPTile), end = (int)((known + kPTile - 1) / kPTile);
+        const int first = c.deal_all_nodes ? 0 : (int)(before / kPTile), end = (int)((known + kPTile - 1) / kPTile);
         for (int j = first + (int)blockIdx.x - stage_blocks; j < end; j += node_blocks) {
             const int64_t u0 = (int64_t)j * kPTile;
             deal_tile(b.n_id + u0, known - u0 < kPTile ? known - u0 : kPTile, (uint32_t)u0,
@@ -1187,7 +1188,7 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
         b.pcount[((size_t)t * P + part) * 2 + 1] = S.cnt_new[t];
     }
     // what the host's choice of the partition count goes by: fullest table, deepest split
-    if (tid == 0 && c.part_stats) {
+    if (tid == 0 && c.part_stats && c.stage == c.n_hops) {      // (the last stage holds the most nodes)
         // (looked at first: a thousand workgroups' atomics on one word would queue up behind each other,
         // and once a few calls have run hardly any workgroup has anything new to report)
         uint32_t QV_G* st = gptr(c.part_stats);
@@ -1474,6 +1475,7 @@ struct Bounds {
     int64_t nodes, edges, frontier;
     int64_t hop_edges[QV_MAX_HOPS + 1];     // [k] bound on hop k's edges (k >= 1)
     int64_t hop_front[QV_MAX_HOPS + 1];     // [k] bound on |F_k|
+    int64_t nodes_after[QV_MAX_HOPS + 1];   // [k] bound on |n_id| after stage k
 };
 
 static qv_status compute_bounds(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, int n_hops,
@@ -1485,6 +1487,7 @@ static qv_status compute_bounds(qv_ctx* ctx, int64_t n_seeds, const int32_t* fan
     b->hop_front[0] = n_seeds;
     b->hop_edges[0] = 0;
     b->nodes = n_seeds < n_nodes ? n_seeds : n_nodes; b->edges = 0; b->frontier = n_seeds;
+    b->nodes_after[0] = b->nodes;
     for (int k = 1; k <= n_hops; ++k) {
         int32_t l = fanouts[k - 1];
         if (l < 1 || l > QV_MAX_FANOUT) return fail(ctx, QV_EINVAL, "fanout %d outside [1, %d]", l, QV_MAX_FANOUT);
@@ -1495,6 +1498,7 @@ static qv_status compute_bounds(qv_ctx* ctx, int64_t n_seeds, const int32_t* fan
         b->frontier += e < n_nodes ? e : n_nodes;
         b->nodes = b->nodes + e < n_nodes ? b->nodes + e : n_nodes;
         b->hop_front[k] = cumulative ? b->nodes : (e < n_nodes ? e : n_nodes);
+        b->nodes_after[k] = b->nodes;
     }
     return QV_OK;
 }
@@ -1862,14 +1866,25 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
         if (rc != QV_OK) return rc;
     }
     if (L.part) {
-        // partitioned form: per stage k_part_dedup + k_part_assign; k_sample only writes the edges
-        c.stage = 0; c.next_fanout = fanouts[0];
+        // Partitioned form: per stage k_part_deal + k_part_dedup + k_part_assign; k_sample only writes
+        // the edges.  Early stages hold few nodes and take fewer partitions (every partition is a
+        // workgroup with a table to clear): the last stage's count scaled by the a-priori node bounds,
+        // times eight because those bounds are the looser the later the stage.
+        auto stage_p_log2 = [&](int k) {
+            int lg = 0;
+            while (lg < L.p_log2 && (bd.nodes << lg) < 8 * (bd.nodes_after[k] << L.p_log2)) ++lg;
+            return lg;
+        };
+        c.stage = 0; c.next_fanout = fanouts[0]; c.p_log2 = stage_p_log2(0); c.deal_all_nodes = 0;
         rc = launch_part_dedup(ctx, c, csr->rowptr_bits, max_seeds, n_batches);
         if (rc != QV_OK) return rc;
         for (int k = 1; k <= n_hops; ++k) {
             c.stage = k; c.hop = k; c.fanout = fanouts[k - 1]; c.next_fanout = k < n_hops ? fanouts[k] : 0;
+            const int lg = stage_p_log2(k);
+            c.deal_all_nodes = lg != c.p_log2;
             rc = launch_sample(ctx, c, bd.hop_front[k - 1], n_batches);
             if (rc != QV_OK) return rc;
+            c.p_log2 = lg;
             rc = launch_part_dedup(ctx, c, csr->rowptr_bits, bd.hop_edges[k], n_batches);
             if (rc != QV_OK) return rc;
         }
