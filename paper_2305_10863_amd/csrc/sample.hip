@@ -1035,7 +1035,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_deal(A c) {
 }
 
 // shared state of one k_part_dedup workgroup
-struct PartLds {
+struct alignas(16) PartLds {
     uint32_t t_key[kPCap];                              // the partition's table: id,
     uint32_t t_min[kPCap];                              //   its smallest position in this stage,
     int32_t t_lid[kPCap];                               //   its local id if an earlier stage numbered it, else -1
@@ -1059,6 +1059,23 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
     const PartStage v = part_stage(c, b);
     const int64_t len = v.end - v.begin;
     const int n_tiles = (int)((len + kPTile - 1) / kPTile);
+    // The nodes numbered by earlier stages come from their dealt records, a wave per tile of n_id, a
+    // lane per record of the run.  Each wave requests its first tile's run right away (up to
+    // kKnownAhead records a lane), so that the answer is there when the table has been cleared.
+    constexpr int kKnownAhead = 3;
+    const int n_ktiles = (int)((v.known + kPTile - 1) / kPTile);
+    uint32_t kbeg = 0, kend = 0;
+    uint2 krec[kKnownAhead];
+    if (wave < n_ktiles) {
+        kbeg = b.krun_off[(size_t)wave * (P + 1) + part];
+        kend = b.krun_off[(size_t)wave * (P + 1) + part + 1];
+#pragma unroll
+        for (int i = 0; i < kKnownAhead; ++i) {
+            const uint32_t k = kbeg + (uint32_t)(i * kWave + lane);
+            krec[i] = make_uint2(kEmptyKey, 0u);
+            if (k < kend) krec[i] = b.kdealt[(size_t)wave * kPTile + k];
+        }
+    }
     // Where this partition's records are: its runs, one per tile, are numbered end to end, so that
     // the workgroup's threads can share them evenly whatever the runs' lengths (run_at = exclusive
     // scan of the run lengths).
@@ -1086,16 +1103,19 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
     }
     lds_barrier();
     const uint32_t n_rec = S.run_at[n_tiles];
-    // address of record e (0 <= e < n_rec) in `dealt` / `result`, and its tile
-    auto locate = [&](uint32_t e, int* tile) -> size_t {
-        int lo = 0, hi = n_tiles;                               // run_at[lo] <= e < run_at[hi]
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (S.run_at[mid] <= e) lo = mid; else hi = mid;
-        }
-        *tile = lo;
-        return (size_t)lo * kPTile + S.run_beg[lo] + (e - S.run_at[lo]);
+    // Index of record e (0 <= e < n_rec) in `dealt` / `result`; its tile is that index / kPTile.  The
+    // runs of a partition are all about as long, so the tile is guessed in proportion and the guess
+    // corrected against run_at (a step or two; a search would take log2(n_tiles) dependent LDS reads).
+    const float tiles_per_rec = n_rec ? (float)n_tiles / (float)n_rec : 0.f;
+    auto locate = [&](uint32_t e) -> uint32_t {
+        int g = (int)((float)e * tiles_per_rec);
+        if (g > n_tiles - 1) g = n_tiles - 1;
+        while (S.run_at[g] > e) --g;                            // run_at[0] = 0 <= e
+        while (S.run_at[g + 1] <= e) ++g;                       // run_at[n_tiles] = n_rec > e
+        return (uint32_t)g * kPTile + S.run_beg[g] + (e - S.run_at[g]);
     };
+    constexpr uint32_t kChunk = kDThreads * kDKeys;             // records the workgroup has in flight
+    const uint32_t n_chunks = (n_rec + kChunk - 1) / kChunk;
     uint32_t fill = 0;
     int split = 0;
     for (;; ++split) {
@@ -1103,75 +1123,100 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
         bool failed = false;
         for (uint32_t r = 0; r < n_rounds && !failed; ++r) {
             lds_barrier();                                      // the table is still being read
-            for (int i = tid; i < kPCap; i += kDThreads) { S.t_key[i] = kEmptyKey; S.t_min[i] = 0xFFFFFFFFu; S.t_lid[i] = -1; }
+            static_assert(kPCap == 4 * kDThreads, "the clear below: four entries a thread");
+            reinterpret_cast<uint4*>(S.t_key)[tid] = make_uint4(kEmptyKey, kEmptyKey, kEmptyKey, kEmptyKey);
+            reinterpret_cast<uint4*>(S.t_min)[tid] = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
+            reinterpret_cast<uint4*>(S.t_lid)[tid] = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
             if (r == 0) for (int t = tid; t < n_tiles; t += kDThreads) { S.cnt_first[t] = 0; S.cnt_new[t] = 0; }
             if (tid == 0) S.s_fill = 0;
             lds_barrier();
-            // nodes numbered by earlier stages, from their dealt records: a wave per tile of n_id, a lane per record of the run
             uint32_t claimed = 0;
-            {
-                const int n_ktiles = (int)((v.known + kPTile - 1) / kPTile);
-                for (int j = wave; j < n_ktiles; j += kDThreads / kWave) {
-                    const uint32_t beg = b.krun_off[(size_t)j * (P + 1) + part], end = b.krun_off[(size_t)j * (P + 1) + part + 1];
-                    for (uint32_t k = beg + (uint32_t)lane; k < end; k += kWave) {
-                        const uint2 rec = b.kdealt[(size_t)j * kPTile + k];
-                        const uint32_t h = fmix32(rec.x);
-                        if (split && (h >> (32 - split)) != r) continue;
-                        const int s2 = lds_insert(S.t_key, rec.x, h & (kPCap - 1), &claimed);
-                        if (s2 < 0) claimed += (uint32_t)kPCap;
-                        else S.t_lid[s2] = (int32_t)rec.y;
+            auto add_known = [&](const uint2 rec) {
+                if (rec.x == kEmptyKey) return;
+                const uint32_t h = fmix32(rec.x);
+                if (split && (h >> (32 - split)) != r) return;
+                const int s2 = lds_insert(S.t_key, rec.x, h & (kPCap - 1), &claimed);
+                if (s2 < 0) claimed += (uint32_t)kPCap;
+                else S.t_lid[s2] = (int32_t)rec.y;
+            };
+            for (int j = wave; j < n_ktiles; j += kDThreads / kWave) {
+                uint32_t beg = kbeg, end = kend;
+                if (j == wave) {
+#pragma unroll
+                    for (int i = 0; i < kKnownAhead; ++i) add_known(krec[i]);
+                    beg += kKnownAhead * kWave;
+                } else {
+                    beg = b.krun_off[(size_t)j * (P + 1) + part]; end = b.krun_off[(size_t)j * (P + 1) + part + 1];
+                }
+                for (uint32_t k0 = beg; k0 < end; k0 += kKnownAhead * kWave) {
+                    uint2 more[kKnownAhead];
+#pragma unroll
+                    for (int i = 0; i < kKnownAhead; ++i) {
+                        const uint32_t k = k0 + (uint32_t)(i * kWave + lane);
+                        more[i] = make_uint2(kEmptyKey, 0u);
+                        if (k < end) more[i] = b.kdealt[(size_t)j * kPTile + k];
                     }
+#pragma unroll
+                    for (int i = 0; i < kKnownAhead; ++i) add_known(more[i]);
                 }
             }
-            // pass 1: register every record (eight per thread requested together)
-            for (uint32_t e0 = 0; e0 < n_rec; e0 += kDThreads * kDKeys) {
-                uint2 rec[kDKeys];
+            // A chunk: kDKeys records per thread, requested together.  slot = the record's table entry,
+            // -1 if it has none (no such record, not this sub-round's, table full).
+            uint2 rec[kDKeys];
+            uint32_t at[kDKeys];
+            int slot[kDKeys];
+            auto load_chunk = [&](uint32_t ci) {
 #pragma unroll
                 for (int i = 0; i < kDKeys; ++i) {
-                    const uint32_t e = e0 + (uint32_t)(i * kDThreads + tid);
-                    int tile;
-                    rec[i] = make_uint2(kEmptyKey, 0u);
-                    if (e < n_rec) rec[i] = b.dealt[locate(e, &tile)];
+                    const uint32_t e = ci * kChunk + (uint32_t)(i * kDThreads + tid);
+                    rec[i] = make_uint2(kEmptyKey, 0u); at[i] = 0;
+                    if (e < n_rec) { at[i] = locate(e); rec[i] = b.dealt[at[i]]; }
                 }
+            };
+            // pass 1: register every record
+            for (uint32_t ci = 0; ci < n_chunks; ++ci) {
+                load_chunk(ci);
 #pragma unroll
                 for (int i = 0; i < kDKeys; ++i) {
+                    slot[i] = -1;
                     if (rec[i].x == kEmptyKey) continue;
                     const uint32_t h = fmix32(rec[i].x);
                     if (split && (h >> (32 - split)) != r) continue;
-                    const int s2 = lds_insert(S.t_key, rec[i].x, h & (kPCap - 1), &claimed);
-                    if (s2 < 0) claimed += (uint32_t)kPCap;
-                    else atomicMin(&S.t_min[s2], rec[i].y);
+                    slot[i] = lds_insert(S.t_key, rec[i].x, h & (kPCap - 1), &claimed);
+                    if (slot[i] < 0) claimed += (uint32_t)kPCap;
+                    else atomicMin(&S.t_min[slot[i]], rec[i].y);
                 }
             }
             if (claimed) atomicAdd(&S.s_fill, claimed);
             lds_barrier();
             fill = S.s_fill;
             if (fill > kPFillMax) { failed = true; break; }
-            // pass 2: every id's smallest position is final
-            for (uint32_t e0 = 0; e0 < n_rec; e0 += kDThreads * kDKeys) {
-                uint2 rec[kDKeys];
-                size_t at[kDKeys];
-                int tile[kDKeys];
+            // pass 2: every id's smallest position is final.  The chunks are taken last to first: the
+            // last one is still in registers with its table entries (mostly it is the only one).
+            for (uint32_t ci = n_chunks; ci-- > 0;) {
+                if (ci != n_chunks - 1) {
+                    load_chunk(ci);
 #pragma unroll
-                for (int i = 0; i < kDKeys; ++i) {
-                    const uint32_t e = e0 + (uint32_t)(i * kDThreads + tid);
-                    rec[i] = make_uint2(kEmptyKey, 0u); at[i] = 0; tile[i] = 0;
-                    if (e < n_rec) { at[i] = locate(e, &tile[i]); rec[i] = b.dealt[at[i]]; }
+                    for (int i = 0; i < kDKeys; ++i) {
+                        slot[i] = -1;
+                        if (rec[i].x == kEmptyKey) continue;
+                        uint32_t x = fmix32(rec[i].x);
+                        if (split && (x >> (32 - split)) != r) continue;
+                        x &= kPCap - 1;
+                        while (S.t_key[x] != rec[i].x) x = (x + 1) & (kPCap - 1);     // pass 1 put it there
+                        slot[i] = (int)x;
+                    }
                 }
 #pragma unroll
                 for (int i = 0; i < kDKeys; ++i) {
-                    if (rec[i].x == kEmptyKey) continue;
-                    uint32_t x = fmix32(rec[i].x);
-                    if (split && (x >> (32 - split)) != r) continue;
-                    x &= kPCap - 1;
-                    while (S.t_key[x] != rec[i].x) x = (x + 1) & (kPCap - 1);         // pass 1 put it there
-                    const uint32_t mp = S.t_min[x];
-                    const int32_t lid = S.t_lid[x];
+                    if (slot[i] < 0) continue;
+                    const uint32_t mp = S.t_min[slot[i]];
+                    const int32_t lid = S.t_lid[slot[i]];
                     const bool first = mp == rec[i].y;
                     b.result[at[i]] = lid >= 0 ? (lid | (first ? 1 << 30 : 0)) : first ? -1 : -2 - (int32_t)mp;
                     if (first) {
-                        atomicAdd(&S.cnt_first[tile[i]], 1u);
-                        if (lid < 0) atomicAdd(&S.cnt_new[tile[i]], 1u);
+                        atomicAdd(&S.cnt_first[at[i] / kPTile], 1u);
+                        if (lid < 0) atomicAdd(&S.cnt_new[at[i] / kPTile], 1u);
                     }
                 }
             }
