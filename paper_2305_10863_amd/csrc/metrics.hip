@@ -23,11 +23,18 @@ __device__ __forceinline__ double group_sum(double v) {
     return v;
 }
 
+// Rows longer than this get a whole workgroup (k_psgs_long, k_fap_pull_long) instead of one group of
+// lanes: a hub would otherwise hold its group for milliseconds after the rest of the grid is done.
+constexpr int64_t kLongRow = 8192;
+
 // One PSGS sweep: group of G lanes per row.  s_next == nullptr is the innermost hop (no edges read).
+// Long rows are left to k_psgs_long; the first edge-reading sweep of a call lists them (collect != 0),
+// the later ones only skip them (the list depends on the graph alone).
 template <int G, typename RP>
 __global__ void __launch_bounds__(256) k_psgs_sweep(const RP* __restrict__ rowptr, const int32_t* __restrict__ col,
                                                     int64_t n, int32_t fanout, const float* __restrict__ s_next,
-                                                    float* __restrict__ s_out, float add) {
+                                                    float* __restrict__ s_out, float add, int32_t* __restrict__ long_rows,
+                                                    int32_t* n_long, int32_t long_cap, int32_t collect) {
     const int sub = threadIdx.x % G;
     const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G;
     const int64_t n_groups = (int64_t)gridDim.x * blockDim.x / G;
@@ -36,6 +43,13 @@ __global__ void __launch_bounds__(256) k_psgs_sweep(const RP* __restrict__ rowpt
         const int64_t deg = re - rs;
         const double m = (double)(deg < fanout ? deg : (int64_t)fanout);
         double val = m;
+        if (s_next && deg > kLongRow) {
+            if (collect && sub == 0) {
+                const int32_t k = atomicAdd(n_long, 1);
+                if (k < long_cap) long_rows[k] = (int32_t)i;
+            }
+            continue;
+        }
         if (s_next && deg > 0) {
             double acc0 = 0.0, acc1 = 0.0;
             int64_t e = rs + sub;
@@ -50,6 +64,42 @@ __global__ void __launch_bounds__(256) k_psgs_sweep(const RP* __restrict__ rowpt
         if (sub == 0) s_out[i] = (float)(val + (double)add);
     }
 }
+
+// the listed long rows of a PSGS sweep, a workgroup per row, four loads a thread in flight
+template <typename RP>
+__global__ void __launch_bounds__(256) k_psgs_long(const RP* __restrict__ rowptr, const int32_t* __restrict__ col,
+                                                   int32_t fanout, const float* __restrict__ s_next,
+                                                   float* __restrict__ s_out, float add,
+                                                   const int32_t* __restrict__ long_rows, const int32_t* n_long,
+                                                   int32_t long_cap) {
+    __shared__ double part[256 / kWave];
+    int32_t count = *n_long;
+    if (count > long_cap) count = long_cap;
+    for (int32_t k = blockIdx.x; k < count; k += gridDim.x) {
+        const int64_t i = long_rows[k];
+        const int64_t rs = (int64_t)rowptr[i], re = (int64_t)rowptr[i + 1];
+        const int64_t deg = re - rs;
+        double acc0 = 0.0, acc1 = 0.0;
+        int64_t e = rs + threadIdx.x;
+        for (; e + 768 < re; e += 1024) {
+            const float x0 = s_next[col[e]], x1 = s_next[col[e + 256]], x2 = s_next[col[e + 512]], x3 = s_next[col[e + 768]];
+            acc0 += (double)x0 + (double)x2; acc1 += (double)x1 + (double)x3;
+        }
+        for (; e < re; e += 256) acc0 += (double)s_next[col[e]];
+        const double w = group_sum<kWave>(acc0 + acc1);
+        __syncthreads();
+        if (threadIdx.x % kWave == 0) part[threadIdx.x / kWave] = w;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double acc = 0.0;
+            for (int q = 0; q < 256 / kWave; ++q) acc += part[q];
+            const double m = (double)(deg < fanout ? deg : (int64_t)fanout);
+            s_out[i] = (float)(m + (m / (double)deg) * acc + (double)add);
+        }
+    }
+}
+
+__global__ void k_psgs_control_clear(int32_t* n_long) { *n_long = 0; }
 
 __global__ void k_psgs_batch_sum(const float* __restrict__ psgs, int64_t n_nodes, const int32_t* __restrict__ seeds,
                                  int64_t n_seeds, double* out, int32_t* status) {
@@ -127,7 +177,6 @@ __global__ void k_fap_fold(int64_t n, const double* __restrict__ p_new, double* 
 // Both kernels of both directions are launched every sweep; the ones not chosen return at once.
 // Rows longer than kLongRow are left to k_fap_pull_long (a whole block per row) so that one hub
 // does not hold a 16-lane group for milliseconds.
-constexpr int64_t kLongRow = 8192;
 constexpr double kAtomicPerLoadCost = 2.5;
 
 struct FapControl {
@@ -332,16 +381,23 @@ static int group_width_for(int64_t n, int64_t e) {
 
 template <typename RP>
 static void launch_psgs_sweep(qv_ctx* ctx, const qv_csr* g, int G, int32_t fanout, const float* s_next, float* s_out,
-                              float add) {
+                              float add, int32_t* long_rows, int32_t* n_long, int32_t long_cap, int32_t collect) {
     int blocks = grid_for(g->n_nodes * G, 256, ctx->n_cu * 32);
     const RP* rp = (const RP*)g->rowptr;
+#define QV_SWEEP(GW)                                                                                                   \
+    hipLaunchKernelGGL((k_psgs_sweep<GW, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout,    \
+                       s_next, s_out, add, long_rows, n_long, long_cap, collect)
     switch (G) {
-        case 4: hipLaunchKernelGGL((k_psgs_sweep<4, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
-        case 8: hipLaunchKernelGGL((k_psgs_sweep<8, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
-        case 16: hipLaunchKernelGGL((k_psgs_sweep<16, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
-        case 32: hipLaunchKernelGGL((k_psgs_sweep<32, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
-        default: hipLaunchKernelGGL((k_psgs_sweep<64, RP>), dim3(blocks), dim3(256), 0, ctx->stream, rp, g->col, g->n_nodes, fanout, s_next, s_out, add); break;
+        case 4: QV_SWEEP(4); break;
+        case 8: QV_SWEEP(8); break;
+        case 16: QV_SWEEP(16); break;
+        case 32: QV_SWEEP(32); break;
+        default: QV_SWEEP(64); break;
     }
+#undef QV_SWEEP
+    if (s_next)
+        hipLaunchKernelGGL((k_psgs_long<RP>), dim3(grid_for(long_cap, 1, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, rp, g->col,
+                           fanout, s_next, s_out, add, (const int32_t*)long_rows, (const int32_t*)n_long, long_cap);
 }
 
 template <typename RP>
@@ -443,9 +499,14 @@ qv_status qv_psgs(qv_ctx* ctx, const qv_csr* g, const int32_t* fanouts, int32_t 
     if (rc != QV_OK) return rc;
     const int64_t n = g->n_nodes;
     if (n == 0) return QV_OK;
-    rc = arena_begin(ctx, align_up((size_t)n * 4) + 4096);
+    const int32_t long_cap = (int32_t)(g->n_edges / kLongRow + 1);
+    rc = arena_begin(ctx, align_up((size_t)n * 4) + align_up((size_t)long_cap * 4) + 4096);
     if (rc != QV_OK) return rc;
     float* tmp = (float*)arena_take(ctx, (size_t)n * 4);
+    int32_t* long_rows = (int32_t*)arena_take(ctx, (size_t)long_cap * 4);
+    int32_t* n_long = (int32_t*)arena_take(ctx, 4);
+    hipLaunchKernelGGL(k_psgs_control_clear, dim3(1), dim3(1), 0, ctx->stream, n_long);
+    bool listed = false;
     const int G = group_width_for(n, g->n_edges);
     const float* prev = nullptr;
     for (int j = 0; j < n_hops; ++j) {                 // hop m = K - j
@@ -453,9 +514,11 @@ qv_status qv_psgs(qv_ctx* ctx, const qv_csr* g, const int32_t* fanouts, int32_t 
         float* dst = ((n_hops - 1 - j) % 2 == 0) ? psgs_out : tmp;
         const float add = (m == 1) ? 1.0f : 0.0f;
         const int Gj = prev ? G : 4;                   // the innermost hop reads no edges
-        if (g->rowptr_bits == 32) launch_psgs_sweep<int32_t>(ctx, g, Gj, fanouts[m - 1], prev, dst, add);
-        else launch_psgs_sweep<int64_t>(ctx, g, Gj, fanouts[m - 1], prev, dst, add);
+        const int32_t collect = (prev && !listed) ? 1 : 0;
+        if (g->rowptr_bits == 32) launch_psgs_sweep<int32_t>(ctx, g, Gj, fanouts[m - 1], prev, dst, add, long_rows, n_long, long_cap, collect);
+        else launch_psgs_sweep<int64_t>(ctx, g, Gj, fanouts[m - 1], prev, dst, add, long_rows, n_long, long_cap, collect);
         QV_LAUNCH_CHECK(ctx, "k_psgs_sweep");
+        if (prev) listed = true;
         prev = dst;
     }
     return QV_OK;

@@ -494,6 +494,27 @@ def transposed_graph(qv, ctx, rowptr, col):
 
 
 @pytest.mark.parametrize("rp_dtype", [np.int32, np.int64])
+def test_psgs_with_out_rows_beyond_the_per_group_limit(qv, ctx, rp_dtype):
+    """A few nodes have tens of thousands of out-edges: their rows are summed a workgroup per row
+    (listed by the first edge-reading sweep, reused by the later ones); one row sits just below
+    the limit, one just above it."""
+    rng = np.random.default_rng(21)
+    n = 50_000
+    deg = rng.integers(0, 10, n)
+    deg[rng.random(n) < 0.1] = 0
+    deg[[5, 777, 49_999]] = [30_001, 8_193, 12_345]
+    deg[6] = 8_192
+    rowptr = np.zeros(n + 1, dtype=rp_dtype)
+    np.cumsum(deg, out=rowptr[1:])
+    col = rng.integers(0, n, int(rowptr[-1])).astype(np.int32)
+    g = make_graph(qv, ctx, rowptr, col)
+    for fanouts in ([15, 10, 5], [3, 1000, 2, 7], [4]):
+        Q = qv.qv_psgs(ctx, g, fanouts)
+        ctx.sync()
+        assert rel_err(Q.cpu().numpy(), oracle.psgs(rowptr, col, fanouts)) <= REL_TOL
+
+
+@pytest.mark.parametrize("rp_dtype", [np.int32, np.int64])
 def test_access_prob_in_edge_form_directed_graph_with_hub_rows(qv, ctx, rp_dtype):
     """A directed graph in which a few nodes receive tens of thousands of edges (in-rows beyond the
     per-group limit, handled a block per row) and some nodes have no out- or no in-edges."""
