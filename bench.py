@@ -138,11 +138,12 @@ def placement_ablation(qv, qvgen, w, ctx, g, table, P_pop, rowptr, col, tdtype):
 
 def hardware_rates(qvgen):
     import torch
+    import bench_probes
     out = {"metric": "hardware_rates", "unit": "1e9 operations/s", "rates": []}
     names = {0: "atomicMin u64 (result unused)", 1: "atomicMin u32 (result unused)", 2: "store 8 B", 3: "load 8 B",
              4: "atomicMin u64, workgroup scope", 5: "atomicMin u64, each XCD in its own eighth of the table",
              6: "atomicMin u64, workgroup scope, each XCD in its own eighth", 7: "load 8 B, each XCD in its own eighth"}
-    xm = qvgen.xcd_map_device(4096).cpu()
+    xm = bench_probes.xcd_map(4096).cpu()
     out["workgroups_on_xcd_blockIdx_mod_8"] = int((xm == (torch.arange(4096, dtype=torch.int32) % 8)).sum().item())
     out["workgroups_checked"] = 4096
     for slots in (111_000_000, 1 << 23, 1 << 20):
@@ -153,7 +154,7 @@ def hardware_rates(qvgen):
                 for rep in range(5):
                     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
                     e0.record()
-                    qvgen.random_ops_device(mode, table, n_ops, salt=rep * 7919 + mode)
+                    bench_probes.random_ops(mode, table, n_ops, salt=rep * 7919 + mode)
                     e1.record()
                     torch.cuda.synchronize()
                     best = min(best, e0.elapsed_time(e1))

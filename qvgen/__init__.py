@@ -80,10 +80,6 @@ def dev():
         _dev.qg_features_device.restype = C.c_int
         _dev.qg_features_device.argtypes = [C.c_uint64, C.c_int64, C.c_int64, C.c_int64, C.c_int,
                                             C.c_void_p, C.c_void_p]
-        _dev.qg_random_ops_device.restype = C.c_int
-        _dev.qg_random_ops_device.argtypes = [C.c_int, C.c_void_p, C.c_int64, C.c_int64, C.c_uint64, C.c_void_p]
-        _dev.qg_xcd_map_device.restype = C.c_int
-        _dev.qg_xcd_map_device.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
         _dev.qg_copy_device.restype = C.c_int
         _dev.qg_copy_device.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p]
     return _dev
@@ -152,28 +148,6 @@ def copy_device(src, dst):
     if rc != 0:
         raise RuntimeError("qg_copy_device failed: hip error %d" % rc)
     return n
-
-
-def random_ops_device(mode, table, n_ops, salt=0):
-    """Yardstick: n_ops random single-word operations over an int64 device tensor.
-    mode 0 atomicMin u64, 1 atomicMin u32, 2 store 8 B, 3 load 8 B, 4 atomicMin u64 at workgroup
-    scope, 5 / 6 atomicMin u64 at device / workgroup scope with each XCD confined to its own eighth
-    of the table, 7 load 8 B confined likewise."""
-    import torch
-    rc = dev().qg_random_ops_device(mode, table.data_ptr(), table.numel(), n_ops, salt,
-                                    torch.cuda.current_stream().cuda_stream)
-    if rc != 0:
-        raise RuntimeError("qg_random_ops_device failed: hip error %d" % rc)
-
-
-def xcd_map_device(n_blocks):
-    """int32 tensor: the XCD that ran each of n_blocks workgroups of one launch."""
-    import torch
-    out = torch.zeros(n_blocks, dtype=torch.int32, device="cuda")
-    rc = dev().qg_xcd_map_device(out.data_ptr(), n_blocks, torch.cuda.current_stream().cuda_stream)
-    if rc != 0:
-        raise RuntimeError("qg_xcd_map_device failed: hip error %d" % rc)
-    return out
 
 
 def seeds(seed, n_nodes, batch, n_seeds, mode=0):
