@@ -187,8 +187,8 @@ def main():
     ap.add_argument("--extra-streams", type=int, default=16,
                     help="after the timed region, time the same region over 1, 2, 4, 8, 16 streams up to this many and "
                          "report ms per step for each (0 = skip; only when --streams is 1)")
-    ap.add_argument("--batches-per-call", type=int, default=64,
-                    help="independent batches per qv_sample_many / qv_gather_many call (1..64)")
+    ap.add_argument("--batches-per-call", type=int, default=128,
+                    help="independent batches per qv_sample_many / qv_gather_many call (1..128)")
     ap.add_argument("--latency-samples", type=int, default=200, help="single-batch calls timed for p50 / p99 (at least 200)")
     ap.add_argument("--table-budget-gib", type=float, default=-1.0,
                     help="dedup table budget per context in GiB for the table forms (0 = always hash; default: the library's 16)")

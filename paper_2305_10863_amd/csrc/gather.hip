@@ -2,8 +2,8 @@
 //
 // Gather kernel: a group of LPR lanes (a power of two, up to the whole wave) copies one row with
 // the widest vector the row starts allow (16, 8, 4 or 2 bytes per lane), one row per group per
-// round with the next row's id already requested, up to QV_MAX_BATCHES id lists per launch
-// (blockIdx.y).  Rows of the host tier are
+// round with the next row's id already requested, up to kGatherJobs id lists per launch
+// (blockIdx.y; a call with more lists is issued as several launches).  Rows of the host tier are
 // read by the same loads through the device mapping of pinned host memory (zero-copy), so
 // placement never changes the result.
 //
@@ -24,6 +24,8 @@ namespace qv {
 typedef uint32_t v4u __attribute__((ext_vector_type(4)));
 typedef uint32_t v2u __attribute__((ext_vector_type(2)));
 
+constexpr int kGatherJobs = 64;     // id lists per launch: the job table travels in the kernel argument block (4 KB at most)
+
 struct GatherArgs {
     const char* hot;
     const char* cold;
@@ -35,7 +37,7 @@ struct GatherArgs {
     int32_t tail_pieces;            // 2-byte pieces after the last whole vector
     int32_t tail_at;                // index of the first tail piece (in 2-byte units)
     int32_t* status;
-    GatherJob jobs[kMaxBatch];      // one id list / output per blockIdx.y
+    GatherJob jobs[kGatherJobs];    // one id list / output per blockIdx.y
 };
 
 // Output rows are written once and not read again by this kernel: non-temporal stores keep them
@@ -95,7 +97,18 @@ static void launch_gather_v(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t m
     else launch_gather_vt<V, false>(ctx, a, lpr, max_ids, n_jobs);
 }
 
+static qv_status launch_gather_some(qv_ctx* ctx, const GatherSource& s, const GatherJob* jobs, int n_jobs, int64_t out_stride);
+
 qv_status launch_gather(qv_ctx* ctx, const GatherSource& s, const GatherJob* jobs, int n_jobs, int64_t out_stride) {
+    for (int first = 0; first < n_jobs; first += kGatherJobs) {
+        const int n = n_jobs - first < kGatherJobs ? n_jobs - first : kGatherJobs;
+        const qv_status rc = launch_gather_some(ctx, s, jobs + first, n, out_stride);
+        if (rc != QV_OK) return rc;
+    }
+    return QV_OK;
+}
+
+static qv_status launch_gather_some(qv_ctx* ctx, const GatherSource& s, const GatherJob* jobs, int n_jobs, int64_t out_stride) {
     // widest vector that divides every row start
     uintptr_t bits = (uintptr_t)s.hot_stride | (uintptr_t)out_stride | (uintptr_t)s.hot;
     if (s.cold) bits |= (uintptr_t)s.cold_stride | (uintptr_t)s.cold;     // a tier that does not exist constrains nothing

@@ -209,17 +209,27 @@ def test_sample_many_and_gather_many(qv, ctx, tiny, n_batches):
     feat.close()
 
 
-def test_call_of_64_batches(qv, ctx, tiny):
+def test_call_of_the_most_batches(qv, ctx, tiny):
     # the largest call: QV_MAX_BATCHES batches of unequal sizes through one set of launches
     w, rowptr, col, g = tiny
     n = qv.QV_MAX_BATCHES
-    assert n == 64
+    assert n == 128
     seeds = [w.seeds(700 + j, 1 + (37 * j) % 300) for j in range(n)]
     rng = [900 + j for j in range(n)]
     outs = qv.qv_sample_many(ctx, g, [dev(s) for s in seeds], [7, 4, 3], rng)
     ctx.sync()
+    wants = [oracle.sample(rowptr, col, seeds[j], [7, 4, 3], rng[j]) for j in range(n)]
     for j in range(n):
-        assert_sample_equal(outs[j].to_host(), oracle.sample(rowptr, col, seeds[j], [7, 4, 3], rng[j]))
+        assert_sample_equal(outs[j].to_host(), wants[j])
+    # the gather of all of them in one call (more id lists than one launch takes)
+    table = qvgen.features_host(w.seed, w.n, w.dim, w.feat_dtype)
+    feat = qv.Features(ctx, dev(table))
+    rows = qv.qv_gather_many(ctx, feat, [o.n_id for o in outs], [o.node_off[-1:] for o in outs])
+    ctx.sync()
+    for j in range(n):
+        U = len(wants[j]["n_id"])
+        assert rows[j][:U].cpu().numpy().tobytes() == oracle.gather(table, wants[j]["n_id"]).tobytes()
+    feat.close()
 
 
 def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
