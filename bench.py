@@ -21,13 +21,14 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
-# Measured HBM bytes of k_gather over its algorithmic bytes (rocprofv3 FETCH_SIZE + WRITE_SIZE,
-# each scaled by a 1 GiB plain copy kernel; profiles/citation_k_gather_and_sampling_kernels.md,
-# profiles/dense_social_and_co_purchase_kernel_durations.md).
-# Only quoted for the configurations that were profiled.
-GATHER_TRAFFIC_RATIO = {("citation", 1.0, 32): 0.969, ("dense_social", 1.0, 32): 1.024, ("co_purchase", 1.0, 32): 1.160,
-                        ("citation", 1.0, 8): 0.972, ("dense_social", 1.0, 8): 1.024, ("co_purchase", 1.0, 8): 1.160}
-GATHER_TRAFFIC_PROFILE = "profiles/ (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 of k_gather over its algorithmic bytes, same workload and batches per call)"
+# Measured HBM bytes of k_gather over its algorithmic bytes (rocprofv3 FETCH_SIZE + WRITE_SIZE, each
+# scaled by a 1 GiB plain copy kernel in the same run), keyed by workload, scale and id lists per
+# k_gather launch; see GATHER_TRAFFIC_PROFILE.  Only quoted for configurations that were profiled.
+GATHER_LISTS_PER_LAUNCH = 64
+GATHER_TRAFFIC_RATIO = {("citation", 1.0, 64): 0.969}
+GATHER_TRAFFIC_PROFILE = ("profiles/citation_call_of_128_batches_kernels_and_counters.md and "
+                          "profiles/other_workloads_kernel_durations_and_gather_traffic.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 "
+                          "of k_gather over its algorithmic bytes, same workload and lists per launch)")
 
 
 def log(msg):
@@ -518,11 +519,14 @@ def main():
     gather_ms = [e[1].elapsed_time(e[2]) for reg in region_ev for e in reg]
     batch_ms = [e[0].elapsed_time(e[2]) for reg in region_ev for e in reg]
     ms_per_step = elapsed * 1e3 / n_batches
-    gather_avg_ms = float(np.mean(gather_ms))
-    gather_bytes_per_launch = gath_b / calls_per_region
+    # a qv_gather_many call issues its id lists GATHER_LISTS_PER_LAUNCH to a k_gather launch, back to back
+    launches_per_call = (B + GATHER_LISTS_PER_LAUNCH - 1) // GATHER_LISTS_PER_LAUNCH
+    gather_call_ms = float(np.mean(gather_ms))
+    gather_avg_ms = gather_call_ms / launches_per_call
+    gather_bytes_per_launch = gath_b / calls_per_region / launches_per_call
     achieved = gather_bytes_per_launch / (gather_avg_ms * 1e-3) / 1e9
     path_bytes = samp_b + reidx_b + gath_b
-    ratio = GATHER_TRAFFIC_RATIO.get((w.name, args.scale, B))
+    ratio = GATHER_TRAFFIC_RATIO.get((w.name, args.scale, min(B, GATHER_LISTS_PER_LAUNCH)))
 
     result = {
         "metric": "sampled_edges_per_s",
@@ -544,7 +548,7 @@ def main():
                           "have been timed and the median region is reported"},
         "sampled_edges_per_batch": round(tot_edges / n_batches, 1),
         "unique_nodes_per_batch": round(tot_unique / n_batches, 1),
-        "gathered_feature_GBps": round(tot_unique * w.row_bytes / calls_per_region / (gather_avg_ms * 1e-3) / 1e9, 2),
+        "gathered_feature_GBps": round(tot_unique * w.row_bytes / calls_per_region / (gather_call_ms * 1e-3) / 1e9, 2),
         "gather_frac_hbm_peak": round(achieved / HBM_PEAK_GBPS, 4),
         "path_algorithmic_GBps": round(path_bytes / elapsed / 1e9, 2),
         "path_frac_hbm_peak": round(path_bytes / elapsed / 1e9 / HBM_PEAK_GBPS, 4),
@@ -553,18 +557,18 @@ def main():
         "latency_samples": len(lat_ms),
         "p50_call_latency_ms": round(float(np.percentile(batch_ms, 50)), 4),
         "sample_ms_avg": round(float(np.mean(sample_ms)), 4),
-        "gather_ms_avg": round(gather_avg_ms, 4),
+        "gather_ms_avg": round(gather_call_ms, 4),
         "roofline": {"bound": "hbm", "kernel": "k_gather", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": round(ratio * gather_bytes_per_launch) if ratio else None,
                      "traffic_source": (GATHER_TRAFFIC_PROFILE if ratio else
                                         "no rocprofv3 counter run is committed for this workload and batches per call"),
                      "bytes_per_launch": round(gather_bytes_per_launch), "avg_launch_ms": round(gather_avg_ms, 5),
-                     "launches_timed": len(gather_ms)},
+                     "launches_timed": len(gather_ms) * launches_per_call, "lists_per_launch": min(B, GATHER_LISTS_PER_LAUNCH)},
     }
     if tiered:
         cold_bytes = extra["cold_row_fraction"] * tot_unique * w.row_bytes
-        extra["cold_tier_GBps"] = round(cold_bytes / calls_per_region / (gather_avg_ms * 1e-3) / 1e9, 2)
+        extra["cold_tier_GBps"] = round(cold_bytes / calls_per_region / (gather_call_ms * 1e-3) / 1e9, 2)
         result["roofline"]["note"] = ("tiered: %.0f%% of the rows come over the host link, which bounds this "
                                       "kernel, not HBM" % (100 * extra["cold_row_fraction"]))
     if sweep:

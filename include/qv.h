@@ -87,7 +87,7 @@ qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes);
  * edges to pay for its extra kernels (a-priori edge bound x batches >= 8 Mi), the tables above
  * otherwise.  QV_DEDUP_TABLE: always tables.  QV_DEDUP_PARTITIONED: the partitioned form
  * wherever it applies, i.e. layer frontiers with at most 4,194,304 ids per stage.
- * partitions_log2: partitions per batch of the partitioned form as a power of two, 0..6, or -1
+ * partitions_log2: partitions per batch of the partitioned form as a power of two, 0..8, or -1
  * to let the library settle on a count from what earlier calls report. */
 #define QV_DEDUP_AUTO 0
 #define QV_DEDUP_TABLE 1

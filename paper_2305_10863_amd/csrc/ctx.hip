@@ -145,7 +145,7 @@ qv_status qv_ctx_set_table_budget(qv_ctx* ctx, int64_t bytes) {
 qv_status qv_ctx_set_dedup(qv_ctx* ctx, int32_t form, int32_t partitions_log2) {
     if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_set_dedup: ctx is NULL");
     if (form < QV_DEDUP_AUTO || form > QV_DEDUP_PARTITIONED) return fail(ctx, QV_EINVAL, "qv_ctx_set_dedup: unknown form %d", form);
-    if (partitions_log2 < -1 || partitions_log2 > 6) return fail(ctx, QV_EINVAL, "qv_ctx_set_dedup: partitions_log2 %d outside [-1, 6]", partitions_log2);
+    if (partitions_log2 < -1 || partitions_log2 > 8) return fail(ctx, QV_EINVAL, "qv_ctx_set_dedup: partitions_log2 %d outside [-1, 8]", partitions_log2);
     ctx->dedup_form = form;
     ctx->part_log2 = partitions_log2;
     return QV_OK;

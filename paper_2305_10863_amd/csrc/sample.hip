@@ -187,7 +187,7 @@ struct BatchArgs {
     uint16_t* run_off;              // [tile][P + 1] where each partition's records start inside the tile's 4096
     uint2* kdealt;                  // n_id dealt the same way, in tiles of 4,096 local ids: (id, local id) records
     uint16_t* krun_off;             // [tile of n_id][P + 1]
-    uint32_t* pcount;               // [tile][partition][first, new] populations
+    uint32_t* pcount;               // [tile][partition][first, new] populations of the partition's earlier tiles
     uint32_t* tile_seg;             // [tile] next-hop edges produced by the tile's first occurrences
     uint16_t* fr_tile;              // per frontier entry: the tile that produced it (fr_seg is then tile-local)
     int64_t* node_off_out; int64_t* edge_off_out; int64_t* frontier_off_out;
@@ -374,7 +374,7 @@ constexpr int kPCapLog2 = 12;
 constexpr int kPCap = 1 << kPCapLog2;               // entries of a partition's LDS table
 constexpr uint32_t kPFillMax = kPCap / 8 * 7;       // a table fuller than this splits its partition further
 constexpr int kPMaxTiles = 1024;                    // tiles per stage and batch (larger stages use the table forms)
-constexpr int kPMaxLog2 = 6;                        // at most 64 partitions per batch
+constexpr int kPMaxLog2 = 8;                        // at most 256 partitions per batch
 constexpr int kPMaxProbes = 128;                    // longer probe sequences count as overflow (unheard of below kPFillMax)
 constexpr int kPMaxSplit = 12;                      // a partition is split into at most 2^12 sub-rounds
 constexpr uint32_t kEmptyKey = 0xFFFFFFFFu;
@@ -945,7 +945,8 @@ constexpr int32_t kResNone = INT32_MIN;            // k_part_assign: a position 
 
 template <typename A>
 __global__ void __launch_bounds__(kPThreads) k_part_deal(A c) {
-    __shared__ uint32_t hist[(1 << kPMaxLog2) + 1], offs[(1 << kPMaxLog2) + 1];
+    __shared__ uint32_t hist[(1 << kPMaxLog2) + 1], offs[(1 << kPMaxLog2) + 1], wsum[(1 << kPMaxLog2) / kWave];
+    static_assert((1 << kPMaxLog2) <= kPThreads, "a thread per partition in the scan");
     __shared__ uint2 sorted[kPTile];
     const BatchG b(c.batch(blockIdx.y));
     const int p_log2 = c.p_log2, P = 1 << p_log2;
@@ -983,19 +984,27 @@ __global__ void __launch_bounds__(kPThreads) k_part_deal(A c) {
         }
         if (bad) atomicOr((int*)gptr(c.status), kStatRange);
         lds_barrier();
-        if (wave == 0) {                                    // exclusive scan of the run lengths
-            const uint32_t x = lane < P ? hist[lane] : 0u;
-            uint32_t inc = x;
+        // exclusive scan of the run lengths: wave w takes partitions 64 w .. 64 w + 63
+        const bool scans = wave * kWave < P;
+        uint32_t x = 0, inc = 0;
+        if (scans) {
+            x = tid < P ? hist[tid] : 0u;
+            inc = x;
 #pragma unroll
             for (int o = 1; o < kWave; o <<= 1) {
                 const uint32_t y = __shfl_up(inc, o);
                 if (lane >= o) inc += y;
             }
-            if (lane < P) {
-                offs[lane] = inc - x;
-                out_off[lane] = (uint16_t)(inc - x);
+            if (lane == kWave - 1) wsum[wave] = inc;
+        }
+        if (P > kWave) lds_barrier();                       // (uniform: P is a launch argument)
+        if (scans) {
+            for (int w = 0; w < wave; ++w) inc += wsum[w];
+            if (tid < P) {
+                offs[tid] = inc - x;
+                out_off[tid] = (uint16_t)(inc - x);
             }
-            if (lane == P - 1) {
+            if (tid == P - 1) {
                 offs[P] = inc;
                 out_off[P] = (uint16_t)inc;
             }
@@ -1228,9 +1237,25 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
         }
     }
     lds_barrier();
-    for (int t = tid; t < n_tiles; t += kDThreads) {
-        b.pcount[((size_t)t * P + part) * 2] = S.cnt_first[t];
-        b.pcount[((size_t)t * P + part) * 2 + 1] = S.cnt_new[t];
+    // What k_part_assign needs is the population of all tiles before its own: each partition writes its
+    // populations scanned over the tiles (exclusive), so that the tile's workgroup adds up P numbers.
+    {
+        static_assert(kPMaxTiles <= kDThreads, "one tile per thread in the scan below");
+        const uint32_t f = tid < n_tiles ? S.cnt_first[tid] : 0u, n = tid < n_tiles ? S.cnt_new[tid] : 0u;
+        uint32_t fi = f, ni = n;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t yf = __shfl_up(fi, o), yn = __shfl_up(ni, o);
+            if (lane >= o) { fi += yf; ni += yn; }
+        }
+        if (lane == kWave - 1) { S.s_wave[wave] = fi; S.run_at[wave] = ni; }    // (run_at is free by now)
+        lds_barrier();
+        uint32_t pf = 0, pn = 0;
+        for (int w = 0; w < wave; ++w) { pf += S.s_wave[w]; pn += S.run_at[w]; }
+        if (tid < n_tiles) {
+            b.pcount[((size_t)tid * P + part) * 2] = pf + fi - f;
+            b.pcount[((size_t)tid * P + part) * 2 + 1] = pn + ni - n;
+        }
     }
     // what the host's choice of the partition count goes by: fullest table, deepest split
     if (tid == 0 && c.part_stats && c.stage == c.n_hops) {      // (the last stage holds the most nodes)
@@ -1256,8 +1281,7 @@ __global__ void __launch_bounds__(kPThreads, 4) k_part_assign(A c) {    // 4 wav
     __shared__ unsigned long long m_first[kPWords], m_new[kPWords];   // bit per position: first occurrence, new node
     __shared__ uint32_t pre_first[kPWords], pre_new[kPWords];
     __shared__ uint32_t seg_tot[kPWords], seg_pre[kPWords];
-    __shared__ uint32_t red[kPThreads / kWave][2];
-    __shared__ uint32_t s_tot[3];
+    __shared__ uint32_t s_tot[3], s_base[2];
 
     const BatchG b(c.batch(blockIdx.y));
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
@@ -1274,16 +1298,18 @@ __global__ void __launch_bounds__(kPThreads, 4) k_part_assign(A c) {    // 4 wav
     if (rel0 >= len && !(len == 0 && t == 0)) return;
     const bool have_tile = rel0 < len;
 
-    // populations of the earlier tiles
-    uint32_t bf = 0, bn = 0;
-    for (int i = tid; i < t * P; i += kPThreads) { bf += b.pcount[2 * (size_t)i]; bn += b.pcount[2 * (size_t)i + 1]; }
+    // populations of the earlier tiles: every partition left its own, scanned over the tiles
+    if (wave == 0) {
+        const uint2 QV_G* pc = reinterpret_cast<const uint2 QV_G*>(b.pcount);
+        uint32_t bf = 0, bn = 0;
+        if (have_tile) for (int q = lane; q < P; q += kWave) { const uint2 x = pc[(size_t)t * P + q]; bf += x.x; bn += x.y; }
 #pragma unroll
-    for (int o = kWave / 2; o > 0; o >>= 1) { bf += __shfl_down(bf, o); bn += __shfl_down(bn, o); }
-    if (lane == 0) { red[wave][0] = bf; red[wave][1] = bn; }
+        for (int o = kWave / 2; o > 0; o >>= 1) { bf += __shfl_down(bf, o); bn += __shfl_down(bn, o); }
+        if (lane == 0) { s_base[0] = bf; s_base[1] = bn; }
+    }
     for (int k = tid; k < kPTile; k += kPThreads) res[k] = kResNone;
     lds_barrier();
-    uint32_t base_first = 0, base_new = 0;
-    for (int w = 0; w < kPThreads / kWave; ++w) { base_first += red[w][0]; base_new += red[w][1]; }
+    const uint32_t base_first = s_base[0], base_new = s_base[1];
     // the tile's records are sorted by partition: bring their results back into position order
     if (have_tile) {
         const uint32_t total = b.run_off[(size_t)t * (P + 1) + P];

@@ -68,7 +68,7 @@ def check_batches(qv, ctx, w, rowptr, col, g, feat, batches, n_seeds=None, table
 
 
 def check_call_of_many(qv, ctx, w, rowptr, col, g, feat, first_batch, n_batches=32):
-    """The launch configuration the bench times: 32 batches through one qv_sample_many and one
+    """The launch configuration the bench times: many batches through one qv_sample_many and one
     qv_gather_many call (device-side row counts), each batch compared with the oracle."""
     idx = list(range(first_batch, first_batch + n_batches))
     seeds = [w.seeds(b) for b in idx]
@@ -118,13 +118,14 @@ def test_dense_social_full(qv, ctx):
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(3), table=table)
     ctx.set_dedup(2)                                            # partitioned dedup
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(4, 6))
-    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)                 # as the bench: 32 batches
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)                 # 32 batches
     ctx.set_dedup(1)                                            # the table forms, kept for cumulative frontiers and huge stages
     ctx.set_table_budget(64 << 30)                              # all 32 tables addressed directly
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)
     ctx.set_table_budget(16 << 30)
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # hashed tables on the citation graph, arguments uploaded
     ctx.set_dedup(0)
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 200, n_batches=128) # as the bench: 128 batches, the form chosen by the library
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()
 
@@ -179,12 +180,13 @@ def test_citation_full(qv, ctx):
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(4))
     ctx.set_dedup(2)                                            # partitioned dedup
     check_batches(qv, ctx, w, rowptr, col, g, feat, range(4, 6))
-    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)                 # as the bench: 32 batches
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)                 # 32 batches
     ctx.set_dedup(1)                                            # the table forms, kept for cumulative frontiers and huge stages
     ctx.set_table_budget(64 << 30)                              # all 32 tables addressed directly
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 20)
     ctx.set_table_budget(16 << 30)
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # hashed tables on the citation graph, arguments uploaded
     ctx.set_dedup(0)
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 200, n_batches=128) # as the bench: 128 batches, the form chosen by the library
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()

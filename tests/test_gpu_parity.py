@@ -31,7 +31,8 @@ DEDUP_FORMS = {
     "hashed": (1, -1, 0),            # open-addressing hash table
     "part": (2, -1, None),           # partitioned (LDS) dedup, partitions chosen per call
     "part1": (2, 0, None),           # one partition: larger cases overflow its LDS table and split into sub-rounds
-    "part64": (2, 6, None),          # the most partitions
+    "part64": (2, 6, None),          # as many partitions as a wave has lanes
+    "part256": (2, 8, None),         # the most partitions
 }
 
 
@@ -45,7 +46,7 @@ def apply_form(c, name):
 
 @pytest.fixture(scope="module", params=list(DEDUP_FORMS))
 def ctx(qv, request):
-    """Every test runs with every dedup form: the two table forms and the partitioned form at three partition counts."""
+    """Every test runs with every dedup form: the two table forms and the partitioned form at four partition counts."""
     c = qv.Context(0)
     apply_form(c, request.param)
     yield c
