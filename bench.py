@@ -460,18 +460,32 @@ def main():
     # With one stream every kernel's duration is its own, which is what the roofline entry needs;
     # several contexts on their own streams let calls overlap (the paper's multiplexed pipelines).
     sweep = {}
+    sweep_note = None
     if args.extra_streams > 0 and not tiered and S == 1:
         sweep_lanes = list(lanes)
         for S2 in (1, 2, 4, 8, 16):
             if S2 > args.extra_streams:
                 continue
-            while len(sweep_lanes) < S2:
-                sweep_lanes.append(Lane(new_context(torch.cuda.Stream())))
+            try:
+                while len(sweep_lanes) < S2:
+                    sweep_lanes.append(Lane(new_context(torch.cuda.Stream())))
+            except (qv.QvError, torch.OutOfMemoryError) as e:   # every context holds scratch for a whole call
+                sweep_note = "stopped before %d streams: %s" % (S2, str(e)[:120])
+                log("stream sweep " + sweep_note)
+                break
             n_calls = max(calls_per_region, 2 * S2)            # at least two calls per stream in flight
             ts, _ = measure(sweep_lanes[:S2], 0.03, 3, False, n_calls)
             sweep[str(S2)] = round(float(np.median(ts)) * 1e3 / (n_calls * B), 5)
-        del sweep_lanes
+        # give the extra contexts' scratch and buffers back before the passes below
+        torch.cuda.synchronize()
         plan_cache = {k: v for k, v in plan_cache.items() if k[0] in {id(ln) for ln in lanes}}
+        for ln in sweep_lanes[len(lanes):]:
+            ln.plan = None
+            ln.bufs = ln.rows = None
+            ln.ctx.close()
+        del sweep_lanes
+        import gc
+        gc.collect()
         torch.cuda.empty_cache()
 
     # ---- latency pass (not part of the timed region): one batch per call, one at a time ---------
@@ -575,6 +589,8 @@ def main():
         extra["stream_sweep"] = {"batches_per_call": B, "ms_per_step_by_streams": sweep,
                                  "best_path_frac_hbm_peak": round(path_bytes / n_batches / (min(sweep.values()) * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
                                  "best_value": round(tot_edges / n_batches / (min(sweep.values()) * 1e-3), 1)}
+        if sweep_note:
+            extra["stream_sweep"]["note"] = sweep_note
     result.update(extra)
 
     # ---- the oracle on this machine's host cores (a reported baseline, not the target) ------------

@@ -84,6 +84,7 @@ qv_status qv_ctx_create(int device, void* hip_stream, qv_ctx** out) {
         (e = hipMalloc((void**)&ctx->d_status, 256)) != hipSuccess ||
         (e = hipHostMalloc((void**)&ctx->h_status, 256, hipHostMallocDefault)) != hipSuccess ||
         (e = hipMemsetAsync(ctx->d_status, 0, 256, ctx->stream)) != hipSuccess) {
+        (void)hipGetLastError();
         qv_status rc = fail(nullptr, QV_EHIP, "qv_ctx_create: %s", hipGetErrorString(e));
         qv_ctx_destroy(ctx);
         return rc;

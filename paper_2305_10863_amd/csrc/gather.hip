@@ -191,9 +191,11 @@ qv_status qv_feat_create(qv_ctx* ctx, const void* table, int32_t table_on_device
     qv_status rc = QV_OK;
     hipError_t e = hipSuccess;
 #define FEAT_TRY(call)                                                                                   \
-    if (rc == QV_OK && (e = (call)) != hipSuccess)                                                        \
+    if (rc == QV_OK && (e = (call)) != hipSuccess) {                                                      \
+        (void)hipGetLastError();                                                                          \
         rc = fail(ctx, e == hipErrorOutOfMemory ? QV_ENOMEM : QV_EHIP, "qv_feat_create: %s failed: %s", #call, \
-                  hipGetErrorString(e));
+                  hipGetErrorString(e));                                                                  \
+    }
     const GatherSource whole{(const char*)table, nullptr, nullptr, n_rows, row_bytes, row_bytes, row_bytes};
     if (all_hot) {
         const bool relayout = table_on_device && (flags & QV_FEAT_OWN_COPY) && pad_stride != row_bytes;

@@ -114,9 +114,11 @@ void set_global_error(const char* msg);
 #define QV_HIP(ctx, call)                                                                   \
     do {                                                                                    \
         hipError_t e_ = (call);                                                             \
-        if (e_ != hipSuccess)                                                               \
+        if (e_ != hipSuccess) {                                                             \
+            (void)hipGetLastError(); /* reported here: a later launch check must not see it again */ \
             return qv::fail((ctx), e_ == hipErrorOutOfMemory ? QV_ENOMEM : QV_EHIP,         \
                             "%s failed: %s", #call, hipGetErrorString(e_));                 \
+        }                                                                                   \
     } while (0)
 
 #define QV_LAUNCH_CHECK(ctx, name)                                                          \

@@ -1,17 +1,22 @@
 // Neighbour sampling (one sub-wave group per frontier node, Philox4x32-10 + Floyd's selection)
-// and dedup / relabel (a table in HBM keyed by global id, addressed directly when the node count
-// allows and by open-addressing hash otherwise; first-occurrence order is recovered from the
-// smallest position at which each id occurs, found with one atomicMin per sampled edge).
+// and dedup / relabel.  The reindex has two forms with identical results:
 //
-// Launches of one qv_sample / qv_sample_many call (no host synchronisation anywhere; every
-// kernel takes up to QV_MAX_BATCHES independent batches along blockIdx.y):
-//   k_insert_ids  seeds -> table (stage 0); also initialises the device-side size block
-//   k_flag        stage 0: which positions are first occurrences / new nodes, per-tile counts
-//   k_assign      stage 0: scan of the counts -> F_0, n_id, local ids, row extents and segment
-//                 offsets of hop 1
-//   per hop k:    k_sample (pick neighbours, write the hop's edges, register them in the table)
-//                 k_flag / k_assign -> F_k, n_id growth, local ids, extents / offsets of hop k+1
-//   k_relabel     col_local of every edge, export of the sizes
+//   partitioned  (calls that carry enough edges; layer frontiers): the ids of a stage are dealt by a
+//                hash into P partitions per batch and every partition is deduplicated by one
+//                workgroup in an LDS table; nothing is kept in HBM between stages or calls and no
+//                global atomic is issued per edge.  Launches of a qv_sample / qv_sample_many call:
+//                  stage 0:   k_part_deal, k_part_dedup, k_part_assign        (seeds -> F_0, n_id)
+//                  per hop k: k_sample, k_part_deal, k_part_dedup, k_part_assign
+//                  k_relabel_links   (repeats of a node new in its hop take its local id; sizes exported)
+//                See the comment above fmix32 for the three kernels.
+//   table        (small calls, cumulative frontiers, stages beyond 4 Mi ids): a table in HBM keyed
+//                by global id, addressed directly when the node count allows and by open-addressing
+//                hash otherwise; first-occurrence order is recovered from the smallest position at
+//                which each id occurs, found with one atomicMin per sampled edge.  Launches:
+//                  k_insert_ids, k_flag, k_assign (stage 0); per hop k_sample, k_flag, k_assign; k_relabel.
+//
+// No host synchronisation anywhere; every kernel takes up to QV_MAX_BATCHES independent batches
+// (blockIdx.y, or folded into blockIdx.x in k_part_dedup).
 // A single-pass variant of k_flag + k_assign (tile scan with decoupled look-back) was measured
 // and dropped: agent-scope atomics across the eight XCDs cost 1.5-2 us per dependent step, so
 // the ticket + publish + look-back chain was slower (12-17 us per stage) than two short kernels
