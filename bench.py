@@ -631,7 +631,12 @@ def main():
     try:
         result["git"] = subprocess.check_output(["git", "-C", ROOT, "rev-parse", "--short", "HEAD"], stderr=subprocess.DEVNULL).decode().strip()
     except Exception:
-        result["git"] = None
+        try:        # a copy of the tree without history: the commit the library was built from
+            with open(os.path.join(ROOT, "paper_2305_10863_amd", "build_info.json")) as f:
+                info = json.load(f)
+            result["git"] = None if info.get("git") is None else info["git"] + (" (built from a modified tree)" if info.get("dirty") else "")
+        except Exception:
+            result["git"] = None
     line = json.dumps(result)
     try:
         os.makedirs(os.path.join(ROOT, "gpurun_out"), exist_ok=True)

@@ -30,7 +30,24 @@ def build(force=True, jobs=5):
         if p.wait() != 0:
             raise RuntimeError("hipcc failed on " + name)
     subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    write_build_info()
     return LIB
+
+
+def write_build_info():
+    """Beside the library: the commit it was built from, for runs on a copy of the tree without history."""
+    import json
+    root = os.path.join(HERE, "..")
+    info = {"git": None, "dirty": None}
+    try:
+        info["git"] = subprocess.check_output(["git", "-C", root, "rev-parse", "--short", "HEAD"],
+                                              stderr=subprocess.DEVNULL).decode().strip()
+        info["dirty"] = bool(subprocess.check_output(["git", "-C", root, "status", "--porcelain", "--untracked-files=no"],
+                                                     stderr=subprocess.DEVNULL).decode().strip())
+    except Exception:
+        pass
+    with open(os.path.join(HERE, "build_info.json"), "w") as f:
+        json.dump(info, f)
 
 
 if __name__ == "__main__":
