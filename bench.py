@@ -591,6 +591,12 @@ def main():
                                  "best_value": round(tot_edges / n_batches / (min(sweep.values()) * 1e-3), 1)}
         if sweep_note:
             extra["stream_sweep"]["note"] = sweep_note
+        best_s = min(sweep, key=sweep.get)
+        extra["best_sustained"] = {"streams": int(best_s), "value": extra["stream_sweep"]["best_value"], "unit": "edges/s",
+                                   "ms_per_step": sweep[best_s],
+                                   "path_frac_hbm_peak": extra["stream_sweep"]["best_path_frac_hbm_peak"],
+                                   "note": "best of the stream sweep (whole calls of batches_per_call on each stream); `value` above is the "
+                                           "one-stream figure, where a kernel's duration is its own"}
     result.update(extra)
 
     # ---- the oracle on this machine's host cores (a reported baseline, not the target) ------------
