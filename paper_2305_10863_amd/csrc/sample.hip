@@ -914,11 +914,8 @@ __device__ __forceinline__ uint32_t part_of(uint32_t key, int p_log2) {
 __device__ __forceinline__ int lds_insert(uint32_t* t_key, uint32_t key, uint32_t start, uint32_t* claimed) {
     uint32_t s = start;
     for (int probes = 0; probes < kPMaxProbes; ++probes) {
-        uint32_t cur = t_key[s];
-        if (cur == kEmptyKey) {
-            cur = atomicCAS(&t_key[s], kEmptyKey, key);
-            if (cur == kEmptyKey) { ++*claimed; return (int)s; }
-        }
+        const uint32_t cur = atomicCAS(&t_key[s], kEmptyKey, key);
+        if (cur == kEmptyKey) { ++*claimed; return (int)s; }
         if (cur == key) return (int)s;
         s = (s + 1) & (kPCap - 1);
     }
