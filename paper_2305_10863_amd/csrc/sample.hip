@@ -8,7 +8,7 @@
 //                  stage 0:   k_part_deal, k_part_dedup, k_part_assign        (seeds -> F_0, n_id)
 //                  per hop k: k_sample, k_part_deal, k_part_dedup, k_part_assign
 //                  k_relabel_links   (repeats of a node new in its hop take its local id; sizes exported)
-//                See the comment above fmix32 for the three kernels.
+//                See the comment above slot_hash for the three kernels.
 //   table        (small calls, cumulative frontiers, stages beyond 4 Mi ids): a table in HBM keyed
 //                by global id, addressed directly when the node count allows and by open-addressing
 //                hash otherwise; first-occurrence order is recovered from the smallest position at
@@ -895,13 +895,18 @@ __global__ void __launch_bounds__(256) k_relabel(A c) {
 // one table fill per sub-round; results do not depend on P or on the split.  Its workgroups are
 // numbered so that the partitions of one batch land on one XCD (workgroup w runs on XCD w mod 8).
 // ---------------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t fmix32(uint32_t h) {
-    h ^= h >> 16; h *= 0x85EBCA6Bu; h ^= h >> 13; h *= 0xC2B2AE35u; h ^= h >> 16;
-    return h;
+// Where an id goes inside its partition's table: multiplicative hashing (one multiply; its best bits
+// are the top ones).  The table index is the top kPCapLog2 bits, the sub-round of a split partition the
+// bits right below them.
+__device__ __forceinline__ uint32_t slot_hash(uint32_t key) { return key * 0x9E3779B1u; }
+__device__ __forceinline__ uint32_t slot_index(uint32_t h) { return h >> (32 - kPCapLog2); }
+__device__ __forceinline__ uint32_t slot_round(uint32_t h, int split) {
+    return (h >> (32 - kPCapLog2 - split)) & ((1u << split) - 1u);
 }
+static_assert(kPCapLog2 + kPMaxSplit <= 32, "table index and sub-round bits come out of one 32-bit hash");
 // Partition of an id: full-rate shifts and xors only (a 32-bit multiply costs four of them, and
 // k_part_dedup evaluates this for every known node in every workgroup).  Any spread will do:
-// the table index inside a partition comes from fmix32.
+// the table index inside a partition comes from slot_hash.
 __device__ __forceinline__ uint32_t part_of(uint32_t key, int p_log2) {
     uint32_t h = key ^ (key >> 15);
     h ^= h >> 7;
@@ -1054,7 +1059,7 @@ struct alignas(16) PartLds {
     int32_t t_lid[kPCap];                               //   its local id if an earlier stage numbered it, else -1
     uint32_t run_at[kPMaxTiles + 1];                    // records of this partition before tile t (its runs laid end to end)
     uint16_t run_beg[kPMaxTiles];                       // where its run starts inside tile t
-    uint32_t cnt_first[kPMaxTiles], cnt_new[kPMaxTiles];// per tile: first occurrences, new nodes
+    uint32_t cnt[kPMaxTiles];                           // per tile: first occurrences | new nodes << 16 (a tile has 4,096 positions)
     uint32_t s_wave[kDThreads / kWave];
     uint32_t s_fill;                                    // entries claimed (+ kPCap for every insertion that found the table full)
 };
@@ -1140,15 +1145,15 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
             reinterpret_cast<uint4*>(S.t_key)[tid] = make_uint4(kEmptyKey, kEmptyKey, kEmptyKey, kEmptyKey);
             reinterpret_cast<uint4*>(S.t_min)[tid] = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
             reinterpret_cast<uint4*>(S.t_lid)[tid] = make_uint4(0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu);
-            if (r == 0) for (int t = tid; t < n_tiles; t += kDThreads) { S.cnt_first[t] = 0; S.cnt_new[t] = 0; }
+            if (r == 0) for (int t = tid; t < n_tiles; t += kDThreads) S.cnt[t] = 0;
             if (tid == 0) S.s_fill = 0;
             lds_barrier();
             uint32_t claimed = 0;
             auto add_known = [&](const uint2 rec) {
                 if (rec.x == kEmptyKey) return;
-                const uint32_t h = fmix32(rec.x);
-                if (split && (h >> (32 - split)) != r) return;
-                const int s2 = lds_insert(S.t_key, rec.x, h & (kPCap - 1), &claimed);
+                const uint32_t h = slot_hash(rec.x);
+                if (split && slot_round(h, split) != r) return;
+                const int s2 = lds_insert(S.t_key, rec.x, slot_index(h), &claimed);
                 if (s2 < 0) claimed += (uint32_t)kPCap;
                 else S.t_lid[s2] = (int32_t)rec.y;
             };
@@ -1193,9 +1198,9 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                 for (int i = 0; i < kDKeys; ++i) {
                     slot[i] = -1;
                     if (rec[i].x == kEmptyKey) continue;
-                    const uint32_t h = fmix32(rec[i].x);
-                    if (split && (h >> (32 - split)) != r) continue;
-                    slot[i] = lds_insert(S.t_key, rec[i].x, h & (kPCap - 1), &claimed);
+                    const uint32_t h = slot_hash(rec[i].x);
+                    if (split && slot_round(h, split) != r) continue;
+                    slot[i] = lds_insert(S.t_key, rec[i].x, slot_index(h), &claimed);
                     if (slot[i] < 0) claimed += (uint32_t)kPCap;
                     else atomicMin(&S.t_min[slot[i]], rec[i].y);
                 }
@@ -1213,9 +1218,9 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                     for (int i = 0; i < kDKeys; ++i) {
                         slot[i] = -1;
                         if (rec[i].x == kEmptyKey) continue;
-                        uint32_t x = fmix32(rec[i].x);
-                        if (split && (x >> (32 - split)) != r) continue;
-                        x &= kPCap - 1;
+                        const uint32_t h = slot_hash(rec[i].x);
+                        if (split && slot_round(h, split) != r) continue;
+                        uint32_t x = slot_index(h);
                         while (S.t_key[x] != rec[i].x) x = (x + 1) & (kPCap - 1);     // pass 1 put it there
                         slot[i] = (int)x;
                     }
@@ -1228,8 +1233,7 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                     const bool first = mp == rec[i].y;
                     b.result[at[i]] = lid >= 0 ? (lid | (first ? 1 << 30 : 0)) : first ? -1 : -2 - (int32_t)mp;
                     if (first) {
-                        atomicAdd(&S.cnt_first[at[i] / kPTile], 1u);
-                        if (lid < 0) atomicAdd(&S.cnt_new[at[i] / kPTile], 1u);
+                        atomicAdd(&S.cnt[at[i] / kPTile], lid < 0 ? 0x10001u : 1u);
                     }
                 }
             }
@@ -1245,7 +1249,8 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
     // populations scanned over the tiles (exclusive), so that the tile's workgroup adds up P numbers.
     {
         static_assert(kPMaxTiles <= kDThreads, "one tile per thread in the scan below");
-        const uint32_t f = tid < n_tiles ? S.cnt_first[tid] : 0u, n = tid < n_tiles ? S.cnt_new[tid] : 0u;
+        static_assert(kPTile < 65536, "two 16-bit counts per tile");
+        const uint32_t both = tid < n_tiles ? S.cnt[tid] : 0u, f = both & 0xFFFFu, n = both >> 16;
         uint32_t fi = f, ni = n;
 #pragma unroll
         for (int o = 1; o < kWave; o <<= 1) {
