@@ -1205,7 +1205,12 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                     else atomicMin(&S.t_min[slot[i]], rec[i].y);
                 }
             }
-            if (claimed) atomicAdd(&S.s_fill, claimed);
+            {   // one LDS atomic per wave, not one per lane on the same word
+                uint32_t w = claimed;
+#pragma unroll
+                for (int o = kWave / 2; o > 0; o >>= 1) w += __shfl_down(w, o);
+                if (lane == 0 && w) atomicAdd(&S.s_fill, w);
+            }
             lds_barrier();
             fill = S.s_fill;
             if (fill > kPFillMax) { failed = true; break; }
@@ -1227,13 +1232,25 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                 }
 #pragma unroll
                 for (int i = 0; i < kDKeys; ++i) {
-                    if (slot[i] < 0) continue;
-                    const uint32_t mp = S.t_min[slot[i]];
-                    const int32_t lid = S.t_lid[slot[i]];
-                    const bool first = mp == rec[i].y;
-                    b.result[at[i]] = lid >= 0 ? (lid | (first ? 1 << 30 : 0)) : first ? -1 : -2 - (int32_t)mp;
-                    if (first) {
-                        atomicAdd(&S.cnt[at[i] / kPTile], lid < 0 ? 0x10001u : 1u);
+                    const bool valid = slot[i] >= 0;
+                    uint32_t mp = 0;
+                    int32_t lid = -1;
+                    if (valid) { mp = S.t_min[slot[i]]; lid = S.t_lid[slot[i]]; }
+                    const bool first = valid && mp == rec[i].y;
+                    const bool isnew = first && lid < 0;
+                    if (valid) b.result[at[i]] = lid >= 0 ? (lid | (first ? 1 << 30 : 0)) : first ? -1 : -2 - (int32_t)mp;
+                    // The tile's counters: the lanes of a wave hold consecutive records, so mostly one tile's;
+                    // then one lane adds for all (LDS atomics on one word go one lane at a time).
+                    const uint32_t tile = at[i] / kPTile;
+                    const unsigned long long mf = __ballot(first), mn = __ballot(isnew);
+                    if (mf) {
+                        const int leader = __ffsll((long long)mf) - 1;
+                        const uint32_t t0 = (uint32_t)__shfl((int)tile, leader);
+                        if (__all(!first || tile == t0)) {
+                            if (lane == leader) atomicAdd(&S.cnt[t0], (uint32_t)__popcll(mf) + ((uint32_t)__popcll(mn) << 16));
+                        } else if (first) {
+                            atomicAdd(&S.cnt[tile], isnew ? 0x10001u : 1u);
+                        }
                     }
                 }
             }
