@@ -1078,22 +1078,9 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
     const int64_t len = v.end - v.begin;
     const int n_tiles = (int)((len + kPTile - 1) / kPTile);
     // The nodes numbered by earlier stages come from their dealt records, a wave per tile of n_id, a
-    // lane per record of the run.  Each wave requests its first tile's run right away (up to
-    // kKnownAhead records a lane), so that the answer is there when the table has been cleared.
+    // lane per record of the run, kKnownAhead records of a lane requested together.
     constexpr int kKnownAhead = 3;
     const int n_ktiles = (int)((v.known + kPTile - 1) / kPTile);
-    uint32_t kbeg = 0, kend = 0;
-    uint2 krec[kKnownAhead];
-    if (wave < n_ktiles) {
-        kbeg = b.krun_off[(size_t)wave * (P + 1) + part];
-        kend = b.krun_off[(size_t)wave * (P + 1) + part + 1];
-#pragma unroll
-        for (int i = 0; i < kKnownAhead; ++i) {
-            const uint32_t k = kbeg + (uint32_t)(i * kWave + lane);
-            krec[i] = make_uint2(kEmptyKey, 0u);
-            if (k < kend) krec[i] = b.kdealt[(size_t)wave * kPTile + k];
-        }
-    }
     // Where this partition's records are: its runs, one per tile, are numbered end to end, so that
     // the workgroup's threads can share them evenly whatever the runs' lengths (run_at = exclusive
     // scan of the run lengths).
@@ -1158,14 +1145,7 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                 else S.t_lid[s2] = (int32_t)rec.y;
             };
             for (int j = wave; j < n_ktiles; j += kDThreads / kWave) {
-                uint32_t beg = kbeg, end = kend;
-                if (j == wave) {
-#pragma unroll
-                    for (int i = 0; i < kKnownAhead; ++i) add_known(krec[i]);
-                    beg += kKnownAhead * kWave;
-                } else {
-                    beg = b.krun_off[(size_t)j * (P + 1) + part]; end = b.krun_off[(size_t)j * (P + 1) + part + 1];
-                }
+                const uint32_t beg = b.krun_off[(size_t)j * (P + 1) + part], end = b.krun_off[(size_t)j * (P + 1) + part + 1];
                 for (uint32_t k0 = beg; k0 < end; k0 += kKnownAhead * kWave) {
                     uint2 more[kKnownAhead];
 #pragma unroll
