@@ -1811,7 +1811,7 @@ static void part_adapt(qv_ctx* ctx, int64_t nodes_bound) {
     const uint32_t fill = (uint32_t)h[0], split = (uint32_t)h[1];
     if (h[2] != ctx->part_auto_log2 + 1 || (fill == 0 && split == 0)) return;  // nothing (new) has arrived
     int lg = ctx->part_auto_log2;
-    if ((split > 0 || fill > kPCap * 5 / 8) && lg < kPMaxLog2) ++lg;
+    if ((split > 0 || fill > kPCap * 3 / 4) && lg < kPMaxLog2) ++lg;
     else if (split == 0 && fill < kPCap * 9 / 32 && lg > 3) --lg;
     if (lg != ctx->part_auto_log2) {
         ctx->part_auto_log2 = lg;
