@@ -1320,10 +1320,21 @@ __global__ void __launch_bounds__(kPThreads, 4) k_part_assign(A c) {    // 4 wav
     if (have_tile) {
         const uint32_t total = b.run_off[(size_t)t * (P + 1) + P];
         const uint32_t pos0 = (uint32_t)(v.begin + rel0);
-        for (uint32_t k = (uint32_t)tid; k < total; k += kPThreads) {
-            const uint2 rec = b.dealt[(size_t)t * kPTile + k];
-            res[(rec.y - pos0) & (kPTile - 1)] = b.result[(size_t)t * kPTile + k];
+        // (all of a thread's records requested before the first is used)
+        uint32_t where[kPKeys];
+        int32_t rv[kPKeys];
+#pragma unroll
+        for (int i = 0; i < kPKeys; ++i) {
+            const uint32_t k = (uint32_t)(i * kPThreads + tid);
+            where[i] = 0; rv[i] = 0;
+            if (k < total) {
+                where[i] = reinterpret_cast<const uint32_t QV_G*>(b.dealt)[((size_t)t * kPTile + k) * 2 + 1];
+                rv[i] = b.result[(size_t)t * kPTile + k];
+            }
         }
+#pragma unroll
+        for (int i = 0; i < kPKeys; ++i)
+            if ((uint32_t)(i * kPThreads + tid) < total) res[(where[i] - pos0) & (kPTile - 1)] = rv[i];
     }
     lds_barrier();
     int32_t rr[kPKeys];
