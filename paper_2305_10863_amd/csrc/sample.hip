@@ -1468,15 +1468,27 @@ __global__ void __launch_bounds__(kPThreads, 4) k_part_assign(A c) {    // 4 wav
 // the link (that position holds the local id by now).  Also exports the sizes.
 template <typename A>
 __global__ void __launch_bounds__(256) k_relabel_links(A c) {
-    const BatchG b(c.batch(blockIdx.y));
+    // Workgroup w runs on XCD w mod 8: the workgroups of a batch are numbered so that they share one,
+    // whose L2 then holds the lines of first positions that the batch's repeats read again and again.
+    const int per_batch = (int)(gridDim.x / (8u * (unsigned)((c.n_batches + 7) / 8)));
+    const int q = (int)(blockIdx.x >> 3);
+    const int batch = (int)(blockIdx.x & 7u) + 8 * (q / per_batch), chunk = q % per_batch;
+    if (batch >= c.n_batches) return;
+    const BatchG b(c.batch(batch));
     const SampleMeta* m = b.meta;
-    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    const int64_t tid = (int64_t)chunk * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)per_batch * blockDim.x;
     int64_t end = m->edge_off[c.stage];                // c.stage = last stage
     if (end > b.edge_cap) end = b.edge_cap;
-    for (int64_t p = tid; p < end; p += stride) {
-        const int32_t x = b.col_local[p];
-        if (x <= -2) b.col_local[p] = b.col_local[-2 - (int64_t)x];
+    constexpr int kU = 4;                               // positions a thread has in flight
+    for (int64_t p0 = tid; p0 < end; p0 += kU * stride) {
+        int32_t x[kU], y[kU];
+#pragma unroll
+        for (int k = 0; k < kU; ++k) { const int64_t p = p0 + k * stride; x[k] = p < end ? b.col_local[p] : 0; }
+#pragma unroll
+        for (int k = 0; k < kU; ++k) y[k] = x[k] <= -2 ? b.col_local[-2 - (int64_t)x[k]] : 0;
+#pragma unroll
+        for (int k = 0; k < kU; ++k) if (x[k] <= -2) b.col_local[p0 + k * stride] = y[k];
     }
     if (tid == 0) {
         if (b.node_off_out) for (int i = 0; i < c.n_hops + 2; ++i) b.node_off_out[i] = m->node_off[i];
@@ -1977,7 +1989,8 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
             if (rc != QV_OK) return rc;
         }
         c.stage = n_hops;
-        dim3 grid((unsigned)grid_for(bd.edges, 256 * 4, ctx->n_cu * 4), (unsigned)n_batches);
+        const unsigned per_batch = (unsigned)grid_for(bd.edges, 256 * 16, ctx->n_cu * 4);
+        dim3 grid(per_batch * 8u * (unsigned)((n_batches + 7) / 8));          // (XCD, batch within XCD, chunk)
         QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(256), k_relabel_links);
         QV_LAUNCH_CHECK(ctx, "k_relabel_links");
         // report back: every call while the count is still moving, every 32nd once it has settled
