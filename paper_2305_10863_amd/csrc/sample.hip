@@ -1480,7 +1480,7 @@ __global__ void __launch_bounds__(256) k_relabel_links(A c) {
     const int64_t stride = (int64_t)per_batch * blockDim.x;
     int64_t end = m->edge_off[c.stage];                // c.stage = last stage
     if (end > b.edge_cap) end = b.edge_cap;
-    constexpr int kU = 4;                               // positions a thread has in flight
+    constexpr int kU = 8;                               // positions a thread has in flight
     for (int64_t p0 = tid; p0 < end; p0 += kU * stride) {
         int32_t x[kU], y[kU];
 #pragma unroll
@@ -1989,7 +1989,7 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
             if (rc != QV_OK) return rc;
         }
         c.stage = n_hops;
-        const unsigned per_batch = (unsigned)grid_for(bd.edges, 256 * 16, ctx->n_cu * 4);
+        const unsigned per_batch = (unsigned)grid_for(bd.edges, 256 * 32, ctx->n_cu * 4);
         dim3 grid(per_batch * 8u * (unsigned)((n_batches + 7) / 8));          // (XCD, batch within XCD, chunk)
         QV_LAUNCH_A(ctx, c, n_batches, grid, dim3(256), k_relabel_links);
         QV_LAUNCH_CHECK(ctx, "k_relabel_links");
