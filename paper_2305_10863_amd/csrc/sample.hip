@@ -1078,9 +1078,15 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
     const int64_t len = v.end - v.begin;
     const int n_tiles = (int)((len + kPTile - 1) / kPTile);
     // The nodes numbered by earlier stages come from their dealt records, a wave per tile of n_id, a
-    // lane per record of the run, kKnownAhead records of a lane requested together.
+    // lane per record of the run, kKnownAhead records of a lane requested together.  The order of the
+    // insertions (these nodes, the stage's records) does not matter: pass 2 runs after all of them.
     constexpr int kKnownAhead = 3;
     const int n_ktiles = (int)((v.known + kPTile - 1) / kPTile);
+    uint32_t kbeg0 = 0, kend0 = 0;                              // extents of the wave's first run of known nodes
+    if (wave < n_ktiles) {
+        kbeg0 = b.krun_off[(size_t)wave * (P + 1) + part];
+        kend0 = b.krun_off[(size_t)wave * (P + 1) + part + 1];
+    }
     // Where this partition's records are: its runs, one per tile, are numbered end to end, so that
     // the workgroup's threads can share them evenly whatever the runs' lengths (run_at = exclusive
     // scan of the run lengths).
@@ -1144,20 +1150,6 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                 if (s2 < 0) claimed += (uint32_t)kPCap;
                 else S.t_lid[s2] = (int32_t)rec.y;
             };
-            for (int j = wave; j < n_ktiles; j += kDThreads / kWave) {
-                const uint32_t beg = b.krun_off[(size_t)j * (P + 1) + part], end = b.krun_off[(size_t)j * (P + 1) + part + 1];
-                for (uint32_t k0 = beg; k0 < end; k0 += kKnownAhead * kWave) {
-                    uint2 more[kKnownAhead];
-#pragma unroll
-                    for (int i = 0; i < kKnownAhead; ++i) {
-                        const uint32_t k = k0 + (uint32_t)(i * kWave + lane);
-                        more[i] = make_uint2(kEmptyKey, 0u);
-                        if (k < end) more[i] = b.kdealt[(size_t)j * kPTile + k];
-                    }
-#pragma unroll
-                    for (int i = 0; i < kKnownAhead; ++i) add_known(more[i]);
-                }
-            }
             // A chunk: kDKeys records per thread, requested together.  slot = the record's table entry,
             // -1 if it has none (no such record, not this sub-round's, table full).
             uint2 rec[kDKeys];
@@ -1183,6 +1175,23 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
                     slot[i] = lds_insert(S.t_key, rec[i].x, slot_index(h), &claimed);
                     if (slot[i] < 0) claimed += (uint32_t)kPCap;
                     else atomicMin(&S.t_min[slot[i]], rec[i].y);
+                }
+            }
+            // the nodes numbered by earlier stages (after the stage's own records: the extents of the wave's
+            // first run were requested at the start, so only the run itself is waited for here)
+            for (int j = wave; j < n_ktiles; j += kDThreads / kWave) {
+                const uint32_t beg = j == wave ? kbeg0 : b.krun_off[(size_t)j * (P + 1) + part];
+                const uint32_t end = j == wave ? kend0 : b.krun_off[(size_t)j * (P + 1) + part + 1];
+                for (uint32_t k0 = beg; k0 < end; k0 += kKnownAhead * kWave) {
+                    uint2 more[kKnownAhead];
+#pragma unroll
+                    for (int i = 0; i < kKnownAhead; ++i) {
+                        const uint32_t k = k0 + (uint32_t)(i * kWave + lane);
+                        more[i] = make_uint2(kEmptyKey, 0u);
+                        if (k < end) more[i] = b.kdealt[(size_t)j * kPTile + k];
+                    }
+#pragma unroll
+                    for (int i = 0; i < kKnownAhead; ++i) add_known(more[i]);
                 }
             }
             {   // one LDS atomic per wave, not one per lane on the same word
