@@ -283,6 +283,16 @@ struct BatchG {
           frontier_len_out(gptr(a.frontier_len_out)) {}
 };
 
+// BatchG of batch y with its size block addressed from the call header, so that the loads of the
+// block do not wait for the argument record.
+template <typename A>
+__device__ __forceinline__ BatchG batch_of(const A& c, int y) {
+    BatchG b(c.batch(y));
+    b.meta = gptr(c.meta_base) + y;
+    return b;
+}
+
+
 
 struct CallHeader {
     // graph
@@ -306,6 +316,7 @@ struct CallHeader {
     uint32_t* part_stats;           // [0] fullest LDS table of the call, [1] deepest split, [2] partitions_log2 + 1 (device, may be NULL)
     int32_t n_batches;
     int32_t* status;
+    SampleMeta* meta_base;          // the batches' size blocks, one after the other: a kernel finds batch y's without its argument record
 };
 
 // The per-batch arguments travel in the kernel argument block while they fit (up to kInlineBatch
@@ -334,7 +345,7 @@ __device__ __forceinline__ TableView table_of(const CallHeader& c, const BatchG&
 // ---------------------------------------------------------------------------------------------
 template <typename A>
 __global__ void __launch_bounds__(256) k_insert_ids(A c) {
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
     const int32_t* ids;
@@ -464,7 +475,7 @@ __device__ __forceinline__ void emit_edge(const CallHeader& c, const BatchG& b, 
 // grid covers the frontier in one round, so a small frontier still spreads over many waves.
 template <int G, typename A>
 __global__ void __launch_bounds__(256) k_sample(A c) {
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const int lane = threadIdx.x % kWave, sub = lane % G;
     const SampleMeta QV_G* m = b.meta;
     const int64_t fbeg = c.cumulative ? 0 : m->frontier_off[c.stage - 1];
@@ -539,7 +550,7 @@ __global__ void __launch_bounds__(256) k_sample(A c) {
 template <typename A>
 __global__ void __launch_bounds__(64) k_sample_wide(A c) {
     __shared__ uint32_t picks[QV_MAX_FANOUT];
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const int lane = threadIdx.x;
     const SampleMeta* m = b.meta;
     const int64_t fbeg = c.cumulative ? 0 : m->frontier_off[c.stage - 1];
@@ -650,7 +661,7 @@ __device__ __forceinline__ uint32_t slot_at(const CallHeader& c, const StageView
 template <typename RP, typename A>
 __global__ void __launch_bounds__(kScanBlock) k_flag(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     const StageView v = stage_view(c, b);
     const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
@@ -698,7 +709,7 @@ __global__ void __launch_bounds__(kScanBlock) k_flag(A c) {
 template <typename RP, typename A>
 __global__ void __launch_bounds__(kScanBlock) k_assign(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     SampleMeta* m = b.meta;
     const StageView v = stage_view(c, b);
@@ -789,7 +800,7 @@ __global__ void __launch_bounds__(kScanBlock) k_assign(A c) {
 template <typename A>
 __global__ void __launch_bounds__(kScanBlock) k_cum_partial(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const int64_t U = b.meta->node_off[c.stage];
     const int64_t t0 = (int64_t)blockIdx.x * kScanBlock * c.items_per_thread;
     if (t0 >= U) return;
@@ -809,7 +820,7 @@ __global__ void __launch_bounds__(kScanBlock) k_cum_partial(A c) {
 template <typename A>
 __global__ void __launch_bounds__(kScanBlock) k_cum_scan(A c) {
     __shared__ uint32_t lds[kScanBlock / kWave][3];
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     SampleMeta* m = b.meta;
     const int64_t U = m->node_off[c.stage];
     const int64_t tile_size = (int64_t)kScanBlock * c.items_per_thread;
@@ -839,7 +850,7 @@ __global__ void __launch_bounds__(kScanBlock) k_cum_scan(A c) {
 // ---------------------------------------------------------------------------------------------
 template <typename A>
 __global__ void __launch_bounds__(256) k_relabel(A c) {
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const SampleMeta* m = b.meta;
     const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)gridDim.x * blockDim.x;
@@ -957,7 +968,7 @@ __global__ void __launch_bounds__(kPThreads) k_part_deal(A c) {
     __shared__ uint32_t hist[(1 << kPMaxLog2) + 1], offs[(1 << kPMaxLog2) + 1], wsum[(1 << kPMaxLog2) / kWave];
     static_assert((1 << kPMaxLog2) <= kPThreads, "a thread per partition in the scan");
     __shared__ uint2 sorted[kPTile];
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const int p_log2 = c.p_log2, P = 1 << p_log2;
     const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const PartStage v = part_stage(c, b);
@@ -1072,7 +1083,7 @@ __global__ void __launch_bounds__(kDThreads, 8) k_part_dedup(A c) {     // 8 wav
     const int batch = (int)(blockIdx.x & 7u) + 8 * (q >> p_log2);
     const uint32_t part = (uint32_t)(q & (P - 1));
     if (batch >= c.n_batches) return;
-    const BatchG b(c.batch(batch));
+    const BatchG b = batch_of(c, batch);
     const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
     const PartStage v = part_stage(c, b);
     const int64_t len = v.end - v.begin;
@@ -1298,7 +1309,7 @@ __global__ void __launch_bounds__(kPThreads, 4) k_part_assign(A c) {    // 4 wav
     __shared__ uint32_t seg_tot[kPWords], seg_pre[kPWords];
     __shared__ uint32_t s_tot[3], s_base[2];
 
-    const BatchG b(c.batch(blockIdx.y));
+    const BatchG b = batch_of(c, blockIdx.y);
     const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
     SampleMeta* m = b.meta;
     const int P = 1 << c.p_log2;
@@ -1483,7 +1494,7 @@ __global__ void __launch_bounds__(256) k_relabel_links(A c) {
     const int q = (int)(blockIdx.x >> 3);
     const int batch = (int)(blockIdx.x & 7u) + 8 * (q / per_batch), chunk = q % per_batch;
     if (batch >= c.n_batches) return;
-    const BatchG b(c.batch(batch));
+    const BatchG b = batch_of(c, batch);
     const SampleMeta* m = b.meta;
     const int64_t tid = (int64_t)chunk * blockDim.x + threadIdx.x;
     const int64_t stride = (int64_t)per_batch * blockDim.x;
@@ -1932,7 +1943,8 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
     Layout L;
     qv_status rc = plan_sample(ctx, max_seeds, fanouts, n_hops, csr->n_nodes, cumulative, n_batches, &bd, &L);
     if (rc != QV_OK) return rc;
-    rc = arena_begin(ctx, per_batch_bytes(L) * n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch));
+    rc = arena_begin(ctx, per_batch_bytes(L) * n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch) +
+                              align_up(sizeof(SampleMeta) * (size_t)kMaxBatch));
     if (rc != QV_OK) return rc;
     CallArgs c{};
     c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
@@ -1955,9 +1967,12 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
             ctx->part_stats_reset = false;
         }
     }
+    c.meta_base = (SampleMeta*)arena_take(ctx, sizeof(SampleMeta) * (size_t)n_batches);
+    if (!c.meta_base) return fail(ctx, QV_ENOMEM, "%s: scratch arena too small (internal sizing error)", who);
     for (int i = 0; i < n_batches; ++i) {
         BatchArgs& b = c.b[i];
         if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "%s: scratch arena too small (internal sizing error)", who);
+        b.meta = c.meta_base + i;
         const qv_sample_out& o = outs[i];
         b.seeds = seeds[i]; b.n_seeds = n_seeds[i]; b.rng_seed = rng_seeds[i];
         b.keyw = (L.part || c.direct) ? nullptr : ctx->table_keyw + (size_t)i * table_slots;
@@ -2095,7 +2110,7 @@ static qv_status sample_hop_run(qv_ctx* ctx, const qv_csr* csr, const int32_t* f
     c.rowptr = csr->rowptr; c.col = csr->col; c.n_nodes = csr->n_nodes;
     c.stage = 1; c.hop = hop; c.fanout = fanout; c.status = ctx->d_status;
     BatchArgs& b = c.b[0];
-    b.rng_seed = rng_seed; b.meta = s.meta;
+    b.rng_seed = rng_seed; b.meta = s.meta; c.meta_base = s.meta;
     b.fr_id = const_cast<int32_t*>(frontier); b.fr_lid = const_cast<int32_t*>(frontier);   // local ids unused (row_local == NULL)
     b.fr_rs = s.fr_rs; b.fr_deg = s.fr_deg; b.fr_seg = s.fr_seg;
     b.nbr = nbr_out; b.row_local = nullptr; b.slot_of = nullptr; b.edge_cap = nbr_cap;
@@ -2152,7 +2167,8 @@ qv_status qv_ctx_reserve(qv_ctx* ctx, int64_t n_seeds, const int32_t* fanouts, i
     Layout L;
     qv_status rc = plan_sample(ctx, n_seeds, fanouts, n_hops, n_nodes, cumulative, n_batches, &bd, &L);
     if (rc != QV_OK) return rc;
-    const size_t want = per_batch_bytes(L) * (size_t)n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch);
+    const size_t want = per_batch_bytes(L) * (size_t)n_batches + align_up(sizeof(BatchArgs) * (size_t)kMaxBatch) +
+                        align_up(sizeof(SampleMeta) * (size_t)kMaxBatch);
     if (want > ctx->arena_bytes) {
         rc = arena_begin(ctx, want);
         if (rc != QV_OK) return rc;
@@ -2242,6 +2258,7 @@ qv_status qv_reindex(qv_ctx* ctx, const int32_t* known, int64_t n_known, const i
     c.epoch = ctx->epoch; c.n_hops = 1; c.status = ctx->d_status;
     BatchArgs& b = c.b[0];
     if (!carve(ctx, L, &b)) return fail(ctx, QV_ENOMEM, "qv_reindex: scratch arena too small (internal sizing error)");
+    c.meta_base = b.meta;
     b.seeds = known; b.n_seeds = n_known; b.rng_seed = 0;
     b.keyw = c.direct ? nullptr : ctx->table_keyw; b.slots = ctx->table_slots;
     b.nbr = const_cast<int32_t*>(nbr);                   // read only on this path
