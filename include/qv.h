@@ -102,6 +102,13 @@ qv_status qv_ctx_set_dedup(qv_ctx* ctx, int32_t form, int32_t partitions_log2);
 #define QV_FAP_SCATTER 2
 qv_status qv_ctx_set_fap_direction(qv_ctx* ctx, int32_t direction);
 
+/* Testing / tuning aid for qv_csr_transpose: the in-edge CSR it builds cuts every row with more than
+ * 8,192 edges into work items whose sources lie in one block of 2^nodes_log2 consecutive node ids,
+ * and qv_access_prob then sums those rows block by block (the values of one block stay in the L2
+ * caches meanwhile).  0 restores the default (18: 2 MB of fp64 values per block); otherwise 6..30.
+ * Graphs that fit one block get no items.  Applies to transposes made after the call. */
+qv_status qv_ctx_set_fap_block(qv_ctx* ctx, int32_t nodes_log2);
+
 /* Testing aid.  The dedup tables are never cleared between calls: every call stamps its entries
  * with a fresh epoch number, and only when the counter is exhausted (about 10^6 calls) are the
  * tables cleared once.  This sets the counter so that a test can cross that point quickly. */
@@ -134,12 +141,22 @@ void qv_csr_destroy(qv_csr* csr);
  * edges stay parallel).  Built on the device (edge sources, one stable radix sort of the edge
  * list by destination, row boundaries from the sorted keys); the new arrays are device memory
  * owned by the handle (rowptr of the same width as the input's; (n_nodes+1)*width + 4*n_edges
- * bytes) and are freed by qv_csr_destroy.  About 8*n_edges bytes more are held during the call.
+ * bytes, plus the work items of the rows longer than 8,192 edges when the graph has more than 2^18
+ * nodes: 16 bytes per such row and block of 2^18 node ids and per 256 of their edges, at most
+ * 1 GiB) and are freed by qv_csr_destroy.  About 8*n_edges bytes more are held during the call.
  * Synchronises the context's stream.  A symmetric graph is its own in-edge CSR and needs none. */
 qv_status qv_csr_transpose(qv_ctx* ctx, const qv_csr* csr, qv_csr** out);
 /* Read-only views of a handle's arrays [dev] (for a transposed handle: the library's arrays). */
 const void* qv_csr_rowptr(const qv_csr* csr);
 const int32_t* qv_csr_col(const qv_csr* csr);
+/* The work items of an in-edge CSR built by qv_csr_transpose, or NULL when it has none.  long_rows
+ * [dev] int32[*n_long]: the rows with more than 8,192 edges, in no particular order.  Returns items
+ * [dev], *n_items records of 16 bytes {int64 first; int32 k; int32 count}: the edges col[first ..
+ * first + count) belong to row long_rows[k], 1 <= count <= 256, and their sources all lie in one
+ * block of 2^*block_log2 node ids.  The items of a long row cover its edges exactly once; items are
+ * listed in ascending order of their block. */
+const void* qv_csr_fap_items(const qv_csr* csr, const int32_t** long_rows, int32_t* n_long, int64_t* n_items,
+                             int32_t* block_log2);
 
 /* ---------------------------------------------------------------------------------------------
  * Sampling  (paper Section 2.1, overview figure: seed -> layer-1 neighbours -> layer-2 ...;
@@ -315,7 +332,8 @@ qv_status qv_psgs_batch_sum(qv_ctx* ctx, const float* psgs, int64_t n_nodes, con
  * either gathers over in-edges (no atomics) or, when few nodes carry mass (a sparse p0, or a
  * graph where most nodes have no in-edges), scatters from those nodes only; the choice is made
  * on the device, the call stays asynchronous.  For a symmetric (undirected) graph pass the graph
- * itself; for any other, qv_csr_transpose builds one. */
+ * itself; for any other, qv_csr_transpose builds one (and a gather over one it built is faster on
+ * graphs with hub rows: those rows are summed block of sources by block of sources). */
 qv_status qv_access_prob(qv_ctx* ctx, const qv_csr* csr, const qv_csr* csr_in,
                          const int32_t* fanouts /*[host]*/, int32_t n_hops, const float* p0,
                          float* prob_out);

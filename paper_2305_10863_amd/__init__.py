@@ -20,7 +20,7 @@ QV_SAMPLE_CUMULATIVE, QV_FEAT_OWN_COPY = 1, 1
 QV_DEDUP_AUTO, QV_DEDUP_TABLE, QV_DEDUP_PARTITIONED = 0, 1, 2
 
 EXPORTS = [
-    "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget", "qv_ctx_set_dedup", "qv_ctx_set_fap_direction",
+    "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget", "qv_ctx_set_dedup", "qv_ctx_set_fap_direction", "qv_ctx_set_fap_block", "qv_csr_fap_items",
     "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_csr_transpose", "qv_csr_rowptr", "qv_csr_col", "qv_sample_hop", "qv_sample_hop_noalloc", "qv_sample", "qv_sample_many",
     "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc", "qv_feat_row_stride",
     "qv_gather", "qv_gather_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
@@ -61,6 +61,7 @@ def lib():
         L.qv_ctx_set_table_budget.argtypes = [vp, i64]
         L.qv_ctx_set_dedup.argtypes = [vp, i32, i32]
         L.qv_ctx_set_fap_direction.argtypes = [vp, i32]
+        L.qv_ctx_set_fap_block.argtypes = [vp, i32]
         L.qv_sample_bounds.argtypes = [i64, C.POINTER(i32), i32, i64, C.c_uint32, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
         L.qv_csr_create.argtypes = [vp, i64, i64, vp, i32, vp, i32, C.POINTER(vp)]
         L.qv_csr_destroy.argtypes = [vp]
@@ -70,6 +71,8 @@ def lib():
         L.qv_csr_rowptr.restype = vp
         L.qv_csr_col.argtypes = [vp]
         L.qv_csr_col.restype = vp
+        L.qv_csr_fap_items.argtypes = [vp, C.POINTER(vp), C.POINTER(i32), C.POINTER(i64), C.POINTER(i32)]
+        L.qv_csr_fap_items.restype = vp
         L.qv_sample_hop.argtypes = [vp, vp, vp, i64, i32, u64, i32, vp, i64, vp]
         L.qv_sample_hop_noalloc.argtypes = [vp, vp, vp, i64, i32, u64, i32, vp, i64, vp]
         L.qv_sample.argtypes = [vp, vp, vp, i64, C.POINTER(i32), i32, u64, C.c_uint32, C.POINTER(_SampleOut)]
@@ -142,6 +145,10 @@ class Context:
         """0 choose per sweep (default), 1 gather only, 2 scatter only; see qv_ctx_set_fap_direction."""
         self.check(lib().qv_ctx_set_fap_direction(self.h, direction))
 
+    def set_fap_block(self, nodes_log2):
+        """Block size (log2 of node ids) of the cut table later transposes build; see qv_ctx_set_fap_block."""
+        self.check(lib().qv_ctx_set_fap_block(self.h, nodes_log2))
+
     def reserve(self, n_seeds, fanouts, n_nodes, cumulative=False, n_batches=8):
         arr, k = _fan(fanouts)
         self.check(lib().qv_ctx_reserve(self.h, n_seeds, arr, k, n_nodes, 1 if cumulative else 0, n_batches))
@@ -184,6 +191,20 @@ class Graph:
         t.ctx, t.rowptr, t.col, t.h = self.ctx, None, None, h
         t.n_nodes, t.n_edges, t._rowptr_dtype = self.n_nodes, self.n_edges, self._rowptr_dtype
         return t
+
+    def fap_items(self):
+        """(long_rows, items[n_items, 4] as int32 words: first lo, first hi, k, count; block_log2) as CUDA tensors
+        (copies), or None; see qv_csr_fap_items."""
+        rows_p, n_long, n_items, log2 = C.c_void_p(), C.c_int32(), C.c_int64(), C.c_int32()
+        items_p = lib().qv_csr_fap_items(self.h, C.byref(rows_p), C.byref(n_long), C.byref(n_items), C.byref(log2))
+        if not items_p:
+            return None
+        out = []
+        for ptr, shape in ((rows_p.value, (n_long.value,)), (items_p, (n_items.value, 4))):
+            view = type("_DevView", (), {"__cuda_array_interface__": {
+                "shape": shape, "typestr": "<i4", "data": (ptr, False), "version": 2, "strides": None}})()
+            out.append(torch.as_tensor(view, device=self.ctx.device).clone())
+        return out[0], out[1], log2.value
 
     def arrays(self):
         """(rowptr, col) as CUDA tensors; for a transposed graph, copies of the library's arrays."""

@@ -159,6 +159,14 @@ qv_status qv_ctx_set_fap_direction(qv_ctx* ctx, int32_t direction) {
     return QV_OK;
 }
 
+qv_status qv_ctx_set_fap_block(qv_ctx* ctx, int32_t nodes_log2) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_ctx_set_fap_block: ctx is NULL");
+    if (nodes_log2 != 0 && (nodes_log2 < 6 || nodes_log2 > 30))
+        return fail(ctx, QV_EINVAL, "qv_ctx_set_fap_block: nodes_log2 %d is neither 0 (default) nor in [6, 30]", nodes_log2);
+    ctx->fap_block_log2 = nodes_log2;
+    return QV_OK;
+}
+
 qv_status qv_sample_bounds(int64_t n_seeds, const int32_t* fanouts, int32_t n_hops, int64_t n_nodes, uint32_t flags,
                            int64_t* max_nodes, int64_t* max_edges, int64_t* max_frontier) {
     if (n_seeds < 0 || n_hops < 1 || n_hops > QV_MAX_HOPS || !fanouts || n_nodes < 0)
@@ -233,6 +241,15 @@ qv_status qv_csr_create(qv_ctx* ctx, int64_t n_nodes, int64_t n_edges, const voi
 
 const void* qv_csr_rowptr(const qv_csr* csr) { return csr ? csr->rowptr : nullptr; }
 const int32_t* qv_csr_col(const qv_csr* csr) { return csr ? csr->col : nullptr; }
+const void* qv_csr_fap_items(const qv_csr* csr, const int32_t** long_rows, int32_t* n_long, int64_t* n_items,
+                             int32_t* block_log2) {
+    const bool has = csr && csr->long_items;
+    if (long_rows) *long_rows = has ? csr->long_rows : nullptr;
+    if (n_long) *n_long = has ? csr->n_long : 0;
+    if (n_items) *n_items = has ? csr->n_items : 0;
+    if (block_log2) *block_log2 = has ? csr->long_block_log2 : 0;
+    return has ? csr->long_items : nullptr;
+}
 
 void qv_csr_destroy(qv_csr* csr) {
     if (!csr) return;
@@ -245,6 +262,8 @@ void qv_csr_destroy(qv_csr* csr) {
     }
     if (csr->owned_rowptr) (void)hipFree(csr->owned_rowptr);
     if (csr->owned_col) (void)hipFree(csr->owned_col);
+    if (csr->long_rows) (void)hipFree(csr->long_rows);
+    if (csr->long_items) (void)hipFree(csr->long_items);
     delete csr;
 }
 

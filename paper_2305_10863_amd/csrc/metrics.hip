@@ -23,10 +23,6 @@ __device__ __forceinline__ double group_sum(double v) {
     return v;
 }
 
-// Rows longer than this get a whole workgroup (k_psgs_long, k_fap_pull_long) instead of one group of
-// lanes: a hub would otherwise hold its group for milliseconds after the rest of the grid is done.
-constexpr int64_t kLongRow = 8192;
-
 // One PSGS sweep: group of G lanes per row.  s_next == nullptr is the innermost hop (no edges read).
 // Long rows are left to k_psgs_long; the first edge-reading sweep of a call lists them (collect != 0),
 // the later ones only skip them (the list depends on the graph alone).
@@ -175,9 +171,14 @@ __global__ void k_fap_fold(int64_t n, const double* __restrict__ p_new, double* 
 // 1/2.5 of the edges are active (a sparse p_0; the later sweeps of a citation-like graph, where
 // two thirds of the nodes are never cited and so carry no mass after the first sweep).
 // Both kernels of both directions are launched every sweep; the ones not chosen return at once.
-// Rows longer than kLongRow are left to k_fap_pull_long (a whole block per row) so that one hub
-// does not hold a 16-lane group for milliseconds.
+// Rows longer than kLongRow are left out by k_fap_pull so that one hub does not hold a 16-lane group
+// for milliseconds.  An in-edge CSR that carries the long rows' cut table (one the library built: its
+// rows list their sources in ascending order) has them summed block of sources by block of sources
+// (k_fap_pull_items): all long rows' edges into block b are visited while the 2 MB of c values of
+// block b sit in the L2 caches, instead of one 128-byte line fetched from HBM per edge.  Any other
+// in-edge CSR gets a workgroup per long row (k_fap_pull_long).
 constexpr double kAtomicPerLoadCost = 2.5;
+constexpr double kBlockedEdgeCost = 0.2;            // an edge of the blocked gather, in random loads from HBM
 
 struct FapControl {
     double active_edges;    // out-edges of nodes whose c of the coming sweep is non-zero (exact: integers below 2^53)
@@ -246,6 +247,7 @@ __global__ void __launch_bounds__(256) k_fap_pull(const RPT* __restrict__ rowptr
                                                   const double* __restrict__ c_cur, double* __restrict__ c_nxt,
                                                   double* __restrict__ p_tot, float* __restrict__ out,
                                                   int32_t* __restrict__ long_rows, FapControl* ctl, int32_t long_cap) {
+    // (long_rows == nullptr: the long rows are known already and only skipped here)
     if (ctl->scatter) return;
     const int sub = threadIdx.x % G;
     const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / G;
@@ -254,7 +256,7 @@ __global__ void __launch_bounds__(256) k_fap_pull(const RPT* __restrict__ rowptr
     for (int64_t i = group; i < n; i += n_groups) {
         const int64_t rs = (int64_t)rowptr_t[i], re = (int64_t)rowptr_t[i + 1];
         if (re - rs > kLongRow) {
-            if (sub == 0) {
+            if (sub == 0 && long_rows) {
                 const int32_t k = atomicAdd(&ctl->n_long, 1);
                 if (k < long_cap) long_rows[k] = (int32_t)i;
             }
@@ -306,6 +308,62 @@ __global__ void __launch_bounds__(256) k_fap_pull_long(const RPT* __restrict__ r
         }
     }
     add_active(ctl, active);
+}
+
+// Long rows, block of sources by block of sources: one group of 32 lanes per work item (at most 256
+// edges of one long row whose sources lie in one block; the in-edge CSR lists them block by block).
+// Workgroups start in the order of their index, so the items being worked on at any time are about as
+// many consecutive ones as the chip holds groups, i.e. they read one or two blocks of c.  A lane
+// requests all its sources, then all their values, then adds; the item's sum goes to psum[k] with one
+// fp64 atomic.
+constexpr int kItemLanes = 32;
+__global__ void __launch_bounds__(256) k_fap_pull_items(const int32_t* __restrict__ col_t, const FapItem* __restrict__ items,
+                                                        int64_t n_items, const double* __restrict__ c_cur,
+                                                        double* __restrict__ psum, const FapControl* ctl) {
+    if (ctl->scatter) return;
+    constexpr int kPer = kFapItemEdges / kItemLanes;
+    const int sub = threadIdx.x % kItemLanes;
+    const int64_t group = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) / kItemLanes;
+    FapItem it{0, 0, 0};
+    if (group < n_items) it = items[group];
+    int32_t src[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int at = j * kItemLanes + sub;
+        src[j] = at < it.count ? __builtin_nontemporal_load(&col_t[it.first + at]) : -1;
+    }
+    double x[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) x[j] = src[j] >= 0 ? c_cur[src[j]] : 0.0;
+    double acc = 0.0;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) acc += x[j];
+    const double p = group_sum<kItemLanes>(acc);
+    if (sub == 0 && p != 0.0) unsafeAtomicAdd(&psum[it.k], p);
+}
+
+// ... then every long row is finished from its sum, which goes back to zero for the next sweep
+template <typename RPF>
+__global__ void __launch_bounds__(256) k_fap_long_finish(const int32_t* __restrict__ long_rows, int32_t n_long,
+                                                         double* __restrict__ psum, const RPF* __restrict__ rowptr_f,
+                                                         int32_t next_fanout, double* __restrict__ c_nxt,
+                                                         double* __restrict__ p_tot, float* __restrict__ out, FapControl* ctl) {
+    if (ctl->scatter) return;
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    double active = 0.0;
+    for (int64_t k = tid; k < n_long; k += stride) {
+        const double p = psum[k];
+        psum[k] = 0.0;
+        active += fap_finish_row((int64_t)long_rows[k], p, rowptr_f, next_fanout, c_nxt, p_tot, out);
+    }
+    add_active(ctl, active);
+}
+
+__global__ void k_fap_zero(double* __restrict__ v, int64_t n) {
+    const int64_t tid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t i = tid; i < n; i += stride) v[i] = 0.0;
 }
 
 // scatter direction, step 1: the accumulator (the next sweep's c array) starts at zero
@@ -430,12 +488,15 @@ static qv_status fap_pull(qv_ctx* ctx, const qv_csr* g, const qv_csr* gin, const
     const int64_t n = g->n_nodes;
     const int64_t long_cap64 = gin->n_edges / kLongRow + 1;
     const int32_t long_cap = (int32_t)long_cap64;
-    qv_status rc = arena_begin(ctx, 3 * align_up((size_t)n * 8) + align_up((size_t)long_cap * 4) + 4096);
+    const bool blocked = gin->long_items != nullptr;        // the long rows came with the in-edge CSR, cut into work items
+    qv_status rc = arena_begin(ctx, 3 * align_up((size_t)n * 8) + align_up((size_t)long_cap * 4) +
+                                        align_up((size_t)gin->n_long * 8) + 4096);
     if (rc != QV_OK) return rc;
     double* c_cur = (double*)arena_take(ctx, (size_t)n * 8);
     double* c_nxt = (double*)arena_take(ctx, (size_t)n * 8);
     double* p_tot = (double*)arena_take(ctx, (size_t)n * 8);
-    int32_t* long_rows = (int32_t*)arena_take(ctx, (size_t)long_cap * 4);
+    int32_t* long_rows = blocked ? (int32_t*)nullptr : (int32_t*)arena_take(ctx, (size_t)long_cap * 4);
+    double* psum = blocked ? (double*)arena_take(ctx, (size_t)gin->n_long * 8) : (double*)nullptr;
     FapControl* ctl = (FapControl*)arena_take(ctx, sizeof(FapControl));
     const RPT* rpt = (const RPT*)gin->rowptr;
     const RPF* rpf = (const RPF*)g->rowptr;
@@ -444,12 +505,20 @@ static qv_status fap_pull(qv_ctx* ctx, const qv_csr* g, const qv_csr* gin, const
     hipLaunchKernelGGL((k_fap_pull_init<RPF>), dim3(ew), dim3(256), 0, ctx->stream, n, p0, 1.0 / (double)n, rpf, fanouts[0],
                        c_cur, p_tot, ctl);
     QV_LAUNCH_CHECK(ctx, "k_fap_pull_init");
-    const int G = group_width_for(n, gin->n_edges);
+    const int G = group_width_for(n, gin->n_edges - (blocked ? gin->long_edges : 0));      // lanes per row that k_fap_pull sums
     const int Gf = group_width_for(n, g->n_edges);
     const int blocks = grid_for(n * G, 256, ctx->n_cu * 32);
     const int blocks_f = grid_for(n * Gf, 256, ctx->n_cu * 32);
     const int32_t allow_scatter = ctx->fap_direction != 1;          // 1: gather only (testing aid)
-    const double edges_for_choice = ctx->fap_direction == 2 ? 1e300 : (double)gin->n_edges;   // 2: scatter whenever possible
+    // what a gather sweep costs, in random loads from HBM; 2: scatter whenever possible
+    const double gather_cost = blocked ? (double)(gin->n_edges - gin->long_edges) + kBlockedEdgeCost * (double)gin->long_edges
+                                       : (double)gin->n_edges;
+    const double edges_for_choice = ctx->fap_direction == 2 ? 1e300 : gather_cost;
+    if (blocked) {
+        hipLaunchKernelGGL(k_fap_zero, dim3(grid_for(gin->n_long, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream, psum,
+                           (int64_t)gin->n_long);
+        QV_LAUNCH_CHECK(ctx, "k_fap_zero");
+    }
     for (int k = 1; k <= n_hops; ++k) {
         const int32_t nf = k < n_hops ? fanouts[k] : 0;
         float* out = k == n_hops ? prob_out : (float*)nullptr;
@@ -466,10 +535,21 @@ static qv_status fap_pull(qv_ctx* ctx, const qv_csr* g, const qv_csr* gin, const
         }
 #undef QV_PULL
         QV_LAUNCH_CHECK(ctx, "k_fap_pull");
-        hipLaunchKernelGGL((k_fap_pull_long<RPT, RPF>), dim3(grid_for(long_cap, 1, ctx->n_cu * 4)), dim3(256), 0, ctx->stream,
-                           rpt, gin->col, rpf, nf, (const double*)c_cur, c_nxt, p_tot, out, (const int32_t*)long_rows, ctl,
-                           long_cap);
-        QV_LAUNCH_CHECK(ctx, "k_fap_pull_long");
+        if (blocked) {
+            const int per_block = 256 / kItemLanes;
+            hipLaunchKernelGGL(k_fap_pull_items, dim3((unsigned)((gin->n_items + per_block - 1) / per_block)), dim3(256), 0,
+                               ctx->stream, gin->col, (const FapItem*)gin->long_items, gin->n_items, (const double*)c_cur, psum,
+                               (const FapControl*)ctl);
+            QV_LAUNCH_CHECK(ctx, "k_fap_pull_items");
+            hipLaunchKernelGGL((k_fap_long_finish<RPF>), dim3(grid_for(gin->n_long, 256, ctx->n_cu * 4)), dim3(256), 0, ctx->stream,
+                               (const int32_t*)gin->long_rows, gin->n_long, psum, rpf, nf, c_nxt, p_tot, out, ctl);
+            QV_LAUNCH_CHECK(ctx, "k_fap_long_finish");
+        } else {
+            hipLaunchKernelGGL((k_fap_pull_long<RPT, RPF>), dim3(grid_for(long_cap, 1, ctx->n_cu * 4)), dim3(256), 0, ctx->stream,
+                               rpt, gin->col, rpf, nf, (const double*)c_cur, c_nxt, p_tot, out, (const int32_t*)long_rows, ctl,
+                               long_cap);
+            QV_LAUNCH_CHECK(ctx, "k_fap_pull_long");
+        }
         hipLaunchKernelGGL(k_fap_scatter_clear, dim3(ew), dim3(256), 0, ctx->stream, n, c_nxt, (const FapControl*)ctl);
 #define QV_SCAT(GW)                                                                                                    \
     hipLaunchKernelGGL((k_fap_scatter<GW, RPF>), dim3(blocks_f), dim3(256), 0, ctx->stream, rpf, g->col, n,                \

@@ -13,6 +13,15 @@ constexpr int kWave = 64;               // CDNA wavefront width
 constexpr int kScanBlock = 256;         // threads per block of the scan kernels
 constexpr int kMaxBatch = QV_MAX_BATCHES;
 constexpr int kArgsRing = 8;            // staging slots for per-batch arguments uploaded to the device
+// Rows of a graph longer than this are not left to one group of lanes by the whole-graph sweeps (a hub would
+// hold its group for milliseconds after the rest of the grid is done): they get a workgroup each, or, in an
+// in-edge CSR the library built, are visited block of sources by block of sources.
+constexpr int64_t kLongRow = 8192;
+constexpr int kFapItemEdges = 256;      // most edges of one work item of the blocked gather
+struct FapItem {                        // edges [first, first + count) of col belong to row long_rows[k]
+    int64_t first;
+    int32_t k, count;
+};
 
 // deferred device status bits (qv_ctx::d_status[0])
 constexpr int kStatRange = 1;
@@ -68,6 +77,7 @@ struct qv_ctx {
     int part_stable = 0;               // reports in a row that left the count alone
     unsigned part_calls = 0;
     int fap_direction = 0;             // qv_access_prob with an in-edge CSR: 0 choose per sweep, 1 gather only, 2 scatter only
+    int fap_block_log2 = 0;            // qv_csr_transpose: sources per block of the long rows' cut table (log2), 0 = default
     uint32_t epoch = 0;
     // pinned staging ring for the per-batch arguments of calls with many batches
     void* args_ring = nullptr;
@@ -90,6 +100,16 @@ struct qv_csr {
     const int32_t* col;
     void* owned_rowptr = nullptr;      // set when the library allocated the arrays (qv_csr_transpose)
     int32_t* owned_col = nullptr;
+    // An in-edge CSR built by qv_csr_transpose lists every row's sources in ascending order.  Its rows
+    // longer than qv::kLongRow are also cut into work items for qv_access_prob: runs of at most
+    // qv::kFapItemEdges edges whose sources all lie in one block of 2^long_block_log2 node ids, listed block
+    // by block, so that a sweep which takes the items in order reads one block's values at a time from the L2
+    // caches.  Absent (null) when the graph has no such row or fits one block.
+    int32_t* long_rows = nullptr;      // [n_long] the long rows, in no particular order
+    qv::FapItem* long_items = nullptr; // [n_items]
+    int32_t n_long = 0, long_blocks = 0, long_block_log2 = 0;
+    int64_t n_items = 0;
+    int64_t long_edges = 0;            // edges of the long rows together
 };
 
 struct qv_feat {

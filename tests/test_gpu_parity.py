@@ -547,6 +547,7 @@ def test_access_prob_in_edge_form_directed_graph_with_hub_rows(qv, ctx, rp_dtype
     g_in = make_graph(qv, ctx, rt.astype(np.int64 if rp_dtype is np.int32 else np.int32), ct)
     # the library's own transpose: identical arrays (sources ascending within a row), same width
     g_lib = g.transpose()
+    assert g_lib.fap_items() is None and g.fap_items() is None      # one block of source ids: no work items
     lrt, lct = g_lib.arrays()
     assert lrt.cpu().numpy().dtype == rp_dtype
     assert np.array_equal(lrt.cpu().numpy(), rt) and np.array_equal(lct.cpu().numpy(), ct)
@@ -575,6 +576,45 @@ def test_access_prob_in_edge_form_directed_graph_with_hub_rows(qv, ctx, rp_dtype
             assert rel_err(P.cpu().numpy(), want) <= REL_TOL, direction
             assert rel_err(Ps.cpu().numpy(), want_sparse) <= REL_TOL, direction
         ctx.set_fap_direction(0)
+    # in-edge CSRs the library built carry the long rows cut into work items (runs of edges whose sources
+    # lie in one block of node ids): those rows are then summed block by block.  Blocks of 4,096 and of 64
+    # ids here, so that the hubs' rows are cut into 15 and into 938 parts (with the default block this
+    # graph fits one block and has no items)
+    for block_log2 in (12, 6):
+        ctx.set_fap_block(block_log2)
+        g_cut = g.transpose()
+        ctx.set_fap_block(0)
+        crt, cct = g_cut.arrays()
+        assert np.array_equal(crt.cpu().numpy(), rt) and np.array_equal(cct.cpu().numpy(), ct)
+        long_rows, items, log2 = g_cut.fap_items()
+        long_rows, items = long_rows.cpu().numpy(), items.cpu().numpy()
+        assert log2 == block_log2 and sorted(long_rows.tolist()) == np.flatnonzero(d_in > 8192).tolist()
+        first = items[:, 0].astype(np.uint32).astype(np.int64) | (items[:, 1].astype(np.int64) << 32)
+        k, count = items[:, 2], items[:, 3].astype(np.int64)
+        assert count.min() >= 1 and count.max() <= 256 and k.min() >= 0 and k.max() < len(long_rows)
+        block_lo, block_hi = ct[first] >> log2, ct[first + count - 1] >> log2
+        assert np.array_equal(block_lo, block_hi) and (np.diff(block_lo) >= 0).all()     # one block each, block by block
+        for kk, i in enumerate(long_rows):                 # the items of a row cover its edges exactly once
+            mine = np.flatnonzero(k == kk)
+            order = mine[np.argsort(first[mine], kind="stable")]
+            assert first[order[0]] == rt[i] and first[order[-1]] + count[order[-1]] == rt[i + 1]
+            assert np.array_equal(first[order[1:]], first[order[:-1]] + count[order[:-1]])
+        for fanouts in ([5, 4, 3], [20]):
+            want = oracle.access_prob(rowptr, col, fanouts)
+            want_sparse = oracle.access_prob(rowptr, col, fanouts, p0=sparse_p0.astype(np.float64))
+            for direction in (0, 1):
+                ctx.set_fap_direction(direction)
+                P = qv.qv_access_prob(ctx, g, fanouts, graph_in=g_cut)
+                Ps = qv.qv_access_prob(ctx, g, fanouts, p0=dev(sparse_p0), graph_in=g_cut)
+                P2 = qv.qv_access_prob(ctx, g, fanouts, graph_in=g_cut)      # the sums start from zero again
+                ctx.sync()
+                assert rel_err(P.cpu().numpy(), want) <= REL_TOL, (block_log2, direction)
+                assert rel_err(Ps.cpu().numpy(), want_sparse) <= REL_TOL, (block_log2, direction)
+                assert rel_err(P2.cpu().numpy(), want) <= REL_TOL, (block_log2, direction)
+            ctx.set_fap_direction(0)
+        del g_cut
+    with pytest.raises(qv.QvError):
+        ctx.set_fap_block(5)
     other_rowptr = np.ones(n, dtype=np.int64)          # n-1 nodes, one edge
     other_rowptr[0] = 0
     other = make_graph(qv, ctx, other_rowptr, np.zeros(1, dtype=np.int32))
