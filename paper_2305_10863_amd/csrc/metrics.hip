@@ -47,13 +47,19 @@ __global__ void __launch_bounds__(256) k_psgs_sweep(const RP* __restrict__ rowpt
             continue;
         }
         if (s_next && deg > 0) {
+            // kAhead neighbours, then their kAhead values, are requested before the first is used
+            constexpr int kAhead = 8;
             double acc0 = 0.0, acc1 = 0.0;
-            int64_t e = rs + sub;
-            for (; e + G < re; e += 2 * G) {
-                float x0 = s_next[col[e]], x1 = s_next[col[e + G]];
-                acc0 += (double)x0; acc1 += (double)x1;
+            for (int64_t e = rs + sub; e < re; e += kAhead * G) {
+                int32_t nb[kAhead];
+#pragma unroll
+                for (int j = 0; j < kAhead; ++j) nb[j] = e + j * G < re ? col[e + j * G] : -1;
+                float x[kAhead];
+#pragma unroll
+                for (int j = 0; j < kAhead; ++j) x[j] = nb[j] >= 0 ? s_next[nb[j]] : 0.0f;
+#pragma unroll
+                for (int j = 0; j < kAhead; j += 2) { acc0 += (double)x[j]; acc1 += (double)x[j + 1]; }
             }
-            if (e < re) acc0 += (double)s_next[col[e]];
             double acc = group_sum<G>(acc0 + acc1);
             val = m + (m / (double)deg) * acc;
         }
@@ -262,13 +268,20 @@ __global__ void __launch_bounds__(256) k_fap_pull(const RPT* __restrict__ rowptr
             }
             continue;
         }
+        // kAhead sources, then their kAhead values, are requested before the first is used: most rows are
+        // done in one round, and the sweep's time is how many of these random reads are in flight
+        constexpr int kAhead = 8;
         double acc0 = 0.0, acc1 = 0.0;
-        int64_t e = rs + sub;
-        for (; e + G < re; e += 2 * G) {
-            const double x0 = c_cur[col_t[e]], x1 = c_cur[col_t[e + G]];
-            acc0 += x0; acc1 += x1;
+        for (int64_t e = rs + sub; e < re; e += kAhead * G) {
+            int32_t src[kAhead];
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) src[j] = e + j * G < re ? col_t[e + j * G] : -1;
+            double x[kAhead];
+#pragma unroll
+            for (int j = 0; j < kAhead; ++j) x[j] = src[j] >= 0 ? c_cur[src[j]] : 0.0;
+#pragma unroll
+            for (int j = 0; j < kAhead; j += 2) { acc0 += x[j]; acc1 += x[j + 1]; }
         }
-        if (e < re) acc0 += c_cur[col_t[e]];
         const double p = group_sum<G>(acc0 + acc1);
         if (sub == 0) active += fap_finish_row(i, p, rowptr_f, next_fanout, c_nxt, p_tot, out);
     }
@@ -434,7 +447,7 @@ __global__ void k_rank_ids(int64_t n, const uint64_t* __restrict__ keys, int32_t
 
 static int group_width_for(int64_t n, int64_t e) {
     double avg = n > 0 ? (double)e / (double)n : 0.0;
-    return avg < 6 ? 4 : avg < 12 ? 8 : avg < 24 ? 16 : avg < 48 ? 32 : 64;
+    return avg < 12 ? 4 : avg < 24 ? 8 : avg < 48 ? 16 : avg < 96 ? 32 : 64;
 }
 
 template <typename RP>
