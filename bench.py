@@ -488,6 +488,37 @@ def main():
         gc.collect()
         torch.cuda.empty_cache()
 
+    # ---- the same batches through qv_step_many, four groups of B on the library's own streams ----
+    step_ms = None
+    if args.extra_streams > 0 and not tiered and S == 1 and B == qv.QV_MAX_BATCHES:
+        nS = qv.QV_MAX_STEP_BATCHES
+        try:
+            s_bufs = lanes[0].bufs + [qv.SampleBuffers(ctx0, batch, w.fanouts, w.n, want_frontier=False, want_nbr_global=False)
+                                      for _ in range(nS - B)]
+            s_rows = lanes[0].rows + [feat.empty_rows(row_cap, "cuda") for _ in range(nS - B)]
+            s_plan = qv.ManyPlan(ctx0, g, feat, s_bufs, s_rows, w.fanouts)
+            for t in range(nS):
+                s_plan.n_ids[t] = row_cap
+            s_seeds = [seeds_dev[t % n_batches] for t in range(nS)]
+            s_rng = [rng_seeds[t % n_batches] for t in range(nS)]
+            ts = []
+            for rep in range(2 + 7):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                s_plan.step(s_seeds, s_rng)
+                s_plan.step(s_seeds, s_rng)
+                torch.cuda.synchronize()
+                if rep >= 2:
+                    ts.append((time.perf_counter() - t0) / 2)
+            ctx0.sync()
+            step_ms = float(np.median(ts)) * 1e3 / nS
+            del s_plan, s_bufs, s_rows
+        except (qv.QvError, torch.OutOfMemoryError) as e:
+            log("qv_step_many pass skipped: " + str(e)[:120])
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+
     # ---- latency pass (not part of the timed region): one batch per call, one at a time ---------
     n_lat = max(220, args.latency_samples + 20)
     lat_plan = qv.ManyPlan(ctx0, g, feat, [lanes[0].bufs[0]], [lanes[0].rows[0]], w.fanouts)
@@ -597,6 +628,11 @@ def main():
                                    "path_frac_hbm_peak": extra["stream_sweep"]["best_path_frac_hbm_peak"],
                                    "note": "best of the stream sweep (whole calls of batches_per_call on each stream); `value` above is the "
                                            "one-stream figure, where a kernel's duration is its own"}
+    if step_ms:
+        extra["step_many"] = {"batches_per_call": qv.QV_MAX_STEP_BATCHES, "ms_per_step": round(step_ms, 5),
+                              "value": round(tot_edges / n_batches / (step_ms * 1e-3), 1), "unit": "edges/s",
+                              "path_frac_hbm_peak": round(path_bytes / n_batches / (step_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                              "note": "one context, qv_step_many: four groups of %d batches, three of them on the library's own streams" % B}
     result.update(extra)
 
     # ---- the oracle on this machine's host cores (a reported baseline, not the target) ------------

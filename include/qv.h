@@ -305,6 +305,29 @@ qv_status qv_gather_many(qv_ctx* ctx, const qv_feat* feat, int32_t n_batches,
                          const int64_t* const* n_ids_dev, void* const* outs,
                          int64_t out_row_stride_bytes);
 
+/* One serving step for many batches: qv_sample_many followed by the gather of every batch's
+ * sampled nodes (Section 3.2, components 5 and 6 back to back), with the overlap done inside the
+ * library.  Calls of more than QV_MAX_BATCHES batches are cut into up to QV_STEP_LANES groups of at
+ * most QV_MAX_BATCHES; the first group runs on the context's stream, the others on streams the
+ * context owns, so that the latency-bound sampling kernels of the groups run side by side
+ * (Section 4.3 (1): pipelines multiplexed on one processor; worth 4 % at 512 batches per call on
+ * a 111 M-node graph, nothing up to QV_MAX_BATCHES, where the call is the two calls).
+ * Every internal stream starts after the work enqueued on the context's stream so far, and the
+ * context's stream continues only after all of them: to the caller the call is ordered on the
+ * context's stream like any other.  Batch b is sampled exactly as qv_sample_many would; then
+ * rows_out[b] [dev] receives table[n_id[r]] for r < min(|n_id|, rows_cap[b], outs[b].n_id_cap) at
+ * byte offset r * out_row_stride_bytes (the count is read on the device: no host round trip).
+ * seeds, rows_out: [host] arrays of [dev] pointers; n_seeds, rng_seeds, rows_cap: [host] arrays.
+ * 1 <= n_batches <= QV_MAX_STEP_BATCHES.  Deferred errors of all groups are reported by
+ * qv_ctx_sync.  The internal contexts hold scratch of their own (as much as the first group's). */
+#define QV_STEP_LANES 4
+#define QV_MAX_STEP_BATCHES (QV_STEP_LANES * QV_MAX_BATCHES)
+qv_status qv_step_many(qv_ctx* ctx, const qv_csr* csr, const qv_feat* feat, int32_t n_batches,
+                       const int32_t* const* seeds, const int64_t* n_seeds, const int32_t* fanouts,
+                       int32_t n_hops, const uint64_t* rng_seeds, uint32_t flags,
+                       const qv_sample_out* outs, void* const* rows_out, const int64_t* rows_cap,
+                       int64_t out_row_stride_bytes);
+
 /* ---------------------------------------------------------------------------------------------
  * Workload metrics
  * ------------------------------------------------------------------------------------------ */

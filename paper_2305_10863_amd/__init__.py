@@ -15,6 +15,7 @@ _lib = None
 
 QV_OK, QV_EINVAL, QV_ENOMEM, QV_EHIP, QV_ECAPACITY, QV_ERANGE = 0, -1, -2, -3, -4, -5
 QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 128
+QV_STEP_LANES, QV_MAX_STEP_BATCHES = 4, 4 * 128
 QV_NOALLOC_MAX_FRONTIER = 1 << 20
 QV_SAMPLE_CUMULATIVE, QV_FEAT_OWN_COPY = 1, 1
 QV_DEDUP_AUTO, QV_DEDUP_TABLE, QV_DEDUP_PARTITIONED = 0, 1, 2
@@ -23,7 +24,7 @@ EXPORTS = [
     "qv_ctx_create", "qv_ctx_destroy", "qv_last_error", "qv_ctx_sync", "qv_ctx_reserve", "qv_ctx_set_epoch", "qv_ctx_set_table_budget", "qv_ctx_set_dedup", "qv_ctx_set_fap_direction", "qv_ctx_set_fap_block", "qv_csr_fap_items",
     "qv_sample_bounds", "qv_csr_create", "qv_csr_destroy", "qv_csr_transpose", "qv_csr_rowptr", "qv_csr_col", "qv_sample_hop", "qv_sample_hop_noalloc", "qv_sample", "qv_sample_many",
     "qv_reindex", "qv_feat_create", "qv_feat_destroy", "qv_feat_hot_rows", "qv_feat_loc", "qv_feat_row_stride",
-    "qv_gather", "qv_gather_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
+    "qv_gather", "qv_gather_many", "qv_step_many", "qv_psgs", "qv_psgs_batch_sum", "qv_access_prob", "qv_place_rank",
 ]
 
 
@@ -79,6 +80,8 @@ def lib():
         L.qv_sample_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i32), i32,
                                      C.POINTER(u64), C.c_uint32, C.POINTER(_SampleOut)]
         L.qv_gather_many.argtypes = [vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(vp), C.POINTER(vp), i64]
+        L.qv_step_many.argtypes = [vp, vp, vp, i32, C.POINTER(vp), C.POINTER(i64), C.POINTER(i32), i32, C.POINTER(u64),
+                                   C.c_uint32, C.POINTER(_SampleOut), C.POINTER(vp), C.POINTER(i64), i64]
         L.qv_reindex.argtypes = [vp, vp, i64, vp, i64, i64, vp, i64, vp, vp, vp, vp]
         L.qv_feat_create.argtypes = [vp, vp, i32, i64, i32, i32, i64, vp, i32, C.POINTER(vp)]
         L.qv_feat_destroy.argtypes = [vp]
@@ -381,6 +384,18 @@ class ManyPlan:
                                  self.flags, self.outs))
         if self.feat is not None:
             c.check(L.qv_gather_many(c.h, self.feat.h, n, self.ids, self.n_ids, self.n_dev, self.out_ptrs, self.stride))
+
+    def step(self, seeds, rng_seeds, n_batches=None):
+        """The same through qv_step_many (up to QV_MAX_STEP_BATCHES batches; groups beyond the first run on the
+        context's own streams); rows are gathered up to each batch's `n_ids` entry."""
+        n = len(seeds) if n_batches is None else n_batches
+        for i in range(n):
+            self.seed_ptrs[i] = seeds[i].data_ptr()
+            self.n_seeds[i] = seeds[i].numel()
+            self.rng[i] = rng_seeds[i]
+        c = self.ctx
+        c.check(lib().qv_step_many(c.h, self.graph.h, self.feat.h, n, self.seed_ptrs, self.n_seeds, self.fan, self.k, self.rng,
+                                   self.flags, self.outs, self.out_ptrs, self.n_ids, self.stride))
 
 
 def qv_sample_many(ctx, graph, seeds_list, fanouts, rng_seeds, outs=None, cumulative=False):

@@ -103,6 +103,11 @@ qv_status qv_ctx_create(int device, void* hip_stream, qv_ctx** out) {
 void qv_ctx_destroy(qv_ctx* ctx) {
     if (!ctx) return;
     (void)hipStreamSynchronize(ctx->stream);
+    for (int g = 0; g < QV_STEP_LANES - 1; ++g) {
+        if (ctx->lanes[g]) qv_ctx_destroy(ctx->lanes[g]);
+        if (ctx->lane_done[g]) (void)hipEventDestroy(ctx->lane_done[g]);
+    }
+    if (ctx->step_fork) (void)hipEventDestroy(ctx->step_fork);
     if (ctx->arena) (void)hipFree(ctx->arena);
     if (ctx->table_keyw) (void)hipFree(ctx->table_keyw);
     if (ctx->table_slots) (void)hipFree(ctx->table_slots);
@@ -111,6 +116,7 @@ void qv_ctx_destroy(qv_ctx* ctx) {
     if (ctx->args_ring) (void)hipHostFree(ctx->args_ring);
     for (int i = 0; i < kArgsRing; ++i)
         if (ctx->args_ev_live[i]) (void)hipEventDestroy(ctx->args_ev[i]);
+    if (ctx->owns_stream && ctx->stream) (void)hipStreamDestroy(ctx->stream);
     delete ctx;
 }
 
@@ -122,11 +128,104 @@ qv_status qv_ctx_sync(qv_ctx* ctx) {
                                ctx->stream));
     QV_HIP(ctx, hipStreamSynchronize(ctx->stream));
     int32_t s = ctx->h_status[0];
+    // the groups of qv_step_many that ran on the context's own streams (their work was joined into
+    // ctx->stream when it was enqueued, so it is complete by now) report here as well
+    for (int g = 0; g < QV_STEP_LANES - 1; ++g) {
+        qv_ctx* lane = ctx->lanes[g];
+        if (!lane) continue;
+        QV_HIP(ctx, hipMemcpyAsync(lane->h_status, lane->d_status, sizeof(int32_t), hipMemcpyDeviceToHost, lane->stream));
+        QV_HIP(ctx, hipStreamSynchronize(lane->stream));
+        if (lane->h_status[0] != 0) {
+            s |= lane->h_status[0];
+            QV_HIP(ctx, hipMemsetAsync(lane->d_status, 0, sizeof(int32_t), lane->stream));
+        }
+    }
     if (s == 0) return QV_OK;
-    QV_HIP(ctx, hipMemsetAsync(ctx->d_status, 0, sizeof(int32_t), ctx->stream));
+    if (ctx->h_status[0] != 0) QV_HIP(ctx, hipMemsetAsync(ctx->d_status, 0, sizeof(int32_t), ctx->stream));
     if (s & kStatInval) return fail(ctx, QV_EINVAL, "device check failed: malformed input (e.g. repeated known ids)");
     if (s & kStatRange) return fail(ctx, QV_ERANGE, "device check failed: an id was outside [0, n)");
     return fail(ctx, QV_ECAPACITY, "device check failed: an output array was too small; results are truncated");
+}
+
+// ---- qv_step_many ---------------------------------------------------------------------------
+static qv_status step_lane(qv_ctx* ctx, int g, qv_ctx** out) {
+    if (!ctx->lanes[g]) {
+        hipStream_t s = nullptr;
+        QV_HIP(ctx, hipSetDevice(ctx->device));
+        QV_HIP(ctx, hipStreamCreateWithFlags(&s, hipStreamNonBlocking));
+        qv_ctx* lane = nullptr;
+        const qv_status rc = qv_ctx_create(ctx->device, (void*)s, &lane);
+        if (rc != QV_OK) {
+            (void)hipStreamDestroy(s);
+            return fail(ctx, rc, "qv_step_many: internal context: %s", qv_last_error(nullptr));
+        }
+        lane->owns_stream = true;
+        ctx->lanes[g] = lane;
+    }
+    if (!ctx->lane_done[g]) QV_HIP(ctx, hipEventCreateWithFlags(&ctx->lane_done[g], hipEventDisableTiming));
+    qv_ctx* lane = ctx->lanes[g];
+    lane->direct_budget_bytes = ctx->direct_budget_bytes;      // the caller's settings apply to every group
+    lane->dedup_form = ctx->dedup_form;
+    lane->part_log2 = ctx->part_log2;
+    *out = lane;
+    return QV_OK;
+}
+
+qv_status qv_step_many(qv_ctx* ctx, const qv_csr* csr, const qv_feat* feat, int32_t n_batches,
+                       const int32_t* const* seeds, const int64_t* n_seeds, const int32_t* fanouts,
+                       int32_t n_hops, const uint64_t* rng_seeds, uint32_t flags,
+                       const qv_sample_out* outs, void* const* rows_out, const int64_t* rows_cap,
+                       int64_t out_row_stride_bytes) {
+    if (!ctx) return fail(nullptr, QV_EINVAL, "qv_step_many: ctx is NULL");
+    if (!csr || !feat || !seeds || !n_seeds || !rng_seeds || !outs || !rows_out || !rows_cap)
+        return fail(ctx, QV_EINVAL, "qv_step_many: null argument");
+    if (n_batches < 1 || n_batches > QV_MAX_STEP_BATCHES)
+        return fail(ctx, QV_EINVAL, "qv_step_many: n_batches %d outside [1, %d]", n_batches, QV_MAX_STEP_BATCHES);
+    if (n_hops < 1 || n_hops > QV_MAX_HOPS) return fail(ctx, QV_EINVAL, "qv_step_many: n_hops %d outside [1, %d]", n_hops, QV_MAX_HOPS);
+    const int groups = (n_batches + kMaxBatch - 1) / kMaxBatch;
+    const int per = (n_batches + groups - 1) / groups;
+    qv_ctx* target[QV_STEP_LANES] = {ctx};
+    for (int g = 1; g < groups; ++g) {
+        const qv_status rc = step_lane(ctx, g - 1, &target[g]);
+        if (rc != QV_OK) return rc;
+    }
+    if (groups > 1) {
+        if (!ctx->step_fork) QV_HIP(ctx, hipEventCreateWithFlags(&ctx->step_fork, hipEventDisableTiming));
+        QV_HIP(ctx, hipEventRecord(ctx->step_fork, ctx->stream));
+        for (int g = 1; g < groups; ++g) QV_HIP(ctx, hipStreamWaitEvent(target[g]->stream, ctx->step_fork, 0));
+    }
+    // Sampling of every group first, then the gathers.  What the groups gain from each other is that their
+    // latency-bound sampling kernels run side by side; a group's sampling beside another's gather gains
+    // nothing (both are limited by the memory system: a chain in which group g+1 sampled while group g
+    // gathered took as long as the parts one after the other).
+    qv_status rc = QV_OK;
+    const int32_t* ids[kMaxBatch];
+    int64_t n_ids[kMaxBatch];
+    const int64_t* n_ids_dev[kMaxBatch];
+    for (int pass = 0; pass < 2 && rc == QV_OK; ++pass) {
+        for (int g = 0; g < groups && rc == QV_OK; ++g) {
+            const int b0 = g * per, nb = (b0 + per <= n_batches ? per : n_batches - b0);
+            if (nb <= 0) continue;
+            if (pass == 0) {
+                rc = qv_sample_many(target[g], csr, nb, seeds + b0, n_seeds + b0, fanouts, n_hops, rng_seeds + b0, flags, outs + b0);
+            } else {
+                for (int i = 0; i < nb; ++i) {
+                    const qv_sample_out& o = outs[b0 + i];
+                    ids[i] = o.n_id;
+                    n_ids[i] = rows_cap[b0 + i] < o.n_id_cap ? rows_cap[b0 + i] : o.n_id_cap;
+                    n_ids_dev[i] = o.node_off + (n_hops + 1);
+                }
+                rc = qv_gather_many(target[g], feat, nb, ids, n_ids, n_ids_dev, rows_out + b0, out_row_stride_bytes);
+            }
+            if (rc != QV_OK && target[g] != ctx) ctx->err = target[g]->err;
+        }
+    }
+    // the join happens whatever was enqueued: the caller's stream must not run ahead of the internal ones
+    for (int g = 1; g < groups; ++g) {
+        QV_HIP(ctx, hipEventRecord(ctx->lane_done[g - 1], target[g]->stream));
+        QV_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->lane_done[g - 1], 0));
+    }
+    return rc;
 }
 
 qv_status qv_ctx_set_epoch(qv_ctx* ctx, uint32_t epoch) {

@@ -89,6 +89,12 @@ struct qv_ctx {
     int32_t* h_status = nullptr;       // pinned mirror
     int n_cu = 256;
     std::string err;
+    // qv_step_many: the contexts (each with a stream of its own) that take the groups after the first,
+    // made on first use; fork / join events
+    qv_ctx* lanes[QV_STEP_LANES - 1] = {};
+    hipEvent_t step_fork = nullptr;
+    hipEvent_t lane_done[QV_STEP_LANES - 1] = {};
+    bool owns_stream = false;          // a lane's stream belongs to it
 };
 
 struct qv_csr {

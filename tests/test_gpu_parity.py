@@ -233,6 +233,53 @@ def test_call_of_the_most_batches(qv, ctx, tiny):
     feat.close()
 
 
+@pytest.mark.parametrize("n", [5, 129, 300, 512])
+def test_step_many_samples_and_gathers_like_the_two_calls(qv, ctx, tiny, n):
+    # one serving step through qv_step_many: 1, 2, 3 and 4 groups (the groups after the first run on streams
+    # of the context's own); every batch against the oracle, rows clamped by the device-side count and by
+    # rows_cap; twice in a row on the same buffers, and a deferred error of a later group reaches qv_ctx_sync
+    w, rowptr, col, g = tiny
+    fan = [6, 3]
+    seeds = [w.seeds(1700 + j, 1 + (53 * j) % 200) for j in range(n)]
+    table = qvgen.features_host(w.seed, w.n, w.dim, w.feat_dtype)
+    feat = qv.Features(ctx, dev(table))
+    bufs = [qv.SampleBuffers(ctx, len(s), fan, w.n) for s in seeds]
+    caps = [b.caps[0] if j % 7 else 3 for j, b in enumerate(bufs)]            # every seventh batch: three rows only
+    rows = [feat.empty_rows(max(c, 1), ctx.device) for c in caps]
+    plan = qv.ManyPlan(ctx, g, feat, bufs, rows, fan)
+    for j in range(n):
+        plan.n_ids[j] = caps[j]
+    d_seeds = [dev(s) for s in seeds]
+    for rnd in range(2):
+        rng = [3100 + 1000 * rnd + j for j in range(n)]
+        for r in rows:
+            r.fill_(0)
+        torch.cuda.synchronize()
+        plan.step(d_seeds, rng)
+        ctx.sync()
+        for j in range(0, n, 1 if n <= 129 else 3):
+            want = oracle.sample(rowptr, col, seeds[j], fan, rng[j])
+            assert_sample_equal(bufs[j].to_host(), want)
+            U = min(len(want["n_id"]), caps[j])
+            got = rows[j].cpu().numpy()
+            assert got[:U].tobytes() == oracle.gather(table, want["n_id"][:U]).tobytes(), j
+            assert not got[U:].any(), j
+    if n > qv.QV_MAX_BATCHES:
+        bad = dev(np.array([w.n + 5], dtype=np.int32))                          # an id outside the graph, in the last group
+        plan.step(d_seeds[:-1] + [bad], rng)
+        with pytest.raises(qv.QvError) as e:
+            ctx.sync()
+        assert e.value.status == qv.QV_ERANGE
+        plan.step(d_seeds, rng)                                                 # ... and the context is usable afterwards
+        ctx.sync()
+        assert_sample_equal(bufs[n - 1].to_host(), oracle.sample(rowptr, col, seeds[n - 1], fan, rng[n - 1]))
+    with pytest.raises(qv.QvError) as e:                                       # one batch more than the call takes
+        ctx.check(qv.lib().qv_step_many(ctx.h, g.h, feat.h, qv.QV_MAX_STEP_BATCHES + 1, plan.seed_ptrs, plan.n_seeds, plan.fan,
+                                        plan.k, plan.rng, 0, plan.outs, plan.out_ptrs, plan.n_ids, plan.stride))
+    assert e.value.status == qv.QV_EINVAL
+    feat.close()
+
+
 def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
     # the dedup tables are not cleared between calls; results must not depend on what earlier
     # calls (of other sizes, other batch counts) left behind, nor on the counter wrapping
