@@ -225,10 +225,16 @@ class Graph:
             out.append(torch.as_tensor(view, device=self.ctx.device).clone())
         return tuple(out)
 
-    def __del__(self):
+    def close(self):
         if getattr(self, "h", None):
             lib().qv_csr_destroy(self.h)
             self.h = None
+
+    def __del__(self):
+        try:                    # at interpreter exit the module's globals may be gone already
+            self.close()
+        except Exception:
+            pass
 
 
 class Features:
