@@ -149,7 +149,7 @@ class Context:
         self.check(lib().qv_ctx_set_fap_direction(self.h, direction))
 
     def set_fap_block(self, nodes_log2):
-        """Block size (log2 of node ids) of the cut table later transposes build; see qv_ctx_set_fap_block."""
+        """Block size (log2 of node ids) of the long rows' work items that later transposes build; see qv_ctx_set_fap_block."""
         self.check(lib().qv_ctx_set_fap_block(self.h, nodes_log2))
 
     def reserve(self, n_seeds, fanouts, n_nodes, cumulative=False, n_batches=8):

@@ -173,12 +173,13 @@ __global__ void k_fap_fold(int64_t n, const double* __restrict__ p_new, double* 
 //   gather  (k_fap_pull, k_fap_pull_long): row i sums c_k over its in-row; no atomics; reads all edges.
 //   scatter (k_fap_scatter + k_fap_scatter_fold): nodes with mass add c_k[j] along their out-edges
 //           with fp64 atomics; reads only those edges.
-// A random atomic costs about 2.5 random loads on this GPU, so scatter is taken when fewer than
-// 1/2.5 of the edges are active (a sparse p_0; the later sweeps of a citation-like graph, where
-// two thirds of the nodes are never cited and so carry no mass after the first sweep).
+// A random atomic costs about 2.5 random loads on this GPU, so scatter is taken when 2.5 x the active
+// edges is below what the gather costs in random loads (a sparse p_0; the later sweeps of a
+// citation-like graph, where two thirds of the nodes are never cited and so carry no mass after the
+// first sweep).
 // Both kernels of both directions are launched every sweep; the ones not chosen return at once.
 // Rows longer than kLongRow are left out by k_fap_pull so that one hub does not hold a 16-lane group
-// for milliseconds.  An in-edge CSR that carries the long rows' cut table (one the library built: its
+// for milliseconds.  An in-edge CSR that carries the long rows' work items (one the library built: its
 // rows list their sources in ascending order) has them summed block of sources by block of sources
 // (k_fap_pull_items): all long rows' edges into block b are visited while the 2 MB of c values of
 // block b sit in the L2 caches, instead of one 128-byte line fetched from HBM per edge.  Any other

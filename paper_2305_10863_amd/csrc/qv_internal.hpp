@@ -77,7 +77,7 @@ struct qv_ctx {
     int part_stable = 0;               // reports in a row that left the count alone
     unsigned part_calls = 0;
     int fap_direction = 0;             // qv_access_prob with an in-edge CSR: 0 choose per sweep, 1 gather only, 2 scatter only
-    int fap_block_log2 = 0;            // qv_csr_transpose: sources per block of the long rows' cut table (log2), 0 = default
+    int fap_block_log2 = 0;            // qv_csr_transpose: node ids per block of the long rows' work items (log2), 0 = default
     uint32_t epoch = 0;
     // pinned staging ring for the per-batch arguments of calls with many batches
     void* args_ring = nullptr;
