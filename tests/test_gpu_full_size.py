@@ -85,6 +85,33 @@ def check_call_of_many(qv, ctx, w, rowptr, col, g, feat, first_batch, n_batches=
         assert got_rows[:U].cpu().numpy().tobytes() == expect.tobytes(), (w.name, "call of many", b, "gather")
 
 
+def check_step_many(qv, ctx, w, rowptr, col, g, feat, first_batch, n_batches=256, every=8):
+    """A serving step of more batches than one set of launches takes, through qv_step_many (the groups after
+    the first run on streams the context owns); every `every`-th batch compared with the oracle."""
+    idx = list(range(first_batch, first_batch + n_batches))
+    seeds = [w.seeds(b) for b in idx]
+    rng = [w.rng_seed(b) for b in idx]
+    probe = qv.qv_sample(ctx, g, torch.from_numpy(seeds[0]).cuda(), w.fanouts, rng[0])
+    ctx.sync()
+    row_cap = 2 * int(probe.node_off[-1].item()) + 1024
+    del probe
+    bufs = [qv.SampleBuffers(ctx, len(s), w.fanouts, w.n) for s in seeds]
+    rows = [feat.empty_rows(row_cap, "cuda") for _ in idx]
+    plan = qv.ManyPlan(ctx, g, feat, bufs, rows, w.fanouts)
+    for t in range(n_batches):
+        plan.n_ids[t] = row_cap
+    plan.step([torch.from_numpy(s).cuda() for s in seeds], rng)
+    ctx.sync()
+    for t in list(range(0, n_batches, every)) + [n_batches - 1]:
+        got, want = bufs[t].to_host(), oracle.sample(rowptr, col, seeds[t], w.fanouts, rng[t])
+        for k in ("node_off", "edge_off", "frontier_off", "n_id", "row_local", "col_local", "nbr_global", "frontier"):
+            assert np.array_equal(got[k], want[k]), (w.name, "step of many", idx[t], k)
+        U = len(want["n_id"])
+        assert U <= row_cap
+        expect = qvgen.feature_rows_host(w.seed, want["n_id"], w.dim, w.feat_dtype)
+        assert rows[t][:U].cpu().numpy().tobytes() == expect.tobytes(), (w.name, "step of many", idx[t], "gather")
+
+
 def check_metrics(qv, ctx, w, rowptr, col, g, p0=None):
     Q = qv.qv_psgs(ctx, g, w.fanouts)
     p0d = None if p0 is None else torch.from_numpy(p0.astype(np.float32)).cuda()
@@ -104,6 +131,17 @@ def check_metrics(qv, ctx, w, rowptr, col, g, p0=None):
     Pi = P_in.cpu().numpy().astype(np.float64)
     assert np.all(Pi[~nz] == 0)
     assert np.max(np.abs(Pi[nz] - oP[nz]) / oP[nz]) <= REL_TOL
+    if w.symmetrise and w.n > (1 << 18):
+        # the same through an in-edge CSR the library built: its rows beyond 8,192 edges come cut into work
+        # items and are summed block of sources by block of sources
+        g_t = g.transpose()
+        assert g_t.fap_items() is not None
+        P_t = qv.qv_access_prob(ctx, g, w.fanouts, p0=p0d, graph_in=g_t)
+        ctx.sync()
+        Pt = P_t.cpu().numpy().astype(np.float64)
+        assert np.all(Pt[~nz] == 0)
+        assert np.max(np.abs(Pt[nz] - oP[nz]) / oP[nz]) <= REL_TOL
+        del g_t
     return Q, P, oQ
 
 
@@ -188,5 +226,6 @@ def test_citation_full(qv, ctx):
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # hashed tables on the citation graph, arguments uploaded
     ctx.set_dedup(0)
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 200, n_batches=128) # as the bench: 128 batches, the form chosen by the library
+    check_step_many(qv, ctx, w, rowptr, col, g, feat, 400, n_batches=512, every=16)   # as the bench's step_many pass: four groups of 128
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()
