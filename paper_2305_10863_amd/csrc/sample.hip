@@ -471,8 +471,8 @@ __device__ __forceinline__ void emit_edge(const CallHeader& c, const BatchG& b, 
 // lanes load one entry each, then the group works through them, one per sub-round, the entry's
 // fields broadcast inside the group.  The neighbour ids of all S sub-rounds are requested before
 // any is stored, so a wave keeps S random col reads per group in flight: with many entries the
-// kernel's time is the latency of those reads.  S is the smallest power of two with which the
-// grid covers the frontier in one round, so a small frontier still spreads over many waves.
+// kernel's time is the latency of those reads.  S is what is left of the frontier divided by the
+// groups of the grid, at most 8.
 template <int G, typename A>
 __global__ void __launch_bounds__(256) k_sample(A c) {
     const BatchG b = batch_of(c, blockIdx.y);
@@ -492,13 +492,15 @@ __global__ void __launch_bounds__(256) k_sample(A c) {
     constexpr int kAhead = 8;                                   // most sub-rounds per round
     constexpr int groups_per_wave = kWave / G;
     const int64_t n_groups = (int64_t)gridDim.x * (256 / G);
-    int S = 1;
-    while (S < kAhead && n_groups * S < F) S <<= 1;
     const int64_t wave_global = (int64_t)blockIdx.x * (256 / kWave) + threadIdx.x / kWave;
-    const int64_t per_wave = (int64_t)groups_per_wave * S;      // entries per wave and round
-    const int64_t round_stride = (int64_t)gridDim.x * (256 / kWave) * per_wave;
-    // the loops are uniform over the wave: every lane runs the same number of iterations
-    for (int64_t w0 = wave_global * per_wave; w0 < F; w0 += round_stride) {
+    // The loops are uniform over the grid: every lane runs the same number of iterations.  Every round
+    // deals what is left evenly over all groups (S entries each, at most kAhead), so the last round keeps
+    // the whole grid busy for a short while instead of a part of it for a full round.
+    for (int64_t done = 0; done < F;) {
+        const int64_t left = F - done;
+        const int S = left >= n_groups * kAhead ? kAhead : (int)((left + n_groups - 1) / n_groups);
+        const int64_t w0 = done + wave_global * (groups_per_wave * S);
+        done += n_groups * S;
         const int64_t f = w0 + (int64_t)(lane / G) * S + sub;   // a group's S entries are consecutive
         uint32_t d_own = 0, off_own = 0, rs_lo = 0, rs_hi = 0;
         int32_t v_own = 0, vl_own = -1;
@@ -1820,7 +1822,7 @@ static qv_status launch_sample(qv_ctx* ctx, const CallArgs& c, int64_t max_front
         // enough workgroups for one group per entry while the frontier is small; beyond the cap the
         // kernel gives every group up to 8 entries per round (its S)
         const int cap = n_batches >= 8 ? ctx->n_cu * 32 / n_batches : ctx->n_cu * 8;
-        dim3 grid((unsigned)grid_for(max_frontier, 256 / G, cap), (unsigned)n_batches);
+        dim3 grid((unsigned)grid_for(max_frontier, (256 / G) * (n_batches >= 8 ? 8 : 1), cap), (unsigned)n_batches);
         switch (G) {
             case 8: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 8); break;
             case 16: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 16); break;
