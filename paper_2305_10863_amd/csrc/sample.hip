@@ -415,6 +415,21 @@ __device__ __forceinline__ void seg_base_prologue(const CallHeader& c, const Bat
     int n_tiles = (int)((plen + kPTile - 1) / kPTile);
     if (n_tiles > c.p_tiles) n_tiles = c.p_tiles;                     // <= kPMaxTiles (host check)
     const int nthr = (int)blockDim.x, tid = (int)threadIdx.x;
+    if (n_tiles <= kWave) {                                           // the usual case: one wave scans them all
+        if (tid < kWave) {
+            const uint32_t x = tid < n_tiles ? b.tile_seg[tid] : 0u;
+            uint32_t inc = x;
+#pragma unroll
+            for (int o = 1; o < kWave; o <<= 1) {
+                const uint32_t y = __shfl_up(inc, o);
+                if (tid >= o) inc += y;
+            }
+            if (tid < n_tiles) s_segbase[tid] = inc - x;
+            if (publish && tid == kWave - 1) m->edge_off[c.stage] = m->edge_off[c.stage - 1] + (int64_t)inc;
+        }
+        lds_barrier();
+        return;
+    }
     const int per = (n_tiles + nthr - 1) / nthr;                      // consecutive tiles per thread
     uint32_t sum = 0;
     for (int i = 0; i < per; ++i) {
