@@ -79,10 +79,24 @@ __global__ void __launch_bounds__(256) k_gather(GatherArgs a) {
     }
 }
 
+// Workgroups per id list.  A group of lanes that takes many rows one after the other has its next id on
+// the way while it copies (and pays its start-up once), but the fewer the workgroups the longer the last
+// ones run on after the rest: about 16 rounds of the workgroups the chip holds at once for a launch of
+// well under a millisecond, 8 for longer ones, never more than the chip holds per list.  Measured with
+// 64 lists per launch, of HBM peak: 256-byte rows 0.78 / 0.80 / 0.80 / 0.78 at 2,048 / 1,024 / 512 / 256
+// workgroups per list, 2,408-byte rows 0.69 / 0.70 / 0.73 / 0.73, 400-byte rows 0.70 / 0.71 / 0.71 / 0.73.
+static int gather_blocks_per_list(const qv_ctx* ctx, int n_jobs, int64_t bytes_bound) {
+    const int resident = ctx->n_cu * 8;
+    const int rounds = bytes_bound > ((int64_t)12 << 30) ? 8 : 16;
+    int per_list = rounds * resident / n_jobs;
+    if (per_list > resident) per_list = resident;
+    return per_list < 1 ? 1 : per_list;
+}
+
 template <typename V, bool TAIL>
-static void launch_gather_vt(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t max_ids, int n_jobs) {
+static void launch_gather_vt(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t max_ids, int n_jobs, int64_t bytes_bound) {
     int64_t threads = max_ids * lpr;
-    dim3 grid((unsigned)grid_for(threads, 256, ctx->n_cu * 8), (unsigned)n_jobs);
+    dim3 grid((unsigned)grid_for(threads, 256, gather_blocks_per_list(ctx, n_jobs, bytes_bound)), (unsigned)n_jobs);
     switch (lpr) {
         case 8: hipLaunchKernelGGL((k_gather<V, 8, TAIL>), grid, dim3(256), 0, ctx->stream, a); break;
         case 16: hipLaunchKernelGGL((k_gather<V, 16, TAIL>), grid, dim3(256), 0, ctx->stream, a); break;
@@ -92,9 +106,9 @@ static void launch_gather_vt(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t 
 }
 
 template <typename V>
-static void launch_gather_v(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t max_ids, int n_jobs) {
-    if (a.tail_pieces > 0) launch_gather_vt<V, true>(ctx, a, lpr, max_ids, n_jobs);
-    else launch_gather_vt<V, false>(ctx, a, lpr, max_ids, n_jobs);
+static void launch_gather_v(qv_ctx* ctx, const GatherArgs& a, int lpr, int64_t max_ids, int n_jobs, int64_t bytes_bound) {
+    if (a.tail_pieces > 0) launch_gather_vt<V, true>(ctx, a, lpr, max_ids, n_jobs, bytes_bound);
+    else launch_gather_vt<V, false>(ctx, a, lpr, max_ids, n_jobs, bytes_bound);
 }
 
 static qv_status launch_gather_some(qv_ctx* ctx, const GatherSource& s, const GatherJob* jobs, int n_jobs, int64_t out_stride);
@@ -112,13 +126,15 @@ static qv_status launch_gather_some(qv_ctx* ctx, const GatherSource& s, const Ga
     // widest vector that divides every row start
     uintptr_t bits = (uintptr_t)s.hot_stride | (uintptr_t)out_stride | (uintptr_t)s.hot;
     if (s.cold) bits |= (uintptr_t)s.cold_stride | (uintptr_t)s.cold;     // a tier that does not exist constrains nothing
-    int64_t max_ids = 0;
+    int64_t max_ids = 0, sum_ids = 0;
     GatherArgs a{s.hot, s.cold, s.loc, s.n_rows, s.hot_stride, s.cold_stride, out_stride, 0, 0, 0, ctx->d_status, {}};
     for (int i = 0; i < n_jobs; ++i) {
         a.jobs[i] = jobs[i];
         if (jobs[i].n_ids > 0) bits |= (uintptr_t)jobs[i].out;
         if (jobs[i].n_ids > max_ids) max_ids = jobs[i].n_ids;
+        sum_ids += jobs[i].n_ids;
     }
+    const int64_t bytes_bound = 2 * sum_ids * s.row_bytes;      // read + written if every list is full
     if (max_ids == 0) return QV_OK;
     if (bits % 2 != 0 || s.row_bytes % 2 != 0) return fail(ctx, QV_EINVAL, "gather: rows must be 2-byte aligned");
     const int vec = (bits % 16 == 0) ? 16 : (bits % 8 == 0) ? 8 : (bits % 4 == 0) ? 4 : 2;
@@ -128,10 +144,10 @@ static qv_status launch_gather_some(qv_ctx* ctx, const GatherSource& s, const Ga
     int lpr = 8;                                        // at least 8 lanes so that a tail (< 16 bytes) fits
     while (lpr < 64 && lpr < a.vecs_per_row) lpr <<= 1;
     switch (vec) {
-        case 16: launch_gather_v<v4u>(ctx, a, lpr, max_ids, n_jobs); break;
-        case 8: launch_gather_v<v2u>(ctx, a, lpr, max_ids, n_jobs); break;
-        case 4: launch_gather_v<uint32_t>(ctx, a, lpr, max_ids, n_jobs); break;
-        default: launch_gather_v<uint16_t>(ctx, a, lpr, max_ids, n_jobs); break;
+        case 16: launch_gather_v<v4u>(ctx, a, lpr, max_ids, n_jobs, bytes_bound); break;
+        case 8: launch_gather_v<v2u>(ctx, a, lpr, max_ids, n_jobs, bytes_bound); break;
+        case 4: launch_gather_v<uint32_t>(ctx, a, lpr, max_ids, n_jobs, bytes_bound); break;
+        default: launch_gather_v<uint16_t>(ctx, a, lpr, max_ids, n_jobs, bytes_bound); break;
     }
     QV_LAUNCH_CHECK(ctx, "k_gather");
     return QV_OK;
