@@ -1922,7 +1922,12 @@ static qv_status launch_part_dedup(qv_ctx* ctx, CallArgs& c, int rowptr_bits, in
     {   // the a-priori bounds are loose (most tiles do not exist): k_part_deal strides over the tiles
         const int64_t cap = n_batches >= 4 ? ctx->n_cu * 8 / n_batches : ctx->n_cu * 2;
         c.deal_blocks = (int32_t)(tiles < cap ? tiles : cap);
-        const int node_blocks = c.stage == 0 ? 0 : n_batches >= 4 ? 8 : 32;      // workgroups of their own for the tiles of n_id
+        int node_blocks = c.stage == 0 ? 0 : n_batches >= 4 ? 8 : 32;            // workgroups of their own for the tiles of n_id
+        // Workgroups go to the eight XCDs in turn by their linear index: with a width that is a multiple of
+        // eight the x-th workgroup of every batch lands on the same XCD, and the stage's tiles and those of
+        // n_id stay unevenly spread; an odd width rotates the batches over the XCDs (128 batches, hop 2:
+        // 24 wide 28.6 us, 25 wide 24.4 us).
+        if (node_blocks && (c.deal_blocks + node_blocks) % 2 == 0) ++node_blocks;
         dim3 deal_grid((unsigned)(c.deal_blocks + node_blocks), (unsigned)n_batches);
         QV_LAUNCH_A(ctx, c, n_batches, deal_grid, dim3(kPThreads), k_part_deal);
     }
