@@ -188,8 +188,9 @@ def main():
     ap.add_argument("--extra-streams", type=int, default=16,
                     help="after the timed region, time the same region over 1, 2, 4, 8, 16 streams up to this many and "
                          "report ms per step for each (0 = skip; only when --streams is 1)")
-    ap.add_argument("--batches-per-call", type=int, default=128,
-                    help="independent batches per qv_sample_many / qv_gather_many call (1..128)")
+    ap.add_argument("--batches-per-call", type=int, default=256,
+                    help="independent batches per qv_sample_many / qv_gather_many call (1..256; halved while a call's "
+                         "buffers would not fit the free device memory)")
     ap.add_argument("--latency-samples", type=int, default=200, help="single-batch calls timed for p50 / p99 (at least 200)")
     ap.add_argument("--table-budget-gib", type=float, default=-1.0,
                     help="dedup table budget per context in GiB for the table forms (0 = always hash; default: the library's 16)")
@@ -347,17 +348,32 @@ def main():
     # inside the region.
     import copy
     import math
+    dedup_form = {"auto": 0, "table": 1, "partitioned": 2}[args.dedup]
+    nb, eb, fb = qv.qv_sample_bounds(batch, w.fanouts, w.n)
+    Kh = len(w.fanouts)
+    L = qv.lib()
+    # output rows are sized from what the batches really produce (the a-priori node bound is 15 x
+    # larger on the citation workload); the sizes of every timed batch are checked against it below
+    ctx0.set_dedup(dedup_form, args.partitions_log2)
+    probe = [qv.qv_sample(ctx0, g, torch.from_numpy(w.seeds(b, batch)).cuda(), w.fanouts, w.rng_seed(b)) for b in range(4)]
+    ctx0.sync()
+    row_cap = min(nb, 2 * max(int(o.node_off[-1].item()) for o in probe) + 1024)
+    del probe
+    # batches per call: as asked, unless one call's buffers (outputs at their a-priori bounds, scratch of
+    # about the same size, gathered rows) would not fit beside the graph and the feature table
     B = max(1, min(args.batches_per_call, qv.QV_MAX_BATCHES))
+    per_batch_bytes = 2 * (eb * 8 + nb * 4) + row_cap * feat.row_stride
+    free_bytes = torch.cuda.mem_get_info()[0]
+    while B > 8 and B * per_batch_bytes > 0.6 * free_bytes:
+        B //= 2
+    if B != args.batches_per_call:
+        log("%d batches per call (%.1f GB of buffers per call, %.0f GB free)" % (B, B * per_batch_bytes / 1e9, free_bytes / 1e9))
     calls_per_region = max(1, math.ceil(K / B))
     calls_per_region = math.ceil(calls_per_region / S) * S          # every stream gets the same number of calls
     n_batches = calls_per_region * B
     seeds_host = [w.seeds(b, batch) for b in range(n_batches)]
     seeds_dev = [torch.from_numpy(s).cuda() for s in seeds_host]
     rng_seeds = [w.rng_seed(b) for b in range(n_batches)]
-    dedup_form = {"auto": 0, "table": 1, "partitioned": 2}[args.dedup]
-    nb, eb, fb = qv.qv_sample_bounds(batch, w.fanouts, w.n)
-    Kh = len(w.fanouts)
-    L = qv.lib()
 
     made_contexts = []
 
@@ -369,14 +385,6 @@ def main():
         c.set_dedup(dedup_form, args.partitions_log2)
         c.reserve(batch, w.fanouts, w.n, n_batches=B)
         return c
-
-    # output rows are sized from what the batches really produce (the a-priori node bound is 15 x
-    # larger on the citation workload); the sizes of every timed batch are checked against it below
-    ctx0.set_dedup(dedup_form, args.partitions_log2)
-    probe = [qv.qv_sample(ctx0, g, seeds_dev[i], w.fanouts, rng_seeds[i]) for i in range(min(4, n_batches))]
-    ctx0.sync()
-    row_cap = min(nb, 2 * max(int(o.node_off[-1].item()) for o in probe) + 1024)
-    del probe
 
     class Lane:
         """One context (stream) with the buffers of one call."""

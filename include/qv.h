@@ -52,7 +52,7 @@ typedef enum {
 
 #define QV_MAX_HOPS 8
 #define QV_MAX_FANOUT 1024
-#define QV_MAX_BATCHES 128   /* batches per qv_sample_many / qv_gather_many call */
+#define QV_MAX_BATCHES 256   /* batches per qv_sample_many / qv_gather_many call */
 
 /* ---------------------------------------------------------------------------------------------
  * Context

@@ -14,8 +14,8 @@ LIB_PATH = os.path.join(_HERE, "libqv.so")
 _lib = None
 
 QV_OK, QV_EINVAL, QV_ENOMEM, QV_EHIP, QV_ECAPACITY, QV_ERANGE = 0, -1, -2, -3, -4, -5
-QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 128
-QV_STEP_LANES, QV_MAX_STEP_BATCHES = 4, 4 * 128
+QV_MAX_HOPS, QV_MAX_FANOUT, QV_MAX_BATCHES = 8, 1024, 256
+QV_STEP_LANES, QV_MAX_STEP_BATCHES = 4, 4 * 256
 QV_NOALLOC_MAX_FRONTIER = 1 << 20
 QV_SAMPLE_CUMULATIVE, QV_FEAT_OWN_COPY = 1, 1
 QV_DEDUP_AUTO, QV_DEDUP_TABLE, QV_DEDUP_PARTITIONED = 0, 1, 2

@@ -1836,7 +1836,7 @@ static qv_status launch_sample(qv_ctx* ctx, const CallArgs& c, int64_t max_front
         const int G = l <= 8 ? 8 : l <= 16 ? 16 : l <= 32 ? 32 : 64;
         // enough workgroups for one group per entry while the frontier is small; beyond the cap the
         // kernel gives every group up to 8 entries per round (its S)
-        const int cap = n_batches >= 8 ? ctx->n_cu * 32 / n_batches : ctx->n_cu * 8;
+        const int cap = n_batches >= 8 ? std::max(64, ctx->n_cu * 32 / n_batches) : ctx->n_cu * 8;
         dim3 grid((unsigned)grid_for(max_frontier, (256 / G) * (n_batches >= 8 ? 8 : 1), cap), (unsigned)n_batches);
         switch (G) {
             case 8: QV_LAUNCH_A1(ctx, c, n_batches, grid, dim3(256), k_sample, 8); break;
@@ -1920,7 +1920,7 @@ static qv_status launch_part_dedup(qv_ctx* ctx, CallArgs& c, int rowptr_bits, in
     if (tiles < 1) tiles = 1;
     dim3 grid((unsigned)tiles, (unsigned)n_batches);
     {   // the a-priori bounds are loose (most tiles do not exist): k_part_deal strides over the tiles
-        const int64_t cap = n_batches >= 4 ? ctx->n_cu * 8 / n_batches : ctx->n_cu * 2;
+        const int64_t cap = n_batches >= 4 ? std::max(16, ctx->n_cu * 8 / n_batches) : ctx->n_cu * 2;
         c.deal_blocks = (int32_t)(tiles < cap ? tiles : cap);
         int node_blocks = c.stage == 0 ? 0 : n_batches >= 4 ? 8 : 32;            // workgroups of their own for the tiles of n_id
         // Workgroups go to the eight XCDs in turn by their linear index: with a width that is a multiple of

@@ -85,7 +85,7 @@ def check_call_of_many(qv, ctx, w, rowptr, col, g, feat, first_batch, n_batches=
         assert got_rows[:U].cpu().numpy().tobytes() == expect.tobytes(), (w.name, "call of many", b, "gather")
 
 
-def check_step_many(qv, ctx, w, rowptr, col, g, feat, first_batch, n_batches=256, every=8):
+def check_step_many(qv, ctx, w, rowptr, col, g, feat, first_batch, n_batches=512, every=8):
     """A serving step of more batches than one set of launches takes, through qv_step_many (the groups after
     the first run on streams the context owns); every `every`-th batch compared with the oracle."""
     idx = list(range(first_batch, first_batch + n_batches))
@@ -163,7 +163,7 @@ def test_dense_social_full(qv, ctx):
     ctx.set_table_budget(16 << 30)
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # hashed tables on the citation graph, arguments uploaded
     ctx.set_dedup(0)
-    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 200, n_batches=128) # as the bench: 128 batches, the form chosen by the library
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 200, n_batches=128) # a call of 128 batches, the form chosen by the library (rows at their a-priori bound: 86 GB)
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()
 
@@ -225,7 +225,7 @@ def test_citation_full(qv, ctx):
     ctx.set_table_budget(16 << 30)
     check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 60, n_batches=12)   # hashed tables on the citation graph, arguments uploaded
     ctx.set_dedup(0)
-    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 200, n_batches=128) # as the bench: 128 batches, the form chosen by the library
-    check_step_many(qv, ctx, w, rowptr, col, g, feat, 400, n_batches=512, every=16)   # as the bench's step_many pass: four groups of 128
+    check_call_of_many(qv, ctx, w, rowptr, col, g, feat, 200, n_batches=256) # as the bench: 256 batches, the form chosen by the library
+    check_step_many(qv, ctx, w, rowptr, col, g, feat, 500, n_batches=1024, every=32)  # as the bench's step_many pass: four groups of 256
     check_metrics(qv, ctx, w, rowptr, col, g)
     feat.close()

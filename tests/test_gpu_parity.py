@@ -214,7 +214,7 @@ def test_call_of_the_most_batches(qv, ctx, tiny):
     # the largest call: QV_MAX_BATCHES batches of unequal sizes through one set of launches
     w, rowptr, col, g = tiny
     n = qv.QV_MAX_BATCHES
-    assert n == 128
+    assert n == 256
     seeds = [w.seeds(700 + j, 1 + (37 * j) % 300) for j in range(n)]
     rng = [900 + j for j in range(n)]
     outs = qv.qv_sample_many(ctx, g, [dev(s) for s in seeds], [7, 4, 3], rng)
@@ -233,7 +233,7 @@ def test_call_of_the_most_batches(qv, ctx, tiny):
     feat.close()
 
 
-@pytest.mark.parametrize("n", [5, 129, 300, 512])
+@pytest.mark.parametrize("n", [5, 257, 600, 1024])
 def test_step_many_samples_and_gathers_like_the_two_calls(qv, ctx, tiny, n):
     # one serving step through qv_step_many: 1, 2, 3 and 4 groups (the groups after the first run on streams
     # of the context's own); every batch against the oracle, rows clamped by the device-side count and by
@@ -257,7 +257,7 @@ def test_step_many_samples_and_gathers_like_the_two_calls(qv, ctx, tiny, n):
         torch.cuda.synchronize()
         plan.step(d_seeds, rng)
         ctx.sync()
-        for j in range(0, n, 1 if n <= 129 else 3):
+        for j in range(0, n, 1 if n <= 257 else 5):
             want = oracle.sample(rowptr, col, seeds[j], fan, rng[j])
             assert_sample_equal(bufs[j].to_host(), want)
             U = min(len(want["n_id"]), caps[j])
