@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0        # MI355X HBM3E, published
 # k_gather launch; see GATHER_TRAFFIC_PROFILE.  Only quoted for configurations that were profiled.
 GATHER_LISTS_PER_LAUNCH = 64
 GATHER_TRAFFIC_RATIO = {("citation", 1.0, 64): 0.968, ("dense_social", 1.0, 64): 1.021, ("co_purchase", 1.0, 64): 1.156}
-GATHER_TRAFFIC_PROFILE = ("profiles/citation_call_of_128_batches_kernels_and_counters.md and "
+GATHER_TRAFFIC_PROFILE = ("profiles/citation_call_of_256_batches_kernels_and_counters.md and "
                           "profiles/other_workloads_kernel_durations_and_gather_traffic.md (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000 "
                           "of k_gather over its algorithmic bytes, same workload and lists per launch)")
 
