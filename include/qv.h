@@ -233,7 +233,7 @@ qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_
  * that the per-batch arguments are copied to the device once per call (a few microseconds).
  * Throughput grows with the batches per call (the fixed cost of a call's 16 launches is shared):
  * on a 111 M-node graph, 1,024 seeds, fanouts 15/10/5: 1.3 x 10^10 sampled edges/s at 32 batches
- * per call, 1.6 x 10^10 at 128. */
+ * per call, 1.6 x 10^10 at 128, 1.7 x 10^10 at 256. */
 qv_status qv_sample_many(qv_ctx* ctx, const qv_csr* csr, int32_t n_batches,
                          const int32_t* const* seeds, const int64_t* n_seeds,
                          const int32_t* fanouts, int32_t n_hops, const uint64_t* rng_seeds,
@@ -310,7 +310,7 @@ qv_status qv_gather_many(qv_ctx* ctx, const qv_feat* feat, int32_t n_batches,
  * library.  Calls of more than QV_MAX_BATCHES batches are cut into up to QV_STEP_LANES groups of at
  * most QV_MAX_BATCHES; the first group runs on the context's stream, the others on streams the
  * context owns, so that the latency-bound sampling kernels of the groups run side by side
- * (Section 4.3 (1): pipelines multiplexed on one processor; worth 7 % at 512 batches per call on
+ * (Section 4.3 (1): pipelines multiplexed on one processor; worth 5 % at 1,024 batches per call on
  * a 111 M-node graph, nothing up to QV_MAX_BATCHES, where the call is the two calls).
  * Every internal stream starts after the work enqueued on the context's stream so far, and the
  * context's stream continues only after all of them: to the caller the call is ordered on the
