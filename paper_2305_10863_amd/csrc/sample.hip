@@ -1501,6 +1501,140 @@ __global__ void __launch_bounds__(kPThreads, 4) k_part_assign(A c) {    // 4 wav
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// k_part_seeds: stage 0 of the partitioned form as one kernel, one workgroup per batch, for batches of
+// at most kSeedMax seeds.  What k_part_deal, k_part_dedup and k_part_assign do for the seeds in three
+// launches (each a chain of dependent memory round trips for a single tile) happens here in LDS: the
+// seeds go into one hash table with their smallest position, first occurrences are ranked by ballot
+// and popcount in position order, and n_id, the frontier entries of hop 1 (row extents read here), the
+// caller's frontier array, the tile's edge total and the size block are written.  Same results.
+// ---------------------------------------------------------------------------------------------
+constexpr int kSeedThreads = 1024;
+constexpr int kSeedKeys = 2;                                    // seeds per thread
+constexpr int kSeedMax = kSeedThreads * kSeedKeys;              // 2,048
+constexpr int kSeedCap = 2 * kSeedMax;                          // table entries: at most half full
+constexpr int kSeedWords = kSeedMax / kWave;
+
+template <typename RP, typename A>
+__global__ void __launch_bounds__(kSeedThreads) k_part_seeds(A c) {
+    __shared__ uint32_t t_key[kSeedCap], t_min[kSeedCap];
+    __shared__ unsigned long long m_first[kSeedWords];
+    __shared__ uint32_t pre_first[kSeedWords], seg_tot[kSeedWords], seg_pre[kSeedWords], s_tot[2];
+    const BatchG b = batch_of(c, blockIdx.x);
+    const RP* __restrict__ rowptr = static_cast<const RP*>(c.rowptr);
+    SampleMeta QV_G* m = b.meta;
+    const int tid = (int)threadIdx.x, lane = tid % kWave, wave = tid / kWave;
+    const int64_t n = b.n_seeds < kSeedMax ? b.n_seeds : kSeedMax;          // (the host sends larger batches the other way)
+    const uint32_t n_valid = c.n_nodes >= 0 ? (uint32_t)c.n_nodes : 0x80000000u;
+    // my seeds, requested before the table is cleared
+    uint32_t key[kSeedKeys];
+    bool valid[kSeedKeys], bad = false;
+#pragma unroll
+    for (int i = 0; i < kSeedKeys; ++i) {
+        const int p = i * kSeedThreads + tid;
+        key[i] = p < n ? (uint32_t)b.seeds[p] : 0xFFFFFFFFu;
+    }
+    for (int k = tid; k < kSeedCap; k += kSeedThreads) { t_key[k] = kEmptyKey; t_min[k] = 0xFFFFFFFFu; }
+    lds_barrier();
+    int slot[kSeedKeys];
+#pragma unroll
+    for (int i = 0; i < kSeedKeys; ++i) {
+        const int p = i * kSeedThreads + tid;
+        valid[i] = key[i] < n_valid;
+        if (p < n && !valid[i]) bad = true;
+        slot[i] = -1;
+        if (valid[i]) {
+            uint32_t x = slot_hash(key[i]) >> (32 - 12);            // kSeedCap = 2^12 entries
+            static_assert(kSeedCap == 1 << 12, "the table index above");
+            for (;;) {                                              // ends: the table is at most half full
+                const uint32_t cur = atomicCAS(&t_key[x], kEmptyKey, key[i]);
+                if (cur == kEmptyKey || cur == key[i]) break;
+                x = (x + 1) & (kSeedCap - 1);
+            }
+            slot[i] = (int)x;
+            atomicMin(&t_min[x], (uint32_t)p);
+        }
+    }
+    if (bad) atomicOr((int*)gptr(c.status), kStatRange);
+    lds_barrier();
+    // first occurrences, a bit per position (position = word * 64 + lane)
+    bool first[kSeedKeys];
+#pragma unroll
+    for (int i = 0; i < kSeedKeys; ++i) {
+        first[i] = valid[i] && t_min[slot[i]] == (uint32_t)(i * kSeedThreads + tid);
+        const unsigned long long mf = __ballot(first[i]);
+        if (lane == 0) m_first[i * (kSeedThreads / kWave) + wave] = mf;
+    }
+    // row extents of the first occurrences (they are hop 1's frontier) and their segment sizes
+    int64_t rs[kSeedKeys];
+    uint32_t deg[kSeedKeys], incl[kSeedKeys];
+#pragma unroll
+    for (int i = 0; i < kSeedKeys; ++i) {
+        rs[i] = 0; deg[i] = 0;
+        if (first[i]) {
+            rs[i] = (int64_t)rowptr[key[i]];
+            deg[i] = (uint32_t)((int64_t)rowptr[key[i] + 1] - rs[i]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < kSeedKeys; ++i) {
+        const uint32_t seg = first[i] ? (deg[i] < (uint32_t)c.next_fanout ? deg[i] : (uint32_t)c.next_fanout) : 0u;
+        uint32_t inc = seg;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t y = __shfl_up(inc, o);
+            if (lane >= o) inc += y;
+        }
+        incl[i] = inc - seg;
+        if (lane == kWave - 1) seg_tot[i * (kSeedThreads / kWave) + wave] = inc;
+    }
+    lds_barrier();
+    static_assert(kSeedWords <= kWave, "one wave scans the words");
+    if (wave < 2) {                                                 // wave 0: ranks of the first occurrences; wave 1: segment offsets
+        const uint32_t x = lane < kSeedWords ? (wave ? seg_tot[lane] : (uint32_t)__popcll(m_first[lane])) : 0u;
+        uint32_t inc = x;
+#pragma unroll
+        for (int o = 1; o < kWave; o <<= 1) {
+            const uint32_t y = __shfl_up(inc, o);
+            if (lane >= o) inc += y;
+        }
+        if (lane < kSeedWords) (wave ? seg_pre : pre_first)[lane] = inc - x;
+        if (lane == kWave - 1) s_tot[wave] = inc;
+    }
+    lds_barrier();
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int i = 0; i < kSeedKeys; ++i) {
+        if (!first[i]) continue;
+        const int word = i * (kSeedThreads / kWave) + wave;
+        const int64_t j = (int64_t)pre_first[word] + (uint32_t)__popcll(m_first[word] & below);   // local id and frontier index
+        if (j < b.n_id_cap) b.n_id[j] = (int32_t)key[i];
+        else atomicOr((int*)gptr(c.status), kStatCapacity);
+        if (j < b.fr_cap) {
+            b.fr_id[j] = (int32_t)key[i];
+            b.fr_lid[j] = (int32_t)j;
+            b.fr_rs[j] = rs[i];
+            b.fr_deg[j] = deg[i];
+            b.fr_seg[j] = seg_pre[word] + incl[i];
+            b.fr_tile[j] = 0;
+        } else {
+            atomicOr((int*)gptr(c.status), kStatCapacity);
+        }
+        if (b.fr_user) {
+            if (j < b.fr_user_cap) b.fr_user[j] = (int32_t)key[i];
+            else atomicOr((int*)gptr(c.status), kStatCapacity);
+        }
+    }
+    if (tid == 0) {                                                 // the size block starts here
+        for (int i = 0; i < QV_MAX_HOPS + 2; ++i) { m->node_off[i] = 0; m->frontier_off[i] = 0; }
+        for (int i = 0; i < QV_MAX_HOPS + 1; ++i) m->edge_off[i] = 0;
+        m->stage_range[0] = 0; m->stage_range[1] = b.n_seeds;
+        m->node_off[1] = s_tot[0];
+        m->frontier_off[1] = s_tot[0];
+        if (n > 0) b.tile_seg[0] = s_tot[1];
+    }
+}
+
 // k_relabel_links: repeats of a node that was new in their hop point at its first position; follow
 // the link (that position holds the local id by now).  Also exports the sizes.
 template <typename A>
@@ -2023,8 +2157,18 @@ static qv_status sample_many(qv_ctx* ctx, const qv_csr* csr, int n_batches, cons
             return lg;
         };
         c.stage = 0; c.next_fanout = fanouts[0]; c.p_log2 = stage_p_log2(0); c.deal_all_nodes = 0;
-        rc = launch_part_dedup(ctx, c, csr->rowptr_bits, max_seeds, n_batches);
-        if (rc != QV_OK) return rc;
+        if (max_seeds <= kSeedMax) {                                // the seeds of a batch fit one workgroup's LDS table
+            if (csr->rowptr_bits == 32)
+                QV_LAUNCH_FORM(ctx, c, n_batches, dim3((unsigned)n_batches), dim3(kSeedThreads), (k_part_seeds<int32_t, CallInline>),
+                               (k_part_seeds<int32_t, CallDevice>));
+            else
+                QV_LAUNCH_FORM(ctx, c, n_batches, dim3((unsigned)n_batches), dim3(kSeedThreads), (k_part_seeds<int64_t, CallInline>),
+                               (k_part_seeds<int64_t, CallDevice>));
+            QV_LAUNCH_CHECK(ctx, "k_part_seeds");
+        } else {
+            rc = launch_part_dedup(ctx, c, csr->rowptr_bits, max_seeds, n_batches);
+            if (rc != QV_OK) return rc;
+        }
         for (int k = 1; k <= n_hops; ++k) {
             c.stage = k; c.hop = k; c.fanout = fanouts[k - 1]; c.next_fanout = k < n_hops ? fanouts[k] : 0;
             const int lg = stage_p_log2(k);
