@@ -231,7 +231,7 @@ qv_status qv_sample(qv_ctx* ctx, const qv_csr* csr, const int32_t* seeds, int64_
  * n_seeds, rng_seeds: [host] arrays; outs: [host] array of output blocks ([dev] arrays inside).
  * 1 <= n_batches <= QV_MAX_BATCHES.  Up to 8 batches travel in the kernel argument block; beyond
  * that the per-batch arguments are copied to the device once per call (a few microseconds).
- * Throughput grows with the batches per call (the fixed cost of a call's 16 launches is shared):
+ * Throughput grows with the batches per call (the fixed cost of a call's 14 launches is shared):
  * on a 111 M-node graph, 1,024 seeds, fanouts 15/10/5: 1.3 x 10^10 sampled edges/s at 32 batches
  * per call, 1.6 x 10^10 at 128, 1.7 x 10^10 at 256. */
 qv_status qv_sample_many(qv_ctx* ctx, const qv_csr* csr, int32_t n_batches,
