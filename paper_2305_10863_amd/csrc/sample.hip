@@ -2031,7 +2031,7 @@ static qv_status plan_sample(qv_ctx* ctx, int64_t max_seeds, const int32_t* fano
     // The partitioned form runs more kernels per stage (a fixed cost per call of some 0.1 ms) and does
     // less work per edge: it pays once a call carries enough edges (measured on a 111 M node graph,
     // batches of 1,024 seeds whose a-priori bound is 0.94 M edges each: 4 batches 135 us of sampling in
-    // the table form against 165 us, 8 batches 216 against 185 us, 12 batches 333 against 211 us).
+    // the table form against about 165 us, 8 batches 216 against 185 us, 12 batches 333 against 211 us).
     const bool big_call = bd->edges * (int64_t)n_batches >= (int64_t)7 << 20;
     L->part = (ctx->dedup_form == QV_DEDUP_PARTITIONED || (ctx->dedup_form == QV_DEDUP_AUTO && big_call)) && !cumulative &&
               largest <= max_stage;
