@@ -280,6 +280,30 @@ def test_step_many_samples_and_gathers_like_the_two_calls(qv, ctx, tiny, n):
     feat.close()
 
 
+def test_step_many_with_cumulative_frontiers(qv, ctx, tiny):
+    # the nested-block variant takes the table forms, here in two groups: the second group's tables belong to
+    # the context's own second stream; two calls in a row (the tables are reused, never cleared)
+    w, rowptr, col, g = tiny
+    fan, n = [4, 3], qv.QV_MAX_BATCHES + 40
+    seeds = [w.seeds(2600 + j, 1 + (29 * j) % 90) for j in range(n)]
+    table = qvgen.features_host(w.seed, w.n, w.dim, w.feat_dtype)
+    feat = qv.Features(ctx, dev(table))
+    bufs = [qv.SampleBuffers(ctx, len(s), fan, w.n, cumulative=True) for s in seeds]
+    rows = [feat.empty_rows(b.caps[0], ctx.device) for b in bufs]
+    plan = qv.ManyPlan(ctx, g, feat, bufs, rows, fan, cumulative=True)
+    d_seeds = [dev(s) for s in seeds]
+    for rnd in range(2):
+        rng = [5200 + 700 * rnd + j for j in range(n)]
+        plan.step(d_seeds, rng)
+        ctx.sync()
+        for j in list(range(0, n, 7)) + [n - 1]:
+            want = oracle.sample(rowptr, col, seeds[j], fan, rng[j], cumulative=True)
+            assert_sample_equal(bufs[j].to_host(), want)
+            U = len(want["n_id"])
+            assert rows[j][:U].cpu().numpy().tobytes() == oracle.gather(table, want["n_id"]).tobytes(), j
+    feat.close()
+
+
 def test_table_reuse_across_calls_and_epoch_wrap(qv, tiny):
     # the dedup tables are not cleared between calls; results must not depend on what earlier
     # calls (of other sizes, other batch counts) left behind, nor on the counter wrapping
