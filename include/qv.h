@@ -319,7 +319,10 @@ qv_status qv_gather_many(qv_ctx* ctx, const qv_feat* feat, int32_t n_batches,
  * byte offset r * out_row_stride_bytes (the count is read on the device: no host round trip).
  * seeds, rows_out: [host] arrays of [dev] pointers; n_seeds, rng_seeds, rows_cap: [host] arrays.
  * 1 <= n_batches <= QV_MAX_STEP_BATCHES.  Deferred errors of all groups are reported by
- * qv_ctx_sync.  The internal contexts hold scratch of their own (as much as the first group's). */
+ * qv_ctx_sync.  A host-side error (bad argument, allocation) returns at once with the failing
+ * group's status and message; work of earlier groups may have been enqueued by then, and the
+ * streams are joined all the same.  The internal contexts hold scratch of their own (as much as
+ * the first group's) and are released with the context. */
 #define QV_STEP_LANES 4
 #define QV_MAX_STEP_BATCHES (QV_STEP_LANES * QV_MAX_BATCHES)
 qv_status qv_step_many(qv_ctx* ctx, const qv_csr* csr, const qv_feat* feat, int32_t n_batches,
