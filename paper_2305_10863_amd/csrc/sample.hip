@@ -5,7 +5,8 @@
 //                hash into P partitions per batch and every partition is deduplicated by one
 //                workgroup in an LDS table; nothing is kept in HBM between stages or calls and no
 //                global atomic is issued per edge.  Launches of a qv_sample / qv_sample_many call:
-//                  stage 0:   k_part_deal, k_part_dedup, k_part_assign        (seeds -> F_0, n_id)
+//                  stage 0:   k_part_seeds for batches of up to 2,048 seeds, else
+//                             k_part_deal, k_part_dedup, k_part_assign        (seeds -> F_0, n_id)
 //                  per hop k: k_sample, k_part_deal, k_part_dedup, k_part_assign
 //                  k_relabel_links   (repeats of a node new in its hop take its local id; sizes exported)
 //                See the comment above slot_hash for the three kernels.
@@ -16,7 +17,7 @@
 //                  k_insert_ids, k_flag, k_assign (stage 0); per hop k_sample, k_flag, k_assign; k_relabel.
 //
 // No host synchronisation anywhere; every kernel takes up to QV_MAX_BATCHES independent batches
-// (blockIdx.y, or folded into blockIdx.x in k_part_dedup).
+// (blockIdx.y, or folded into blockIdx.x in k_part_seeds, k_part_dedup and k_relabel_links).
 // A single-pass variant of k_flag + k_assign (tile scan with decoupled look-back) was measured
 // and dropped: agent-scope atomics across the eight XCDs cost 1.5-2 us per dependent step, so
 // the ticket + publish + look-back chain was slower (12-17 us per stage) than two short kernels
