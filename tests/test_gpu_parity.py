@@ -233,6 +233,29 @@ def test_call_of_the_most_batches(qv, ctx, tiny):
     feat.close()
 
 
+@pytest.mark.parametrize("sizes", [[2048, 2047, 1, 0], [2049, 5], [2048] * 9, [4096, 100]])
+def test_seed_stage_at_the_limit_of_its_one_kernel_form(qv, ctx, tiny, sizes):
+    # batches of up to 2,048 seeds go through stage 0 in one kernel (partitioned form), larger ones through the
+    # three general kernels; seeds drawn from 300 ids, so nearly all of them repeat, plus ids outside the graph
+    w, rowptr, col, g = tiny
+    rng0 = np.random.default_rng(len(sizes) * 10_000 + sizes[0])
+    seeds = [rng0.integers(0, 300, n).astype(np.int32) for n in sizes]
+    rngs = [77 + i for i in range(len(sizes))]
+    outs = qv.qv_sample_many(ctx, g, [dev(s) if len(s) else torch.zeros(0, dtype=torch.int32, device="cuda") for s in seeds],
+                             [5, 3], rngs)
+    ctx.sync()
+    for i, s_ in enumerate(seeds):
+        assert_sample_equal(outs[i].to_host(), oracle.sample(rowptr, col, s_, [5, 3], rngs[i]))
+    if sizes[0] >= 2048:                                            # an id outside the graph is reported, the rest of the call is unaffected
+        bad = [s_.copy() for s_ in seeds]
+        bad[0][7] = w.n
+        outs = qv.qv_sample_many(ctx, g, [dev(s_) for s_ in bad], [5, 3], rngs)
+        with pytest.raises(qv.QvError) as e:
+            ctx.sync()
+        assert e.value.status == qv.QV_ERANGE
+        assert_sample_equal(outs[1].to_host(), oracle.sample(rowptr, col, seeds[1], [5, 3], rngs[1]))
+
+
 @pytest.mark.parametrize("n", [5, 257, 600, 1024])
 def test_step_many_samples_and_gathers_like_the_two_calls(qv, ctx, tiny, n):
     # one serving step through qv_step_many: 1, 2, 3 and 4 groups (the groups after the first run on streams
