@@ -716,6 +716,41 @@ def test_access_prob_in_edge_form_directed_graph_with_hub_rows(qv, ctx, rp_dtype
         qv.qv_access_prob(ctx, g, [3], graph_in=other)
 
 
+def test_access_prob_rows_at_the_long_row_limit(qv, ctx):
+    # in-rows of exactly 8,192 edges (summed by a group of lanes) and of 8,193 (the long-row paths: a workgroup
+    # per row, or work items by block of sources when the library built the in-edge CSR with small blocks)
+    rng = np.random.default_rng(31)
+    n, A, B = 20_000, 19_000, 19_001
+    rows = [list(rng.integers(100, 18_000, 2)) for _ in range(n)]
+    for j in range(8192):
+        rows[j].append(A)
+    for j in range(8193):
+        rows[j].append(B)
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    np.cumsum([len(r) for r in rows], out=rowptr[1:])
+    col = np.concatenate([np.array(r, dtype=np.int32) for r in rows])
+    g = make_graph(qv, ctx, rowptr, col)
+    want = oracle.access_prob(rowptr, col, [3, 2])
+    rt, ct = transpose_csr(rowptr, col)
+    assert rt[A + 1] - rt[A] == 8192 and rt[B + 1] - rt[B] == 8193
+    for block_log2 in (0, 6):
+        ctx.set_fap_block(block_log2)
+        g_in = g.transpose()
+        ctx.set_fap_block(0)
+        items = g_in.fap_items()
+        if block_log2:
+            assert items is not None and items[0].cpu().tolist() == [B]
+        else:
+            assert items is None
+        for direction in (0, 1):
+            ctx.set_fap_direction(direction)
+            P = qv.qv_access_prob(ctx, g, [3, 2], graph_in=g_in)
+            ctx.sync()
+            assert rel_err(P.cpu().numpy(), want) <= REL_TOL, (block_log2, direction)
+        ctx.set_fap_direction(0)
+        del g_in
+
+
 def test_csr_transpose_degenerate_graphs(qv, ctx):
     # no edges at all, a single node with a self loop, and parallel edges
     g0 = make_graph(qv, ctx, np.zeros(6, dtype=np.int64), np.zeros(0, dtype=np.int32))
